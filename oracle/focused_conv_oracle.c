@@ -1,0 +1,224 @@
+/*
+ * CPU oracle for the focused convolution (Tung et al., "Irrelevant Pixels are
+ * Everywhere", Sec. III-A and III-B).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It exists so that the GPU
+ * library can be checked against something that is slow, plain and easy to
+ * compare with the paper by eye.  Nothing under the product package may call
+ * it; only the tests, the smoke check and the benchmark's cpu_baseline leg do.
+ * It shares no code, header, table or helper with the HIP path.
+ *
+ * What the method computes has a plain definition, so the oracle is that
+ * definition written out, not a re-enactment of im2col:
+ *
+ *   - Sec. III-A: a patch labelled irrelevant is never turned into a column of
+ *     the GEMM matrix, so no output feature is produced for it; every other
+ *     patch is multiplied by the unchanged weights and gets the unchanged bias.
+ *     With no mask the layer is the standard convolution.
+ *   - Sec. III-B: the pixel mask is carried through the network by rescaling it
+ *     to each layer's spatial size.
+ *
+ * Readings fixed where the paper is silent (listed with reasons in the design
+ * document of this repository):
+ *   - a patch's label is the mask value under the centre tap of its receptive
+ *     field (nearest-neighbour rescaling of the mask, Sec. III-B; it is the
+ *     only rule that keeps the kept fraction constant through the layers, as
+ *     Table I's multiply-add ratios require);
+ *   - a kept patch sees zero at input pixels the input mask marks irrelevant;
+ *   - irrelevant output positions hold +0.0 in every channel, no bias;
+ *   - output size is floor((H + 2p - d(K-1) - 1)/s) + 1 (the Fig. 5 caption's
+ *     4x6 input / 3x3 kernel / stride 1 -> 8 columns fixes the "+1");
+ *   - masks are one byte per pixel, per image, nonzero = relevant.
+ *
+ * Layouts: x[N][H][W][C_in], w[C_out][KH][KW][C_in], bias[C_out] (float),
+ * masks uint8 [N][H][W], out double [N][Ho][Wo][C_out].  Inputs arrive already
+ * rounded to their storage type (float32, bfloat16 or IEEE half); they are
+ * widened exactly and accumulated in double in the loop order
+ * n, oh, ow, co, kh, kw, ci.  The result is left unrounded.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_pins.py
+ * (figure counts, closed forms, hand-computed cases, an independently written
+ * im2col+matmul, a library convolution, invariants).
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { FCO_F32 = 0, FCO_BF16 = 1, FCO_F16 = 2 };
+
+typedef struct {
+    int32_t n, h, w, c_in, c_out, kh, kw;
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int32_t dtype; /* storage type of x and w */
+    int32_t relu;  /* apply max(.,0) at kept positions */
+} fco_conv;
+
+/* ---- exact widening of the storage types ------------------------------- */
+
+static double widen_f32(const void *p, size_t i) { return (double)((const float *)p)[i]; }
+
+static double widen_bf16(const void *p, size_t i)
+{
+    /* bfloat16 is the upper half of a float32 */
+    uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static double widen_f16(const void *p, size_t i)
+{
+    uint16_t hbits = ((const uint16_t *)p)[i];
+    int sign = hbits >> 15, e = (hbits >> 10) & 31, frac = hbits & 1023;
+    double v;
+    if (e == 0)
+        v = (double)frac * (1.0 / 16777216.0); /* subnormal: frac * 2^-24 */
+    else if (e == 31)
+        v = frac ? (0.0 / 0.0) : (1.0 / 0.0);
+    else {
+        v = 1.0 + (double)frac / 1024.0;
+        int k = e - 15;
+        while (k > 0) { v *= 2.0; --k; }
+        while (k < 0) { v *= 0.5; ++k; }
+    }
+    return sign ? -v : v;
+}
+
+typedef double (*widen_fn)(const void *, size_t);
+
+static widen_fn pick_widen(int dtype)
+{
+    return dtype == FCO_BF16 ? widen_bf16 : dtype == FCO_F16 ? widen_f16 : widen_f32;
+}
+
+/* ---- output size (Sec. III-A operation count; Fig. 5 caption) ---------- */
+
+int32_t fco_out_dim(int32_t in, int32_t k, int32_t stride, int32_t pad, int32_t dil)
+{
+    int32_t span = in + 2 * pad - dil * (k - 1) - 1;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+/* threads the convolution loops will use (for the benchmark's report) */
+int32_t fco_num_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static int32_t clampi(int32_t v, int32_t lo, int32_t hi) { return v < lo ? lo : (v > hi ? hi : v); }
+
+/* ---- mask propagation (Sec. III-B) -------------------------------------
+ * The output-resolution mask takes, for each output position, the input mask
+ * under the centre tap of that position's receptive field, clamped into the
+ * image.  Output bytes are exactly 0 or 1.  Returns 0, or -1 on bad sizes. */
+int32_t fco_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
+                            int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                            int32_t ph, int32_t pw, int32_t dh, int32_t dw,
+                            uint8_t *mask_out)
+{
+    int32_t ho = fco_out_dim(h, kh, sh, ph, dh), wo = fco_out_dim(w, kw, sw, pw, dw);
+    if (n <= 0 || ho <= 0 || wo <= 0) return -1;
+    for (int32_t b = 0; b < n; ++b)
+        for (int32_t oh = 0; oh < ho; ++oh)
+            for (int32_t ow = 0; ow < wo; ++ow) {
+                int32_t ih = clampi(oh * sh - ph + dh * ((kh - 1) / 2), 0, h - 1);
+                int32_t iw = clampi(ow * sw - pw + dw * ((kw - 1) / 2), 0, w - 1);
+                uint8_t v = mask_in ? mask_in[((size_t)b * h + ih) * w + iw] : 1;
+                mask_out[((size_t)b * ho + oh) * wo + ow] = v ? 1 : 0;
+            }
+    return 0;
+}
+
+/* ---- which columns survive (Sec. III-A) --------------------------------
+ * Ascending list of the flat positions whose mask byte is nonzero. */
+int64_t fco_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx)
+{
+    int64_t j = 0;
+    for (int64_t p = 0; p < m; ++p)
+        if (mask[p]) idx[j++] = (int32_t)p;
+    return j;
+}
+
+/* ---- one output position, all channels --------------------------------- */
+static void conv_position(const fco_conv *c, widen_fn wd, const void *x, const uint8_t *mask_in,
+                          const void *w, const float *bias, int32_t b, int32_t oh, int32_t ow,
+                          double *out_row)
+{
+    int32_t ch = oh * c->stride_h - c->pad_h + c->dil_h * ((c->kh - 1) / 2);
+    int32_t cw = ow * c->stride_w - c->pad_w + c->dil_w * ((c->kw - 1) / 2);
+    ch = clampi(ch, 0, c->h - 1);
+    cw = clampi(cw, 0, c->w - 1);
+    if (mask_in && !mask_in[((size_t)b * c->h + ch) * c->w + cw]) {
+        for (int32_t co = 0; co < c->c_out; ++co) out_row[co] = 0.0;
+        return;
+    }
+    for (int32_t co = 0; co < c->c_out; ++co) {
+        double acc = bias ? (double)bias[co] : 0.0;
+        for (int32_t kh = 0; kh < c->kh; ++kh)
+            for (int32_t kw = 0; kw < c->kw; ++kw) {
+                int32_t ih = oh * c->stride_h - c->pad_h + kh * c->dil_h;
+                int32_t iw = ow * c->stride_w - c->pad_w + kw * c->dil_w;
+                if (ih < 0 || ih >= c->h || iw < 0 || iw >= c->w) continue; /* zero padding */
+                size_t pix = ((size_t)b * c->h + ih) * c->w + iw;
+                if (mask_in && !mask_in[pix]) continue; /* irrelevant input pixel counts as zero */
+                size_t xo = pix * c->c_in;
+                size_t wo = (((size_t)co * c->kh + kh) * c->kw + kw) * c->c_in;
+                for (int32_t ci = 0; ci < c->c_in; ++ci)
+                    acc += wd(x, xo + ci) * wd(w, wo + ci);
+            }
+        if (c->relu && acc < 0.0) acc = 0.0;
+        out_row[co] = acc;
+    }
+}
+
+/* ---- the whole layer ----------------------------------------------------
+ * out[N][Ho][Wo][C_out] in double.  mask_in NULL = every pixel relevant (the
+ * standard convolution, Sec. III-A last paragraph).  bias NULL = no bias. */
+int32_t fco_focused_conv2d(const fco_conv *c, const void *x, const uint8_t *mask_in,
+                           const void *w, const float *bias, double *out)
+{
+    int32_t ho = fco_out_dim(c->h, c->kh, c->stride_h, c->pad_h, c->dil_h);
+    int32_t wo = fco_out_dim(c->w, c->kw, c->stride_w, c->pad_w, c->dil_w);
+    if (c->n <= 0 || ho <= 0 || wo <= 0 || c->c_in <= 0 || c->c_out <= 0) return -1;
+    widen_fn wd = pick_widen(c->dtype);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int32_t b = 0; b < c->n; ++b)
+        for (int32_t oh = 0; oh < ho; ++oh)
+            for (int32_t ow = 0; ow < wo; ++ow)
+                conv_position(c, wd, x, mask_in, w, bias, b, oh, ow,
+                              out + (((size_t)b * ho + oh) * wo + ow) * c->c_out);
+    return 0;
+}
+
+/* ---- the same definition at a list of flat output positions -------------
+ * positions[j] = (b*Ho + oh)*Wo + ow; out[npos][C_out].  Lets large layers be
+ * checked on a sample. */
+int32_t fco_focused_conv2d_at(const fco_conv *c, const void *x, const uint8_t *mask_in,
+                              const void *w, const float *bias, const int64_t *positions,
+                              int64_t npos, double *out)
+{
+    int32_t ho = fco_out_dim(c->h, c->kh, c->stride_h, c->pad_h, c->dil_h);
+    int32_t wo = fco_out_dim(c->w, c->kw, c->stride_w, c->pad_w, c->dil_w);
+    if (c->n <= 0 || ho <= 0 || wo <= 0 || c->c_in <= 0 || c->c_out <= 0) return -1;
+    int64_t m = (int64_t)c->n * ho * wo;
+    for (int64_t j = 0; j < npos; ++j)
+        if (positions[j] < 0 || positions[j] >= m) return -2;
+    widen_fn wd = pick_widen(c->dtype);
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t j = 0; j < npos; ++j) {
+        int64_t p = positions[j];
+        int32_t ow = (int32_t)(p % wo);
+        int32_t oh = (int32_t)((p / wo) % ho);
+        int32_t b = (int32_t)(p / ((int64_t)wo * ho));
+        conv_position(c, wd, x, mask_in, w, bias, b, oh, ow, out + (size_t)j * c->c_out);
+    }
+    return 0;
+}

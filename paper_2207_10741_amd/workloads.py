@@ -1,0 +1,92 @@
+"""Layer lists of the benchmark workloads (shapes only, no arithmetic).
+
+The paper evaluates on whole detection networks with pretrained weights
+(Sec. III-B); those are not available, so conv stacks with the shapes of
+well-known classification backbones stand in.  A stack is a list of `Op`s; each
+reads the output of an earlier op (`src`, -1 = the stack's input) so that the
+1x1 projection convs of residual networks can consume their block's input.
+There are no batch-norms and no residual adds: every conv is followed by ReLU.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List
+
+
+@dataclass(frozen=True)
+class Op:
+    kind: str      # "conv" or "maxpool"
+    name: str
+    c_in: int
+    c_out: int
+    k: int
+    stride: int
+    pad: int
+    src: int       # index of the op whose output is read; -1 = stack input
+    relu: bool = True
+
+
+def resnet18() -> List[Op]:
+    """All 20 convs of ResNet-18 (7x7/2 stem, 16 3x3, three 1x1/2 projections)
+    and the 3x3/2 stem max-pool."""
+    ops: List[Op] = [Op("conv", "conv1", 3, 64, 7, 2, 3, -1), Op("maxpool", "pool1", 64, 64, 3, 2, 1, 0)]
+    c_prev = 64
+    last = 1
+    for stage, c in enumerate((64, 128, 256, 512), start=1):
+        for blk in range(2):
+            block_in = last
+            s = 2 if (stage > 1 and blk == 0) else 1
+            ops.append(Op("conv", "s%db%d_a" % (stage, blk), c_prev, c, 3, s, 1, block_in))
+            ops.append(Op("conv", "s%db%d_b" % (stage, blk), c, c, 3, 1, 1, len(ops) - 1))
+            last = len(ops) - 1
+            if s == 2:
+                ops.append(Op("conv", "s%db%d_down" % (stage, blk), c_prev, c, 1, 2, 0, block_in))
+            c_prev = c
+    return ops
+
+
+def resnet50_bottlenecks() -> List[Op]:
+    """The 52 convs of ResNet-50's 16 bottleneck blocks (1x1 / 3x3 / 1x1, plus a
+    1x1 projection on the first block of each stage).  Stride 2 sits on the 3x3
+    of the first block of stages 2-4.  Input: the post-stem activation, 64
+    channels at 1/4 of the image side."""
+    ops: List[Op] = []
+    c_prev = 64
+    last = -1
+    for stage, (mid, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3)), start=1):
+        c_out = 4 * mid
+        for blk in range(blocks):
+            block_in = last
+            s = 2 if (stage > 1 and blk == 0) else 1
+            ops.append(Op("conv", "s%db%d_1x1a" % (stage, blk), c_prev, mid, 1, 1, 0, block_in))
+            ops.append(Op("conv", "s%db%d_3x3" % (stage, blk), mid, mid, 3, s, 1, len(ops) - 1))
+            ops.append(Op("conv", "s%db%d_1x1b" % (stage, blk), mid, c_out, 1, 1, 0, len(ops) - 1))
+            last = len(ops) - 1
+            if blk == 0:
+                ops.append(Op("conv", "s%db%d_down" % (stage, blk), c_prev, c_out, 1, s, 0, block_in))
+            c_prev = c_out
+    return ops
+
+
+def vgg16() -> List[Op]:
+    """VGG-16's 13 3x3 convs with 2x2/2 max-pools after convs 2, 4, 7 and 10."""
+    ops: List[Op] = []
+    c_prev = 3
+    i = 0
+    for c, reps in ((64, 2), (128, 2), (256, 3), (512, 3), (512, 3)):
+        for _ in range(reps):
+            i += 1
+            ops.append(Op("conv", "conv%d" % i, c_prev, c, 3, 1, 1, len(ops) - 1))
+            c_prev = c
+        if i < 13:
+            ops.append(Op("maxpool", "pool%d" % i, c, c, 2, 2, 0, len(ops) - 1))
+    return ops
+
+
+def sweep_shapes():
+    """(C, side) of ResNet-50's four 3x3 layer shapes for a 512x512 image."""
+    return [(64, 128), (128, 64), (256, 32), (512, 16)]
+
+
+SWEEP_BATCH = 16
+HEADLINE_IRRELEVANT = 0.48   # Sec. II-B: the paper's overall irrelevant-pixel share
