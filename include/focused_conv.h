@@ -1,0 +1,142 @@
+/*
+ * focused_conv.h - C ABI of the focused convolution library for AMD MI355X
+ * (gfx950).
+ *
+ * The focused convolution (Tung et al., "Irrelevant Pixels are Everywhere",
+ * Sec. III-A) is a GEMM convolution whose im2col step skips every patch that a
+ * binary pixel mask labels irrelevant, so that the matrix product has fewer
+ * columns; weights and bias are those of the dense layer, and with no mask the
+ * layer is the standard convolution.  Sec. III-B carries the mask through a
+ * network by rescaling it to each layer's spatial size.
+ *
+ * Semantics fixed by this library (the paper leaves them open):
+ *   - mask: one byte per pixel, per image, [N][H][W]; nonzero = relevant.
+ *   - a patch (= an output position) is kept iff the INPUT mask under the
+ *     centre tap of its receptive field is relevant:
+ *         ih_c = clamp(oh*stride_h - pad_h + dil_h*((KH-1)/2), 0, H-1)
+ *     (same for iw_c).  This is nearest-neighbour rescaling of the mask.
+ *   - a kept output equals the dense convolution of the input with irrelevant
+ *     input pixels (and padding) treated as zero.  Gated taps are skipped, not
+ *     multiplied: NaN/Inf at irrelevant input pixels never reach an output.
+ *   - an irrelevant output position holds +0.0 in every channel (no bias), or
+ *     is left untouched when FC_SKIP_ZERO_FILL is set.
+ *   - Ho = floor((H + 2*pad_h - dil_h*(KH-1) - 1)/stride_h) + 1 (same for Wo).
+ *   - arithmetic: products of the stored inputs accumulated in fp32, bias added
+ *     in fp32, optional ReLU, one round-to-nearest-even to the output type.
+ *
+ * Layouts (all dense, no strides): x[N][H][W][C_in] (NHWC),
+ * w[C_out][KH][KW][C_in], bias[C_out] float32, out[N][Ho][Wo][C_out].
+ *
+ * Conventions for every entry point:
+ *   - pointers marked "device" are HIP device memory owned by the caller; the
+ *     library allocates nothing, frees nothing and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     All device work is enqueued on it; no call waits for the device and no
+ *     call reads results back to the host.
+ *   - the return value is an fc_status.  Argument errors are found on the host
+ *     before anything is launched and leave every output untouched.
+ *   - device base pointers must be 16-byte aligned.
+ */
+#ifndef FOCUSED_CONV_H
+#define FOCUSED_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FC_OK = 0,
+    FC_ERR_NULL = -1,      /* a required pointer is NULL */
+    FC_ERR_SHAPE = -2,     /* a size is zero/negative or gives an empty output */
+    FC_ERR_DTYPE = -3,     /* unknown or unsupported type combination */
+    FC_ERR_ALIGN = -4,     /* a device pointer is not 16-byte aligned */
+    FC_ERR_WORKSPACE = -5, /* workspace missing or smaller than fc_workspace_bytes */
+    FC_ERR_RANGE = -6,     /* N*Ho*Wo or N*H*W does not fit the 31-bit index type */
+    FC_ERR_HIP = -7        /* the HIP runtime refused a launch */
+} fc_status;
+
+typedef enum { FC_F32 = 0, FC_BF16 = 1, FC_F16 = 2 } fc_dtype;
+
+enum {
+    FC_RELU = 1u,           /* max(.,0) at kept positions */
+    FC_SKIP_ZERO_FILL = 2u  /* leave irrelevant output positions untouched */
+};
+
+/* One convolution layer.  in_dtype is the storage type of x and w; out_dtype is
+ * in_dtype or FC_F32. */
+typedef struct fc_conv_desc {
+    int32_t n, h, w, c_in, c_out, kh, kw;
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    int32_t in_dtype, out_dtype; /* fc_dtype */
+    uint32_t flags;
+} fc_conv_desc;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *fc_status_string(int32_t status);
+
+/* Output size of a layer (Sec. III-A operation count; the Fig. 5 caption's 4x6
+ * input with a 3x3 kernel giving 8 patches fixes the "+1").  Host only. */
+int32_t fc_out_dims(const fc_conv_desc *desc, int32_t *ho, int32_t *wo);
+
+/* Bytes of device workspace fc_focused_conv2d needs when the caller passes no
+ * index list (mask_out + idx + count + scan scratch), and
+ * fc_active_index_compact needs for `m` positions.  Host only. */
+int32_t fc_workspace_bytes(const fc_conv_desc *desc, size_t *bytes);
+int32_t fc_compact_workspace_bytes(int64_t m, size_t *bytes);
+
+/* Mask propagation (Sec. III-B: the mask is rescaled to each layer's size).
+ * mask_out[n][oh][ow] = (mask_in under the centre tap of (oh,ow)) != 0, written
+ * as 0/1 bytes.  Takes the geometry of the layer (or pooling window) that
+ * changes the resolution.
+ *   mask_in  device, [n][h][w] bytes, read only
+ *   mask_out device, [n][ho][wo] bytes, fully overwritten */
+int32_t fc_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
+                           int32_t kh, int32_t kw, int32_t stride_h, int32_t stride_w,
+                           int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w,
+                           uint8_t *mask_out, void *stream);
+
+/* Which patches become columns (Sec. III-A: an irrelevant patch is not
+ * converted).  Writes the ascending list of flat positions p in [0,m) with
+ * mask[p] != 0 and their number.  One list serves every layer at that
+ * resolution.
+ *   mask      device, m bytes, read only
+ *   idx       device, capacity m int32; idx[0..count) written, rest unspecified
+ *   count     device, one int32, overwritten
+ *   workspace device, >= fc_compact_workspace_bytes(m) */
+int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* The layer (Sec. III-A).  Gathers the receptive fields of the kept positions
+ * (implicit im2col), multiplies by the unchanged weights on the matrix cores,
+ * adds bias, applies ReLU if asked, writes each kept row, zero-fills the rest.
+ *   x         device, NHWC, in_dtype, read only
+ *   mask_in   device [n][h][w] bytes, or NULL = every pixel relevant (the dense
+ *             layer; idx/count/mask_out must then be NULL too)
+ *   w         device, [c_out][kh][kw][c_in], in_dtype, read only
+ *   bias      device, c_out floats, or NULL
+ *   mask_out  device [n][ho][wo] 0/1 bytes as fc_mask_downsample writes them for
+ *             this layer's geometry, or NULL (then derived from mask_in)
+ *   idx,count device, as fc_active_index_compact writes them from mask_out; both
+ *             NULL = computed here into the workspace
+ *   out       device, NHWC, out_dtype; must not overlap x
+ *   workspace device, >= fc_workspace_bytes(desc) when idx is NULL and mask_in is
+ *             not; otherwise may be NULL
+ * `count` is read on the device only; the launch grid does not depend on it. */
+int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in,
+                          const void *w, const float *bias, const uint8_t *mask_out,
+                          const int32_t *idx, const int32_t *count, void *out,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Helper for conv stacks with pooling between layers (not part of the paper's
+ * method): NHWC max-pool over the full tensor, window k, stride s, padding p
+ * (padding never wins the max).  x/out device, dtype as given. */
+int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype,
+                     int32_t k, int32_t stride, int32_t pad, void *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOCUSED_CONV_H */

@@ -1,0 +1,189 @@
+"""Python binding of the C ABI in include/focused_conv.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libfocused_conv.so.  PyTorch supplies device memory and the stream.  There is
+no fallback - if the library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfocused_conv.so")
+
+F32, BF16, F16 = 0, 1, 2
+RELU, SKIP_ZERO_FILL = 1, 2
+
+FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
+             "fc_mask_downsample", "fc_active_index_compact", "fc_focused_conv2d", "fc_maxpool2d")
+
+
+class FcError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (what, status_string(status)))
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of fc_conv_desc."""
+    _fields_ = [(k, ctypes.c_int32) for k in (
+        "n", "h", "w", "c_in", "c_out", "kh", "kw", "stride_h", "stride_w",
+        "pad_h", "pad_w", "dil_h", "dil_w", "in_dtype", "out_dtype")] + [("flags", ctypes.c_uint32)]
+
+
+def conv_desc(n, h, w, c_in, c_out, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1),
+              in_dtype=BF16, out_dtype=None, flags=0) -> ConvDesc:
+    return ConvDesc(n, h, w, c_in, c_out, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
+                    dil[0], dil[1], in_dtype, in_dtype if out_dtype is None else out_dtype, flags)
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "%s is missing: build it with `python -m paper_2207_10741_amd.build` "
+                "(hipcc --offload-arch=gfx950); there is no CPU fallback" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.fc_status_string.restype = ctypes.c_char_p
+        L.fc_status_string.argtypes = [i32]
+        L.fc_out_dims.restype = i32
+        L.fc_out_dims.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.fc_workspace_bytes.restype = i32
+        L.fc_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ctypes.c_size_t)]
+        L.fc_compact_workspace_bytes.restype = i32
+        L.fc_compact_workspace_bytes.argtypes = [i64, ctypes.POINTER(ctypes.c_size_t)]
+        L.fc_mask_downsample.restype = i32
+        L.fc_mask_downsample.argtypes = [vp] + [i32] * 11 + [vp, vp]
+        L.fc_active_index_compact.restype = i32
+        L.fc_active_index_compact.argtypes = [vp, i64, vp, vp, vp, ctypes.c_size_t, vp]
+        L.fc_focused_conv2d.restype = i32
+        L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.fc_maxpool2d.restype = i32
+        L.fc_maxpool2d.argtypes = [vp] + [i32] * 8 + [vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().fc_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise FcError(status, what)
+
+
+def out_dims(desc: ConvDesc):
+    ho, wo = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().fc_out_dims(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo)), "fc_out_dims")
+    return ho.value, wo.value
+
+
+def workspace_bytes(desc: ConvDesc) -> int:
+    b = ctypes.c_size_t()
+    _check(lib().fc_workspace_bytes(ctypes.byref(desc), ctypes.byref(b)), "fc_workspace_bytes")
+    return b.value
+
+
+def compact_workspace_bytes(m: int) -> int:
+    b = ctypes.c_size_t()
+    _check(lib().fc_compact_workspace_bytes(int(m), ctypes.byref(b)), "fc_compact_workspace_bytes")
+    return b.value
+
+
+# ---- device-side calls (torch tensors in, torch tensors out) ----------------
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = _torch().cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def torch_dtype(code: int):
+    torch = _torch()
+    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[code]
+
+
+def _require_cuda(*tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def mask_downsample(mask_in, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1), out=None, stream=None):
+    """fc_mask_downsample: uint8 [N,H,W] -> uint8 [N,Ho,Wo] (0/1)."""
+    torch = _torch()
+    _require_cuda(mask_in, out)
+    n, h, w = mask_in.shape
+    d = conv_desc(n, h, w, 1, 1, k, stride, pad, dil, F32)
+    ho, wo = out_dims(d)
+    if out is None:
+        out = torch.empty((n, ho, wo), dtype=torch.uint8, device=mask_in.device)
+    _check(lib().fc_mask_downsample(_ptr(mask_in), n, h, w, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
+                                    dil[0], dil[1], _ptr(out), _stream(stream)), "fc_mask_downsample")
+    return out
+
+
+def active_index_compact(mask, idx=None, count=None, workspace=None, stream=None):
+    """fc_active_index_compact: uint8 [...] -> (idx int32 [m] (first `count` valid), count int32 [1])."""
+    torch = _torch()
+    _require_cuda(mask, idx, count, workspace)
+    m = mask.numel()
+    if idx is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=mask.device)
+    if count is None:
+        count = torch.empty((1,), dtype=torch.int32, device=mask.device)
+    if workspace is None:
+        workspace = torch.empty((compact_workspace_bytes(m),), dtype=torch.uint8, device=mask.device)
+    _check(lib().fc_active_index_compact(_ptr(mask), m, _ptr(idx), _ptr(count), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream)),
+           "fc_active_index_compact")
+    return idx, count
+
+
+def focused_conv2d(desc: ConvDesc, x, w, bias=None, mask_in=None, mask_out=None, idx=None, count=None,
+                   out=None, workspace=None, stream=None):
+    """fc_focused_conv2d.  x NHWC, w [C_out,KH,KW,C_in]; returns out NHWC."""
+    torch = _torch()
+    _require_cuda(x, w, bias, mask_in, mask_out, idx, count, out, workspace)
+    ho, wo = out_dims(desc)
+    if out is None:
+        out = torch.empty((desc.n, ho, wo, desc.c_out), dtype=torch_dtype(desc.out_dtype), device=x.device)
+    if workspace is None and mask_in is not None and idx is None:
+        workspace = torch.empty((workspace_bytes(desc),), dtype=torch.uint8, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fc_focused_conv2d(ctypes.byref(desc), _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias),
+                                   _ptr(mask_out), _ptr(idx), _ptr(count), _ptr(out), _ptr(workspace),
+                                   ws_bytes, _stream(stream)), "fc_focused_conv2d")
+    return out
+
+
+def maxpool2d(x, k: int, stride: int, pad: int, dtype: int, out=None, stream=None):
+    """fc_maxpool2d helper: NHWC max-pool of the whole tensor."""
+    torch = _torch()
+    _require_cuda(x, out)
+    n, h, w, c = x.shape
+    d = conv_desc(n, h, w, 1, 1, (k, k), (stride, stride), (pad, pad), (1, 1), F32)
+    ho, wo = out_dims(d)
+    if out is None:
+        out = torch.empty((n, ho, wo, c), dtype=x.dtype, device=x.device)
+    _check(lib().fc_maxpool2d(_ptr(x), n, h, w, c, dtype, k, stride, pad, _ptr(out), _stream(stream)),
+           "fc_maxpool2d")
+    return out

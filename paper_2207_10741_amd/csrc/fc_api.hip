@@ -1,0 +1,193 @@
+// C ABI of the library: argument checks on the host, then launches.
+#include "fc_internal.hpp"
+
+using namespace fc;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int32_t out_dim(int32_t in, int32_t k, int32_t s, int32_t p, int32_t d)
+{
+    const int64_t span = (int64_t)in + 2 * (int64_t)p - (int64_t)d * (k - 1) - 1;
+    if (span < 0) return 0;
+    return (int32_t)(span / s + 1);
+}
+
+// Validates the descriptor and fills the kernel geometry.
+int32_t make_geom(const fc_conv_desc *d, Geom *g)
+{
+    if (!d) return FC_ERR_NULL;
+    if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c_in <= 0 || d->c_out <= 0 || d->kh <= 0 || d->kw <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0 || d->dil_h <= 0 || d->dil_w <= 0)
+        return FC_ERR_SHAPE;
+    if (d->in_dtype != FC_F32 && d->in_dtype != FC_BF16 && d->in_dtype != FC_F16) return FC_ERR_DTYPE;
+    if (d->out_dtype != d->in_dtype && d->out_dtype != FC_F32) return FC_ERR_DTYPE;
+    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL)) return FC_ERR_DTYPE;
+    const int32_t ho = out_dim(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
+    const int32_t wo = out_dim(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
+    if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
+    const int64_t m = (int64_t)d->n * ho * wo, pix = (int64_t)d->n * d->h * d->w;
+    if (m >= INT32_MAX || pix >= INT32_MAX) return FC_ERR_RANGE;
+    if ((int64_t)d->kh * d->kw * d->c_in >= INT32_MAX) return FC_ERR_RANGE;
+    g->n = d->n; g->h = d->h; g->w = d->w; g->c_in = d->c_in; g->c_out = d->c_out;
+    g->kh = d->kh; g->kw = d->kw; g->sh = d->stride_h; g->sw = d->stride_w;
+    g->ph = d->pad_h; g->pw = d->pad_w; g->dh = d->dil_h; g->dw = d->dil_w;
+    g->ho = ho; g->wo = wo; g->m = (int32_t)m; g->flags = d->flags;
+    return FC_OK;
+}
+
+size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }
+
+struct ConvWorkspace {
+    size_t mask_out, idx, count, scan, total;
+};
+
+ConvWorkspace conv_ws_layout(int64_t m)
+{
+    ConvWorkspace l;
+    l.mask_out = 0;
+    l.idx = align_up((size_t)m, 256);
+    l.count = l.idx + align_up((size_t)m * sizeof(int32_t), 256);
+    l.scan = l.count + 256;
+    l.total = l.scan + compact_ws(m);
+    return l;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *fc_status_string(int32_t status)
+{
+    switch (status) {
+    case FC_OK: return "FC_OK";
+    case FC_ERR_NULL: return "FC_ERR_NULL: a required pointer is NULL";
+    case FC_ERR_SHAPE: return "FC_ERR_SHAPE: a size is not positive or the output is empty";
+    case FC_ERR_DTYPE: return "FC_ERR_DTYPE: unsupported type or flag combination";
+    case FC_ERR_ALIGN: return "FC_ERR_ALIGN: a device pointer is not 16-byte aligned";
+    case FC_ERR_WORKSPACE: return "FC_ERR_WORKSPACE: workspace missing or too small";
+    case FC_ERR_RANGE: return "FC_ERR_RANGE: position count does not fit 31 bits";
+    case FC_ERR_HIP: return "FC_ERR_HIP: the HIP runtime refused a launch";
+    default: return "unknown fc_status";
+    }
+}
+
+int32_t fc_out_dims(const fc_conv_desc *desc, int32_t *ho, int32_t *wo)
+{
+    if (!desc || !ho || !wo) return FC_ERR_NULL;
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != FC_OK) return rc;
+    *ho = g.ho;
+    *wo = g.wo;
+    return FC_OK;
+}
+
+int32_t fc_compact_workspace_bytes(int64_t m, size_t *bytes)
+{
+    if (!bytes) return FC_ERR_NULL;
+    if (m <= 0) return FC_ERR_SHAPE;
+    if (m >= INT32_MAX) return FC_ERR_RANGE;
+    *bytes = compact_ws(m);
+    return FC_OK;
+}
+
+int32_t fc_workspace_bytes(const fc_conv_desc *desc, size_t *bytes)
+{
+    if (!desc || !bytes) return FC_ERR_NULL;
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != FC_OK) return rc;
+    *bytes = conv_ws_layout(g.m).total;
+    return FC_OK;
+}
+
+int32_t fc_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                           int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t dil_h,
+                           int32_t dil_w, uint8_t *mask_out, void *stream)
+{
+    if (!mask_in || !mask_out) return FC_ERR_NULL;
+    if (n <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0 || dil_h <= 0 || dil_w <= 0)
+        return FC_ERR_SHAPE;
+    const int32_t ho = out_dim(h, kh, stride_h, pad_h, dil_h), wo = out_dim(w, kw, stride_w, pad_w, dil_w);
+    if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
+    if ((int64_t)n * ho * wo >= INT32_MAX || (int64_t)n * h * w >= INT32_MAX) return FC_ERR_RANGE;
+    const hipError_t e = launch_mask_downsample(mask_in, n, h, w, kh, kw, stride_h, stride_w, pad_h, pad_w,
+                                                dil_h, dil_w, ho, wo, mask_out, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
+int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (!mask || !idx || !count) return FC_ERR_NULL;
+    if (m <= 0) return FC_ERR_SHAPE;
+    if (m >= INT32_MAX) return FC_ERR_RANGE;
+    if (!workspace || workspace_bytes < compact_ws(m)) return FC_ERR_WORKSPACE;
+    if (!aligned16(mask) || !aligned16(idx) || !aligned16(workspace)) return FC_ERR_ALIGN;
+    const hipError_t e = launch_compact(mask, m, idx, count, (int32_t *)workspace, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
+int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in, const void *w,
+                          const float *bias, const uint8_t *mask_out, const int32_t *idx, const int32_t *count,
+                          void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != FC_OK) return rc;
+    if (!x || !w || !out) return FC_ERR_NULL;
+    if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
+    if (!mask_in && (idx || mask_out)) return FC_ERR_NULL; // a kept list without the mask that gates the taps
+    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(idx)) return FC_ERR_ALIGN;
+    if (x == out) return FC_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (mask_in && !idx) {
+        // derive mask_out, the index list and its length here, in the workspace
+        const ConvWorkspace l = conv_ws_layout(g.m);
+        if (!workspace || workspace_bytes < l.total) return FC_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return FC_ERR_ALIGN;
+        uint8_t *ws = (uint8_t *)workspace;
+        uint8_t *m_out = ws + l.mask_out;
+        hipError_t e = launch_mask_downsample(mask_in, g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh,
+                                              g.dw, g.ho, g.wo, m_out, s);
+        if (e != hipSuccess) return FC_ERR_HIP;
+        e = launch_compact(m_out, g.m, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                           (int32_t *)(ws + l.scan), s);
+        if (e != hipSuccess) return FC_ERR_HIP;
+        mask_out = m_out;
+        idx = (const int32_t *)(ws + l.idx);
+        count = (const int32_t *)(ws + l.count);
+    }
+
+    hipError_t e;
+    if (conv_mfma_supported(g, desc->in_dtype, desc->out_dtype))
+        e = launch_conv_mfma(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s);
+    else
+        e = launch_conv_direct(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s);
+    if (e != hipSuccess) return FC_ERR_HIP;
+
+    if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL)) {
+        e = launch_zero_fill(g, mask_in, mask_out, out, desc->out_dtype, s);
+        if (e != hipSuccess) return FC_ERR_HIP;
+    }
+    return FC_OK;
+}
+
+int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,
+                     int32_t stride, int32_t pad, void *out, void *stream)
+{
+    if (!x || !out) return FC_ERR_NULL;
+    if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || k <= 0 || stride <= 0 || pad < 0 || 2 * pad > k)
+        return FC_ERR_SHAPE;
+    if (dtype != FC_F32 && dtype != FC_BF16 && dtype != FC_F16) return FC_ERR_DTYPE;
+    const int32_t ho = out_dim(h, k, stride, pad, 1), wo = out_dim(w, k, stride, pad, 1);
+    if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
+    const hipError_t e = launch_maxpool(x, n, h, w, c, dtype, k, stride, pad, ho, wo, out, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
+} // extern "C"

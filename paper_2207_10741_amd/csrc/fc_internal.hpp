@@ -1,0 +1,82 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "focused_conv.h"
+
+namespace fc {
+
+// Geometry handed to every kernel (plain ints, passed by value).
+struct Geom {
+    int32_t n, h, w, c_in, c_out, kh, kw;
+    int32_t sh, sw, ph, pw, dh, dw;
+    int32_t ho, wo;
+    int32_t m;        // n*ho*wo
+    uint32_t flags;
+};
+
+// 16-bit storage types are carried as raw bit patterns.
+struct bf16_t { uint16_t bits; };
+struct f16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+__device__ __forceinline__ float to_float(f16_t v)
+{
+    _Float16 h;
+    __builtin_memcpy(&h, &v.bits, 2);
+    return (float)h;
+}
+
+// float -> storage, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint16_t bf16_bits_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ uint16_t f16_bits_rne(float f)
+{
+    _Float16 h = (_Float16)f;
+    uint16_t b;
+    __builtin_memcpy(&b, &h, 2);
+    return b;
+}
+__device__ __forceinline__ void from_float(float f, float *o) { *o = f; }
+__device__ __forceinline__ void from_float(float f, bf16_t *o) { o->bits = bf16_bits_rne(f); }
+__device__ __forceinline__ void from_float(float f, f16_t *o) { o->bits = f16_bits_rne(f); }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr int kCompactBlockThreads = 256;
+constexpr int kCompactBytesPerThread = 16;
+constexpr int kCompactBlockElems = kCompactBlockThreads * kCompactBytesPerThread; // 4096
+
+static inline int64_t compact_blocks(int64_t m) { return (m + kCompactBlockElems - 1) / kCompactBlockElems; }
+
+// ---- launchers (each enqueues on `s`, returns a hipError_t) ----------------
+hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, int kh, int kw,
+                                  int sh, int sw, int ph, int pw, int dh, int dw, int ho, int wo,
+                                  uint8_t *mask_out, hipStream_t s);
+hipError_t launch_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
+                          int32_t *block_counts, hipStream_t s);
+hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
+                            int out_dtype, hipStream_t s);
+hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,
+                          int pad, int ho, int wo, void *out, hipStream_t s);
+
+// Direct convolution over the active rows; any shape, any dtype.
+hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const void *x,
+                              const uint8_t *mask_in, const void *w, const float *bias,
+                              const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
+
+// Matrix-core path; returns hipErrorNotSupported when the shape does not fit it.
+bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype);
+hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x,
+                            const uint8_t *mask_in, const void *w, const float *bias,
+                            const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
+
+} // namespace fc

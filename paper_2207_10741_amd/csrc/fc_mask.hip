@@ -1,0 +1,269 @@
+// Mask-side kernels: mask propagation (Sec. III-B), ordered compaction of the kept
+// positions (Sec. III-A: which patches become columns), zero-fill of the irrelevant
+// output rows, and the max-pool helper.  All of them are HBM-bound byte/row movers.
+#include "fc_internal.hpp"
+
+namespace fc {
+
+// ---------------------------------------------------------------------------
+// Mask propagation: one thread per output byte; the byte under the centre tap.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_mask_downsample(const uint8_t *__restrict__ mask_in, int n, int h,
+                                                         int w, int ch0, int cw0, int sh, int sw, int ho,
+                                                         int wo, uint8_t *__restrict__ mask_out)
+{
+    const int64_t total = (int64_t)n * ho * wo;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total;
+         p += (int64_t)gridDim.x * blockDim.x) {
+        int ow = (int)(p % wo);
+        int64_t t = p / wo;
+        int oh = (int)(t % ho);
+        int b = (int)(t / ho);
+        int ih = min(max(oh * sh + ch0, 0), h - 1);
+        int iw = min(max(ow * sw + cw0, 0), w - 1);
+        mask_out[p] = mask_in[((int64_t)b * h + ih) * w + iw] ? 1 : 0;
+    }
+}
+
+hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, int kh, int kw, int sh,
+                                  int sw, int ph, int pw, int dh, int dw, int ho, int wo,
+                                  uint8_t *mask_out, hipStream_t s)
+{
+    const int64_t total = (int64_t)n * ho * wo;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 65536) blocks = 65536;
+    const int ch0 = -ph + dh * ((kh - 1) / 2), cw0 = -pw + dw * ((kw - 1) / 2);
+    hipLaunchKernelGGL(k_mask_downsample, dim3(blocks), dim3(256), 0, s, mask_in, n, h, w, ch0, cw0, sh, sw,
+                       ho, wo, mask_out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Ordered compaction.  A block owns 4096 consecutive mask bytes, a lane 16 of
+// them (one 128-bit load).  Pass 1 counts the kept bytes of every block.  Pass 2
+// gives each block the sum of the counts before it, ranks its own kept bytes with
+// a wave prefix sum (ballot + mbcnt inside a wave, LDS across the four waves),
+// stages the indices in LDS in order and copies them out coalesced.  Neither pass
+// waits on another block, so the grid always drains.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t load_flags16(const uint8_t *__restrict__ mask, int64_t base, int64_t m)
+{
+    // bit j = (mask[base + j] != 0), bytes past m read as 0
+    uint32_t flags = 0;
+    if (base + 16 <= m) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(mask + base);
+        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
+    } else {
+        for (int j = 0; j < 16; ++j)
+            if (base + j < m && mask[base + j]) flags |= 1u << j;
+    }
+    return flags;
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    const int lane = __lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_compact_count(const uint8_t *__restrict__ mask,
+                                                                         int64_t m,
+                                                                         int32_t *__restrict__ block_counts)
+{
+    __shared__ int wave_sum[kCompactBlockThreads / 64];
+    const int64_t base = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)threadIdx.x * kCompactBytesPerThread;
+    int c = __popc(load_flags16(mask, base, m));
+    // wave total through ballots of the count's bits (counts are 0..16: 5 bits)
+    int total = 0;
+#pragma unroll
+    for (int b = 0; b < 5; ++b) total += __popcll(__ballot((c >> b) & 1)) << b;
+    if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < kCompactBlockThreads / 64; ++i) s += wave_sum[i];
+        block_counts[blockIdx.x] = s;
+    }
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(const uint8_t *__restrict__ mask,
+                                                                           int64_t m,
+                                                                           const int32_t *__restrict__ block_counts,
+                                                                           int32_t *__restrict__ idx,
+                                                                           int32_t *__restrict__ count)
+{
+    __shared__ int wave_sum[kCompactBlockThreads / 64];
+    __shared__ int base_sum[kCompactBlockThreads / 64];
+    __shared__ int32_t stage[kCompactBlockElems];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    // offset of this block = sum of the counts of all blocks before it
+    int part = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += kCompactBlockThreads) part += block_counts[i];
+    part = wave_inclusive_scan(part);
+    if (lane == 63) base_sum[wave] = part;
+
+    const int64_t base = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)tid * kCompactBytesPerThread;
+    const uint32_t flags = load_flags16(mask, base, m);
+    const int c = __popc(flags);
+    const int incl = wave_inclusive_scan(c);
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+
+    int block_base = 0, before = 0, block_total = 0;
+#pragma unroll
+    for (int i = 0; i < kCompactBlockThreads / 64; ++i) {
+        block_base += base_sum[i];
+        if (i < wave) before += wave_sum[i];
+        block_total += wave_sum[i];
+    }
+    int pos = before + incl - c;
+    uint32_t f = flags;
+    while (f) {
+        const int j = __ffs(f) - 1;
+        f &= f - 1;
+        stage[pos++] = (int32_t)(base + j);
+    }
+    __syncthreads();
+    for (int i = tid; i < block_total; i += kCompactBlockThreads) idx[(int64_t)block_base + i] = stage[i];
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) *count = block_base + block_total;
+}
+
+hipError_t launch_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
+                          int32_t *block_counts, hipStream_t s)
+{
+    const int nb = (int)compact_blocks(m);
+    hipLaunchKernelGGL(k_compact_count, dim3(nb), dim3(kCompactBlockThreads), 0, s, mask, m, block_counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_compact_scatter, dim3(nb), dim3(kCompactBlockThreads), 0, s, mask, m, block_counts, idx,
+                       count);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Zero-fill of the irrelevant output rows: a lane owns 16 bytes of one row.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ bool position_kept(const Geom &g, const uint8_t *__restrict__ mask_in,
+                                              const uint8_t *__restrict__ mask_out, int64_t p)
+{
+    if (mask_out) return mask_out[p] != 0;
+    int ow = (int)(p % g.wo);
+    int64_t t = p / g.wo;
+    int oh = (int)(t % g.ho);
+    int b = (int)(t / g.ho);
+    int ih = min(max(oh * g.sh - g.ph + g.dh * ((g.kh - 1) / 2), 0), g.h - 1);
+    int iw = min(max(ow * g.sw - g.pw + g.dw * ((g.kw - 1) / 2), 0), g.w - 1);
+    return mask_in[((int64_t)b * g.h + ih) * g.w + iw] != 0;
+}
+
+__global__ __launch_bounds__(256) void k_zero_fill16(Geom g, const uint8_t *__restrict__ mask_in,
+                                                     const uint8_t *__restrict__ mask_out,
+                                                     uint4 *__restrict__ out, int chunks_per_row)
+{
+    const int64_t total = (int64_t)g.m * chunks_per_row;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < total;
+         c += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t p = c / chunks_per_row;
+        if (!position_kept(g, mask_in, mask_out, p)) out[c] = make_uint4(0, 0, 0, 0);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_zero_fill_bytes(Geom g, const uint8_t *__restrict__ mask_in,
+                                                         const uint8_t *__restrict__ mask_out,
+                                                         uint8_t *__restrict__ out, int row_bytes)
+{
+    const int64_t total = (int64_t)g.m * row_bytes;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < total;
+         c += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t p = c / row_bytes;
+        if (!position_kept(g, mask_in, mask_out, p)) out[c] = 0;
+    }
+}
+
+hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
+                            int out_dtype, hipStream_t s)
+{
+    const int esz = out_dtype == FC_F32 ? 4 : 2;
+    const int row_bytes = g.c_out * esz;
+    if (row_bytes % 16 == 0) {
+        const int cpr = row_bytes / 16;
+        int64_t total = (int64_t)g.m * cpr;
+        int blocks = (int)((total + 255) / 256 > 16384 ? 16384 : (total + 255) / 256);
+        hipLaunchKernelGGL(k_zero_fill16, dim3(blocks), dim3(256), 0, s, g, mask_in, mask_out, (uint4 *)out, cpr);
+    } else {
+        int64_t total = (int64_t)g.m * row_bytes;
+        int blocks = (int)((total + 255) / 256 > 16384 ? 16384 : (total + 255) / 256);
+        hipLaunchKernelGGL(k_zero_fill_bytes, dim3(blocks), dim3(256), 0, s, g, mask_in, mask_out, (uint8_t *)out,
+                           row_bytes);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Max-pool helper (NHWC, whole tensor).  Padding never wins.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void k_maxpool(const T *__restrict__ x, int n, int h, int w, int c, int k,
+                                                 int stride, int pad, int ho, int wo, T *__restrict__ out)
+{
+    const int64_t total = (int64_t)n * ho * wo * c;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        int ch = (int)(i % c);
+        int64_t t = i / c;
+        int ow = (int)(t % wo);
+        t /= wo;
+        int oh = (int)(t % ho);
+        int b = (int)(t / ho);
+        bool have = false;
+        float best = 0.f;
+        T best_raw = x[0];
+        for (int a = 0; a < k; ++a) {
+            int ih = oh * stride - pad + a;
+            if (ih < 0 || ih >= h) continue;
+            for (int q = 0; q < k; ++q) {
+                int iw = ow * stride - pad + q;
+                if (iw < 0 || iw >= w) continue;
+                T raw = x[(((int64_t)b * h + ih) * w + iw) * c + ch];
+                float v = to_float(raw);
+                if (!have || v > best) {
+                    best = v;
+                    best_raw = raw;
+                    have = true;
+                }
+            }
+        }
+        out[i] = best_raw;
+    }
+}
+
+hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride, int pad,
+                          int ho, int wo, void *out, hipStream_t s)
+{
+    const int64_t total = (int64_t)n * ho * wo * c;
+    int blocks = (int)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
+    if (dtype == FC_F32)
+        hipLaunchKernelGGL(k_maxpool<float>, dim3(blocks), dim3(256), 0, s, (const float *)x, n, h, w, c, k, stride,
+                           pad, ho, wo, (float *)out);
+    else if (dtype == FC_BF16)
+        hipLaunchKernelGGL(k_maxpool<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)x, n, h, w, c, k,
+                           stride, pad, ho, wo, (bf16_t *)out);
+    else
+        hipLaunchKernelGGL(k_maxpool<f16_t>, dim3(blocks), dim3(256), 0, s, (const f16_t *)x, n, h, w, c, k, stride,
+                           pad, ho, wo, (f16_t *)out);
+    return hipGetLastError();
+}
+
+} // namespace fc

@@ -1,0 +1,212 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on
+the same seeded inputs.  Bars: index and mask work bit-exact; features with fp32
+output within 1e-4 of the oracle relative to the RMS of the kept outputs (any storage
+type: products of stored values, fp32 accumulation); bf16/f16 output equal to the
+round-to-nearest-even of the fp32 output, and within 2e-2 of RMS."""
+import numpy as np
+import pytest
+
+from oracle import fc_oracle as O
+from paper_2207_10741_amd import binding as B, synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32_OUT = 1e-4
+TOL_16BIT_OUT = 2e-2
+
+
+# ------------------------------------------------------------------ masks ----
+
+@pytest.mark.parametrize("n,h,w,k,s,p,d", [
+    (1, 56, 56, 3, 1, 1, 1), (2, 57, 43, 3, 2, 1, 1), (3, 224, 224, 7, 2, 3, 1), (2, 135, 241, 2, 2, 0, 1),
+    (1, 9, 300, 1, 2, 0, 1), (2, 33, 35, 3, 1, 2, 2), (1, 5, 5, 1, 1, 1, 1), (1, 1, 1, 1, 1, 0, 1),
+])
+def test_mask_downsample_bit_exact(n, h, w, k, s, p, d):
+    mask = synth.mask_bernoulli(n, h, w, 0.45, 101, h, w) * np.uint8(3)      # nonzero, not just 1
+    got = B.mask_downsample(G.mask_dev(mask), (k, k), (s, s), (p, p), (d, d)).cpu().numpy()
+    want = O.mask_downsample(mask, k, k, (s, s), (p, p), (d, d))
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("m", [1, 15, 16, 17, 63, 64, 65, 4095, 4096, 4097, 8192, 12289, 100003, 1 << 20, 3000017])
+@pytest.mark.parametrize("irr", [0.48, 0.0, 1.0, 0.97])
+def test_active_index_compact_bit_exact(m, irr):
+    mask = synth.mask_bernoulli(1, 1, m, irr, 102, m).reshape(-1) * np.uint8(255)
+    idx, count = B.active_index_compact(G.mask_dev(mask))
+    want_idx, want_cnt = O.active_index_compact(mask)
+    cnt = int(count.cpu().item())
+    assert cnt == want_cnt
+    np.testing.assert_array_equal(idx[:cnt].cpu().numpy(), want_idx)
+
+
+def test_active_index_compact_blobs_large():
+    mask = synth.mask_objects(3, 480, 640, [0.3, 0.5, 0.7], 103)
+    idx, count = B.active_index_compact(G.mask_dev(mask))
+    want_idx, want_cnt = O.active_index_compact(mask)
+    assert int(count.cpu().item()) == want_cnt
+    np.testing.assert_array_equal(idx[:want_cnt].cpu().numpy(), want_idx)
+
+
+# ------------------------------------------------------------- conv layers ----
+
+def _run_layer(n, h, w, ci, co, k, s, p, d, dtype, *, irr=0.48, relu=True, use_bias=True, out_dtype=B.F32,
+               mask_kind="objects", seed=200, flags_extra=0, precomputed=False):
+    torch = G.torch_mod()
+    x = synth.activations((n, h, w, ci), dtype, seed, 1)
+    wt = synth.he_weights(co, k, k, ci, dtype, seed, 2)
+    bias = synth.bias(co, seed, 3) if use_bias else None
+    if mask_kind == "objects":
+        mask = synth.mask_objects(n, h, w, irr, seed, 4)
+    elif mask_kind == "bernoulli":
+        mask = synth.mask_bernoulli(n, h, w, irr, seed, 4)
+    elif mask_kind == "band":
+        mask = synth.mask_band_and_boxes(n, h, w, irr, seed, 4)
+    else:
+        mask = None
+    flags = (B.RELU if relu else 0) | flags_extra
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s, s), (p, p), (d, d), dtype, out_dtype, flags)
+    xd, wd = G.to_dev(x, dtype), G.to_dev(wt, dtype)
+    bd = None if bias is None else torch.from_numpy(bias).to(G.dev())
+    md = None if mask is None else G.mask_dev(mask)
+    kw = {}
+    if precomputed and mask is not None:
+        m_out = B.mask_downsample(md, (k, k), (s, s), (p, p), (d, d))
+        idx, count = B.active_index_compact(m_out)
+        kw = dict(mask_out=m_out, idx=idx, count=count)
+    out = B.focused_conv2d(desc, xd, wd, bd, mask_in=md, **kw)
+    torch.cuda.synchronize()
+    shape = O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=relu)
+    want = O.focused_conv2d(shape, x, wt, bias=bias, mask_in=mask, dtype=dtype)
+    keep = (O.mask_downsample(mask, k, k, (s, s), (p, p), (d, d)) != 0) if mask is not None \
+        else np.ones(want.shape[:3], bool)
+    return out, want, keep
+
+
+LAYERS = [
+    # n, h, w, ci, co, k, s, p, d
+    (1, 56, 56, 64, 64, 3, 1, 1, 1),        # the single-layer config
+    (2, 30, 41, 64, 64, 3, 1, 1, 1),        # ragged spatial size
+    (2, 28, 28, 128, 128, 3, 1, 1, 1),
+    (1, 19, 23, 64, 128, 3, 2, 1, 1),       # stride-2 3x3
+    (2, 20, 24, 64, 256, 1, 1, 0, 1),       # 1x1
+    (1, 21, 21, 128, 256, 1, 2, 0, 1),      # 1x1 / 2 projection
+    (1, 14, 14, 256, 256, 3, 1, 1, 1),
+    (1, 7, 9, 512, 512, 3, 1, 1, 1),        # few rows, long K
+    (1, 64, 48, 3, 64, 7, 2, 3, 1),         # RGB stem
+    (1, 40, 40, 3, 64, 3, 1, 1, 1),         # VGG first layer
+    (1, 24, 24, 32, 48, 3, 1, 2, 2),        # dilation
+    (1, 17, 13, 24, 40, 3, 1, 1, 1),        # channel counts off the tile sizes
+    (1, 12, 12, 5, 7, 3, 1, 1, 1),          # odd channel counts
+]
+
+
+@pytest.mark.parametrize("layer", LAYERS)
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16, synth.F32])
+def test_layer_matches_oracle_fp32_out(layer, dtype):
+    out, want, keep = _run_layer(*layer, dtype)
+    got = G.to_f64(out)
+    assert G.rel_err(got, want, keep) <= TOL_F32_OUT
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()        # +0.0 bit pattern
+
+
+@pytest.mark.parametrize("layer", LAYERS[:8])
+@pytest.mark.parametrize("mask_kind", ["bernoulli", "band", None])
+def test_layer_mask_structures(layer, mask_kind):
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=0.5, seed=201)
+    assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+
+
+@pytest.mark.parametrize("layer", [LAYERS[0], LAYERS[3], LAYERS[4], LAYERS[8]])
+@pytest.mark.parametrize("irr", [0.0, 1.0, 0.9])
+def test_layer_extreme_densities(layer, irr):
+    out, want, keep = _run_layer(*layer, synth.BF16, irr=irr, seed=202)
+    assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+    if irr == 1.0:
+        assert not out.cpu().numpy().view(np.uint32).any()
+
+
+@pytest.mark.parametrize("layer", [LAYERS[1], LAYERS[3], LAYERS[5], LAYERS[9]])
+def test_variants_no_bias_no_relu_precomputed_list(layer):
+    a, want, keep = _run_layer(*layer, synth.BF16, relu=False, use_bias=False, seed=203)
+    assert G.rel_err(G.to_f64(a), want, keep) <= TOL_F32_OUT
+    assert (want < 0).any()
+    b, _, _ = _run_layer(*layer, synth.BF16, relu=False, use_bias=False, seed=203, precomputed=True)
+    assert G.torch_mod().equal(a, b)          # same kernels, same order: bit-identical
+
+
+@pytest.mark.parametrize("layer", [LAYERS[0], LAYERS[2], LAYERS[4], LAYERS[8], LAYERS[11]])
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16])
+def test_16bit_output_is_rne_of_fp32_output(layer, dtype):
+    torch = G.torch_mod()
+    o32, want, keep = _run_layer(*layer, dtype, seed=204)
+    o16, _, _ = _run_layer(*layer, dtype, seed=204, out_dtype=dtype)
+    assert torch.equal(o16, o32.to(o16.dtype))                      # one rounding, to nearest even
+    err = G.rel_err(G.to_f64(o16), want, keep)
+    if err > TOL_16BIT_OUT:
+        # an outlier activation can exceed the RMS-relative bar through output rounding alone;
+        # then every element must still be within one unit in the last place of the oracle
+        ulp = np.abs(want) * (2.0 ** -8 if dtype == synth.BF16 else 2.0 ** -11)
+        assert (np.abs(G.to_f64(o16) - want) <= ulp + 1e-30).all()
+    assert not o16.view(torch.int16).cpu().numpy()[~keep].any()
+
+
+def test_dense_path_is_standard_convolution():
+    out, want, keep = _run_layer(2, 21, 27, 64, 128, 3, 1, 1, 1, synth.BF16, mask_kind=None, seed=205)
+    assert keep.all() and G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+
+
+def test_nan_at_irrelevant_inputs_does_not_leak():
+    torch = G.torch_mod()
+    n, h, w, c = 1, 30, 30, 64
+    x = synth.activations((n, h, w, c), synth.BF16, 206, 1)
+    wt = synth.he_weights(c, 3, 3, c, synth.BF16, 206, 2)
+    mask = synth.mask_objects(n, h, w, 0.48, 206, 4)
+    desc = B.conv_desc(n, h, w, c, c, in_dtype=B.BF16, out_dtype=B.F32)
+    md = G.mask_dev(mask)
+    clean = B.focused_conv2d(desc, G.to_dev(x, synth.BF16), G.to_dev(wt, synth.BF16), mask_in=md)
+    xp = x.copy()
+    xp[mask == 0] = 0x7FC0            # bf16 quiet NaN
+    dirty = B.focused_conv2d(desc, G.to_dev(xp, synth.BF16), G.to_dev(wt, synth.BF16), mask_in=md)
+    assert torch.equal(clean, dirty)
+
+
+def test_skip_zero_fill_leaves_irrelevant_rows_untouched_and_guard_bytes_intact():
+    torch = G.torch_mod()
+    n, h, w, ci, co = 2, 25, 31, 64, 64
+    x = synth.activations((n, h, w, ci), synth.BF16, 207, 1)
+    wt = synth.he_weights(co, 3, 3, ci, synth.BF16, 207, 2)
+    mask = synth.mask_objects(n, h, w, 0.48, 207, 4)
+    guard = 4096
+    for flags in (B.SKIP_ZERO_FILL, 0):
+        desc = B.conv_desc(n, h, w, ci, co, in_dtype=B.BF16, out_dtype=B.BF16, flags=flags)
+        buf = torch.full((n * h * w * co + 2 * guard,), 7.0, dtype=torch.bfloat16, device=G.dev())
+        out = buf[guard:guard + n * h * w * co].view(n, h, w, co)
+        B.focused_conv2d(desc, G.to_dev(x, synth.BF16), G.to_dev(wt, synth.BF16), mask_in=G.mask_dev(mask), out=out)
+        torch.cuda.synchronize()
+        assert (buf[:guard] == 7.0).all() and (buf[-guard:] == 7.0).all()
+        o = out.float().cpu().numpy()
+        keep = mask != 0
+        if flags:
+            assert (o[~keep] == 7.0).all()
+        else:
+            assert not o[~keep].any()
+        want = O.focused_conv2d(O.ConvShape(n, h, w, ci, co), x, wt, mask_in=mask, dtype=O.BF16)
+        assert np.abs(o[keep] - want[keep]).max() <= TOL_16BIT_OUT * np.sqrt(np.mean(want[keep] ** 2))
+
+
+def test_two_runs_are_bit_identical():
+    torch = G.torch_mod()
+    a, _, _ = _run_layer(2, 28, 28, 128, 128, 3, 1, 1, 1, synth.BF16, seed=208)
+    b, _, _ = _run_layer(2, 28, 28, 128, 128, 3, 1, 1, 1, synth.BF16, seed=208)
+    assert torch.equal(a, b)
+
+
+def test_maxpool_helper():
+    torch = G.torch_mod()
+    x = synth.from_storage(synth.activations((2, 13, 17, 24), synth.F32, 209) - 0.5, synth.F32)
+    xd = torch.from_numpy(x).to(G.dev())
+    for (k, s, p) in ((2, 2, 0), (3, 2, 1)):
+        got = B.maxpool2d(xd, k, s, p, B.F32).cpu()
+        ref = torch.nn.functional.max_pool2d(torch.from_numpy(x).permute(0, 3, 1, 2), k, s, p).permute(0, 2, 3, 1)
+        assert torch.equal(got, ref.contiguous())

@@ -1,0 +1,114 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2207_10741_amd import binding as B
+from oracle import fc_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "focused_conv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(B.FUNCTIONS)
+    L = B.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    assert B.status_string(0) == "FC_OK"
+    for code in range(-7, 0):
+        assert B.status_string(code).startswith("FC_ERR_")
+    assert "unknown" in B.status_string(5)
+
+
+@pytest.mark.parametrize("h,w,k,s,p,d", [(224, 224, 7, 2, 3, 1), (56, 56, 3, 1, 1, 1), (135, 240, 2, 2, 0, 1),
+                                          (17, 9, 3, 2, 1, 2), (4, 6, 3, 1, 0, 1), (1080, 1920, 3, 1, 1, 1)])
+def test_out_dims_match_oracle(h, w, k, s, p, d):
+    desc = B.conv_desc(1, h, w, 8, 8, (k, k), (s, s), (p, p), (d, d))
+    assert B.out_dims(desc) == (O.out_dim(h, k, s, p, d), O.out_dim(w, k, s, p, d))
+
+
+def test_descriptor_errors():
+    def rc(**kw):
+        base = dict(n=1, h=8, w=8, c_in=8, c_out=8)
+        base.update(kw)
+        d = B.conv_desc(**base)
+        ho, wo = ctypes.c_int32(), ctypes.c_int32()
+        return B.lib().fc_out_dims(ctypes.byref(d), ctypes.byref(ho), ctypes.byref(wo))
+    assert rc() == 0
+    assert rc(n=0) == -2 and rc(c_in=-1) == -2 and rc(stride=(0, 1)) == -2 and rc(pad=(-1, 0)) == -2
+    assert rc(h=2, pad=(0, 0)) == -2                      # empty output
+    assert rc(in_dtype=7) == -3
+    assert rc(in_dtype=B.F32, out_dtype=B.BF16) == -3     # output narrower than the input type
+    assert rc(flags=64) == -3
+    assert rc(n=40000, h=1000, w=1000, k=(1, 1), pad=(0, 0)) == -6
+    assert B.lib().fc_out_dims(None, None, None) == -1
+
+
+def test_workspace_sizes():
+    d = B.conv_desc(2, 30, 40, 16, 16)
+    m = 2 * 30 * 40
+    ws = B.workspace_bytes(d)
+    assert ws >= m + 4 * m + 4 + B.compact_workspace_bytes(m)
+    assert B.compact_workspace_bytes(1) >= 4
+    assert B.compact_workspace_bytes(4097) >= 8
+    with pytest.raises(B.FcError):
+        B.compact_workspace_bytes(0)
+    with pytest.raises(B.FcError) as e:
+        B.compact_workspace_bytes(2 ** 31)
+    assert e.value.status == -6
+
+
+def test_null_pointers_rejected_before_any_launch():
+    L = B.lib()
+    d = B.conv_desc(1, 8, 8, 8, 8)
+    assert L.fc_focused_conv2d(ctypes.byref(d), None, None, None, None, None, None, None, None, None, 0, None) == -1
+    assert L.fc_mask_downsample(None, 1, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, None, None) == -1
+    assert L.fc_active_index_compact(None, 10, None, None, None, 0, None) == -1
+    assert L.fc_maxpool2d(None, 1, 8, 8, 8, 0, 2, 2, 0, None, None) == -1
+    # fake but well-formed addresses: the checks below fail before anything touches them
+    a = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    assert L.fc_active_index_compact(a, 10, a, a, None, 0, None) == -5
+    assert L.fc_active_index_compact(a, 10, a, a, a, 1, None) == -5
+    assert L.fc_active_index_compact(odd, 10, a, a, a, 4096, None) == -4
+    assert L.fc_active_index_compact(a, 0, a, a, a, 4096, None) == -2
+    o = ctypes.c_void_p(0x2000)
+    conv = lambda *args: L.fc_focused_conv2d(ctypes.byref(d), *args)
+    #            x    mask_in w  bias  mask_out idx  count out ws    ws_bytes stream
+    assert conv(odd, None, a, None, None, None, None, o, None, 0, None) == -4
+    assert conv(a, None, a, None, None, a, None, o, None, 0, None) == -1      # idx without count
+    assert conv(a, None, a, None, None, a, a, o, None, 0, None) == -1         # idx without the input mask
+    assert conv(a, a, a, None, None, None, None, o, None, 0, None) == -5      # needs a workspace
+    assert conv(a, a, a, None, None, None, None, o, a, 16, None) == -5        # workspace too small
+    assert conv(a, None, a, None, None, None, None, a, None, 0, None) == -1   # out aliases x
+    assert L.fc_maxpool2d(a, 1, 8, 8, 8, 0, 2, 2, 2, a, None) == -2
+    assert L.fc_maxpool2d(a, 1, 8, 8, 8, 9, 2, 2, 0, a, None) == -3
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libfocused_conv.so"))
+    with pytest.raises(ImportError):
+        B.lib()
+
+
+def test_product_package_does_not_use_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2207_10741_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "fc_oracle" not in src and "fco_" not in src and "import oracle" not in src, f
