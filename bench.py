@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the focused-convolution hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input: for every
+layer of the workload, mask propagation, ordered compaction of the kept positions
+and the focused convolution itself (gather + matrix-core GEMM + bias/ReLU/scatter
++ zero-fill of the irrelevant rows), with all inputs already resident in HBM.
+
+Default workload: the four 3x3 layer shapes of ResNet-50 (C = 64/128/256/512 at
+128/64/32/16 pixels a side), batch 16, bf16, seeded blob masks with 48 % of the
+pixels irrelevant - the operating point the paper's census gives (Sec. II-B) and
+the one the metric is quoted on.  `value` is effective TFLOP/s counted on kept
+positions only; the same JSON line carries the speed-up over the library's own
+dense path, ms per image, the roofline fraction of the dominant kernel and the
+CPU oracle's throughput on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "focused-conv effective TFLOP/s + speedup vs dense at 48% irrelevant pixels"
+BF16_MFMA_PEAK_TFLOPS = 2500.0
+
+
+def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch):
+    """Device tensors for the four ResNet-50 3x3 shapes."""
+    dev = torch.device("cuda:0")
+    layers = []
+    for li, (c, side) in enumerate(workloads.sweep_shapes()):
+        key = (5, li)
+        x = synth.activations((batch, side, side, c), synth.BF16, *key, 1)
+        w = synth.he_weights(c, 3, 3, c, synth.BF16, *key, 2)
+        bias = synth.bias(c, *key, 3)
+        if mask_kind == "bernoulli":
+            mask = synth.mask_bernoulli(batch, side, side, irrelevant, *key, 4)
+        else:
+            mask = synth.mask_objects(batch, side, side, irrelevant, *key, 4)
+        desc = B.conv_desc(batch, side, side, c, c, in_dtype=B.BF16, out_dtype=B.BF16, flags=B.RELU)
+        to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        L = dict(name="c%d@%d" % (c, side), desc=desc, c=c, side=side,
+                 x=to_dev(x), w=to_dev(w), bias=torch.from_numpy(bias).to(dev),
+                 mask=torch.from_numpy(mask).to(dev), host=(x, w, bias, mask),
+                 kept=int(np.count_nonzero(mask)), m=mask.size, k=9 * c)
+        L["out"] = torch.empty((batch, side, side, c), dtype=torch.bfloat16, device=dev)
+        L["ws"] = torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=dev)
+        L["flops_kept"] = 2.0 * L["kept"] * L["k"] * c
+        L["flops_dense"] = 2.0 * L["m"] * L["k"] * c
+        layers.append(L)
+    return layers
+
+
+def time_loop(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(layers, images):
+    """The oracle as it stands, on `images` images of every layer, all host threads."""
+    from oracle import fc_oracle as O
+    O.lib()
+    flops = 0.0
+    t = 0.0
+    for L in layers:
+        x, w, bias, mask = L["host"]
+        c, side = L["c"], L["side"]
+        s = O.ConvShape(images, side, side, c, c, relu=True)
+        t0 = time.perf_counter()
+        O.focused_conv2d(s, x[:images], w, bias=bias, mask_in=mask[:images], dtype=O.BF16)
+        t += time.perf_counter() - t0
+        flops += 2.0 * int(np.count_nonzero(mask[:images])) * L["k"] * c
+    return flops / t / 1e12, O.num_threads(), t
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--irrelevant", type=float, default=None, help="irrelevant-pixel share (default 0.48)")
+    ap.add_argument("--mask", choices=["blobs", "bernoulli"], default="blobs")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-images", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2207_10741_amd import binding as B, synth, workloads
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+
+    irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
+    batch = workloads.SWEEP_BATCH if args.batch is None else args.batch
+    layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch)
+
+    # ---- the whole hot path: a1 + a2 + a3..a6 for every layer ------------------
+    def step_focused():
+        for L in layers:
+            B.focused_conv2d(L["desc"], L["x"], L["w"], L["bias"], mask_in=L["mask"], out=L["out"], workspace=L["ws"])
+
+    def step_dense():
+        for L in layers:
+            B.focused_conv2d(L["desc"], L["x"], L["w"], L["bias"], out=L["out"])
+
+    t_focused = time_loop(torch, step_focused, args.steps, args.warmup)
+    t_dense = time_loop(torch, step_dense, args.steps, args.warmup)
+
+    # ---- the convolution alone (index list reused, as within one resolution) ----
+    for L in layers:
+        L["m_out"] = B.mask_downsample(L["mask"])
+        L["idx"], L["count"] = B.active_index_compact(L["m_out"])
+
+    def step_conv_only():
+        for L in layers:
+            B.focused_conv2d(L["desc"], L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
+                             idx=L["idx"], count=L["count"], out=L["out"])
+
+    t_conv_only = time_loop(torch, step_conv_only, args.steps, args.warmup)
+
+    # ---- dominant kernel: the matrix-core conv kernel, one launch per call -------
+    skip = []
+    for L in layers:
+        d = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=B.BF16, out_dtype=B.BF16,
+                        flags=B.RELU | B.SKIP_ZERO_FILL)
+        skip.append(d)
+    per_layer_ms = []
+    for L, d in zip(layers, skip):
+        call = lambda: B.focused_conv2d(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
+                                        idx=L["idx"], count=L["count"], out=L["out"])
+        for _ in range(args.warmup):
+            call()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for a, b in evs:
+            a.record()
+            call()
+            b.record()
+        torch.cuda.synchronize()
+        per_layer_ms.append(float(np.mean([a.elapsed_time(b) for a, b in evs])))
+    flops_kept = sum(L["flops_kept"] for L in layers)
+    kern_avg_s = sum(per_layer_ms) / 1e3 / len(layers)
+    achieved = (flops_kept / len(layers)) / kern_avg_s / 1e12
+
+    value = flops_kept / t_focused / 1e12
+    images = batch * len(layers)
+    result = {
+        "metric": METRIC,
+        "value": round(value, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(t_focused * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "ResNet-50 3x3 layer shapes (C64@128, C128@64, C256@32, C512@16), batch %d, "
+                        "%s masks, %.0f %% irrelevant; step = mask propagation + compaction + focused conv "
+                        "+ zero-fill for all four layers" % (batch, args.mask, 100 * irr),
+            "batch": batch, "irrelevant": irr, "mask": args.mask,
+            "kept_fraction": round(sum(L["kept"] for L in layers) / sum(L["m"] for L in layers), 4),
+        },
+        "speedup_vs_dense": round(t_dense / t_focused, 3),
+        "dense_ms_per_step": round(t_dense * 1e3, 4),
+        "dense_tflops": round(sum(L["flops_dense"] for L in layers) / t_dense / 1e12, 3),
+        "conv_only_ms_per_step": round(t_conv_only * 1e3, 4),
+        "conv_only_tflops": round(flops_kept / t_conv_only / 1e12, 3),
+        "ms_per_image": round(t_focused * 1e3 / images, 6),
+        "per_layer_conv_kernel_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, per_layer_ms)},
+        "roofline": {
+            "bound": "mfma", "kernel": "k_conv_mfma", "achieved": round(achieved, 3), "peak": BF16_MFMA_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+        },
+    }
+    if not args.no_cpu_baseline:
+        v, cores, secs = cpu_baseline(layers, min(args.cpu_images, batch))
+        result["cpu_baseline"] = {
+            "value": round(v, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of the %d images of each of the four layers, same masks, %.1f s" % (
+                min(args.cpu_images, batch), batch, secs),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -3,27 +3,44 @@
 //
 // GEMM view: rows = kept output positions (from the index list), reduction
 // K = (tap, input channel), columns = output channels.  The patch matrix is never
-// stored: for every (tap, 64-channel chunk) the workgroup gathers, for each of
-// its TM positions, the 128 contiguous bytes of that tap's NHWC pixel into LDS
-// (zeros where the tap falls outside the image or on an irrelevant input pixel),
-// next to the TN x 64 slab of weights for the same tap, and feeds both to
-// v_mfma_f32_32x32x16 with fp32 accumulators.
+// stored: for every (tap, 64-channel chunk) = one pipeline stage, the workgroup
+// gathers, for each of its TM positions, the 128 contiguous bytes of that tap's NHWC
+// pixel into LDS (zeros where the tap falls outside the image or on an irrelevant
+// input pixel), next to the TN x 64 slab of weights for the same tap, and feeds both
+// to v_mfma_f32_32x32x16 with fp32 accumulators.
+//
+// Data path.  The gathers go straight from global memory into LDS ("buffer_load ...
+// lds", 16 bytes per lane) without passing through registers: measured on this chip a
+// 128-bit LDS write from registers costs three times a 128-bit LDS read, and staging
+// through registers also serialises the workgroup behind bursts of loads.  A wave-wide
+// load writes 64 x 16 contiguous bytes of LDS, i.e. 8 tile rows of 128 bytes with no
+// padding; bank conflicts on the fragment reads are avoided instead by an XOR swizzle
+// applied on the global side: LDS slot c of row r holds the row's 16-byte piece
+// c ^ ((r >> 1) & 7).  The loads are issued from inline assembly and waited for with
+// explicit s_waitcnt vmcnt(N), so that NB-1 stages stay in flight while one is being
+// multiplied (left to itself the compiler drains every outstanding LDS-bound load
+// before each LDS read).  A gated lane (padding, irrelevant input pixel, channel
+// tail, stage past the end) gets an offset that is out of range for its buffer
+// descriptor, for which the hardware writes zeros without touching memory; nothing
+// in the gather branches.
 //
 // The weights are the MFMA's A operand (rows = output channel) and the gathered
-// activations its B operand (columns = position), so a lane's accumulators hold
-// 4 consecutive output channels of one position: the epilogue (bias, ReLU, one
-// round-to-nearest-even) stores 8 or 16 contiguous bytes per lane straight into
-// the position's NHWC row.
+// activations its B operand (columns = position), so a lane's accumulators hold 4
+// consecutive output channels of one position.  The epilogue adds bias, applies ReLU,
+// rounds once to the output type, transposes the tile through LDS and stores each
+// kept row as whole 16-byte pieces; the same kernel then clears the irrelevant rows.
 //
-// The launch grid never depends on the kept count: workgroups stride over the
-// tiles and read the count on the device.
+// The launch grid never depends on the kept count: workgroups stride over the tiles
+// and read the count on the device.
 #include "fc_internal.hpp"
+#include <cstdlib>
 
 namespace fc {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int DT>
 __device__ __forceinline__ f32x16_t mfma32(const uint4 &a, const uint4 &b, const f32x16_t &c)
@@ -36,15 +53,15 @@ __device__ __forceinline__ f32x16_t mfma32(const uint4 &a, const uint4 &b, const
                                                       __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
 }
 
-constexpr int kTK = 64;         // reduction elements per stage (one 128-byte pixel chunk)
-constexpr int kTKP = kTK + 8;   // LDS row pitch in elements: 144 B keeps 128-bit reads conflict-free
-constexpr int kMaxTaps = 32;    // tap-valid bits per row live in one 32-bit word
+// LDS swizzle: slot of a row's 16-byte piece p is p ^ FC_SWZ(row)
+#ifndef FC_SWZ
+#define FC_SWZ(r) (((r) >> 1) & 7)
+#endif
 
-template <int TM, int TN>
-constexpr size_t mfma_lds_bytes()
-{
-    return (size_t)2 * (TM + TN) * kTKP * sizeof(uint16_t) + (size_t)TM * 3 * sizeof(int32_t);
-}
+constexpr uint32_t kBufferLimit = 0xF0000000u; // tensors handled through one descriptor stay below this
+constexpr uint32_t kOutOfRange = kBufferLimit; // offset that is out of range for every descriptor
+constexpr int kTK = 64;                        // reduction elements per stage (one 128-byte pixel chunk)
+constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
 
 template <int DT, typename TO>
 __device__ __forceinline__ void store4(TO *dst, float a, float b, float c, float d)
@@ -66,82 +83,184 @@ __device__ __forceinline__ void store4(TO *dst, float a, float b, float c, float
 
 __device__ __forceinline__ float relu_keep_nan(float v) { return (v > 0.f || v != v) ? v : 0.f; }
 
-// DT: storage type of x and w; TO: float or a 16-bit carrier; TM x TN: workgroup
-// tile (positions x output channels); WM x WN: wave grid inside it.
-template <int DT, typename TO, int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64) void k_conv_mfma(Geom g, const uint16_t *__restrict__ x,
-                                                            const uint8_t *__restrict__ mask_in,
-                                                            const uint16_t *__restrict__ w,
-                                                            const float *__restrict__ bias,
-                                                            const int32_t *__restrict__ idx,
-                                                            const int32_t *__restrict__ count,
-                                                            TO *__restrict__ out)
+// Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
+// plain byte offsets and anything at or beyond `bytes` reads as zero.
+__device__ __forceinline__ u32x4_t make_rsrc_words(const void *p, uint32_t bytes)
+{
+    const uint64_t a = reinterpret_cast<uint64_t>(p);
+    u32x4_t r;
+    r.x = (uint32_t)a;
+    r.y = (uint32_t)(a >> 32) & 0xffffu;
+    r.z = bytes;
+    r.w = 0x00020000u;
+    return r;
+}
+
+// One wave-wide 16-byte-per-lane load into LDS at lds_addr + 16 * lane (lds_addr is
+// wave-uniform and goes through M0).
+__device__ __forceinline__ void dma_load16(const u32x4_t &rsrc, uint32_t byte_offset, uint32_t lds_addr)
+{
+    __asm__ volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     :
+                     : "s"(lds_addr), "v"(byte_offset), "s"(rsrc)
+                     : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __asm__ volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+template <int TM, int TN, int NB>
+constexpr size_t dma_lds_bytes()
+{
+    return (size_t)NB * (TM + TN) * 128 + (size_t)TM * 5 * sizeof(int32_t) + (size_t)TN * sizeof(float);
+}
+
+// DT: storage type of x and w; TO: float or a 16-bit carrier; TM x TN: workgroup tile
+// (positions x output channels); WM x WN: wave grid inside it; TAPC: 1 (1x1 kernels),
+// 9 (3x3 kernels) or 32 (any kernel of up to 32 taps); NB: LDS stage buffers (NB-1
+// stages of loads in flight); MINW: waves per SIMD the register budget leaves room for.
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW>
+__global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
+                                                                 const uint8_t *__restrict__ mask_in,
+                                                                 const uint8_t *__restrict__ mask_out,
+                                                                 const uint16_t *__restrict__ w,
+                                                                 const float *__restrict__ bias,
+                                                                 const int32_t *__restrict__ idx,
+                                                                 const int32_t *__restrict__ count,
+                                                                 TO *__restrict__ out)
 {
     constexpr int NT = WM * WN * 64;
-    constexpr int RPP = NT / 8;        // rows covered by one pass of 16-byte loads
-    constexpr int XR = TM / RPP;       // 16-byte pieces of the activation tile per thread
-    constexpr int WR = TN / RPP;       // ... of the weight tile
+    constexpr int RPP = NT / 8;        // rows covered by one pass of wave loads
+    constexpr int XR = TM / RPP;       // wave loads per thread for the activation tile
+    constexpr int WR = TN / RPP;       // ... for the weight tile
+    constexpr int L = XR + WR;         // loads per thread per stage
     constexpr int WTM = TM / WM, WTN = TN / WN;
     constexpr int PB = WTM / 32, CB = WTN / 32;
+    constexpr int KK = kTK / 16;
+    constexpr int PAIR_IT = (TM * TAPC + NT - 1) / NT;
+    constexpr int PAIR_CH = PAIR_IT < 5 ? PAIR_IT : 5;
+    constexpr int STAGE_BYTES = (TM + TN) * 128;
     static_assert(TM % RPP == 0 && TN % RPP == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+    static_assert(TM <= NT && TN <= NT, "set-up assumes one thread per row / channel");
+    static_assert(NB >= 2 && (NB - 1) * L <= 63, "vmcnt is a 6-bit counter");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    uint16_t *Xs = reinterpret_cast<uint16_t *>(smem_raw);             // [2][TM][kTKP]
-    uint16_t *Ws = Xs + 2 * TM * kTKP;                                 // [2][TN][kTKP]
-    int32_t *row_p = reinterpret_cast<int32_t *>(Ws + 2 * TN * kTKP);  // flat output position or -1
-    int32_t *row_base = row_p + TM;                                    // pixel index of tap (0,0)
-    uint32_t *row_bits = reinterpret_cast<uint32_t *>(row_base + TM);  // bit t: tap t is inside and relevant
+    unsigned char *stage0 = smem_raw;                                   // [NB][TM + TN][128]
+    float *bias_s = reinterpret_cast<float *>(smem_raw + NB * STAGE_BYTES);
+    int32_t *row_p = reinterpret_cast<int32_t *>(bias_s + TN);
+    int32_t *row_base = row_p + TM;
+    int32_t *row_img = row_base + TM;
+    int32_t *row_hw = row_img + TM;
+    uint32_t *row_bits = reinterpret_cast<uint32_t *>(row_hw + TM);
+    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw); // LDS byte address of the stage buffers
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave % WM, wave_n = wave / WM;
-    const int piece = tid & 7, prow = tid >> 3;
+    const int slot = tid & 7, prow = tid >> 3;
 
     const int rows = idx ? *count : g.m;
     const int n_nt = (g.c_out + TN - 1) / TN;
     const int ntiles = ((rows + TM - 1) / TM) * n_nt;
-    const int taps = g.kh * g.kw;
+    const int taps = TAPC == 32 ? g.kh * g.kw : TAPC;
+    const int kwid = TAPC == 32 ? g.kw : (TAPC == 9 ? 3 : 1);
     const int cchunks = (g.c_in + kTK - 1) / kTK;
     const int stages = taps * cchunks;
+    const u32x4_t rsrc_x = make_rsrc_words(x, (uint32_t)g.n * g.h * g.w * g.c_in * 2u);
+    const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * taps * g.c_in * 2u);
 
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        const int mt = tile / n_nt, nt = tile - mt * n_nt;
+    // fragment addressing: lane reads row (lane & 31) of a 32-row block, 16-byte piece
+    // 2*kk + (lane >> 5), stored at slot piece ^ ((row >> 1) & 7); all block bases are
+    // multiples of 32 rows, so the swizzle term depends on the lane only
+    const uint32_t frag_row = (uint32_t)(lane & 31) * 128u;
+    const uint32_t frag_t16 = (uint32_t)((lane >> 5) ^ FC_SWZ(lane & 31)) * 16u;
+
+    // Tile order: all row tiles of channel tile 0, then of channel tile 1, ...  Workgroups
+    // are dispatched round-robin over the 8 XCDs, each with its own L2, so XCD j takes the
+    // j-th contiguous eighth of that order: its tiles share one weight slab and
+    // neighbouring image rows (the halo of the 3x3 taps) in that L2.
+    const int n_mt = (rows + TM - 1) / TM;
+    const int per_xcd = (ntiles + 7) >> 3;
+    const int xcd = blockIdx.x & 7;
+    for (int slot_t = blockIdx.x >> 3; slot_t < per_xcd; slot_t += gridDim.x >> 3) {
+        const int tile = xcd * per_xcd + slot_t;
+        if (tile >= ntiles) break;
+        const int nt = tile / n_mt, mt = tile - nt * n_mt;
         const int co0 = nt * TN;
 
-        __syncthreads(); // the previous tile's epilogue and last stage are done with LDS
-        for (int r = tid; r < TM; r += NT) {
-            const int m = mt * TM + r;
-            int p = -1, base = 0;
-            uint32_t bits = 0;
+        __syncthreads(); // the previous tile's epilogue is done with LDS
+        if (tid < TM) {
+            const int m = mt * TM + tid;
+            int p = -1, base = 0, b = 0, hw = 0;
             if (m < rows) {
                 p = idx ? idx[m] : m;
                 const int ow = p % g.wo;
                 const int q = p / g.wo;
                 const int oh = q % g.ho;
-                const int b = q / g.ho;
+                b = q / g.ho;
                 const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
                 base = (b * g.h + ih0) * g.w + iw0;
-                for (int kh = 0; kh < g.kh; ++kh) {
-                    const int ih = ih0 + kh * g.dh;
-                    for (int kw = 0; kw < g.kw; ++kw) {
-                        const int iw = iw0 + kw * g.dw;
-                        bool ok = ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
-                        if (ok && mask_in) ok = mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
-                        bits |= ok ? (1u << (kh * g.kw + kw)) : 0u;
-                    }
-                }
+                hw = (int)(((uint32_t)ih0 & 0xffffu) | ((uint32_t)iw0 << 16));
             }
-            row_p[r] = p;
-            row_base[r] = base;
-            row_bits[r] = bits;
+            row_p[tid] = p;
+            row_base[tid] = base;
+            row_img[tid] = b;
+            row_hw[tid] = hw;
+            row_bits[tid] = 0;
+        }
+        if (tid < TN) {
+            const int co = co0 + tid;
+            bias_s[tid] = (bias && co < g.c_out) ? bias[co] : 0.f;
+        }
+        __syncthreads();
+        for (int i0 = 0; i0 < PAIR_IT; i0 += PAIR_CH) {
+            int prow_[PAIR_CH], ptap_[PAIR_CH], ppix_[PAIR_CH];
+            bool pin_[PAIR_CH];
+#pragma unroll
+            for (int i = 0; i < PAIR_CH; ++i) {
+                const int pair = tid + (i0 + i) * NT;
+                const int r = pair / taps, t = pair - r * taps;
+                const bool live = pair < TM * taps;
+                const int rr = live ? r : 0;
+                const int kh = t / kwid, kw = t - kh * kwid;
+                const int hw = row_hw[rr];
+                const int ih = (int)(int16_t)(hw & 0xffff) + kh * g.dh;
+                const int iw = (hw >> 16) + kw * g.dw;
+                const bool inb = live && row_p[rr] >= 0 && ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
+                prow_[i] = rr;
+                ptap_[i] = t;
+                pin_[i] = inb;
+                ppix_[i] = inb ? (row_img[rr] * g.h + ih) * g.w + iw : 0;
+            }
+            uint8_t mv[PAIR_CH];
+#pragma unroll
+            for (int i = 0; i < PAIR_CH; ++i) mv[i] = mask_in ? mask_in[ppix_[i]] : (uint8_t)1;
+#pragma unroll
+            for (int i = 0; i < PAIR_CH; ++i)
+                if (pin_[i] && mv[i]) atomicOr(&row_bits[prow_[i]], 1u << ptap_[i]);
         }
         __syncthreads();
 
-        int xbase[XR];
-        uint32_t xbits[XR];
+        // per-thread, loop-invariant byte offsets; gp = the global 16-byte piece this lane
+        // fetches for its LDS slot (the swizzle)
+        uint32_t xoff[XR], xbits[XR], woff[WR];
+        int xgp[XR], wgp[WR];
 #pragma unroll
         for (int j = 0; j < XR; ++j) {
-            xbase[j] = row_base[prow + j * RPP];
-            xbits[j] = row_bits[prow + j * RPP];
+            const int r = prow + j * RPP;
+            xgp[j] = slot ^ FC_SWZ(r);
+            xoff[j] = ((uint32_t)row_base[r] * (uint32_t)g.c_in + (uint32_t)xgp[j] * 8u) * 2u;
+            xbits[j] = row_bits[r];
+        }
+#pragma unroll
+        for (int j = 0; j < WR; ++j) {
+            const int r = prow + j * RPP;
+            const int co = co0 + r;
+            wgp[j] = slot ^ FC_SWZ(r);
+            woff[j] = co < g.c_out ? ((uint32_t)co * (uint32_t)(taps * g.c_in) + (uint32_t)wgp[j] * 8u) * 2u
+                                   : kOutOfRange;
         }
 
         f32x16_t acc[PB][CB];
@@ -152,95 +271,156 @@ __global__ __launch_bounds__(WM *WN * 64) void k_conv_mfma(Geom g, const uint16_
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-        uint4 xr[XR], wr[WR];
-        int tap = 0, cc = 0, kh = 0, kw = 0; // of the stage being loaded
+        int tap = 0, cc = 0, kh = 0, kw = 0; // cursor: the next stage to be issued
+        int ibuf = 0;                        // LDS buffer that stage goes to
 
-        auto load_stage = [&]() {
-            const int ci = cc * kTK + piece * 8;
-            const bool ci_ok = ci < g.c_in;
-            const int tapoff = (kh * g.dh) * g.w + kw * g.dw;
-#pragma unroll
-            for (int j = 0; j < XR; ++j) {
-                const bool ok = ci_ok && ((xbits[j] >> tap) & 1u);
-                xr[j] = ok ? *reinterpret_cast<const uint4 *>(x + (int64_t)(xbase[j] + tapoff) * g.c_in + ci)
-                           : make_uint4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < WR; ++j) {
-                const int co = co0 + prow + j * RPP;
-                const bool ok = ci_ok && co < g.c_out;
-                wr[j] = ok ? *reinterpret_cast<const uint4 *>(w + ((int64_t)co * taps + tap) * g.c_in + ci)
-                           : make_uint4(0, 0, 0, 0);
-            }
-            if (++cc == cchunks) {
-                cc = 0;
-                ++tap;
-                if (++kw == g.kw) {
-                    kw = 0;
-                    ++kh;
-                }
-            }
-        };
-        auto store_stage = [&](int buf) {
-            uint16_t *xs = Xs + buf * TM * kTKP, *ws = Ws + buf * TN * kTKP;
-#pragma unroll
-            for (int j = 0; j < XR; ++j)
-                *reinterpret_cast<uint4 *>(xs + (prow + j * RPP) * kTKP + piece * 8) = xr[j];
-#pragma unroll
-            for (int j = 0; j < WR; ++j)
-                *reinterpret_cast<uint4 *>(ws + (prow + j * RPP) * kTKP + piece * 8) = wr[j];
-        };
+        // Offsets and LDS targets of the cursor's stage (L wave loads), then advance the cursor.
+        uint32_t ld_off[L], ld_lds[L];
+#define FC_PREPARE_STAGE()                                                                                \
+    {                                                                                                     \
+        const uint32_t sx = (uint32_t)(((kh * g.dh) * g.w + kw * g.dw) * g.c_in + cc * kTK) * 2u;         \
+        const uint32_t sw = (uint32_t)(tap * g.c_in + cc * kTK) * 2u;                                     \
+        const uint32_t ldsx = lds0 + (uint32_t)ibuf * STAGE_BYTES + (uint32_t)wave * 1024u;               \
+        const bool in_k = tap < taps;                                                                     \
+        _Pragma("unroll") for (int j = 0; j < XR; ++j)                                                    \
+        {                                                                                                 \
+            const bool ok = in_k && cc * kTK + xgp[j] * 8 < g.c_in && ((xbits[j] >> (tap & 31)) & 1u);    \
+            ld_off[j] = ok ? xoff[j] + sx : kOutOfRange;                                                  \
+            ld_lds[j] = ldsx + (uint32_t)j * (RPP * 128);                                                 \
+        }                                                                                                 \
+        _Pragma("unroll") for (int j = 0; j < WR; ++j)                                                    \
+        {                                                                                                 \
+            const bool ok = in_k && cc * kTK + wgp[j] * 8 < g.c_in;                                       \
+            ld_off[XR + j] = ok ? woff[j] + sw : kOutOfRange;                                             \
+            ld_lds[XR + j] = ldsx + (uint32_t)(TM * 128 + j * (RPP * 128));                               \
+        }                                                                                                 \
+        const int wrap_c = (cc + 1 == cchunks);                                                           \
+        cc = wrap_c ? 0 : cc + 1;                                                                         \
+        tap += wrap_c;                                                                                    \
+        const int wrap_w = wrap_c & (kw + 1 == kwid);                                                     \
+        kw = wrap_c ? (wrap_w ? 0 : kw + 1) : kw;                                                         \
+        kh += wrap_w;                                                                                     \
+        ibuf = (ibuf + 1 == NB) ? 0 : ibuf + 1;                                                           \
+    }
+#define FC_ISSUE_LOADS(first, last)                                                                       \
+    _Pragma("unroll") for (int j = (first); j < (last); ++j)                                              \
+        if (j < L) dma_load16(j < XR ? rsrc_x : rsrc_w, ld_off[j], __builtin_amdgcn_readfirstlane(ld_lds[j]));
 
-        load_stage();
-        store_stage(0);
-        __syncthreads();
+        // prologue: NB-1 stages in flight (stages past the end are all out of range: free)
+#pragma unroll
+        for (int d = 0; d < NB - 1; ++d) {
+            FC_PREPARE_STAGE()
+            FC_ISSUE_LOADS(0, L)
+        }
 
+        constexpr int LPK = (L + KK - 1) / KK; // wave loads issued per 16-wide k-step
+        int cbuf = 0;                          // buffer of the stage being multiplied
         for (int s = 0; s < stages; ++s) {
-            const int cur = s & 1;
-            if (s + 1 < stages) load_stage();
-            const uint16_t *xs = Xs + cur * TM * kTKP + (wave_m * WTM + (lane & 31)) * kTKP + (lane >> 5) * 8;
-            const uint16_t *ws = Ws + cur * TN * kTKP + (wave_n * WTN + (lane & 31)) * kTKP + (lane >> 5) * 8;
+            FC_PREPARE_STAGE()          // stage s + NB - 1: addresses only
+            wait_vmcnt<(NB - 2) * L>(); // this thread's loads of stage s have landed
+            __syncthreads();            // ... and everyone else's; buffer (s-1) % NB is free
+            const unsigned char *xs = stage0 + cbuf * STAGE_BYTES + (wave_m * WTM) * 128 + frag_row;
+            const unsigned char *ws = stage0 + cbuf * STAGE_BYTES + (TM + wave_n * WTN) * 128 + frag_row;
+            uint4 wf[2][CB], xf[2][PB];
 #pragma unroll
-            for (int kk = 0; kk < kTK / 16; ++kk) {
-                uint4 wf[CB], xf[PB];
+            for (int b = 0; b < CB; ++b) wf[0][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + frag_t16);
 #pragma unroll
-                for (int b = 0; b < CB; ++b) wf[b] = *reinterpret_cast<const uint4 *>(ws + b * 32 * kTKP + kk * 16);
+            for (int a = 0; a < PB; ++a) xf[0][a] = *reinterpret_cast<const uint4 *>(xs + a * 4096 + frag_t16);
 #pragma unroll
-                for (int a = 0; a < PB; ++a) xf[a] = *reinterpret_cast<const uint4 *>(xs + a * 32 * kTKP + kk * 16);
+            for (int kk = 0; kk < KK; ++kk) {
+                if (kk + 1 < KK) {
+                    const uint32_t o = ((uint32_t)(kk + 1) * 32u) ^ frag_t16;
+#pragma unroll
+                    for (int b = 0; b < CB; ++b)
+                        wf[(kk + 1) & 1][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + o);
+#pragma unroll
+                    for (int a = 0; a < PB; ++a)
+                        xf[(kk + 1) & 1][a] = *reinterpret_cast<const uint4 *>(xs + a * 4096 + o);
+                }
+                // keep the order "fetch step kk+1, then multiply step kk": the LDS latency
+                // then hides under the MFMAs
+                __builtin_amdgcn_sched_barrier(0);
+                // the gathers of stage s + NB - 1 are spread over the k-steps, so that the
+                // wave never queues behind a burst of loads with its matrix pipe idle
+                FC_ISSUE_LOADS(kk * LPK, (kk + 1) * LPK)
 #pragma unroll
                 for (int a = 0; a < PB; ++a)
 #pragma unroll
-                    for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[b], xf[a], acc[a][b]);
+                    for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[kk & 1][b], xf[kk & 1][a], acc[a][b]);
             }
-            if (s + 1 < stages) store_stage(cur ^ 1);
-            __syncthreads();
+            cbuf = (cbuf + 1 == NB) ? 0 : cbuf + 1;
         }
+#undef FC_ISSUE_LOADS
+#undef FC_PREPARE_STAGE
 
-        // epilogue: lane holds position (lane & 31) of each 32-block and channels
-        // 8*q + 4*(lane >> 5) + {0..3} of each 32-channel block
+        // ---- epilogue: bias, ReLU, one rounding; the tile is transposed through LDS so that
+        // every lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
+        wait_vmcnt<0>();
+        __syncthreads();
+        constexpr int OP = TN * (int)sizeof(TO) + 16;
+        static_assert((size_t)TM * OP <= (size_t)NB * STAGE_BYTES, "output tile fits");
+        unsigned char *Os = smem_raw;
 #pragma unroll
         for (int a = 0; a < PB; ++a) {
-            const int p = row_p[wave_m * WTM + a * 32 + (lane & 31)];
-            if (p < 0) continue;
-            TO *orow = out + (int64_t)p * g.c_out;
+            const int r = wave_m * WTM + a * 32 + (lane & 31);
 #pragma unroll
             for (int b = 0; b < CB; ++b)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int co = co0 + wave_n * WTN + b * 32 + q * 8 + (lane >> 5) * 4;
-                    if (co >= g.c_out) continue;
-                    float v0 = acc[a][b][q * 4 + 0], v1 = acc[a][b][q * 4 + 1];
-                    float v2 = acc[a][b][q * 4 + 2], v3 = acc[a][b][q * 4 + 3];
-                    if (bias) {
-                        const float4 bv = *reinterpret_cast<const float4 *>(bias + co);
-                        v0 += bv.x; v1 += bv.y; v2 += bv.z; v3 += bv.w;
-                    }
+                    const int cl = wave_n * WTN + b * 32 + q * 8 + (lane >> 5) * 4;
+                    const float4 bv = *reinterpret_cast<const float4 *>(bias_s + cl);
+                    float v0 = acc[a][b][q * 4 + 0] + bv.x, v1 = acc[a][b][q * 4 + 1] + bv.y;
+                    float v2 = acc[a][b][q * 4 + 2] + bv.z, v3 = acc[a][b][q * 4 + 3] + bv.w;
                     if (g.flags & FC_RELU) {
                         v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
                         v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
                     }
-                    store4<DT, TO>(orow + co, v0, v1, v2, v3);
+                    store4<DT, TO>(reinterpret_cast<TO *>(Os + r * OP) + cl, v0, v1, v2, v3);
                 }
+        }
+        __syncthreads();
+        constexpr int PPR = TN * (int)sizeof(TO) / 16;
+        constexpr int EPT = 16 / (int)sizeof(TO);
+        for (int i = tid; i < TM * PPR; i += NT) {
+            const int r = i / PPR, pc = i - r * PPR;
+            const int p = row_p[r];
+            const int co = co0 + pc * EPT;
+            if (p >= 0 && co < g.c_out)
+                *reinterpret_cast<uint4 *>(out + (int64_t)p * g.c_out + co) =
+                    *reinterpret_cast<const uint4 *>(Os + r * OP + pc * 16);
+        }
+    }
+
+    // ---- zero-fill of the irrelevant output rows (skipped for the dense layer) ----
+    if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL)) {
+        const int cpr = g.c_out * (int)sizeof(TO) / 16;
+        uint4 *o4 = reinterpret_cast<uint4 *>(out);
+        const int ch0 = -g.ph + g.dh * ((g.kh - 1) / 2), cw0 = -g.pw + g.dw * ((g.kw - 1) / 2);
+        for (int p0 = blockIdx.x * 64; p0 < g.m; p0 += gridDim.x * 64) {
+            const int pp = p0 + lane;
+            bool kept = true;
+            if (pp < g.m) {
+                if (mask_out) {
+                    kept = mask_out[pp] != 0;
+                } else {
+                    const int ow = pp % g.wo;
+                    const int q = pp / g.wo;
+                    const int oh = q % g.ho;
+                    const int b = q / g.ho;
+                    const int ih = min(max(oh * g.sh + ch0, 0), g.h - 1);
+                    const int iw = min(max(ow * g.sw + cw0, 0), g.w - 1);
+                    kept = mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
+                }
+            }
+            uint64_t drop = __ballot(!kept);
+            int k = 0;
+            while (drop) {
+                const int r = __ffsll((unsigned long long)drop) - 1;
+                drop &= drop - 1;
+                if ((k++ % (NT / 64)) != wave) continue;
+                uint4 *orow = o4 + (int64_t)(p0 + r) * cpr;
+                for (int c = lane; c < cpr; c += 64) orow[c] = make_uint4(0, 0, 0, 0);
+            }
         }
     }
 }
@@ -253,51 +433,91 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
     if (out_dtype != in_dtype && out_dtype != FC_F32) return false;
     if (g.c_in % 8 != 0 || g.c_out % 8 != 0) return false; // 16-byte gathers, 4-channel stores
     if (g.kh * g.kw > kMaxTaps) return false;
+    // row origins are packed into signed 16-bit halves
+    if (g.h > 16384 || g.w > 16384 || g.ph > 8192 || g.pw > 8192) return false;
+    // x and w are each addressed through one buffer descriptor with 32-bit byte offsets
+    if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
+    if ((uint64_t)g.c_out * g.kh * g.kw * g.c_in * 2u >= kBufferLimit) return false;
     return true;
 }
 
-template <int DT, typename TO, int TM, int TN, int WM, int WN>
-static hipError_t launch_cfg(const Geom &g, const void *x, const uint8_t *mask_in, const void *w,
-                             const float *bias, const int32_t *idx, const int32_t *count, void *out,
-                             hipStream_t s)
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW>
+static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
+                             const void *w, const float *bias, const int32_t *idx, const int32_t *count,
+                             void *out, hipStream_t s)
 {
-    auto kern = k_conv_mfma<DT, TO, TM, TN, WM, WN>;
-    constexpr size_t lds = mfma_lds_bytes<TM, TN>();
-    static bool attr_set = false; // per instantiation; the attribute is idempotent
+    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW>;
+    constexpr size_t lds = dma_lds_bytes<TM, TN, NB>();
+    static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    // grid for the dense row count; workgroups beyond the kept tiles exit at once
     const int64_t max_tiles = (int64_t)((g.m + TM - 1) / TM) * ((g.c_out + TN - 1) / TN);
     const int64_t cap = 256 * 8;
-    const int blocks = (int)(max_tiles < cap ? max_tiles : cap);
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64), lds, s, g, (const uint16_t *)x, mask_in,
+    const int blocks = (int)((max_tiles < cap ? max_tiles : cap) + 7) & ~7; // a multiple of the XCD count
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64), lds, s, g, (const uint16_t *)x, mask_in, mask_out,
                        (const uint16_t *)w, bias, idx, count, (TO *)out);
     return hipGetLastError();
 }
 
-template <int DT, typename TO>
-static hipError_t launch_dt(const Geom &g, const void *x, const uint8_t *mask_in, const void *w,
-                            const float *bias, const int32_t *idx, const int32_t *count, void *out,
-                            hipStream_t s)
-{
-    if (g.c_out > 64) return launch_cfg<DT, TO, 128, 128, 2, 2>(g, x, mask_in, w, bias, idx, count, out, s);
-    return launch_cfg<DT, TO, 128, 64, 2, 2>(g, x, mask_in, w, bias, idx, count, out, s);
-}
+#define FC_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
 
-hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
+template <int DT, typename TO, int TAPC>
+static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
+                              const void *w, const float *bias, const int32_t *idx, const int32_t *count,
+                              void *out, hipStream_t s)
+{
+#ifdef FC_TUNE
+    // tuning builds only: pick a tile configuration by number (bf16 in/out, 3x3 only)
+    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 9) {
+        static const int cfg = getenv("FC_TILE_CONFIG") ? atoi(getenv("FC_TILE_CONFIG")) : 0;
+        switch (cfg) {
+        case 20: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 4, 1>(FC_ARGS);
+        case 21: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
+        case 22: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
+        case 23: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
+        case 24: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 4, 1>(FC_ARGS);
+        case 25: return launch_dma<DT, TO, 256, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
+        case 26: return launch_dma<DT, TO, 256, 128, 4, 1, TAPC, 3, 1>(FC_ARGS);
+        case 27: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
+        default: break;
+        }
+    }
+#endif
+    // 128 x 128 tiles when there are enough of them to give every CU two workgroups;
+    // otherwise 128 x 64, which doubles the tile count (the kept count is not known here,
+    // so the dense row count decides)
+    const int64_t tiles128 = (int64_t)((g.m + 127) / 128) * ((g.c_out + 127) / 128);
+    if (g.c_out > 64 && tiles128 >= 512)
+        return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, (sizeof(TO) == 4 ? 3 : 2), 2>(FC_ARGS);
+    return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
+}
+#undef FC_ARGS
+
+template <int DT, typename TO>
+static hipError_t launch_dt(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                             const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                             void *out, hipStream_t s)
 {
+    if (g.kh == 1 && g.kw == 1) return launch_tile<DT, TO, 1>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+    if (g.kh == 3 && g.kw == 3) return launch_tile<DT, TO, 9>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+    return launch_tile<DT, TO, 32>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+}
+
+hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
+                            const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
+                            const int32_t *count, void *out, hipStream_t s)
+{
     if (in_dtype == FC_BF16) {
-        if (out_dtype == FC_F32) return launch_dt<FC_BF16, float>(g, x, mask_in, w, bias, idx, count, out, s);
-        return launch_dt<FC_BF16, uint16_t>(g, x, mask_in, w, bias, idx, count, out, s);
+        if (out_dtype == FC_F32)
+            return launch_dt<FC_BF16, float>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+        return launch_dt<FC_BF16, uint16_t>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
     }
-    if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(g, x, mask_in, w, bias, idx, count, out, s);
-    return launch_dt<FC_F16, uint16_t>(g, x, mask_in, w, bias, idx, count, out, s);
+    if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+    return launch_dt<FC_F16, uint16_t>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
 }
 
 } // namespace fc

@@ -73,10 +73,12 @@ hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const 
                               const uint8_t *mask_in, const void *w, const float *bias,
                               const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
-// Matrix-core path; returns hipErrorNotSupported when the shape does not fit it.
+// Matrix-core path (only for shapes conv_mfma_supported accepts).  It also clears
+// the irrelevant output rows unless FC_SKIP_ZERO_FILL is set; mask_out may be NULL.
 bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype);
 hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x,
-                            const uint8_t *mask_in, const void *w, const float *bias,
-                            const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
+                            const uint8_t *mask_in, const uint8_t *mask_out, const void *w,
+                            const float *bias, const int32_t *idx, const int32_t *count, void *out,
+                            hipStream_t s);
 
 } // namespace fc
