@@ -175,6 +175,37 @@ def focused_conv2d(desc: ConvDesc, x, w, bias=None, mask_in=None, mask_out=None,
     return out
 
 
+class PreparedConv:
+    """fc_focused_conv2d with its arguments marshalled once: calling it costs one
+    foreign call, which matters when layers take a few microseconds.  The tensors
+    must stay alive and in place; `stream=None` means the stream current at call
+    time (so the same object works eagerly and under graph capture)."""
+
+    def __init__(self, desc: ConvDesc, x, w, bias=None, mask_in=None, mask_out=None, idx=None, count=None,
+                 out=None, workspace=None):
+        torch = _torch()
+        _require_cuda(x, w, bias, mask_in, mask_out, idx, count, out, workspace)
+        ho, wo = out_dims(desc)
+        if out is None:
+            out = torch.empty((desc.n, ho, wo, desc.c_out), dtype=torch_dtype(desc.out_dtype), device=x.device)
+        if workspace is None and mask_in is not None and idx is None:
+            workspace = torch.empty((workspace_bytes(desc),), dtype=torch.uint8, device=x.device)
+        self.out = out
+        self._keep = (desc, x, w, bias, mask_in, mask_out, idx, count, out, workspace)
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        self._args = (ctypes.byref(desc), _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias), _ptr(mask_out), _ptr(idx),
+                      _ptr(count), _ptr(out), _ptr(workspace), ws_bytes)
+        self._fn = lib().fc_focused_conv2d
+        self._current_stream = torch.cuda.current_stream
+
+    def __call__(self, stream=None):
+        h = (self._current_stream() if stream is None else stream).cuda_stream
+        rc = self._fn(*self._args, ctypes.c_void_p(h))
+        if rc != 0:
+            raise FcError(rc, "fc_focused_conv2d")
+        return self.out
+
+
 def maxpool2d(x, k: int, stride: int, pad: int, dtype: int, out=None, stream=None):
     """fc_maxpool2d helper: NHWC max-pool of the whole tensor."""
     torch = _torch()

@@ -127,7 +127,11 @@ int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, in
     if (m >= INT32_MAX) return FC_ERR_RANGE;
     if (!workspace || workspace_bytes < compact_ws(m)) return FC_ERR_WORKSPACE;
     if (!aligned16(mask) || !aligned16(idx) || !aligned16(workspace)) return FC_ERR_ALIGN;
-    const hipError_t e = launch_compact(mask, m, idx, count, (int32_t *)workspace, (hipStream_t)stream);
+    // a flat mask is a 1 x 1 x m image seen through a 1x1 stride-1 window
+    MaskGeom g = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
+    g.w = g.wo = (int32_t)m;
+    g.m = m;
+    const hipError_t e = launch_compact(g, mask, nullptr, idx, count, (int32_t *)workspace, (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 
@@ -152,11 +156,9 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
         if (!aligned16(workspace)) return FC_ERR_ALIGN;
         uint8_t *ws = (uint8_t *)workspace;
         uint8_t *m_out = ws + l.mask_out;
-        hipError_t e = launch_mask_downsample(mask_in, g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh,
-                                              g.dw, g.ho, g.wo, m_out, s);
-        if (e != hipSuccess) return FC_ERR_HIP;
-        e = launch_compact(m_out, g.m, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
-                           (int32_t *)(ws + l.scan), s);
+        const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
+        const hipError_t e = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                                            (int32_t *)(ws + l.scan), s);
         if (e != hipSuccess) return FC_ERR_HIP;
         mask_out = m_out;
         idx = (const int32_t *)(ws + l.idx);

@@ -184,6 +184,53 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     const int n_mt = (rows + TM - 1) / TM;
     const int per_xcd = (ntiles + 7) >> 3;
     const int xcd = blockIdx.x & 7;
+
+    // ---- zero-fill of the irrelevant output rows (none for the dense layer) ----
+    // The grid is sized for the dense row count, so with a kept share r about 1 - r of
+    // the workgroups have no tile: when there are enough of them they alone clear the
+    // irrelevant rows (about one tile's worth of rows each, off the critical path of the
+    // tiles); otherwise every workgroup clears its share before its tiles.  A wave looks
+    // at 64 positions at a time and stores whole 16-byte pieces with all lanes.
+    if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL)) {
+        const int slots = gridDim.x >> 3;
+        const int idle_slots = slots > per_xcd ? slots - per_xcd : 0;
+        const bool idle_only = idle_slots > 0 && idle_slots * 8 >= (int)(gridDim.x >> 4);
+        const int my_slot = blockIdx.x >> 3;
+        if (!idle_only || my_slot >= per_xcd) {
+            const int nworkers = (idle_only ? idle_slots * 8 : (int)gridDim.x) * (NT / 64);
+            const int worker = (idle_only ? (my_slot - per_xcd) * 8 + xcd : (int)blockIdx.x) * (NT / 64) + wave;
+            int32_t *dropped = reinterpret_cast<int32_t *>(smem_raw) + wave * 64; // per-wave list
+            const int cpr = g.c_out * (int)sizeof(TO) / 16; // 16-byte pieces per row
+            uint4 *o4 = reinterpret_cast<uint4 *>(out);
+            const int ch0 = -g.ph + g.dh * ((g.kh - 1) / 2), cw0 = -g.pw + g.dw * ((g.kw - 1) / 2);
+            for (int p0 = worker * 64; p0 < g.m; p0 += nworkers * 64) {
+                const int pp = p0 + lane;
+                bool kept = true;
+                if (pp < g.m) {
+                    if (mask_out) {
+                        kept = mask_out[pp] != 0;
+                    } else {
+                        const int ow = pp % g.wo;
+                        const int q = pp / g.wo;
+                        const int oh = q % g.ho;
+                        const int b = q / g.ho;
+                        const int ih = min(max(oh * g.sh + ch0, 0), g.h - 1);
+                        const int iw = min(max(ow * g.sw + cw0, 0), g.w - 1);
+                        kept = mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
+                    }
+                }
+                const uint64_t drop = __ballot(!kept);
+                const int nd = __popcll(drop);
+                if (!kept) dropped[__popcll(drop & ((1ull << lane) - 1ull))] = pp; // in position order
+                // (same wave wrote and reads the list: program order suffices)
+                const int total = nd * cpr;
+                for (int c = lane; c < total; c += 64) {
+                    const int rk = c / cpr, pc = c - rk * cpr;
+                    o4[(int64_t)dropped[rk] * cpr + pc] = make_uint4(0, 0, 0, 0);
+                }
+            }
+        }
+    }
     for (int slot_t = blockIdx.x >> 3; slot_t < per_xcd; slot_t += gridDim.x >> 3) {
         const int tile = xcd * per_xcd + slot_t;
         if (tile >= ntiles) break;
@@ -391,38 +438,6 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         }
     }
 
-    // ---- zero-fill of the irrelevant output rows (skipped for the dense layer) ----
-    if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL)) {
-        const int cpr = g.c_out * (int)sizeof(TO) / 16;
-        uint4 *o4 = reinterpret_cast<uint4 *>(out);
-        const int ch0 = -g.ph + g.dh * ((g.kh - 1) / 2), cw0 = -g.pw + g.dw * ((g.kw - 1) / 2);
-        for (int p0 = blockIdx.x * 64; p0 < g.m; p0 += gridDim.x * 64) {
-            const int pp = p0 + lane;
-            bool kept = true;
-            if (pp < g.m) {
-                if (mask_out) {
-                    kept = mask_out[pp] != 0;
-                } else {
-                    const int ow = pp % g.wo;
-                    const int q = pp / g.wo;
-                    const int oh = q % g.ho;
-                    const int b = q / g.ho;
-                    const int ih = min(max(oh * g.sh + ch0, 0), g.h - 1);
-                    const int iw = min(max(ow * g.sw + cw0, 0), g.w - 1);
-                    kept = mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
-                }
-            }
-            uint64_t drop = __ballot(!kept);
-            int k = 0;
-            while (drop) {
-                const int r = __ffsll((unsigned long long)drop) - 1;
-                drop &= drop - 1;
-                if ((k++ % (NT / 64)) != wave) continue;
-                uint4 *orow = o4 + (int64_t)(p0 + r) * cpr;
-                for (int c = lane; c < cpr; c += 64) orow[c] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------

@@ -55,14 +55,37 @@ constexpr int kCompactBlockThreads = 256;
 constexpr int kCompactBytesPerThread = 16;
 constexpr int kCompactBlockElems = kCompactBlockThreads * kCompactBytesPerThread; // 4096
 
+constexpr int kCompactSingleLaunchBlocks = 16; // up to this many blocks the compaction is one launch
+
 static inline int64_t compact_blocks(int64_t m) { return (m + kCompactBlockElems - 1) / kCompactBlockElems; }
+
+// How output positions map to input-mask pixels (centre tap of the receptive field).
+struct MaskGeom {
+    int32_t n, h, w, ho, wo, sh, sw, ch0, cw0;
+    int32_t identity; // output position p reads input pixel p (stride 1, same size, centred)
+    int64_t m;        // n*ho*wo
+};
+
+static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, int sw, int ph, int pw, int dh,
+                                 int dw, int ho, int wo)
+{
+    MaskGeom g;
+    g.n = n; g.h = h; g.w = w; g.ho = ho; g.wo = wo; g.sh = sh; g.sw = sw;
+    g.ch0 = -ph + dh * ((kh - 1) / 2);
+    g.cw0 = -pw + dw * ((kw - 1) / 2);
+    g.identity = (sh == 1 && sw == 1 && ho == h && wo == w && g.ch0 == 0 && g.cw0 == 0) ? 1 : 0;
+    g.m = (int64_t)n * ho * wo;
+    return g;
+}
 
 // ---- launchers (each enqueues on `s`, returns a hipError_t) ----------------
 hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, int kh, int kw,
                                   int sh, int sw, int ph, int pw, int dh, int dw, int ho, int wo,
                                   uint8_t *mask_out, hipStream_t s);
-hipError_t launch_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
-                          int32_t *block_counts, hipStream_t s);
+// Kept positions of the layer whose mask geometry is g: writes mask_out (0/1 bytes;
+// may be NULL), the ascending index list and its length.
+hipError_t launch_compact(const MaskGeom &g, const uint8_t *mask_in, uint8_t *mask_out, int32_t *idx,
+                          int32_t *count, int32_t *block_counts, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,

@@ -1,6 +1,7 @@
 // Mask-side kernels: mask propagation (Sec. III-B), ordered compaction of the kept
-// positions (Sec. III-A: which patches become columns), zero-fill of the irrelevant
-// output rows, and the max-pool helper.  All of them are HBM-bound byte/row movers.
+// positions (Sec. III-A: which patches become columns) fused with it, zero-fill of
+// the irrelevant output rows for the direct-convolution path, and the max-pool
+// helper.  All of them are byte/row movers bound by HBM bandwidth or launch latency.
 #include "fc_internal.hpp"
 
 namespace fc {
@@ -39,28 +40,50 @@ hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, i
 }
 
 // ---------------------------------------------------------------------------
-// Ordered compaction.  A block owns 4096 consecutive mask bytes, a lane 16 of
-// them (one 128-bit load).  Pass 1 counts the kept bytes of every block.  Pass 2
-// gives each block the sum of the counts before it, ranks its own kept bytes with
-// a wave prefix sum (ballot + mbcnt inside a wave, LDS across the four waves),
-// stages the indices in LDS in order and copies them out coalesced.  Neither pass
-// waits on another block, so the grid always drains.
+// Ordered compaction, fused with the mask propagation.  A block owns 4096
+// consecutive output positions, a lane 16 of them.  The output-resolution mask is
+// never needed as an input: every kernel recomputes a position's flag from the
+// input mask (centre tap), which for a stride-1 "same" layer is one 128-bit load
+// per lane.  Ranks inside a block come from a wave prefix sum (shuffles inside a
+// wave, LDS across the four waves); the indices are staged in LDS in order and
+// copied out coalesced.  No block ever waits on another block, so every grid drains:
+//   - small inputs (up to 16 blocks): ONE launch; a block counts the kept
+//     positions of all blocks before it by itself (at most 60 KB of mask re-read
+//     per block, out of L2, all loads in flight together);
+//   - larger inputs: two launches, per-block counts first, then prefix + scatter.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t load_flags16(const uint8_t *__restrict__ mask, int64_t base, int64_t m)
+
+// bit j = output position p0 + j is kept (positions at or past g.m read as 0)
+__device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_t *__restrict__ mask_in,
+                                                 int64_t p0)
 {
-    // bit j = (mask[base + j] != 0), bytes past m read as 0
     uint32_t flags = 0;
-    if (base + 16 <= m) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(mask + base);
+    if (p0 >= g.m) return 0;
+    if (g.identity && p0 + 16 <= g.m) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(mask_in + p0);
         const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
                 flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
-    } else {
-        for (int j = 0; j < 16; ++j)
-            if (base + j < m && mask[base + j]) flags |= 1u << j;
+        return flags;
+    }
+    int ow = (int)(p0 % g.wo);
+    int64_t t = p0 / g.wo;
+    int oh = (int)(t % g.ho);
+    int b = (int)(t / g.ho);
+    for (int j = 0; j < 16 && p0 + j < g.m; ++j) {
+        const int ih = min(max(oh * g.sh + g.ch0, 0), g.h - 1);
+        const int iw = min(max(ow * g.sw + g.cw0, 0), g.w - 1);
+        if (mask_in[((int64_t)b * g.h + ih) * g.w + iw]) flags |= 1u << j;
+        if (++ow == g.wo) {
+            ow = 0;
+            if (++oh == g.ho) {
+                oh = 0;
+                ++b;
+            }
+        }
     }
     return flags;
 }
@@ -76,13 +99,27 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
     return v;
 }
 
-__global__ __launch_bounds__(kCompactBlockThreads) void k_compact_count(const uint8_t *__restrict__ mask,
-                                                                         int64_t m,
+// sum of v over the block (all threads get it); scratch holds one int per wave
+__device__ __forceinline__ int block_sum(int v, int *scratch)
+{
+    // wave total through ballots of the value's bits would need its width; use the scan
+    const int incl = wave_inclusive_scan(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 63) scratch[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < kCompactBlockThreads / 64; ++i) s += scratch[i];
+    return s;
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_compact_count(MaskGeom g,
+                                                                         const uint8_t *__restrict__ mask_in,
                                                                          int32_t *__restrict__ block_counts)
 {
     __shared__ int wave_sum[kCompactBlockThreads / 64];
-    const int64_t base = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)threadIdx.x * kCompactBytesPerThread;
-    int c = __popc(load_flags16(mask, base, m));
+    const int64_t p0 = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)threadIdx.x * kCompactBytesPerThread;
+    const int c = __popc(kept_flags16(g, mask_in, p0));
     // wave total through ballots of the count's bits (counts are 0..16: 5 bits)
     int total = 0;
 #pragma unroll
@@ -97,34 +134,57 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_compact_count(const ui
     }
 }
 
-__global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(const uint8_t *__restrict__ mask,
-                                                                           int64_t m,
+// SELF = true: the block counts everything before it by itself (single launch);
+// otherwise it sums the per-block counts of the first launch.
+template <bool SELF>
+__global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(MaskGeom g,
+                                                                           const uint8_t *__restrict__ mask_in,
                                                                            const int32_t *__restrict__ block_counts,
+                                                                           uint8_t *__restrict__ mask_out,
                                                                            int32_t *__restrict__ idx,
                                                                            int32_t *__restrict__ count)
 {
     __shared__ int wave_sum[kCompactBlockThreads / 64];
-    __shared__ int base_sum[kCompactBlockThreads / 64];
+    __shared__ int scratch[kCompactBlockThreads / 64];
     __shared__ int32_t stage[kCompactBlockElems];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    // offset of this block = sum of the counts of all blocks before it
+    // offset of this block = number of kept positions in all blocks before it
     int part = 0;
-    for (int i = tid; i < (int)blockIdx.x; i += kCompactBlockThreads) part += block_counts[i];
-    part = wave_inclusive_scan(part);
-    if (lane == 63) base_sum[wave] = part;
+    if (SELF) {
+        // all loads of the (at most kCompactSingleLaunchBlocks - 1) earlier chunks are
+        // independent: unrolled, so that they are in flight together
+#pragma unroll
+        for (int pb = 0; pb < kCompactSingleLaunchBlocks - 1; ++pb)
+            if (pb < (int)blockIdx.x)
+                part += __popc(kept_flags16(g, mask_in, (int64_t)pb * kCompactBlockElems + (int64_t)tid * 16));
+    } else {
+        for (int i = tid; i < (int)blockIdx.x; i += kCompactBlockThreads) part += block_counts[i];
+    }
+    const int block_base = block_sum(part, scratch);
 
-    const int64_t base = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)tid * kCompactBytesPerThread;
-    const uint32_t flags = load_flags16(mask, base, m);
+    const int64_t p0 = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)tid * kCompactBytesPerThread;
+    const uint32_t flags = kept_flags16(g, mask_in, p0);
+    if (mask_out) {
+        if (p0 + 16 <= g.m) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                wds[q] = ((flags >> (4 * q)) & 1u) | (((flags >> (4 * q + 1)) & 1u) << 8) |
+                         (((flags >> (4 * q + 2)) & 1u) << 16) | (((flags >> (4 * q + 3)) & 1u) << 24);
+            *reinterpret_cast<uint4 *>(mask_out + p0) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+        } else {
+            for (int j = 0; j < 16 && p0 + j < g.m; ++j) mask_out[p0 + j] = (flags >> j) & 1u;
+        }
+    }
     const int c = __popc(flags);
     const int incl = wave_inclusive_scan(c);
     if (lane == 63) wave_sum[wave] = incl;
     __syncthreads();
 
-    int block_base = 0, before = 0, block_total = 0;
+    int before = 0, block_total = 0;
 #pragma unroll
     for (int i = 0; i < kCompactBlockThreads / 64; ++i) {
-        block_base += base_sum[i];
         if (i < wave) before += wave_sum[i];
         block_total += wave_sum[i];
     }
@@ -133,22 +193,29 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(const 
     while (f) {
         const int j = __ffs(f) - 1;
         f &= f - 1;
-        stage[pos++] = (int32_t)(base + j);
+        stage[pos++] = (int32_t)(p0 + j);
     }
     __syncthreads();
     for (int i = tid; i < block_total; i += kCompactBlockThreads) idx[(int64_t)block_base + i] = stage[i];
     if (blockIdx.x == gridDim.x - 1 && tid == 0) *count = block_base + block_total;
 }
 
-hipError_t launch_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
-                          int32_t *block_counts, hipStream_t s)
+hipError_t launch_compact(const MaskGeom &g_in, const uint8_t *mask_in, uint8_t *mask_out, int32_t *idx,
+                          int32_t *count, int32_t *block_counts, hipStream_t s)
 {
-    const int nb = (int)compact_blocks(m);
-    hipLaunchKernelGGL(k_compact_count, dim3(nb), dim3(kCompactBlockThreads), 0, s, mask, m, block_counts);
+    MaskGeom g = g_in;
+    if (reinterpret_cast<uintptr_t>(mask_in) & 15u) g.identity = 0; // the 128-bit path needs alignment
+    const int nb = (int)compact_blocks(g.m);
+    if (nb <= kCompactSingleLaunchBlocks) {
+        hipLaunchKernelGGL(k_compact_scatter<true>, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in,
+                           (const int32_t *)nullptr, mask_out, idx, count);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(k_compact_count, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in, block_counts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_compact_scatter, dim3(nb), dim3(kCompactBlockThreads), 0, s, mask, m, block_counts, idx,
-                       count);
+    hipLaunchKernelGGL(k_compact_scatter<false>, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in,
+                       (const int32_t *)block_counts, mask_out, idx, count);
     return hipGetLastError();
 }
 

@@ -74,7 +74,10 @@ def _run_layer(n, h, w, ci, co, k, s, p, d, dtype, *, irr=0.48, relu=True, use_b
         m_out = B.mask_downsample(md, (k, k), (s, s), (p, p), (d, d))
         idx, count = B.active_index_compact(m_out)
         kw = dict(mask_out=m_out, idx=idx, count=count)
-    out = B.focused_conv2d(desc, xd, wd, bd, mask_in=md, **kw)
+    # the output buffer starts full of a canary, so a row nobody writes cannot pass as zero
+    ho, wo = B.out_dims(desc)
+    out = torch.full((n, ho, wo, co), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
+    B.focused_conv2d(desc, xd, wd, bd, mask_in=md, out=out, **kw)
     torch.cuda.synchronize()
     shape = O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=relu)
     want = O.focused_conv2d(shape, x, wt, bias=bias, mask_in=mask, dtype=dtype)
