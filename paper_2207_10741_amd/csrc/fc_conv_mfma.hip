@@ -498,6 +498,10 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
         case 25: return launch_dma<DT, TO, 256, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
         case 26: return launch_dma<DT, TO, 256, 128, 4, 1, TAPC, 3, 1>(FC_ARGS);
         case 27: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
+        case 28: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
+        case 29: return launch_dma<DT, TO, 256, 64, 4, 1, TAPC, 2, 1>(FC_ARGS);
+        case 30: return launch_dma<DT, TO, 128, 64, 4, 1, TAPC, 2, 3>(FC_ARGS);
+        case 31: return launch_dma<DT, TO, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
         default: break;
         }
     }

@@ -1,0 +1,115 @@
+"""Runs a conv stack (workloads.Op list) through the library: mask propagation and
+kept-position lists are built once per (mask, window geometry) and shared by every
+layer that sees the same mask through the same geometry (Sec. III-B: one mask,
+rescaled per layer); each conv is one fc_focused_conv2d call.
+
+Plumbing only: the order of library calls and which tensor feeds which.  Max-pools
+(not part of the paper's method) go through the library's helper.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from . import binding as B
+from . import synth
+
+
+class ConvStack:
+    def __init__(self, ops, n: int, h: int, w: int, dtype: int = B.BF16, seed: int = 0, relu: bool = True):
+        import torch
+        self.torch = torch
+        self.ops = list(ops)
+        self.n, self.h, self.w, self.dtype = n, h, w, dtype
+        self.dev = torch.device("cuda:0")
+        self.relu = relu
+        self.weights: Dict[int, object] = {}
+        self.biases: Dict[int, object] = {}
+        self.host_weights: Dict[int, np.ndarray] = {}
+        self.host_biases: Dict[int, np.ndarray] = {}
+        for i, op in enumerate(self.ops):
+            if op.kind != "conv":
+                continue
+            wt = synth.he_weights(op.c_out, op.k, op.k, op.c_in, dtype, seed, i, 2)
+            bs = synth.bias(op.c_out, seed, i, 3)
+            self.host_weights[i], self.host_biases[i] = wt, bs
+            self.weights[i] = self._to_dev(wt)
+            self.biases[i] = torch.from_numpy(bs).to(self.dev)
+        # spatial size of every op's output
+        self.sizes = {-1: (h, w)}
+        for i, op in enumerate(self.ops):
+            hi, wi = self.sizes[op.src]
+            d = B.conv_desc(n, hi, wi, 1, 1, (op.k, op.k), (op.stride, op.stride), (op.pad, op.pad), (1, 1), B.F32)
+            self.sizes[i] = B.out_dims(d)
+
+    def _to_dev(self, storage: np.ndarray):
+        torch = self.torch
+        if self.dtype == B.F32:
+            return torch.from_numpy(np.ascontiguousarray(storage, dtype=np.float32)).to(self.dev)
+        t = torch.from_numpy(np.ascontiguousarray(storage).view(np.int16)).to(self.dev)
+        return t.view(torch.bfloat16 if self.dtype == B.BF16 else torch.float16)
+
+    def desc(self, i: int, out_dtype: Optional[int] = None, flags_extra: int = 0) -> B.ConvDesc:
+        op = self.ops[i]
+        hi, wi = self.sizes[op.src]
+        flags = (B.RELU if (self.relu and op.relu) else 0) | flags_extra
+        return B.conv_desc(self.n, hi, wi, op.c_in, op.c_out, (op.k, op.k), (op.stride, op.stride),
+                           (op.pad, op.pad), (1, 1), self.dtype, out_dtype, flags)
+
+    def run(self, x, mask=None, keep_outputs: bool = True, skip_zero_fill: bool = False):
+        """x: device NHWC tensor; mask: device uint8 [N,H,W] or None (dense).
+        Returns (outputs, masks): per-op output tensors and per-op output masks
+        (index -1 = the stack's input)."""
+        outs: Dict[int, object] = {-1: x}
+        masks: Dict[int, object] = {-1: mask}
+        plans: Dict[tuple, tuple] = {}
+        produced: Dict[int, tuple] = {}   # 0/1 masks this run wrote, with their kept lists
+        last_use = {}
+        for i, op in enumerate(self.ops):
+            last_use[op.src] = i
+        for i, op in enumerate(self.ops):
+            src, m_in = outs[op.src], masks[op.src]
+            geo = ((op.k, op.k), (op.stride, op.stride), (op.pad, op.pad), (1, 1))
+            plan = None
+            if m_in is not None:
+                hi, wi = self.sizes[op.src]
+                same_view = (op.stride == 1 and self.sizes[i] == (hi, wi) and op.pad == (op.k - 1) // 2)
+                key = (id(m_in), op.k, op.stride, op.pad)
+                if same_view and id(m_in) in produced:
+                    # the window is centred and does not change the resolution: the mask this op
+                    # keeps is the (already 0/1) mask it reads, and so is the kept list
+                    plan = produced[id(m_in)]
+                elif key in plans:
+                    plan = plans[key]
+                else:
+                    m_out = B.mask_downsample(m_in, *geo)
+                    idx, count = B.active_index_compact(m_out)
+                    plan = plans[key] = produced[id(m_out)] = (m_out, idx, count)
+            if op.kind == "conv":
+                d = self.desc(i, flags_extra=B.SKIP_ZERO_FILL if skip_zero_fill else 0)
+                if plan is None:
+                    outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i])
+                else:
+                    outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], mask_in=m_in,
+                                               mask_out=plan[0], idx=plan[1], count=plan[2])
+            else:
+                outs[i] = B.maxpool2d(src, op.k, op.stride, op.pad, self.dtype)
+            masks[i] = None if plan is None else plan[0]
+            if not keep_outputs:
+                for j in [j for j in outs if j != i and last_use.get(j, -2) <= i and j != -1]:
+                    del outs[j]
+        return outs, masks
+
+    def conv_flops(self, masks_host: Optional[Dict[int, np.ndarray]] = None):
+        """(dense FLOPs, kept FLOPs) of the stack; kept needs the host copies of the masks."""
+        dense = kept = 0.0
+        for i, op in enumerate(self.ops):
+            if op.kind != "conv":
+                continue
+            ho, wo = self.sizes[i]
+            per_pos = 2.0 * op.k * op.k * op.c_in * op.c_out
+            dense += self.n * ho * wo * per_pos
+            if masks_host is not None:
+                kept += float(np.count_nonzero(masks_host[i])) * per_pos
+        return dense, kept
