@@ -30,6 +30,10 @@ if ROOT not in sys.path:
 
 METRIC = "focused-conv effective TFLOP/s + speedup vs dense at 48% irrelevant pixels"
 BF16_MFMA_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the conv kernel on the default workload (mean of the four layers),
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the counter read for a
+# 256 MiB streaming copy (x2.00 and x1.00): profiles/k_conv_dma_resnet50_3x3_b16_48pct.md
+TRAFFIC_BYTES_PER_LAUNCH = 34.3e6
 
 
 def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch):
@@ -110,7 +114,12 @@ def main():
     ap.add_argument("--mask", choices=["blobs", "bernoulli"], default="blobs")
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-images", type=int, default=8)
+    ap.add_argument("--cpu-images", type=int, default=16)
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="run only the dominant-kernel loop (for rocprofv3 --kernel-trace --stats)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -142,6 +151,19 @@ def main():
         L["call_kernel"] = B.PreparedConv(dk, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
                                           idx=L["idx"], count=L["count"], out=L["out"])
 
+    if args.traffic_probe:
+        src = torch.ones((64 << 20,), dtype=torch.int32, device="cuda:0")   # 256 MiB
+        dst = torch.empty_like(src)
+        torch.add(src, 0, out=dst)               # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        for _ in range(args.steps):
+            for L in layers:
+                L["call_focused"]()
+            torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": src.numel() * 4, "steps": args.steps,
+                          "kept_rows": {L["name"]: L["kept"] for L in layers}}))
+        return
+
     def step_of(key):
         calls = [L[key] for L in layers]
 
@@ -151,12 +173,13 @@ def main():
         return step
 
     timings = {}
-    for key in ("call_focused", "call_dense", "call_conv_only"):
+    for key in (() if args.roofline_only else ("call_focused", "call_dense", "call_conv_only")):
         step = step_of(key)
         timings[key + "_eager"] = time_loop(torch, step, args.steps, args.warmup)
         graph = capture(torch, step)
         timings[key] = time_loop(torch, graph.replay, args.steps, args.warmup)
-    t_focused, t_dense, t_conv_only = (timings[k] for k in ("call_focused", "call_dense", "call_conv_only"))
+    if not args.roofline_only:
+        t_focused, t_dense, t_conv_only = (timings[k] for k in ("call_focused", "call_dense", "call_conv_only"))
 
     # ---- dominant kernel: the matrix-core conv kernel, one launch per call, timed
     # with events on the stream it is launched on ----------------------------------
@@ -165,16 +188,33 @@ def main():
         call = L["call_kernel"]
         for _ in range(args.warmup):
             call()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        # events bracket runs of 10 back-to-back launches of this one kernel, so that the
+        # cost of the event records themselves is spread thin
+        burst = 10
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(max(1, args.steps // burst))]
         for a, b in evs:
             a.record()
-            call()
+            for _ in range(burst):
+                call()
             b.record()
         torch.cuda.synchronize()
-        per_layer_ms.append(float(np.mean([a.elapsed_time(b) for a, b in evs])))
+        per_layer_ms.append(float(np.mean([a.elapsed_time(b) for a, b in evs])) / burst)
     flops_kept = sum(L["flops_kept"] for L in layers)
     kern_avg_s = sum(per_layer_ms) / 1e3 / len(layers)
     achieved = (flops_kept / len(layers)) / kern_avg_s / 1e12
+    default_workload = (args.irrelevant is None and args.mask == "blobs" and args.batch is None)
+    roofline = {
+        "bound": "mfma", "kernel": "k_conv_dma", "achieved": round(achieved, 3), "peak": BF16_MFMA_PEAK_TFLOPS,
+        "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+        "traffic": TRAFFIC_BYTES_PER_LAUNCH if default_workload else None,
+        "avg_launch_us": round(kern_avg_s * 1e6, 3),
+        "flops_per_launch": round(flops_kept / len(layers)),
+    }
+    if args.roofline_only:
+        print(json.dumps({"roofline": roofline,
+                          "per_layer_conv_kernel_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, per_layer_ms)}}))
+        return
 
     value = flops_kept / t_focused / 1e12
     images = batch * len(layers)
@@ -207,10 +247,7 @@ def main():
         "conv_only_tflops": round(flops_kept / t_conv_only / 1e12, 3),
         "ms_per_image": round(t_focused * 1e3 / images, 6),
         "per_layer_conv_kernel_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, per_layer_ms)},
-        "roofline": {
-            "bound": "mfma", "kernel": "k_conv_dma", "achieved": round(achieved, 3), "peak": BF16_MFMA_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
-        },
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         v, cores, secs = cpu_baseline(layers, min(args.cpu_images, batch))
