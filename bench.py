@@ -143,13 +143,13 @@ def main():
         d = L["desc"]
         L["call_focused"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], out=L["out"],
                                            workspace=L["ws"])
-        L["call_dense"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], out=L["out"])
+        L["call_dense"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"])
         L["call_conv_only"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
-                                             idx=L["idx"], count=L["count"], out=L["out"])
+                                             idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"])
         dk = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=B.BF16, out_dtype=B.BF16,
                          flags=B.RELU | B.SKIP_ZERO_FILL)
         L["call_kernel"] = B.PreparedConv(dk, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
-                                          idx=L["idx"], count=L["count"], out=L["out"])
+                                          idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"])
 
     if args.traffic_probe:
         src = torch.ones((64 << 20,), dtype=torch.int32, device="cuda:0")   # 256 MiB

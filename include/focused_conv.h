@@ -82,7 +82,8 @@ const char *fc_status_string(int32_t status);
 int32_t fc_out_dims(const fc_conv_desc *desc, int32_t *ho, int32_t *wo);
 
 /* Bytes of device workspace fc_focused_conv2d needs when the caller passes no
- * index list (mask_out + idx + count + scan scratch), and
+ * index list (split-K scratch for small layers + mask_out + idx + count + scan
+ * scratch), and
  * fc_active_index_compact needs for `m` positions.  Host only. */
 int32_t fc_workspace_bytes(const fc_conv_desc *desc, size_t *bytes);
 int32_t fc_compact_workspace_bytes(int64_t m, size_t *bytes);
@@ -123,7 +124,10 @@ int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, in
  *             NULL = computed here into the workspace
  *   out       device, NHWC, out_dtype; must not overlap x
  *   workspace device, >= fc_workspace_bytes(desc) when idx is NULL and mask_in is
- *             not; otherwise may be NULL
+ *             not; otherwise optional: when given (any call, also the dense
+ *             layer), layers with few tiles split their reduction over more
+ *             workgroups and park fp32 partial tiles there (deterministic:
+ *             partials are always added in the same order)
  * `count` is read on the device only; the launch grid does not depend on it. */
 int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in,
                           const void *w, const float *bias, const uint8_t *mask_out,

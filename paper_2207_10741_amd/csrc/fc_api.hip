@@ -40,14 +40,20 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }
 
 struct ConvWorkspace {
-    size_t mask_out, idx, count, scan, total;
+    size_t counters, partials, mask_out, idx, count, scan, total, split_only;
 };
 
-ConvWorkspace conv_ws_layout(int64_t m)
+// [tile counters | fp32 partial tiles] (split-K; empty for layers with many tiles), then
+// [mask_out | idx | count | per-block counts] (only used when the call builds the list).
+ConvWorkspace conv_ws_layout(const Geom &g)
 {
+    const int64_t m = g.m;
     ConvWorkspace l;
-    l.mask_out = 0;
-    l.idx = align_up((size_t)m, 256);
+    l.counters = 0;
+    l.partials = split_k_counter_bytes(g);
+    l.split_only = l.partials + split_k_partial_bytes(g);
+    l.mask_out = l.split_only;
+    l.idx = l.mask_out + align_up((size_t)m, 256);
     l.count = l.idx + align_up((size_t)m * sizeof(int32_t), 256);
     l.scan = l.count + 256;
     l.total = l.scan + compact_ws(m);
@@ -99,7 +105,7 @@ int32_t fc_workspace_bytes(const fc_conv_desc *desc, size_t *bytes)
     Geom g;
     const int32_t rc = make_geom(desc, &g);
     if (rc != FC_OK) return rc;
-    *bytes = conv_ws_layout(g.m).total;
+    *bytes = conv_ws_layout(g).total;
     return FC_OK;
 }
 
@@ -151,7 +157,7 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
 
     if (mask_in && !idx) {
         // derive mask_out, the index list and its length here, in the workspace
-        const ConvWorkspace l = conv_ws_layout(g.m);
+        const ConvWorkspace l = conv_ws_layout(g);
         if (!workspace || workspace_bytes < l.total) return FC_ERR_WORKSPACE;
         if (!aligned16(workspace)) return FC_ERR_ALIGN;
         uint8_t *ws = (uint8_t *)workspace;
@@ -167,8 +173,19 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
 
     hipError_t e;
     if (conv_mfma_supported(g, desc->in_dtype, desc->out_dtype)) {
+        // split-K scratch, when the layer is small enough to want it and the caller gave room
+        float *partials = nullptr;
+        int32_t *tile_counters = nullptr;
+        const ConvWorkspace l = conv_ws_layout(g);
+        if (split_k_possible(g) && workspace && workspace_bytes >= l.split_only && aligned16(workspace)) {
+            tile_counters = (int32_t *)((uint8_t *)workspace + l.counters);
+            partials = (float *)((uint8_t *)workspace + l.partials);
+            e = launch_zero_i32(tile_counters, kSplitGrid, s);
+            if (e != hipSuccess) return FC_ERR_HIP;
+        }
         // gather + matrix cores + epilogue + zero-fill in one kernel
-        e = launch_conv_mfma(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
+        e = launch_conv_mfma(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out,
+                             partials, tile_counters, s);
         if (e != hipSuccess) return FC_ERR_HIP;
     } else {
         e = launch_conv_direct(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s);

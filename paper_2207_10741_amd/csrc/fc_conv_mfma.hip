@@ -61,27 +61,37 @@ __device__ __forceinline__ f32x16_t mfma32(const uint4 &a, const uint4 &b, const
 constexpr uint32_t kBufferLimit = 0xF0000000u; // tensors handled through one descriptor stay below this
 constexpr uint32_t kOutOfRange = kBufferLimit; // offset that is out of range for every descriptor
 constexpr int kTK = 64;                        // reduction elements per stage (one 128-byte pixel chunk)
+constexpr int kMaxSplits = 16;                 // most K-splits of one tile
 constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// Four fp32 values -> four stored values; the narrowing is the hardware's
+// round-to-nearest-even conversion (v_cvt_pk_bf16_f32 / v_cvt_f16_f32).
 template <int DT, typename TO>
 __device__ __forceinline__ void store4(TO *dst, float a, float b, float c, float d)
 {
     if constexpr (sizeof(TO) == 4) {
         *reinterpret_cast<float4 *>(dst) = make_float4(a, b, c, d);
     } else if constexpr (DT == FC_BF16) {
+        const f32x2_t lo = {a, b}, hi = {c, d};
         uint2 v;
-        v.x = (uint32_t)bf16_bits_rne(a) | ((uint32_t)bf16_bits_rne(b) << 16);
-        v.y = (uint32_t)bf16_bits_rne(c) | ((uint32_t)bf16_bits_rne(d) << 16);
+        v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2_t));
+        v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2_t));
         *reinterpret_cast<uint2 *>(dst) = v;
     } else {
+        const f32x2_t lo = {a, b}, hi = {c, d};
         uint2 v;
-        v.x = (uint32_t)f16_bits_rne(a) | ((uint32_t)f16_bits_rne(b) << 16);
-        v.y = (uint32_t)f16_bits_rne(c) | ((uint32_t)f16_bits_rne(d) << 16);
+        v.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, f16x2_t));
+        v.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, f16x2_t));
         *reinterpret_cast<uint2 *>(dst) = v;
     }
 }
 
-__device__ __forceinline__ float relu_keep_nan(float v) { return (v > 0.f || v != v) ? v : 0.f; }
+// max(v, 0) that keeps NaN (and -0) as the reference does
+__device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.f ? 0.f : v; }
 
 // Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
 // plain byte offsets and anything at or beyond `bytes` reads as zero.
@@ -130,7 +140,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                                                                  const float *__restrict__ bias,
                                                                  const int32_t *__restrict__ idx,
                                                                  const int32_t *__restrict__ count,
-                                                                 TO *__restrict__ out)
+                                                                 TO *__restrict__ out,
+                                                                 float *__restrict__ partials,
+                                                                 int32_t *__restrict__ tile_counters)
 {
     constexpr int NT = WM * WN * 64;
     constexpr int RPP = NT / 8;        // rows covered by one pass of wave loads
@@ -182,7 +194,19 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     // j-th contiguous eighth of that order: its tiles share one weight slab and
     // neighbouring image rows (the halo of the 3x3 taps) in that L2.
     const int n_mt = (rows + TM - 1) / TM;
-    const int per_xcd = (ntiles + 7) >> 3;
+    // Split-K: when there are fewer tiles than workgroups (small layers, or few kept rows)
+    // the reduction of every tile is cut into S equal runs of stages, one work unit each, so
+    // that the serial K loop of a workgroup gets S times shorter and the chip fills up.
+    // Units of one tile are adjacent in the order, so they share an XCD.  S is the same in
+    // every workgroup (it depends on the kept count and the grid only).
+    int S = 1;
+    if (partials && ntiles > 0) {
+        S = (int)gridDim.x / ntiles;
+        S = S < 1 ? 1 : (S > stages ? stages : S);
+        if (S > kMaxSplits) S = kMaxSplits;
+    }
+    const int nunits = ntiles * S;
+    const int per_xcd = (nunits + 7) >> 3;
     const int xcd = blockIdx.x & 7;
 
     // ---- zero-fill of the irrelevant output rows (none for the dense layer) ----
@@ -232,8 +256,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         }
     }
     for (int slot_t = blockIdx.x >> 3; slot_t < per_xcd; slot_t += gridDim.x >> 3) {
-        const int tile = xcd * per_xcd + slot_t;
-        if (tile >= ntiles) break;
+        const int unit = xcd * per_xcd + slot_t;
+        if (unit >= nunits) break;
+        const int tile = unit / S, split = unit - tile * S;
+        const int s_begin = (int)((int64_t)split * stages / S), s_end = (int)((int64_t)(split + 1) * stages / S);
+        const int nst = s_end - s_begin; // stages of this unit
         const int nt = tile / n_mt, mt = tile - nt * n_mt;
         const int co0 = nt * TN;
 
@@ -318,8 +345,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-        int tap = 0, cc = 0, kh = 0, kw = 0; // cursor: the next stage to be issued
-        int ibuf = 0;                        // LDS buffer that stage goes to
+        // cursor: the next stage to be issued (starts at this unit's first stage)
+        int tap = s_begin / cchunks, cc = s_begin - tap * cchunks;
+        int kh = tap / kwid, kw = tap - kh * kwid;
+        int to_issue = nst; // stages of this unit not yet issued
+        int ibuf = 0;       // LDS buffer the next stage goes to
 
         // Offsets and LDS targets of the cursor's stage (L wave loads), then advance the cursor.
         uint32_t ld_off[L], ld_lds[L];
@@ -328,7 +358,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         const uint32_t sx = (uint32_t)(((kh * g.dh) * g.w + kw * g.dw) * g.c_in + cc * kTK) * 2u;         \
         const uint32_t sw = (uint32_t)(tap * g.c_in + cc * kTK) * 2u;                                     \
         const uint32_t ldsx = lds0 + (uint32_t)ibuf * STAGE_BYTES + (uint32_t)wave * 1024u;               \
-        const bool in_k = tap < taps;                                                                     \
+        const bool in_k = to_issue > 0;                                                                   \
+        --to_issue;                                                                                       \
         _Pragma("unroll") for (int j = 0; j < XR; ++j)                                                    \
         {                                                                                                 \
             const bool ok = in_k && cc * kTK + xgp[j] * 8 < g.c_in && ((xbits[j] >> (tap & 31)) & 1u);    \
@@ -362,7 +393,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 
         constexpr int LPK = (L + KK - 1) / KK; // wave loads issued per 16-wide k-step
         int cbuf = 0;                          // buffer of the stage being multiplied
-        for (int s = 0; s < stages; ++s) {
+        for (int s = 0; s < nst; ++s) {
             FC_PREPARE_STAGE()          // stage s + NB - 1: addresses only
             wait_vmcnt<(NB - 2) * L>(); // this thread's loads of stage s have landed
             __syncthreads();            // ... and everyone else's; buffer (s-1) % NB is free
@@ -404,6 +435,57 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         // every lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
         wait_vmcnt<0>();
         __syncthreads();
+        if (S > 1) {
+            // Park this unit's fp32 partial tile (accumulator order, coalesced), then count
+            // in; the unit that arrives last adds the S partials in split order - a fixed
+            // order, so the result does not depend on which unit that is - and finishes the
+            // tile.  Nobody waits for anybody.  The partials and the counter are written and
+            // read with device-scope accesses, which go through to the memory side of the
+            // per-XCD L2s, so no cache-wide write-back or invalidate is needed.
+            uint64_t *mine = reinterpret_cast<uint64_t *>(partials + (size_t)unit * (TM * TN));
+#pragma unroll
+            for (int a = 0; a < PB; ++a)
+#pragma unroll
+                for (int b = 0; b < CB; ++b)
+#pragma unroll
+                    for (int h = 0; h < 8; ++h) {
+                        const uint64_t v = (uint64_t)__float_as_uint(acc[a][b][2 * h]) |
+                                           ((uint64_t)__float_as_uint(acc[a][b][2 * h + 1]) << 32);
+                        __hip_atomic_store(mine + ((a * CB + b) * 8 + h) * NT + tid, v, __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+                    }
+            wait_vmcnt<0>(); // this thread's partial stores have been acknowledged
+            __syncthreads(); // ... and every other thread's
+            if (tid == 0)
+                row_bits[0] = (uint32_t)__hip_atomic_fetch_add(&tile_counters[tile], 1, __ATOMIC_RELAXED,
+                                                               __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            const bool last = (int)row_bits[0] == S - 1;
+            if (!last) continue; // uniform: the whole workgroup moves on
+            if (tid == 0)        // leave the counters as they were found
+                __hip_atomic_store(&tile_counters[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int a = 0; a < PB; ++a)
+#pragma unroll
+                for (int b = 0; b < CB; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+            for (int sp = 0; sp < S; ++sp) {
+                const uint64_t *theirs =
+                    reinterpret_cast<const uint64_t *>(partials + (size_t)(tile * S + sp) * (TM * TN));
+#pragma unroll
+                for (int a = 0; a < PB; ++a)
+#pragma unroll
+                    for (int b = 0; b < CB; ++b)
+#pragma unroll
+                        for (int h = 0; h < 8; ++h) {
+                            const uint64_t v = __hip_atomic_load(theirs + ((a * CB + b) * 8 + h) * NT + tid,
+                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            acc[a][b][2 * h] += __uint_as_float((uint32_t)v);
+                            acc[a][b][2 * h + 1] += __uint_as_float((uint32_t)(v >> 32));
+                        }
+            }
+        }
         constexpr int OP = TN * (int)sizeof(TO) + 16;
         static_assert((size_t)TM * OP <= (size_t)NB * STAGE_BYTES, "output tile fits");
         unsigned char *Os = smem_raw;
@@ -459,7 +541,7 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW>
 static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                              const void *w, const float *bias, const int32_t *idx, const int32_t *count,
-                             void *out, hipStream_t s)
+                             void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
     auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW>;
     constexpr size_t lds = dma_lds_bytes<TM, TN, NB>();
@@ -472,18 +554,19 @@ static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_i
     }
     const int64_t max_tiles = (int64_t)((g.m + TM - 1) / TM) * ((g.c_out + TN - 1) / TN);
     const int64_t cap = 256 * 8;
-    const int blocks = (int)((max_tiles < cap ? max_tiles : cap) + 7) & ~7; // a multiple of the XCD count
+    int blocks = (int)((max_tiles < cap ? max_tiles : cap) + 7) & ~7; // a multiple of the XCD count
+    if (partials) blocks = kSplitGrid; // few tiles: enough workgroups for the K-split to fill the chip
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64), lds, s, g, (const uint16_t *)x, mask_in, mask_out,
-                       (const uint16_t *)w, bias, idx, count, (TO *)out);
+                       (const uint16_t *)w, bias, idx, count, (TO *)out, partials, tile_counters);
     return hipGetLastError();
 }
 
-#define FC_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
+#define FC_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, partials, tile_counters, s
 
 template <int DT, typename TO, int TAPC>
 static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                               const void *w, const float *bias, const int32_t *idx, const int32_t *count,
-                              void *out, hipStream_t s)
+                              void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
 #ifdef FC_TUNE
     // tuning builds only: pick a tile configuration by number (bf16 in/out, 3x3 only)
@@ -512,31 +595,37 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
     const int64_t tiles128 = (int64_t)((g.m + 127) / 128) * ((g.c_out + 127) / 128);
     if (g.c_out > 64 && tiles128 >= 512)
         return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, (sizeof(TO) == 4 ? 3 : 2), 2>(FC_ARGS);
+    // narrow layers with many tiles: two stage buffers, so that three workgroups fit a CU
+    // and overlap each other's set-up and epilogue
+    if (g.c_out <= 64 && !partials) return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
     return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
 }
 #undef FC_ARGS
 
+#define FC_ARGS2 g, x, mask_in, mask_out, w, bias, idx, count, out, partials, tile_counters, s
+
 template <int DT, typename TO>
 static hipError_t launch_dt(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                             const void *w, const float *bias, const int32_t *idx, const int32_t *count,
-                            void *out, hipStream_t s)
+                            void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-    if (g.kh == 1 && g.kw == 1) return launch_tile<DT, TO, 1>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
-    if (g.kh == 3 && g.kw == 3) return launch_tile<DT, TO, 9>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
-    return launch_tile<DT, TO, 32>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+    if (g.kh == 1 && g.kw == 1) return launch_tile<DT, TO, 1>(FC_ARGS2);
+    if (g.kh == 3 && g.kw == 3) return launch_tile<DT, TO, 9>(FC_ARGS2);
+    return launch_tile<DT, TO, 32>(FC_ARGS2);
 }
 
 hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
                             const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
-                            const int32_t *count, void *out, hipStream_t s)
+                            const int32_t *count, void *out, float *partials, int32_t *tile_counters,
+                            hipStream_t s)
 {
     if (in_dtype == FC_BF16) {
         if (out_dtype == FC_F32)
-            return launch_dt<FC_BF16, float>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
-        return launch_dt<FC_BF16, uint16_t>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+            return launch_dt<FC_BF16, float>(FC_ARGS2);
+        return launch_dt<FC_BF16, uint16_t>(FC_ARGS2);
     }
-    if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
-    return launch_dt<FC_F16, uint16_t>(g, x, mask_in, mask_out, w, bias, idx, count, out, s);
+    if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(FC_ARGS2);
+    return launch_dt<FC_F16, uint16_t>(FC_ARGS2);
 }
 
 } // namespace fc

@@ -96,12 +96,28 @@ hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const 
                               const uint8_t *mask_in, const void *w, const float *bias,
                               const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
+// Split-K scratch of the matrix-core path (optional): fp32 partial tiles and one counter
+// per tile.  Only layers with few tiles use it; for the others the sizes are zero.
+constexpr int kSplitGrid = 512;                          // workgroups launched when split-K may run
+constexpr size_t kSplitTileFloats = 128 * 128;           // largest tile
+static inline bool split_k_possible(const Geom &g)
+{
+    const int64_t tiles64 = (int64_t)((g.m + 127) / 128) * ((g.c_out + 63) / 64);
+    return tiles64 < kSplitGrid; // fewer tiles than workgroups even for the dense row count
+}
+static inline size_t split_k_counter_bytes(const Geom &g) { return split_k_possible(g) ? align_up(kSplitGrid * sizeof(int32_t), 256) : 0; }
+static inline size_t split_k_partial_bytes(const Geom &g)
+{
+    return split_k_possible(g) ? (size_t)kSplitGrid * kSplitTileFloats * sizeof(float) : 0;
+}
+hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s);
+
 // Matrix-core path (only for shapes conv_mfma_supported accepts).  It also clears
 // the irrelevant output rows unless FC_SKIP_ZERO_FILL is set; mask_out may be NULL.
 bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype);
 hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x,
                             const uint8_t *mask_in, const uint8_t *mask_out, const void *w,
                             const float *bias, const int32_t *idx, const int32_t *count, void *out,
-                            hipStream_t s);
+                            float *partials, int32_t *tile_counters, hipStream_t s);
 
 } // namespace fc

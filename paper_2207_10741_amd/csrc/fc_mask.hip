@@ -278,6 +278,19 @@ hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t
     return hipGetLastError();
 }
 
+// Small fill kernel (a kernel rather than a memset node, so that callers can record it
+// into HIP graphs).
+__global__ __launch_bounds__(256) void k_zero_i32(int32_t *__restrict__ p, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
+hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_zero_i32, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // Max-pool helper (NHWC, whole tensor).  Padding never wins.
 // ---------------------------------------------------------------------------

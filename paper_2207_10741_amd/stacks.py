@@ -42,6 +42,10 @@ class ConvStack:
             hi, wi = self.sizes[op.src]
             d = B.conv_desc(n, hi, wi, 1, 1, (op.k, op.k), (op.stride, op.stride), (op.pad, op.pad), (1, 1), B.F32)
             self.sizes[i] = B.out_dims(d)
+        # one workspace for all layers (calls are ordered on one stream): lets small layers
+        # split their reduction over more workgroups
+        need = max(B.workspace_bytes(self.desc(i)) for i, op in enumerate(self.ops) if op.kind == "conv")
+        self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.dev)
 
     def _to_dev(self, storage: np.ndarray):
         torch = self.torch
@@ -89,10 +93,11 @@ class ConvStack:
             if op.kind == "conv":
                 d = self.desc(i, flags_extra=B.SKIP_ZERO_FILL if skip_zero_fill else 0)
                 if plan is None:
-                    outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i])
+                    outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], workspace=self.workspace)
                 else:
                     outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], mask_in=m_in,
-                                               mask_out=plan[0], idx=plan[1], count=plan[2])
+                                               mask_out=plan[0], idx=plan[1], count=plan[2],
+                                               workspace=self.workspace)
             else:
                 outs[i] = B.maxpool2d(src, op.k, op.stride, op.pad, self.dtype)
             masks[i] = None if plan is None else plan[0]
