@@ -137,7 +137,8 @@ int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, in
     MaskGeom g = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
     g.w = g.wo = (int32_t)m;
     g.m = m;
-    const hipError_t e = launch_compact(g, mask, nullptr, idx, count, (int32_t *)workspace, (hipStream_t)stream);
+    const hipError_t e =
+        launch_compact(g, mask, nullptr, idx, count, (int32_t *)workspace, CompactExtras(), (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 
@@ -155,31 +156,42 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     if (x == out) return FC_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
 
+    const bool mfma = conv_mfma_supported(g, desc->in_dtype, desc->out_dtype);
+    const ConvWorkspace l = conv_ws_layout(g);
+    // split-K scratch of the matrix-core path, when the layer is small enough to want it and
+    // the caller gave room
+    float *partials = nullptr;
+    int32_t *tile_counters = nullptr;
+    if (mfma && split_k_possible(g) && workspace && workspace_bytes >= l.split_only && aligned16(workspace)) {
+        tile_counters = (int32_t *)((uint8_t *)workspace + l.counters);
+        partials = (float *)((uint8_t *)workspace + l.partials);
+    }
+    bool counters_cleared = false;
+
     if (mask_in && !idx) {
         // derive mask_out, the index list and its length here, in the workspace
-        const ConvWorkspace l = conv_ws_layout(g);
         if (!workspace || workspace_bytes < l.total) return FC_ERR_WORKSPACE;
         if (!aligned16(workspace)) return FC_ERR_ALIGN;
         uint8_t *ws = (uint8_t *)workspace;
         uint8_t *m_out = ws + l.mask_out;
         const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
-        const hipError_t e = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
-                                            (int32_t *)(ws + l.scan), s);
-        if (e != hipSuccess) return FC_ERR_HIP;
+        CompactExtras ex;
+        if (tile_counters) {
+            ex.zero = tile_counters;
+            ex.zero_n = kSplitGrid;
+            counters_cleared = true;
+        }
+        const hipError_t ec = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                                             (int32_t *)(ws + l.scan), ex, s);
+        if (ec != hipSuccess) return FC_ERR_HIP;
         mask_out = m_out;
         idx = (const int32_t *)(ws + l.idx);
         count = (const int32_t *)(ws + l.count);
     }
 
     hipError_t e;
-    if (conv_mfma_supported(g, desc->in_dtype, desc->out_dtype)) {
-        // split-K scratch, when the layer is small enough to want it and the caller gave room
-        float *partials = nullptr;
-        int32_t *tile_counters = nullptr;
-        const ConvWorkspace l = conv_ws_layout(g);
-        if (split_k_possible(g) && workspace && workspace_bytes >= l.split_only && aligned16(workspace)) {
-            tile_counters = (int32_t *)((uint8_t *)workspace + l.counters);
-            partials = (float *)((uint8_t *)workspace + l.partials);
+    if (mfma) {
+        if (tile_counters && !counters_cleared) {
             e = launch_zero_i32(tile_counters, kSplitGrid, s);
             if (e != hipSuccess) return FC_ERR_HIP;
         }

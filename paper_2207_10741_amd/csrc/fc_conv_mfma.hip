@@ -289,6 +289,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             bias_s[tid] = (bias && co < g.c_out) ? bias[co] : 0.f;
         }
         __syncthreads();
+        // set-up B: one thread per (row, tap) decides "inside the image and relevant" (for a
+        // masked layer it fetches the mask byte under the tap; all of a thread's bytes are in
+        // flight together)
         for (int i0 = 0; i0 < PAIR_IT; i0 += PAIR_CH) {
             int prow_[PAIR_CH], ptap_[PAIR_CH], ppix_[PAIR_CH];
             bool pin_[PAIR_CH];

@@ -82,10 +82,16 @@ static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, in
 hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, int kh, int kw,
                                   int sh, int sw, int ph, int pw, int dh, int dw, int ho, int wo,
                                   uint8_t *mask_out, hipStream_t s);
+// What the compaction can do on the side for the convolution that follows it.
+struct CompactExtras {
+    int32_t *zero = nullptr; // zero_n ints to clear (the split-K tile counters)
+    int32_t zero_n = 0;
+};
+
 // Kept positions of the layer whose mask geometry is g: writes mask_out (0/1 bytes;
 // may be NULL), the ascending index list and its length.
 hipError_t launch_compact(const MaskGeom &g, const uint8_t *mask_in, uint8_t *mask_out, int32_t *idx,
-                          int32_t *count, int32_t *block_counts, hipStream_t s);
+                          int32_t *count, int32_t *block_counts, const CompactExtras &extras, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,

@@ -142,7 +142,8 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(MaskGe
                                                                            const int32_t *__restrict__ block_counts,
                                                                            uint8_t *__restrict__ mask_out,
                                                                            int32_t *__restrict__ idx,
-                                                                           int32_t *__restrict__ count)
+                                                                           int32_t *__restrict__ count,
+                                                                           CompactExtras ex)
 {
     __shared__ int wave_sum[kCompactBlockThreads / 64];
     __shared__ int scratch[kCompactBlockThreads / 64];
@@ -198,24 +199,28 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(MaskGe
     __syncthreads();
     for (int i = tid; i < block_total; i += kCompactBlockThreads) idx[(int64_t)block_base + i] = stage[i];
     if (blockIdx.x == gridDim.x - 1 && tid == 0) *count = block_base + block_total;
+
+    // on the side, for the convolution that follows: clear its split-K tile counters
+    if (ex.zero && blockIdx.x == 0)
+        for (int i = tid; i < ex.zero_n; i += kCompactBlockThreads) ex.zero[i] = 0;
 }
 
 hipError_t launch_compact(const MaskGeom &g_in, const uint8_t *mask_in, uint8_t *mask_out, int32_t *idx,
-                          int32_t *count, int32_t *block_counts, hipStream_t s)
+                          int32_t *count, int32_t *block_counts, const CompactExtras &extras, hipStream_t s)
 {
     MaskGeom g = g_in;
     if (reinterpret_cast<uintptr_t>(mask_in) & 15u) g.identity = 0; // the 128-bit path needs alignment
     const int nb = (int)compact_blocks(g.m);
     if (nb <= kCompactSingleLaunchBlocks) {
         hipLaunchKernelGGL(k_compact_scatter<true>, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in,
-                           (const int32_t *)nullptr, mask_out, idx, count);
+                           (const int32_t *)nullptr, mask_out, idx, count, extras);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(k_compact_count, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in, block_counts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_compact_scatter<false>, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in,
-                       (const int32_t *)block_counts, mask_out, idx, count);
+                       (const int32_t *)block_counts, mask_out, idx, count, extras);
     return hipGetLastError();
 }
 
