@@ -105,6 +105,60 @@ def cpu_baseline(layers, images):
     return flops / t / 1e12, O.num_threads(), t
 
 
+def sweep(torch, B, synth, workloads, args, batch):
+    """Mask-density sweep of the four layer shapes: irrelevant share 0, 0.1, ... 1 for blob and
+    Bernoulli masks; per layer the conv kernel alone (kept list given) and the whole call
+    (mask propagation + compaction + conv + zero-fill), each as a HIP-graph replay; a
+    least-squares line t = a + b * kept_share per layer and mask structure."""
+    shares = [round(0.1 * i, 1) for i in range(11)]
+    out = {"sweep": True, "batch": batch, "unit": "us", "launch_floor_us": None, "layers": {}}
+    # what one (near-)empty kernel costs inside a replayed graph: 16 of them, divided by 16
+    tiny = torch.zeros((64,), dtype=torch.int32, device="cuda:0")
+    def sixteen():
+        for _ in range(16):
+            tiny.add_(1)
+    g = capture(torch, sixteen)
+    out["launch_floor_us"] = round(time_loop(torch, g.replay, args.steps, args.warmup) / 16 * 1e6, 2)
+    layers = build_sweep_layers(torch, B, synth, workloads, 0.0, "blobs", batch)   # tensors made once
+    for L in layers:
+        L["dense"] = B.PreparedConv(L["desc"], L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"])
+
+    def timed(call):
+        def fn():
+            for _ in range(4):
+                call()
+        return time_loop(torch, capture(torch, fn).replay, args.steps, args.warmup) / 4 * 1e6
+
+    for li, L in enumerate(layers):
+        L["dense_us"] = timed(L["dense"])
+    for kind in ("blobs", "bernoulli"):
+        gen = synth.mask_bernoulli if kind == "bernoulli" else synth.mask_objects
+        for li, L in enumerate(layers):
+            pts = []
+            for f in shares:
+                mask_host = gen(batch, L["side"], L["side"], f, 5, li, 4)
+                L["mask"].copy_(torch.from_numpy(mask_host))
+                m_out = B.mask_downsample(L["mask"])
+                idx, count = B.active_index_compact(m_out)
+                d = L["desc"]
+                full = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], out=L["out"], workspace=L["ws"])
+                conv = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=m_out, idx=idx,
+                                      count=count, out=L["out"], workspace=L["ws"])
+                pts.append((float(np.count_nonzero(mask_host)) / mask_host.size, timed(conv), timed(full)))
+            r = np.array([p[0] for p in pts])
+            entry = {"kept_share": [round(float(v), 4) for v in r], "dense_us": round(L["dense_us"], 2)}
+            for col, name in ((1, "conv_only_us"), (2, "whole_call_us")):
+                t = np.array([p[col] for p in pts])
+                b, a = np.polyfit(r, t, 1)
+                ss_res = float(np.sum((t - (a + b * r)) ** 2))
+                ss_tot = float(np.sum((t - t.mean()) ** 2))
+                entry[name] = [round(float(v), 2) for v in t]
+                entry[name + "_fit"] = {"a_us": round(float(a), 2), "b_us": round(float(b), 2),
+                                        "r2": round(1.0 - ss_res / ss_tot, 4) if ss_tot > 0 else None}
+            out["layers"].setdefault(L["name"], {})[kind] = entry
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +171,9 @@ def main():
     ap.add_argument("--cpu-images", type=int, default=16)
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel loop (for rocprofv3 --kernel-trace --stats)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="mask-density sweep (irrelevant share 0..1, blob and Bernoulli masks) with a "
+                         "linear fit of time against kept share per layer, instead of the bench line")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
@@ -134,6 +191,9 @@ def main():
 
     irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
     batch = workloads.SWEEP_BATCH if args.batch is None else args.batch
+    if args.sweep:
+        sweep(torch, B, synth, workloads, args, batch)
+        return
     layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch)
 
     # ---- the whole hot path: a1 + a2 + a3..a6 for every layer ------------------

@@ -122,17 +122,40 @@ __device__ __forceinline__ void wait_vmcnt()
     __asm__ volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
-template <int TM, int TN, int NB>
+// Bytes of the LDS stage region: NB buffers of (TM + TN) rows for the tap-by-tap loop; with the
+// shared-halo loop (SL > 0) also room for two buffers of SL pixel slots and NBW weight buffers.
+template <int TM, int TN, int NB, int SL, int NBW>
+constexpr size_t dma_stage_region_bytes()
+{
+    const size_t classic = (size_t)NB * (TM + TN) * 128;
+    const size_t halo = SL > 0 ? (size_t)2 * SL * 128 + (size_t)NBW * TN * 128 : 0;
+    return classic > halo ? classic : halo;
+}
+
+template <int TM, int TN, int NB, int SL, int NBW>
 constexpr size_t dma_lds_bytes()
 {
-    return (size_t)NB * (TM + TN) * 128 + (size_t)TM * 5 * sizeof(int32_t) + (size_t)TN * sizeof(float);
+    return dma_stage_region_bytes<TM, TN, NB, SL, NBW>() + (size_t)TM * 5 * sizeof(int32_t) +
+           (size_t)TN * sizeof(float) + (SL > 0 ? (size_t)(TM + 3 * SL + 8) * sizeof(int32_t) : 0);
 }
 
 // DT: storage type of x and w; TO: float or a 16-bit carrier; TM x TN: workgroup tile
 // (positions x output channels); WM x WN: wave grid inside it; TAPC: 1 (1x1 kernels),
 // 9 (3x3 kernels) or 32 (any kernel of up to 32 taps); NB: LDS stage buffers (NB-1
 // stages of loads in flight); MINW: waves per SIMD the register budget leaves room for.
-template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW>
+//
+// SL > 0 (3x3 kernels with unit horizontal stride and dilation only) adds the shared-halo
+// loop.  The three horizontal taps of a kept position read the pixels left of, at and right
+// of its centre column, and the kept positions of a tile are sorted, so along a run of
+// horizontally adjacent kept positions the left pixel of one is the centre pixel of the one
+// before it.  The tile therefore lays its pixels out on a line of "slots": one per kept
+// position, plus one before the first and one after the last position of every run; position
+// r's taps kw = 0, 1, 2 are then slots cs(r) - 1, cs(r), cs(r) + 1.  For every (kernel row,
+// 64-channel chunk) the line is gathered into LDS once and multiplied three times, each time
+// against the weights of another horizontal tap, which cuts the gathered bytes by up to three.
+// A tile whose line would need more than SL slots (a fragmented mask) runs the tap-by-tap
+// loop instead.  NBW: LDS buffers for the per-tap weight slabs of the shared-halo loop.
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW>
 __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
                                                                  const uint8_t *__restrict__ mask_in,
                                                                  const uint8_t *__restrict__ mask_out,
@@ -158,15 +181,26 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     static_assert(TM % RPP == 0 && TN % RPP == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
     static_assert(TM <= NT && TN <= NT, "set-up assumes one thread per row / channel");
     static_assert(NB >= 2 && (NB - 1) * L <= 63, "vmcnt is a 6-bit counter");
+    constexpr bool HALO = SL > 0;
+    constexpr size_t REGION = dma_stage_region_bytes<TM, TN, NB, SL, NBW>();
+    static_assert(!HALO || (TAPC == 9 && SL % RPP == 0 && SL <= NT && SL > TM && (NBW == 2 || NBW == 3)),
+                  "shared-halo loop: 3x3 kernels, whole load passes, one thread per slot");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     unsigned char *stage0 = smem_raw;                                   // [NB][TM + TN][128]
-    float *bias_s = reinterpret_cast<float *>(smem_raw + NB * STAGE_BYTES);
+    float *bias_s = reinterpret_cast<float *>(smem_raw + REGION);
     int32_t *row_p = reinterpret_cast<int32_t *>(bias_s + TN);
     int32_t *row_base = row_p + TM;
     int32_t *row_img = row_base + TM;
     int32_t *row_hw = row_img + TM;
     uint32_t *row_bits = reinterpret_cast<uint32_t *>(row_hw + TM);
+    // shared-halo loop only: centre slot of every row, and per slot the pixel of kernel row 0,
+    // its packed (ih, iw) and one "inside the image and relevant" bit per kernel row
+    int32_t *row_cs = reinterpret_cast<int32_t *>(row_bits + TM);
+    int32_t *slot_pix = row_cs + TM;
+    int32_t *slot_hw = slot_pix + SL;
+    uint32_t *slot_bits = reinterpret_cast<uint32_t *>(slot_hw + SL);
+    int32_t *scan_part = reinterpret_cast<int32_t *>(slot_bits + SL);
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw); // LDS byte address of the stage buffers
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -202,7 +236,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     int S = 1;
     if (partials && ntiles > 0) {
         S = (int)gridDim.x / ntiles;
-        S = S < 1 ? 1 : (S > stages ? stages : S);
+        const int work = HALO ? g.kh * cchunks : stages; // (kernel row, chunk) groups or stages
+        S = S < 1 ? 1 : (S > work ? work : S);
         if (S > kMaxSplits) S = kMaxSplits;
     }
     const int nunits = ntiles * S;
@@ -265,6 +300,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         const int co0 = nt * TN;
 
         __syncthreads(); // the previous tile's epilogue is done with LDS
+        int sa_p = -1, sa_ow = 0, sa_ih0 = 0, sa_iw0 = 0, sa_b = 0; // this thread's row (tid < TM)
         if (tid < TM) {
             const int m = mt * TM + tid;
             int p = -1, base = 0, b = 0, hw = 0;
@@ -275,6 +311,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                 const int oh = q % g.ho;
                 b = q / g.ho;
                 const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
+                sa_p = p; sa_ow = ow; sa_ih0 = ih0; sa_iw0 = iw0; sa_b = b;
                 base = (b * g.h + ih0) * g.w + iw0;
                 hw = (int)(((uint32_t)ih0 & 0xffffu) | ((uint32_t)iw0 << 16));
             }
@@ -289,10 +326,88 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             bias_s[tid] = (bias && co < g.c_out) ? bias[co] : 0.f;
         }
         __syncthreads();
+        bool use_halo = false;
+        int ns = 0; // slots on this tile's pixel line
+        if constexpr (HALO) {
+            int cnt = 0, lead = 0;
+            bool ladj = false, radj = false;
+            if (tid < TM) {
+                cnt = 1;
+                if (sa_p >= 0) {
+                    ladj = tid > 0 && row_p[tid - 1] == sa_p - 1 && sa_ow > 0;
+                    radj = tid < TM - 1 && row_p[tid + 1] == sa_p + 1 && sa_ow < g.wo - 1;
+                    lead = ladj ? 0 : 1;
+                    cnt = 1 + lead + (radj ? 0 : 1);
+                }
+            }
+            const int incl = wave_inclusive_scan(cnt);
+            if (lane == 63) scan_part[wave] = incl;
+            if (tid < SL) slot_bits[tid] = 0;
+            __syncthreads();
+            int before = 0;
+#pragma unroll
+            for (int v = 0; v < NT / 64; ++v) {
+                const int t = scan_part[v];
+                before += v < wave ? t : 0;
+                ns += t;
+            }
+            // (one slot to spare: a row past the end of the list still reads "its" three slots)
+            use_halo = ns + 1 <= SL;
+            if (use_halo && tid < TM) {
+                const int cs = before + incl - cnt + lead;
+                row_cs[tid] = cs;
+                if (sa_p >= 0) {
+                    const int iwc = sa_iw0 + 1; // kw = 1, unit dilation
+                    const int pixc = (sa_b * g.h + sa_ih0) * g.w + iwc;
+                    const int ih16 = (int)((uint32_t)sa_ih0 & 0xffffu);
+                    slot_pix[cs] = pixc;
+                    slot_hw[cs] = ih16 | (int)((uint32_t)iwc << 16);
+                    if (!ladj) {
+                        slot_pix[cs - 1] = pixc - 1;
+                        slot_hw[cs - 1] = ih16 | (int)((uint32_t)(iwc - 1) << 16);
+                    }
+                    if (!radj) {
+                        slot_pix[cs + 1] = pixc + 1;
+                        slot_hw[cs + 1] = ih16 | (int)((uint32_t)(iwc + 1) << 16);
+                    }
+                } else {
+                    slot_pix[cs] = 0;
+                    slot_hw[cs] = (int)((uint32_t)(-20000) << 16); // never inside an image
+                }
+            }
+            __syncthreads();
+            if (use_halo) {
+                // one thread per (slot, kernel row): inside the image and relevant?
+                constexpr int SIT = (SL * 3 + NT - 1) / NT;
+                int ssl_[SIT], skh_[SIT], spix_[SIT];
+                bool sin_[SIT];
+#pragma unroll
+                for (int i = 0; i < SIT; ++i) {
+                    const int pair = tid + i * NT;
+                    const int sl = pair / 3, kh_i = pair - sl * 3;
+                    const bool live = sl < ns;
+                    const int s2 = live ? sl : 0;
+                    const int hw = slot_hw[s2];
+                    const int ih = (int)(int16_t)(hw & 0xffff) + kh_i * g.dh;
+                    const int iw = hw >> 16;
+                    const bool inb = live && ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
+                    ssl_[i] = s2;
+                    skh_[i] = kh_i;
+                    sin_[i] = inb;
+                    spix_[i] = inb ? slot_pix[s2] + kh_i * g.dh * g.w : 0;
+                }
+                uint8_t smv[SIT];
+#pragma unroll
+                for (int i = 0; i < SIT; ++i) smv[i] = mask_in ? mask_in[spix_[i]] : (uint8_t)1;
+#pragma unroll
+                for (int i = 0; i < SIT; ++i)
+                    if (sin_[i] && smv[i]) atomicOr(&slot_bits[ssl_[i]], 1u << skh_[i]);
+            }
+        }
         // set-up B: one thread per (row, tap) decides "inside the image and relevant" (for a
         // masked layer it fetches the mask byte under the tap; all of a thread's bytes are in
         // flight together)
-        for (int i0 = 0; i0 < PAIR_IT; i0 += PAIR_CH) {
+        for (int i0 = 0; i0 < (use_halo ? 0 : PAIR_IT); i0 += PAIR_CH) {
             int prow_[PAIR_CH], ptap_[PAIR_CH], ppix_[PAIR_CH];
             bool pin_[PAIR_CH];
 #pragma unroll
@@ -318,19 +433,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             for (int i = 0; i < PAIR_CH; ++i)
                 if (pin_[i] && mv[i]) atomicOr(&row_bits[prow_[i]], 1u << ptap_[i]);
         }
-        __syncthreads();
 
         // per-thread, loop-invariant byte offsets; gp = the global 16-byte piece this lane
         // fetches for its LDS slot (the swizzle)
-        uint32_t xoff[XR], xbits[XR], woff[WR];
-        int xgp[XR], wgp[WR];
-#pragma unroll
-        for (int j = 0; j < XR; ++j) {
-            const int r = prow + j * RPP;
-            xgp[j] = slot ^ FC_SWZ(r);
-            xoff[j] = ((uint32_t)row_base[r] * (uint32_t)g.c_in + (uint32_t)xgp[j] * 8u) * 2u;
-            xbits[j] = row_bits[r];
-        }
+        uint32_t woff[WR];
+        int wgp[WR];
 #pragma unroll
         for (int j = 0; j < WR; ++j) {
             const int r = prow + j * RPP;
@@ -348,6 +455,155 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
+        if (HALO && use_halo) {
+            // ---------------- shared-halo loop ----------------
+            // LDS: two buffers of SL pixel slots, then NBW buffers of TN weight rows.  A group =
+            // one (kernel row, 64-channel chunk): its pixel line is gathered once (XL wave loads
+            // per thread, issued a whole group ahead), its three taps are three stages, each
+            // with its own weight slab (WR wave loads per thread, issued NBW - 1 stages ahead).
+            __syncthreads(); // slot_bits complete
+            constexpr int XL = HALO ? SL / RPP : 1;
+            constexpr uint32_t XB = (uint32_t)SL * 128u;
+            constexpr uint32_t WB = (uint32_t)TN * 128u;
+            uint32_t hxoff[XL], hxbits[XL];
+            int hxgp[XL];
+#pragma unroll
+            for (int j = 0; j < XL; ++j) {
+                const int sl = prow + j * RPP;
+                hxgp[j] = slot ^ FC_SWZ(sl);
+                hxoff[j] = ((uint32_t)slot_pix[sl] * (uint32_t)g.c_in + (uint32_t)hxgp[j] * 8u) * 2u;
+                hxbits[j] = slot_bits[sl];
+            }
+            // fragment addressing: the three slots of this lane's rows
+            uint32_t xfa[PB][3];
+#pragma unroll
+            for (int a = 0; a < PB; ++a) {
+                const int cs = row_cs[wave_m * WTM + a * 32 + (lane & 31)];
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    const int sl = cs + t - 1;
+                    xfa[a][t] = (uint32_t)sl * 128u + (uint32_t)((lane >> 5) ^ FC_SWZ(sl)) * 16u;
+                }
+            }
+            const int groups = g.kh * cchunks;
+            const int g_begin = (int)((int64_t)split * groups / S), g_end = (int)((int64_t)(split + 1) * groups / S);
+            const int ng = g_end - g_begin;
+            // cursors: next pixel line to gather, next weight slab to fetch
+            int xkh = g_begin / cchunks, xcc = g_begin - xkh * cchunks, xleft = ng, xbuf_i = 0;
+            int wkh = xkh, wcc = xcc, wkw = 0, wleft = 3 * ng, wbuf_i = 0;
+            uint32_t ld_off[WR + XL], ld_lds[WR + XL];
+#define FC_HALO_PREP_X(at)                                                                                \
+    {                                                                                                     \
+        const uint32_t sx = (uint32_t)((xkh * g.dh) * g.w * g.c_in + xcc * kTK) * 2u;                     \
+        const uint32_t l0 = lds0 + (uint32_t)xbuf_i * XB + (uint32_t)wave * 1024u;                        \
+        const bool in_k = xleft > 0;                                                                      \
+        --xleft;                                                                                          \
+        _Pragma("unroll") for (int j = 0; j < XL; ++j)                                                    \
+        {                                                                                                 \
+            const bool ok = in_k && xcc * kTK + hxgp[j] * 8 < g.c_in && ((hxbits[j] >> (xkh & 31)) & 1u); \
+            ld_off[(at) + j] = ok ? hxoff[j] + sx : kOutOfRange;                                          \
+            ld_lds[(at) + j] = l0 + (uint32_t)j * (RPP * 128);                                            \
+        }                                                                                                 \
+        const int wrap = (xcc + 1 == cchunks);                                                            \
+        xcc = wrap ? 0 : xcc + 1;                                                                         \
+        xkh += wrap;                                                                                      \
+        xbuf_i ^= 1;                                                                                      \
+    }
+#define FC_HALO_PREP_W()                                                                                  \
+    {                                                                                                     \
+        const uint32_t sw = (uint32_t)((wkh * 3 + wkw) * g.c_in + wcc * kTK) * 2u;                        \
+        const uint32_t l0 = lds0 + 2u * XB + (uint32_t)wbuf_i * WB + (uint32_t)wave * 1024u;              \
+        const bool in_k = wleft > 0;                                                                      \
+        --wleft;                                                                                          \
+        _Pragma("unroll") for (int j = 0; j < WR; ++j)                                                    \
+        {                                                                                                 \
+            const bool ok = in_k && wcc * kTK + wgp[j] * 8 < g.c_in;                                      \
+            ld_off[j] = ok ? woff[j] + sw : kOutOfRange;                                                  \
+            ld_lds[j] = l0 + (uint32_t)j * (RPP * 128);                                                   \
+        }                                                                                                 \
+        const int w3 = (wkw == 2);                                                                        \
+        wkw = w3 ? 0 : wkw + 1;                                                                           \
+        const int wc = w3 & (wcc + 1 == cchunks);                                                         \
+        wcc = w3 ? (wc ? 0 : wcc + 1) : wcc;                                                              \
+        wkh += wc;                                                                                        \
+        wbuf_i = (wbuf_i + 1 == NBW) ? 0 : wbuf_i + 1;                                                    \
+    }
+#define FC_HALO_ISSUE(first, last, total)                                                                 \
+    _Pragma("unroll") for (int j = (first); j < (last); ++j)                                              \
+        if (j < (total)) dma_load16(j < WR ? rsrc_w : rsrc_x, ld_off[j], __builtin_amdgcn_readfirstlane(ld_lds[j]));
+
+            // prologue, in this order: first pixel line, then NBW - 1 weight slabs
+            FC_HALO_PREP_X(WR)
+            FC_HALO_ISSUE(WR, WR + XL, WR + XL)
+#pragma unroll
+            for (int d = 0; d < NBW - 1; ++d) {
+                FC_HALO_PREP_W()
+                FC_HALO_ISSUE(0, WR, WR)
+            }
+            int cxb = 0, cwb = 0; // buffers being multiplied
+            for (int gi = 0; gi < ng; ++gi) {
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    // this stage issues the weight slab NBW - 1 stages ahead and, on the first
+                    // tap, after it, the next group's pixel line
+                    FC_HALO_PREP_W()
+                    if (t == 0) FC_HALO_PREP_X(WR)
+                    constexpr int kBehindW = (NBW - 2) * WR; // loads issued after this stage's slab ...
+                    // ... on tap 0 (the line of this group was issued before that slab); on taps
+                    // 1 and 2 the next group's line is in flight behind it as well
+                    if (t == 0) wait_vmcnt<kBehindW>();
+                    if (t == 1) wait_vmcnt<kBehindW + XL>();
+                    if (t == 2) wait_vmcnt<(NBW == 3 ? WR + XL : 0)>();
+                    __syncthreads();
+                    const unsigned char *xs = stage0 + (uint32_t)cxb * XB;
+                    const unsigned char *ws =
+                        stage0 + 2u * XB + (uint32_t)cwb * WB + (wave_n * WTN) * 128 + frag_row;
+                    const int nld = t == 0 ? WR + XL : WR;
+                    const int lpk = t == 0 ? (WR + XL + KK - 1) / KK : (WR + KK - 1) / KK;
+                    uint4 wf[2][CB], xf[2][PB];
+#pragma unroll
+                    for (int b = 0; b < CB; ++b)
+                        wf[0][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + frag_t16);
+#pragma unroll
+                    for (int a = 0; a < PB; ++a) xf[0][a] = *reinterpret_cast<const uint4 *>(xs + xfa[a][t]);
+#pragma unroll
+                    for (int kk = 0; kk < KK; ++kk) {
+                        if (kk + 1 < KK) {
+                            const uint32_t o = ((uint32_t)(kk + 1) * 32u) ^ frag_t16;
+#pragma unroll
+                            for (int b = 0; b < CB; ++b)
+                                wf[(kk + 1) & 1][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + o);
+#pragma unroll
+                            for (int a = 0; a < PB; ++a)
+                                xf[(kk + 1) & 1][a] = *reinterpret_cast<const uint4 *>(
+                                    xs + (xfa[a][t] ^ ((uint32_t)(kk + 1) * 32u)));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        FC_HALO_ISSUE(kk * lpk, (kk + 1) * lpk, nld)
+#pragma unroll
+                        for (int a = 0; a < PB; ++a)
+#pragma unroll
+                            for (int b = 0; b < CB; ++b)
+                                acc[a][b] = mfma32<DT>(wf[kk & 1][b], xf[kk & 1][a], acc[a][b]);
+                    }
+                    cwb = (cwb + 1 == NBW) ? 0 : cwb + 1;
+                }
+                cxb ^= 1;
+            }
+#undef FC_HALO_ISSUE
+#undef FC_HALO_PREP_W
+#undef FC_HALO_PREP_X
+        } else {
+        __syncthreads(); // row_bits complete
+        uint32_t xoff[XR], xbits[XR];
+        int xgp[XR];
+#pragma unroll
+        for (int j = 0; j < XR; ++j) {
+            const int r = prow + j * RPP;
+            xgp[j] = slot ^ FC_SWZ(r);
+            xoff[j] = ((uint32_t)row_base[r] * (uint32_t)g.c_in + (uint32_t)xgp[j] * 8u) * 2u;
+            xbits[j] = row_bits[r];
+        }
         // cursor: the next stage to be issued (starts at this unit's first stage)
         int tap = s_begin / cchunks, cc = s_begin - tap * cchunks;
         int kh = tap / kwid, kw = tap - kh * kwid;
@@ -433,6 +689,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         }
 #undef FC_ISSUE_LOADS
 #undef FC_PREPARE_STAGE
+        } // tap-by-tap loop
 
         // ---- epilogue: bias, ReLU, one rounding; the tile is transposed through LDS so that
         // every lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
@@ -490,7 +747,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             }
         }
         constexpr int OP = TN * (int)sizeof(TO) + 16;
-        static_assert((size_t)TM * OP <= (size_t)NB * STAGE_BYTES, "output tile fits");
+        static_assert((size_t)TM * OP <= REGION, "output tile fits");
         unsigned char *Os = smem_raw;
 #pragma unroll
         for (int a = 0; a < PB; ++a) {
@@ -541,13 +798,13 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
     return true;
 }
 
-template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW>
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2>
 static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                              const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                              void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW>;
-    constexpr size_t lds = dma_lds_bytes<TM, TN, NB>();
+    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW>;
+    constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW>();
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -588,6 +845,8 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
         case 29: return launch_dma<DT, TO, 256, 64, 4, 1, TAPC, 2, 1>(FC_ARGS);
         case 30: return launch_dma<DT, TO, 128, 64, 4, 1, TAPC, 2, 3>(FC_ARGS);
         case 31: return launch_dma<DT, TO, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
+        case 41: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
+        case 44: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
         default: break;
         }
     }
@@ -596,6 +855,17 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
     // otherwise 128 x 64, which doubles the tile count (the kept count is not known here,
     // so the dense row count decides)
     const int64_t tiles128 = (int64_t)((g.m + 127) / 128) * ((g.c_out + 127) / 128);
+    // 3x3 kernels that step one pixel at a time horizontally share the gathered pixels
+    // between their three horizontal taps (worth it when image rows are long enough for runs
+    // of adjacent kept positions; narrow layers with many tiles do better with three
+    // workgroups per CU, see below)
+    if constexpr (TAPC == 9) {
+        if (g.sw == 1 && g.dw == 1 && g.wo >= 32) {
+            if (g.c_out > 64 && tiles128 >= 512)
+                return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
+            if (g.c_out > 64 || partials) return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+        }
+    }
     if (g.c_out > 64 && tiles128 >= 512)
         return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, (sizeof(TO) == 4 ? 3 : 2), 2>(FC_ARGS);
     // narrow layers with many tiles: two stage buffers, so that three workgroups fit a CU

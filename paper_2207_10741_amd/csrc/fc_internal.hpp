@@ -78,6 +78,18 @@ static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, in
     return g;
 }
 
+// inclusive prefix sum over the 64 lanes of a wave
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    const int lane = __lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
 // ---- launchers (each enqueues on `s`, returns a hipError_t) ----------------
 hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, int kh, int kw,
                                   int sh, int sw, int ph, int pw, int dh, int dw, int ho, int wo,

@@ -88,16 +88,6 @@ __device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_
     return flags;
 }
 
-__device__ __forceinline__ int wave_inclusive_scan(int v)
-{
-    const int lane = __lane_id();
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        int t = __shfl_up(v, d, 64);
-        if (lane >= d) v += t;
-    }
-    return v;
-}
 
 // sum of v over the block (all threads get it); scratch holds one int per wave
 __device__ __forceinline__ int block_sum(int v, int *scratch)

@@ -62,16 +62,24 @@ def _run_layer(n, h, w, ci, co, k, s, p, d, dtype, *, irr=0.48, relu=True, use_b
         mask = synth.mask_bernoulli(n, h, w, irr, seed, 4)
     elif mask_kind == "band":
         mask = synth.mask_band_and_boxes(n, h, w, irr, seed, 4)
+    elif mask_kind == "mixed":
+        # left part of every image row fragmented, right part solid, a few rows empty: tiles
+        # with long runs of adjacent kept positions next to tiles with none
+        mask = synth.mask_bernoulli(n, h, w, 0.5, seed, 4)
+        mask[:, :, w // 3:] = 1
+        mask[:, ::7, :] = 0
     else:
         mask = None
     flags = (B.RELU if relu else 0) | flags_extra
-    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s, s), (p, p), (d, d), dtype, out_dtype, flags)
+    pair = lambda v: tuple(v) if isinstance(v, (tuple, list)) else (v, v)
+    s, p, d = pair(s), pair(p), pair(d)
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), s, p, d, dtype, out_dtype, flags)
     xd, wd = G.to_dev(x, dtype), G.to_dev(wt, dtype)
     bd = None if bias is None else torch.from_numpy(bias).to(G.dev())
     md = None if mask is None else G.mask_dev(mask)
     kw = {}
     if precomputed and mask is not None:
-        m_out = B.mask_downsample(md, (k, k), (s, s), (p, p), (d, d))
+        m_out = B.mask_downsample(md, (k, k), s, p, d)
         idx, count = B.active_index_compact(m_out)
         # same workspace size as the internal path, so that small layers split their
         # reduction the same way (the result is then bit-identical by construction)
@@ -82,9 +90,9 @@ def _run_layer(n, h, w, ci, co, k, s, p, d, dtype, *, irr=0.48, relu=True, use_b
     out = torch.full((n, ho, wo, co), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
     B.focused_conv2d(desc, xd, wd, bd, mask_in=md, out=out, **kw)
     torch.cuda.synchronize()
-    shape = O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=relu)
+    shape = O.ConvShape(n, h, w, ci, co, k, k, s, p, d, relu=relu)
     want = O.focused_conv2d(shape, x, wt, bias=bias, mask_in=mask, dtype=dtype)
-    keep = (O.mask_downsample(mask, k, k, (s, s), (p, p), (d, d)) != 0) if mask is not None \
+    keep = (O.mask_downsample(mask, k, k, s, p, d) != 0) if mask is not None \
         else np.ones(want.shape[:3], bool)
     return out, want, keep
 
@@ -155,6 +163,40 @@ def test_16bit_output_is_rne_of_fp32_output(layer, dtype):
         ulp = np.abs(want) * (2.0 ** -8 if dtype == synth.BF16 else 2.0 ** -11)
         assert (np.abs(G.to_f64(o16) - want) <= ulp + 1e-30).all()
     assert not o16.view(torch.int16).cpu().numpy()[~keep].any()
+
+
+# 3x3 layers that step one pixel at a time horizontally and are at least 32 wide: the three
+# horizontal taps share one gathered pixel line per tile (runs of adjacent kept positions), and
+# tiles whose line would be too long (fragmented masks) take the tap-by-tap loop
+HALO_LAYERS = [
+    # n, h, w, ci, co, k, s, p, d
+    (2, 40, 56, 64, 128, 3, 1, 1, 1),               # 128 x 64 tiles
+    (8, 96, 96, 64, 128, 3, 1, 1, 1),               # 128 x 128 tiles (576 of them)
+    (1, 36, 64, 64, 64, 3, 1, 1, 1),                # narrow layer, reduction split over workgroups
+    (1, 33, 47, 72, 136, 3, (2, 1), (0, 2), (2, 1)),  # vertical stride and dilation, wide padding, channel tails
+    (3, 17, 32, 128, 72, 3, (1, 1), (1, 0), (1, 1)),  # no horizontal padding: the output is narrower
+]
+
+
+@pytest.mark.parametrize("layer", HALO_LAYERS)
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", "mixed", None])
+def test_shared_halo_layers_match_oracle(layer, mask_kind):
+    if layer[0] == 8 and mask_kind == "bernoulli":
+        pytest.skip("covered by the smaller shapes")
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=0.45, seed=207)
+    assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()
+
+
+@pytest.mark.parametrize("layer", [HALO_LAYERS[0], HALO_LAYERS[2], HALO_LAYERS[3]])
+def test_shared_halo_precomputed_list_and_16bit_output(layer):
+    torch = G.torch_mod()
+    a, want, keep = _run_layer(*layer, synth.F16, mask_kind="mixed", seed=208)
+    b, _, _ = _run_layer(*layer, synth.F16, mask_kind="mixed", seed=208, precomputed=True)
+    assert torch.equal(a, b)
+    c, _, _ = _run_layer(*layer, synth.F16, mask_kind="mixed", seed=208, out_dtype=synth.F16)
+    assert torch.equal(c, a.to(c.dtype))
+    assert G.rel_err(G.to_f64(a), want, keep) <= TOL_F32_OUT
 
 
 def test_dense_path_is_standard_convolution():
