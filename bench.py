@@ -159,6 +159,79 @@ def sweep(torch, B, synth, workloads, args, batch):
     print(json.dumps(out))
 
 
+STACKS = {
+    # name: (layer list, batch, height, width, input channels, what it stands for)
+    "resnet18": ("resnet18", 1, 224, 224, 3, "ResNet-18-shaped stack, batch 1, 224x224x3, boxes + sky band, 48 % irrelevant"),
+    "resnet50": ("resnet50_bottlenecks", 32, 120, 160, 64,
+                 "ResNet-50 bottleneck convs on the post-stem activation of 480x640 images, batch 32, "
+                 "per-image irrelevant share uniform in [0.3, 0.7]"),
+    "vgg16": ("vgg16", 8, 1080, 1920, 3, "VGG-16 convs on 1080x1920 frames, batch 8, depth-ramp mask, 50 % irrelevant"),
+}
+
+
+def stack_bench(torch, B, synth, workloads, args):
+    """A whole conv stack (every conv one library call, masks and kept lists built once per
+    resolution): dense, focused with every output zero-filled, and focused with conv-to-conv
+    outputs left unwritten at irrelevant rows.  One HIP graph replay per pass."""
+    from paper_2207_10741_amd.stacks import ConvStack
+    fn_name, n, h, w, c_in, what = STACKS[args.stack]
+    n = n if args.batch is None else args.batch
+    ops = getattr(workloads, fn_name)()
+    if args.stack == "resnet50":
+        shares = list(synth.rng(3, 0, 5).uniform(0.3, 0.7, size=n))
+        mask = synth.mask_objects(n, h, w, shares, 3, 0, 4)
+    elif args.stack == "vgg16":
+        mask = synth.mask_depth_ramp(n, h, w, 0.5, 4, 0, 4)
+    else:
+        mask = synth.mask_objects(n, h, w, workloads.HEADLINE_IRRELEVANT, 2, 0, 4)
+    stack = ConvStack(ops, n, h, w, B.BF16, seed=len(args.stack))
+    x_host = synth.activations((n, h, w, c_in), synth.BF16, 9, 0, 1)
+    x = torch.from_numpy(x_host.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+    md = torch.from_numpy(mask).to("cuda:0")
+    del x_host
+
+    # kept rows per conv, from the propagated masks of one eager pass
+    _, masks = stack.run(x, md, keep_outputs=False)
+    torch.cuda.synchronize()
+    dense_flops = kept_flops = 0.0
+    for i, op in enumerate(ops):
+        if op.kind != "conv":
+            continue
+        per_pos = 2.0 * op.k * op.k * op.c_in * op.c_out
+        dense_flops += masks[i].numel() * per_pos
+        kept_flops += float(torch.count_nonzero(masks[i]).item()) * per_pos
+    del masks
+
+    def timed(**kw):
+        def one():
+            stack.run(x, kw.get("mask"), keep_outputs=False, chain=kw.get("chain", False))
+        try:
+            graph = capture(torch, one)
+            t = time_loop(torch, graph.replay, args.steps, args.warmup)
+            del graph
+            how = "one HIP graph replay per pass"
+        except Exception:   # capture not possible: time the eager calls
+            torch.cuda.synchronize()
+            t = time_loop(torch, one, args.steps, args.warmup)
+            how = "eager calls"
+        torch.cuda.empty_cache()
+        return t, how
+
+    t_dense, how = timed()
+    t_strict, _ = timed(mask=md)
+    t_chain, _ = timed(mask=md, chain=True)
+    print(json.dumps({
+        "stack": args.stack, "workload": what, "batch": n, "convs": sum(op.kind == "conv" for op in ops),
+        "launch": how, "steps": args.steps, "dtype": "bf16", "data": "synthetic",
+        "kept_flop_share": round(kept_flops / dense_flops, 4),
+        "dense_ms": round(t_dense * 1e3, 4), "dense_tflops": round(dense_flops / t_dense / 1e12, 2),
+        "focused_ms": round(t_strict * 1e3, 4), "focused_effective_tflops": round(kept_flops / t_strict / 1e12, 2),
+        "speedup_vs_dense": round(t_dense / t_strict, 3),
+        "focused_chain_ms": round(t_chain * 1e3, 4), "speedup_chain_vs_dense": round(t_dense / t_chain, 3),
+        "ms_per_image": round(t_strict * 1e3 / n, 5),
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -174,6 +247,9 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="mask-density sweep (irrelevant share 0..1, blob and Bernoulli masks) with a "
                          "linear fit of time against kept share per layer, instead of the bench line")
+    ap.add_argument("--stack", choices=sorted(STACKS), default=None,
+                    help="time a whole conv stack (dense / focused / focused without zero-fill between "
+                         "convs) instead of the bench line")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
@@ -193,6 +269,9 @@ def main():
     batch = workloads.SWEEP_BATCH if args.batch is None else args.batch
     if args.sweep:
         sweep(torch, B, synth, workloads, args, batch)
+        return
+    if args.stack:
+        stack_bench(torch, B, synth, workloads, args)
         return
     layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch)
 

@@ -1,49 +1,141 @@
 // Direct focused convolution for shapes the matrix-core path does not take
-// (odd channel counts such as RGB stems, fp32 storage).  One lane owns one
-// (active row, output channel) pair and walks the taps in the order kh, kw, ci
-// with an fp32 accumulator (Sec. III-A: only the kept patches are evaluated).
+// (odd channel counts such as RGB stems, fp32 storage, very large kernels).
+// Sec. III-A: only the kept patches are evaluated.
+//
+// One lane owns one kept position and CO_T of its output channels, held as fp32
+// accumulators in registers; it walks the taps in the order kh, kw, ci.  The
+// weights of those CO_T channels are staged once per workgroup in LDS as fp32,
+// transposed to [k][channel], so that the inner loop reads them as broadcasts
+// (every lane the same address) and does CO_T fused multiply-adds per loaded input
+// value.  Lanes of a wave hold consecutive kept positions, so for an RGB stem their
+// input loads fall on neighbouring pixels.  A gated tap (padding, irrelevant input
+// pixel) is skipped, not multiplied.
 #include "fc_internal.hpp"
 
 namespace fc {
 
-template <typename TI, typename TO>
-__global__ __launch_bounds__(256) void k_conv_direct(Geom g, const TI *__restrict__ x,
-                                                     const uint8_t *__restrict__ mask_in,
-                                                     const TI *__restrict__ w, const float *__restrict__ bias,
-                                                     const int32_t *__restrict__ idx,
-                                                     const int32_t *__restrict__ count, TO *__restrict__ out)
+constexpr int kRowsThreads = 256;
+constexpr int kRowsLdsFloats = 12288; // 48 KB of staged weights per workgroup
+
+template <typename TI, typename TO, int CO_T>
+__global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__restrict__ x,
+                                                            const uint8_t *__restrict__ mask_in,
+                                                            const TI *__restrict__ w,
+                                                            const float *__restrict__ bias,
+                                                            const int32_t *__restrict__ idx,
+                                                            const int32_t *__restrict__ count,
+                                                            TO *__restrict__ out)
 {
+    constexpr int KC = kRowsLdsFloats / CO_T; // reduction elements staged at a time
+    __shared__ float wt[KC * CO_T];           // [k][channel]
+    const int tid = threadIdx.x;
     const int rows = idx ? *count : g.m;
-    const int64_t total = (int64_t)rows * g.c_out;
-    const int taps_k = g.kh * g.kw * g.c_in;
-    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-         t += (int64_t)gridDim.x * blockDim.x) {
-        const int co = (int)(t % g.c_out);
-        const int r = (int)(t / g.c_out);
-        const int p = idx ? idx[r] : r;
-        const int ow = p % g.wo;
-        const int q = p / g.wo;
-        const int oh = q % g.ho;
-        const int b = q / g.ho;
-        float acc = 0.f;
-        const TI *wrow = w + (int64_t)co * taps_k;
-        for (int kh = 0; kh < g.kh; ++kh) {
-            const int ih = oh * g.sh - g.ph + kh * g.dh;
-            if (ih < 0 || ih >= g.h) continue;
-            for (int kw = 0; kw < g.kw; ++kw) {
-                const int iw = ow * g.sw - g.pw + kw * g.dw;
-                if (iw < 0 || iw >= g.w) continue;
-                const int64_t pix = ((int64_t)b * g.h + ih) * g.w + iw;
-                if (mask_in && !mask_in[pix]) continue;
-                const TI *xp = x + pix * g.c_in;
-                const TI *wp = wrow + (kh * g.kw + kw) * g.c_in;
-                for (int ci = 0; ci < g.c_in; ++ci) acc = fmaf(to_float(xp[ci]), to_float(wp[ci]), acc);
+    const int K = g.kh * g.kw * g.c_in;
+    const int co0 = blockIdx.y * CO_T;
+    const int nchunks = (K + KC - 1) / KC;
+    bool staged = false; // with a single chunk the weights are staged once for all row blocks
+
+    for (int r0 = blockIdx.x * kRowsThreads; r0 < rows; r0 += gridDim.x * kRowsThreads) {
+        const int r = r0 + tid;
+        const bool live = r < rows;
+        int p = 0, ih0 = 0, iw0 = 0, b = 0;
+        if (live) {
+            p = idx ? idx[r] : r;
+            const int ow = p % g.wo;
+            const int q = p / g.wo;
+            const int oh = q % g.ho;
+            b = q / g.ho;
+            ih0 = oh * g.sh - g.ph;
+            iw0 = ow * g.sw - g.pw;
+        }
+        float acc[CO_T];
+#pragma unroll
+        for (int j = 0; j < CO_T; ++j) acc[j] = 0.f;
+
+        // cursor over the reduction index k = (kh, kw, ci), carried across chunks
+        int kh = 0, kw = 0, ci = 0;
+        bool tap_ok = false;
+        const TI *xp = x;
+        bool new_tap = true;
+        for (int c = 0; c < nchunks; ++c) {
+            const int k0 = c * KC;
+            const int kc = K - k0 < KC ? K - k0 : KC;
+            if (!staged) {
+                __syncthreads(); // the previous chunk has been consumed
+                for (int i = tid; i < CO_T * kc; i += kRowsThreads) {
+                    const int j = i / kc, k = i - j * kc; // k fastest: contiguous global reads
+                    const int co = co0 + j;
+                    wt[k * CO_T + j] = co < g.c_out ? to_float(w[(int64_t)co * K + k0 + k]) : 0.f;
+                }
+                __syncthreads();
+                staged = nchunks == 1;
+            }
+            for (int k = 0; k < kc; ++k) {
+                if (new_tap) {
+                    const int ih = ih0 + kh * g.dh, iw = iw0 + kw * g.dw;
+                    tap_ok = live && ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
+                    if (tap_ok) {
+                        const int64_t pix = ((int64_t)b * g.h + ih) * g.w + iw;
+                        tap_ok = !mask_in || mask_in[pix] != 0;
+                        xp = x + pix * g.c_in;
+                    }
+                    new_tap = false;
+                }
+                if (tap_ok) {
+                    const float xv = to_float(xp[ci]);
+                    const float *wk = wt + k * CO_T;
+#pragma unroll
+                    for (int j = 0; j < CO_T; ++j) acc[j] = fmaf(xv, wk[j], acc[j]);
+                }
+                if (++ci == g.c_in) {
+                    ci = 0;
+                    new_tap = true;
+                    if (++kw == g.kw) {
+                        kw = 0;
+                        ++kh;
+                    }
+                }
             }
         }
-        if (bias) acc += bias[co];
-        if ((g.flags & FC_RELU) && !(acc > 0.f)) acc = (acc != acc) ? acc : 0.f;
-        from_float(acc, &out[(int64_t)p * g.c_out + co]);
+        if (live) {
+            TO *orow = out + (int64_t)p * g.c_out + co0;
+            constexpr int EPV = 16 / (int)sizeof(TO); // elements per 16-byte store
+            const bool whole_pieces = g.c_out % EPV == 0;
+#pragma unroll
+            for (int j0 = 0; j0 < CO_T; j0 += EPV) {
+                if (co0 + j0 >= g.c_out) break;
+                __align__(16) TO piece[EPV];
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    const int co = co0 + j0 + e;
+                    float v = acc[j0 + e] + ((bias && co < g.c_out) ? bias[co] : 0.f);
+                    if ((g.flags & FC_RELU) && !(v > 0.f)) v = (v != v) ? v : 0.f;
+                    from_float(v, &piece[e]);
+                }
+                if (whole_pieces) {
+                    *reinterpret_cast<uint4 *>(orow + j0) = *reinterpret_cast<const uint4 *>(piece);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e)
+                        if (co0 + j0 + e < g.c_out) orow[j0 + e] = piece[e];
+                }
+            }
+        }
     }
+}
+
+template <typename TI, typename TO, int CO_T>
+static hipError_t launch_rows(const Geom &g, const void *x, const uint8_t *mask_in, const void *w,
+                              const float *bias, const int32_t *idx, const int32_t *count, void *out,
+                              hipStream_t s)
+{
+    // grid sized for the dense row count: the kept count is only known on the device
+    const int64_t row_blocks = ((int64_t)g.m + kRowsThreads - 1) / kRowsThreads;
+    const int gx = (int)(row_blocks > 8192 ? 8192 : row_blocks);
+    const int gy = (g.c_out + CO_T - 1) / CO_T;
+    hipLaunchKernelGGL((k_conv_rows<TI, TO, CO_T>), dim3(gx, gy), dim3(kRowsThreads), 0, s, g, (const TI *)x,
+                       mask_in, (const TI *)w, bias, idx, count, (TO *)out);
+    return hipGetLastError();
 }
 
 template <typename TI, typename TO>
@@ -51,12 +143,9 @@ static hipError_t launch_t(const Geom &g, const void *x, const uint8_t *mask_in,
                            const float *bias, const int32_t *idx, const int32_t *count, void *out,
                            hipStream_t s)
 {
-    // grid sized for the dense row count: the kept count is only known on the device
-    const int64_t total = (int64_t)g.m * g.c_out;
-    int blocks = (int)((total + 255) / 256 > 32768 ? 32768 : (total + 255) / 256);
-    hipLaunchKernelGGL((k_conv_direct<TI, TO>), dim3(blocks), dim3(256), 0, s, g, (const TI *)x, mask_in,
-                       (const TI *)w, bias, idx, count, (TO *)out);
-    return hipGetLastError();
+    // wide accumulator blocks when the layer is wide enough to use them
+    if (g.c_out > 32) return launch_rows<TI, TO, 64>(g, x, mask_in, w, bias, idx, count, out, s);
+    return launch_rows<TI, TO, 16>(g, x, mask_in, w, bias, idx, count, out, s);
 }
 
 hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const void *x,

@@ -61,10 +61,20 @@ class ConvStack:
         return B.conv_desc(self.n, hi, wi, op.c_in, op.c_out, (op.k, op.k), (op.stride, op.stride),
                            (op.pad, op.pad), (1, 1), self.dtype, out_dtype, flags)
 
-    def run(self, x, mask=None, keep_outputs: bool = True, skip_zero_fill: bool = False):
+    def run(self, x, mask=None, keep_outputs: bool = True, chain: bool = False, canary=None):
         """x: device NHWC tensor; mask: device uint8 [N,H,W] or None (dense).
         Returns (outputs, masks): per-op output tensors and per-op output masks
-        (index -1 = the stack's input)."""
+        (index -1 = the stack's input).
+
+        chain: a conv whose output is read only by other convs leaves its irrelevant rows
+        unwritten (FC_SKIP_ZERO_FILL): every reader gates its taps by the same mask, so those
+        rows are never looked at (Sec. III-A: irrelevant pixels are excluded from the
+        product; Sec. III-B: the mask is the same all the way).  Outputs that a pooling
+        layer or nobody reads are still zero-filled.
+        canary: value every conv output buffer is pre-filled with (tests)."""
+        readers: Dict[int, List[str]] = {}
+        for op in self.ops:
+            readers.setdefault(op.src, []).append(op.kind)
         outs: Dict[int, object] = {-1: x}
         masks: Dict[int, object] = {-1: mask}
         plans: Dict[tuple, tuple] = {}
@@ -91,12 +101,20 @@ class ConvStack:
                     idx, count = B.active_index_compact(m_out)
                     plan = plans[key] = produced[id(m_out)] = (m_out, idx, count)
             if op.kind == "conv":
-                d = self.desc(i, flags_extra=B.SKIP_ZERO_FILL if skip_zero_fill else 0)
+                gated_readers_only = bool(readers.get(i)) and all(k == "conv" for k in readers[i])
+                skip = chain and plan is not None and gated_readers_only
+                d = self.desc(i, flags_extra=B.SKIP_ZERO_FILL if skip else 0)
+                out = None
+                if canary is not None:
+                    ho, wo = self.sizes[i]
+                    out = self.torch.full((self.n, ho, wo, op.c_out), canary, dtype=B.torch_dtype(self.dtype),
+                                          device=self.dev)
                 if plan is None:
-                    outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], workspace=self.workspace)
+                    outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], out=out,
+                                               workspace=self.workspace)
                 else:
                     outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], mask_in=m_in,
-                                               mask_out=plan[0], idx=plan[1], count=plan[2],
+                                               mask_out=plan[0], idx=plan[1], count=plan[2], out=out,
                                                workspace=self.workspace)
             else:
                 outs[i] = B.maxpool2d(src, op.k, op.stride, op.pad, self.dtype)

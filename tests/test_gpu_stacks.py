@@ -200,6 +200,40 @@ def test_resnet50_bottlenecks_small_batch():
     _check_stack(workloads.resnet50_bottlenecks(), n, h, w, 64, mask, 365)
 
 
+def test_chain_mode_never_reads_the_unwritten_rows():
+    """Convs read only by convs leave their irrelevant rows unwritten; the readers gate their
+    taps by the same mask, so every kept output is bit-identical to the zero-filled run even
+    when the unwritten rows hold NaN.  Outputs that a pool or nobody reads stay zero-filled."""
+    torch = G.torch_mod()
+    dtype = synth.BF16
+    for ops, (n, h, w, c_in), mask in (
+        (workloads.resnet50_bottlenecks()[:13], (2, 48, 64, 64), synth.mask_objects(2, 48, 64, [0.4, 0.6], 366)),
+        (workloads.vgg16()[:8], (1, 48, 64, 3), synth.mask_depth_ramp(1, 48, 64, 0.5, 367)),
+    ):
+        stack = ConvStack(ops, n, h, w, dtype, seed=368)
+        x = G.to_dev(synth.activations((n, h, w, c_in), dtype, 368, 1), dtype)
+        md = G.mask_dev(mask)
+        strict, masks = stack.run(x, md)
+        chained, _ = stack.run(x, md, chain=True, canary=float("nan"))
+        torch.cuda.synchronize()
+        readers = {}
+        for op in ops:
+            readers.setdefault(op.src, []).append(op.kind)
+        skipped = 0
+        for i, op in enumerate(ops):
+            keep = masks[i].bool()
+            a, b = strict[i], chained[i]
+            assert torch.equal(a[keep].view(torch.int16), b[keep].view(torch.int16)), op.name
+            if op.kind != "conv":
+                continue
+            if readers.get(i) and all(k == "conv" for k in readers[i]):
+                assert torch.isnan(b[~keep].float()).all(), op.name      # untouched canary
+                skipped += 1
+            else:
+                assert not b[~keep].view(torch.int16).any(), op.name     # zero-filled as usual
+        assert skipped >= 3
+
+
 # ------------------------------------------------------- graph capture ----
 
 def test_graph_replays_match_eager():
