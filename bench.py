@@ -33,7 +33,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the conv kernel on the default workload (mean of the four layers),
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the counter read for a
 # 256 MiB streaming copy (x2.00 and x1.00): profiles/k_conv_dma_resnet50_3x3_b16_48pct.md
-TRAFFIC_BYTES_PER_LAUNCH = 34.3e6
+TRAFFIC_BYTES_PER_LAUNCH = 41.5e6
 
 
 def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch):
@@ -56,7 +56,8 @@ def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch)
                  mask=torch.from_numpy(mask).to(dev), host=(x, w, bias, mask),
                  kept=int(np.count_nonzero(mask)), m=mask.size, k=9 * c)
         L["out"] = torch.empty((batch, side, side, c), dtype=torch.bfloat16, device=dev)
-        L["ws"] = torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=dev)
+        # one workspace per layer, counters cleared once: the timed calls carry FC_WORKSPACE_READY
+        L["ws"] = B.ready_workspace(torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=dev))
         L["flops_kept"] = 2.0 * L["kept"] * L["k"] * c
         L["flops_dense"] = 2.0 * L["m"] * L["k"] * c
         layers.append(L)
@@ -121,7 +122,7 @@ def sweep(torch, B, synth, workloads, args, batch):
     out["launch_floor_us"] = round(time_loop(torch, g.replay, args.steps, args.warmup) / 16 * 1e6, 2)
     layers = build_sweep_layers(torch, B, synth, workloads, 0.0, "blobs", batch)   # tensors made once
     for L in layers:
-        L["dense"] = B.PreparedConv(L["desc"], L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"])
+        L["dense"] = B.PreparedConv(L["desc"], L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"], workspace_ready=True)
 
     def timed(call):
         def fn():
@@ -141,9 +142,9 @@ def sweep(torch, B, synth, workloads, args, batch):
                 m_out = B.mask_downsample(L["mask"])
                 idx, count = B.active_index_compact(m_out)
                 d = L["desc"]
-                full = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], out=L["out"], workspace=L["ws"])
+                full = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], out=L["out"], workspace=L["ws"], workspace_ready=True)
                 conv = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=m_out, idx=idx,
-                                      count=count, out=L["out"], workspace=L["ws"])
+                                      count=count, out=L["out"], workspace=L["ws"], workspace_ready=True)
                 pts.append((float(np.count_nonzero(mask_host)) / mask_host.size, timed(conv), timed(full)))
             r = np.array([p[0] for p in pts])
             entry = {"kept_share": [round(float(v), 4) for v in r], "dense_us": round(L["dense_us"], 2)}
@@ -281,14 +282,14 @@ def main():
         L["idx"], L["count"] = B.active_index_compact(L["m_out"])
         d = L["desc"]
         L["call_focused"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], out=L["out"],
-                                           workspace=L["ws"])
-        L["call_dense"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"])
+                                           workspace=L["ws"], workspace_ready=True)
+        L["call_dense"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"], workspace_ready=True)
         L["call_conv_only"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
-                                             idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"])
+                                             idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"], workspace_ready=True)
         dk = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=B.BF16, out_dtype=B.BF16,
                          flags=B.RELU | B.SKIP_ZERO_FILL)
         L["call_kernel"] = B.PreparedConv(dk, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
-                                          idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"])
+                                          idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"], workspace_ready=True)
 
     if args.traffic_probe:
         src = torch.ones((64 << 20,), dtype=torch.int32, device="cuda:0")   # 256 MiB

@@ -62,8 +62,15 @@ typedef enum { FC_F32 = 0, FC_BF16 = 1, FC_F16 = 2 } fc_dtype;
 
 enum {
     FC_RELU = 1u,           /* max(.,0) at kept positions */
-    FC_SKIP_ZERO_FILL = 2u  /* leave irrelevant output positions untouched */
+    FC_SKIP_ZERO_FILL = 2u, /* leave irrelevant output positions untouched */
+    FC_WORKSPACE_READY = 4u /* the caller vouches that the counters at the start of `workspace` are
+                               zero: true for a workspace that was zeroed once, and from then on
+                               after every completed fc_focused_conv2d call that was given it (the
+                               library leaves them zero).  Saves the launch that clears them. */
 };
+
+/* The arrival counters of FC_WORKSPACE_READY live in this many leading bytes of the workspace. */
+enum { FC_WORKSPACE_COUNTER_BYTES = 2048 };
 
 /* One convolution layer.  in_dtype is the storage type of x and w; out_dtype is
  * in_dtype or FC_F32. */
@@ -127,7 +134,9 @@ int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, in
  *             not; otherwise optional: when given (any call, also the dense
  *             layer), layers with few tiles split their reduction over more
  *             workgroups and park fp32 partial tiles there (deterministic:
- *             partials are always added in the same order)
+ *             partials are always added in the same order).  Its first bytes
+ *             hold arrival counters that every call finds and leaves at zero;
+ *             a call clears them first unless FC_WORKSPACE_READY is set
  * `count` is read on the device only; the launch grid does not depend on it. */
 int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in,
                           const void *w, const float *bias, const uint8_t *mask_out,

@@ -14,7 +14,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfocused_conv.so")
 
 F32, BF16, F16 = 0, 1, 2
-RELU, SKIP_ZERO_FILL = 1, 2
+RELU, SKIP_ZERO_FILL, WORKSPACE_READY = 1, 2, 4
+WORKSPACE_COUNTER_BYTES = 2048
 
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
              "fc_mask_downsample", "fc_active_index_compact", "fc_focused_conv2d", "fc_maxpool2d")
@@ -182,8 +183,14 @@ class PreparedConv:
     time (so the same object works eagerly and under graph capture)."""
 
     def __init__(self, desc: ConvDesc, x, w, bias=None, mask_in=None, mask_out=None, idx=None, count=None,
-                 out=None, workspace=None):
+                 out=None, workspace=None, workspace_ready: bool = False):
+        """workspace_ready: the caller has cleared the workspace's leading counters once
+        (`ready_workspace`) and only this library writes to it since: every call is then made
+        with FC_WORKSPACE_READY and skips the launch that clears them."""
         torch = _torch()
+        if workspace_ready:
+            desc = ConvDesc.from_buffer_copy(desc)
+            desc.flags |= WORKSPACE_READY
         _require_cuda(x, w, bias, mask_in, mask_out, idx, count, out, workspace)
         ho, wo = out_dims(desc)
         if out is None:
@@ -204,6 +211,13 @@ class PreparedConv:
         if rc != 0:
             raise FcError(rc, "fc_focused_conv2d")
         return self.out
+
+
+def ready_workspace(workspace):
+    """Clears the arrival counters at the start of a workspace (a fill kernel on the current
+    stream), after which calls may carry FC_WORKSPACE_READY."""
+    workspace.view(_torch().uint8)[:WORKSPACE_COUNTER_BYTES].zero_()
+    return workspace
 
 
 def maxpool2d(x, k: int, stride: int, pad: int, dtype: int, out=None, stream=None):

@@ -23,7 +23,7 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
         return FC_ERR_SHAPE;
     if (d->in_dtype != FC_F32 && d->in_dtype != FC_BF16 && d->in_dtype != FC_F16) return FC_ERR_DTYPE;
     if (d->out_dtype != d->in_dtype && d->out_dtype != FC_F32) return FC_ERR_DTYPE;
-    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL)) return FC_ERR_DTYPE;
+    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY)) return FC_ERR_DTYPE;
     const int32_t ho = out_dim(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
     const int32_t wo = out_dim(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
     if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
@@ -39,6 +39,7 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
 
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }
 
+static_assert(kSplitGrid * sizeof(int32_t) == FC_WORKSPACE_COUNTER_BYTES, "the header promises this size");
 struct ConvWorkspace {
     size_t counters, partials, mask_out, idx, count, scan, total, split_only;
 };
@@ -191,7 +192,7 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
 
     hipError_t e;
     if (mfma) {
-        if (tile_counters && !counters_cleared) {
+        if (tile_counters && !counters_cleared && !(g.flags & FC_WORKSPACE_READY)) {
             e = launch_zero_i32(tile_counters, kSplitGrid, s);
             if (e != hipSuccess) return FC_ERR_HIP;
         }

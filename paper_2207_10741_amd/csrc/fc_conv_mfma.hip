@@ -260,7 +260,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             const int worker = (idle_only ? (my_slot - per_xcd) * 8 + xcd : (int)blockIdx.x) * (NT / 64) + wave;
             int32_t *dropped = reinterpret_cast<int32_t *>(smem_raw) + wave * 64; // per-wave list
             const int cpr = g.c_out * (int)sizeof(TO) / 16; // 16-byte pieces per row
-            uint4 *o4 = reinterpret_cast<uint4 *>(out);
+            u32x4_t *o4 = reinterpret_cast<u32x4_t *>(out);
+            const u32x4_t zero4 = {0u, 0u, 0u, 0u};
             const int ch0 = -g.ph + g.dh * ((g.kh - 1) / 2), cw0 = -g.pw + g.dw * ((g.kw - 1) / 2);
             for (int p0 = worker * 64; p0 < g.m; p0 += nworkers * 64) {
                 const int pp = p0 + lane;
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                 const int total = nd * cpr;
                 for (int c = lane; c < total; c += 64) {
                     const int rk = c / cpr, pc = c - rk * cpr;
-                    o4[(int64_t)dropped[rk] * cpr + pc] = make_uint4(0, 0, 0, 0);
+                    __builtin_nontemporal_store(zero4, o4 + (int64_t)dropped[rk] * cpr + pc);
                 }
             }
         }
@@ -774,9 +775,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             const int r = i / PPR, pc = i - r * PPR;
             const int p = row_p[r];
             const int co = co0 + pc * EPT;
+            // streaming stores: the output is not read again by this kernel
             if (p >= 0 && co < g.c_out)
-                *reinterpret_cast<uint4 *>(out + (int64_t)p * g.c_out + co) =
-                    *reinterpret_cast<const uint4 *>(Os + r * OP + pc * 16);
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(Os + r * OP + pc * 16),
+                                            reinterpret_cast<u32x4_t *>(out + (int64_t)p * g.c_out + co));
         }
     }
 
@@ -847,6 +849,20 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
         case 31: return launch_dma<DT, TO, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
         case 41: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
         case 44: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+        default: break;
+        }
+    }
+    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 1) {
+        static const int cfg1 = getenv("FC_TILE_CONFIG_1X1") ? atoi(getenv("FC_TILE_CONFIG_1X1")) : 0;
+        switch (cfg1) {
+        case 22: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
+        case 23: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
+        case 28: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
+        case 27: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
+        case 50: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 4>(FC_ARGS);
+        case 51: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 2, 5>(FC_ARGS);
+        case 52: return launch_dma<DT, TO, 256, 64, 4, 1, TAPC, 2, 2>(FC_ARGS);
+        case 53: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 3>(FC_ARGS);
         default: break;
         }
     }

@@ -324,9 +324,74 @@ __global__ __launch_bounds__(256) void k_maxpool(const T *__restrict__ x, int n,
     }
 }
 
+// 16-bit types, channel count a multiple of 8: one lane owns 8 consecutive channels of an
+// output position (16-byte loads and one 16-byte store).
+template <typename T>
+__global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int n, int h, int w, int c, int k,
+                                                    int stride, int pad, int ho, int wo, T *__restrict__ out)
+{
+    const int cg = c / 8;
+    const int64_t total = (int64_t)n * ho * wo * cg;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int g8 = (int)(i % cg);
+        int64_t t = i / cg;
+        const int ow = (int)(t % wo);
+        t /= wo;
+        const int oh = (int)(t % ho);
+        const int b = (int)(t / ho);
+        bool have = false;
+        float best[8];
+        uint16_t raw[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            best[e] = 0.f;
+            raw[e] = 0;
+        }
+        for (int a = 0; a < k; ++a) {
+            const int ih = oh * stride - pad + a;
+            if (ih < 0 || ih >= h) continue;
+            for (int q = 0; q < k; ++q) {
+                const int iw = ow * stride - pad + q;
+                if (iw < 0 || iw >= w) continue;
+                const uint4 v = *reinterpret_cast<const uint4 *>(x + (((int64_t)b * h + ih) * w + iw) * c + g8 * 8);
+                const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    T one;
+                    one.bits = (uint16_t)(wd[e >> 1] >> (16 * (e & 1)));
+                    const float f = to_float(one);
+                    if (!have || f > best[e]) {
+                        best[e] = f;
+                        raw[e] = one.bits;
+                    }
+                }
+                have = true;
+            }
+        }
+        uint4 o;
+        o.x = raw[0] | ((uint32_t)raw[1] << 16);
+        o.y = raw[2] | ((uint32_t)raw[3] << 16);
+        o.z = raw[4] | ((uint32_t)raw[5] << 16);
+        o.w = raw[6] | ((uint32_t)raw[7] << 16);
+        *reinterpret_cast<uint4 *>(out + i * 8) = o;
+    }
+}
+
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride, int pad,
                           int ho, int wo, void *out, hipStream_t s)
 {
+    if (dtype != FC_F32 && c % 8 == 0) {
+        const int64_t total8 = (int64_t)n * ho * wo * (c / 8);
+        const int blocks8 = (int)((total8 + 255) / 256 > 65536 ? 65536 : (total8 + 255) / 256);
+        if (dtype == FC_BF16)
+            hipLaunchKernelGGL(k_maxpool_x8<bf16_t>, dim3(blocks8), dim3(256), 0, s, (const bf16_t *)x, n, h, w, c, k,
+                               stride, pad, ho, wo, (bf16_t *)out);
+        else
+            hipLaunchKernelGGL(k_maxpool_x8<f16_t>, dim3(blocks8), dim3(256), 0, s, (const f16_t *)x, n, h, w, c, k,
+                               stride, pad, ho, wo, (f16_t *)out);
+        return hipGetLastError();
+    }
     const int64_t total = (int64_t)n * ho * wo * c;
     int blocks = (int)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
     if (dtype == FC_F32)

@@ -46,6 +46,9 @@ class ConvStack:
         # split their reduction over more workgroups
         need = max(B.workspace_bytes(self.desc(i)) for i, op in enumerate(self.ops) if op.kind == "conv")
         self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.dev)
+        # its arrival counters are cleared once here; every library call leaves them at zero,
+        # so the calls carry FC_WORKSPACE_READY and none of them launches a clear
+        B.ready_workspace(self.workspace)
 
     def _to_dev(self, storage: np.ndarray):
         torch = self.torch
@@ -103,7 +106,7 @@ class ConvStack:
             if op.kind == "conv":
                 gated_readers_only = bool(readers.get(i)) and all(k == "conv" for k in readers[i])
                 skip = chain and plan is not None and gated_readers_only
-                d = self.desc(i, flags_extra=B.SKIP_ZERO_FILL if skip else 0)
+                d = self.desc(i, flags_extra=B.WORKSPACE_READY | (B.SKIP_ZERO_FILL if skip else 0))
                 out = None
                 if canary is not None:
                     ho, wo = self.sizes[i]

@@ -243,6 +243,32 @@ def test_skip_zero_fill_leaves_irrelevant_rows_untouched_and_guard_bytes_intact(
         assert np.abs(o[keep] - want[keep]).max() <= TOL_16BIT_OUT * np.sqrt(np.mean(want[keep] ** 2))
 
 
+def test_workspace_ready_flag_skips_the_clear_and_leaves_the_counters_zero():
+    """A layer small enough to split its reduction: with the counters cleared once and
+    FC_WORKSPACE_READY on every call, repeated calls (dense and masked, sharing the workspace)
+    reproduce the result of the ordinary call bit for bit, and the counters read zero after."""
+    torch = G.torch_mod()
+    n, h, w, c = 1, 20, 24, 256
+    x = G.to_dev(synth.activations((n, h, w, c), synth.BF16, 209, 1), synth.BF16)
+    wt = G.to_dev(synth.he_weights(c, 3, 3, c, synth.BF16, 209, 2), synth.BF16)
+    md = G.mask_dev(synth.mask_objects(n, h, w, 0.4, 209, 4))
+    m_out = B.mask_downsample(md)
+    idx, count = B.active_index_compact(m_out)
+    plain = B.conv_desc(n, h, w, c, c, in_dtype=B.BF16, out_dtype=B.F32)
+    ws = torch.empty((B.workspace_bytes(plain),), dtype=torch.uint8, device=G.dev())
+    ws.fill_(0xAB)                                            # garbage an ordinary call must cope with
+    want_masked = B.focused_conv2d(plain, x, wt, mask_in=md, mask_out=m_out, idx=idx, count=count, workspace=ws)
+    want_dense = B.focused_conv2d(plain, x, wt, workspace=ws)
+    B.ready_workspace(ws)
+    masked = B.PreparedConv(plain, x, wt, mask_in=md, mask_out=m_out, idx=idx, count=count, workspace=ws,
+                            workspace_ready=True)
+    dense = B.PreparedConv(plain, x, wt, workspace=ws, workspace_ready=True)
+    for _ in range(3):
+        assert torch.equal(masked().clone(), want_masked)
+        assert torch.equal(dense().clone(), want_dense)
+        assert not ws[:B.WORKSPACE_COUNTER_BYTES].any()
+
+
 def test_two_runs_are_bit_identical():
     torch = G.torch_mod()
     a, _, _ = _run_layer(2, 28, 28, 128, 128, 3, 1, 1, 1, synth.BF16, seed=208)
@@ -258,3 +284,11 @@ def test_maxpool_helper():
         got = B.maxpool2d(xd, k, s, p, B.F32).cpu()
         ref = torch.nn.functional.max_pool2d(torch.from_numpy(x).permute(0, 3, 1, 2), k, s, p).permute(0, 2, 3, 1)
         assert torch.equal(got, ref.contiguous())
+    # 16-bit storage: channel counts on and off the 8-channel vector path, negative values too
+    for dtype, c in ((synth.BF16, 24), (synth.F16, 64), (synth.BF16, 20)):
+        bits = synth.to_storage(synth.from_storage(synth.activations((2, 13, 17, c), synth.F32, 210, c), synth.F32) - 0.7, dtype)
+        xd = G.to_dev(bits, dtype)
+        for (k, s, p) in ((2, 2, 0), (3, 2, 1)):
+            got = B.maxpool2d(xd, k, s, p, dtype)
+            ref = torch.nn.functional.max_pool2d(xd.float().permute(0, 3, 1, 2), k, s, p).permute(0, 2, 3, 1)
+            assert torch.equal(got.float(), ref.contiguous())

@@ -10,6 +10,7 @@ from paper_2207_10741_amd import binding as B
 from oracle import fc_oracle as O
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER_TEXT = open(os.path.join(ROOT, "include", "focused_conv.h")).read()
 
 
 def _declared():
@@ -53,6 +54,8 @@ def test_descriptor_errors():
     assert rc(in_dtype=7) == -3
     assert rc(in_dtype=B.F32, out_dtype=B.BF16) == -3     # output narrower than the input type
     assert rc(flags=64) == -3
+    assert rc(flags=B.RELU | B.SKIP_ZERO_FILL | B.WORKSPACE_READY) == 0
+    assert B.WORKSPACE_COUNTER_BYTES == int(re.search(r"FC_WORKSPACE_COUNTER_BYTES\s*=\s*(\d+)", HEADER_TEXT).group(1))
     assert rc(n=40000, h=1000, w=1000, k=(1, 1), pad=(0, 0)) == -6
     assert B.lib().fc_out_dims(None, None, None) == -1
 
