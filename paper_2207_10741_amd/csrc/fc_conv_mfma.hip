@@ -322,9 +322,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             row_hw[tid] = hw;
             row_bits[tid] = 0;
         }
+        // the bias is only needed by the epilogue: fetch it now, park it in LDS after the loop
+        float bias_v = 0.f;
         if (tid < TN) {
             const int co = co0 + tid;
-            bias_s[tid] = (bias && co < g.c_out) ? bias[co] : 0.f;
+            bias_v = (bias && co < g.c_out) ? bias[co] : 0.f;
         }
         __syncthreads();
         bool use_halo = false;
@@ -695,6 +697,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         // ---- epilogue: bias, ReLU, one rounding; the tile is transposed through LDS so that
         // every lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
         wait_vmcnt<0>();
+        if (tid < TN) bias_s[tid] = bias_v;
         __syncthreads();
         if (S > 1) {
             // Park this unit's fp32 partial tile (accumulator order, coalesced), then count
@@ -771,14 +774,27 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         __syncthreads();
         constexpr int PPR = TN * (int)sizeof(TO) / 16;
         constexpr int EPT = 16 / (int)sizeof(TO);
-        for (int i = tid; i < TM * PPR; i += NT) {
-            const int r = i / PPR, pc = i - r * PPR;
-            const int p = row_p[r];
+        // a thread keeps its 16-byte column and walks down the rows; all LDS reads of the walk
+        // are issued before the first store
+        constexpr int RPI = NT / PPR;   // rows per pass of the workgroup
+        constexpr int NPASS = TM / RPI;
+        static_assert(NT % PPR == 0 && TM % RPI == 0, "store walk");
+        {
+            const int pc = tid % PPR, r0 = tid / PPR;
             const int co = co0 + pc * EPT;
+            int pp[NPASS];
+            u32x4_t pv[NPASS];
+#pragma unroll
+            for (int k = 0; k < NPASS; ++k) {
+                const int r = r0 + k * RPI;
+                pp[k] = row_p[r];
+                pv[k] = *reinterpret_cast<const u32x4_t *>(Os + r * OP + pc * 16);
+            }
             // streaming stores: the output is not read again by this kernel
-            if (p >= 0 && co < g.c_out)
-                __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(Os + r * OP + pc * 16),
-                                            reinterpret_cast<u32x4_t *>(out + (int64_t)p * g.c_out + co));
+#pragma unroll
+            for (int k = 0; k < NPASS; ++k)
+                if (pp[k] >= 0 && co < g.c_out)
+                    __builtin_nontemporal_store(pv[k], reinterpret_cast<u32x4_t *>(out + (int64_t)pp[k] * g.c_out + co));
         }
     }
 
@@ -849,6 +865,8 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
         case 31: return launch_dma<DT, TO, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
         case 41: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
         case 44: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+        case 45: return launch_dma<DT, TO, 256, 128, 4, 2, TAPC, 2, 2, 320, 3>(FC_ARGS);
+        case 46: return launch_dma<DT, TO, 256, 128, 4, 2, TAPC, 2, 2, 320, 2>(FC_ARGS);
         default: break;
         }
     }

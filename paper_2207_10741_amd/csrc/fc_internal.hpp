@@ -78,15 +78,19 @@ static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, in
     return g;
 }
 
-// inclusive prefix sum over the 64 lanes of a wave
+// inclusive prefix sum over the 64 lanes of a wave, on the cross-lane data path of the
+// vector ALU (no LDS traffic): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last
+// lane of row 0 / row 2 is broadcast into row 1 / row 3, then lane 31 into rows 2 and 3.
 __device__ __forceinline__ int wave_inclusive_scan(int v)
 {
-    const int lane = __lane_id();
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        int t = __shfl_up(v, d, 64);
-        if (lane >= d) v += t;
-    }
+    // row_shr:n = 0x110 + n (a lane with no source inside its row adds 0)
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+    // row_bcast:15 into rows 1 and 3 (row mask 0b1010), row_bcast:31 into rows 2 and 3 (0b1100)
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
     return v;
 }
 
