@@ -153,7 +153,7 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     if (!x || !w || !out) return FC_ERR_NULL;
     if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
     if (!mask_in && (idx || mask_out)) return FC_ERR_NULL; // a kept list without the mask that gates the taps
-    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(idx)) return FC_ERR_ALIGN;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(idx) || !aligned16(bias)) return FC_ERR_ALIGN;
     if (x == out) return FC_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
 

@@ -93,6 +93,16 @@ __device__ __forceinline__ void store4(TO *dst, float a, float b, float c, float
 // max(v, 0) that keeps NaN (and -0) as the reference does
 __device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.f ? 0.f : v; }
 
+// ReLU of two packed 16-bit floats (bf16 or f16): a value with the sign bit set becomes +0.
+// (-0 becomes +0, and a NaN with the sign bit set becomes 0: neither is a value the
+// accumulation produces from finite inputs.)
+typedef short i16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t relu_packed16(uint32_t two)
+{
+    const i16x2_t zero = {0, 0};
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2_t, two), zero));
+}
+
 // Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
 // plain byte offsets and anything at or beyond `bytes` reads as zero.
 __device__ __forceinline__ u32x4_t make_rsrc_words(const void *p, uint32_t bytes)
@@ -136,7 +146,7 @@ template <int TM, int TN, int NB, int SL, int NBW>
 constexpr size_t dma_lds_bytes()
 {
     return dma_stage_region_bytes<TM, TN, NB, SL, NBW>() + (size_t)TM * 5 * sizeof(int32_t) +
-           (size_t)TN * sizeof(float) + (SL > 0 ? (size_t)(TM + 3 * SL + 8) * sizeof(int32_t) : 0);
+           (SL > 0 ? (size_t)(TM + 3 * SL + 8) * sizeof(int32_t) : 0);
 }
 
 // DT: storage type of x and w; TO: float or a 16-bit carrier; TM x TN: workgroup tile
@@ -188,8 +198,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     unsigned char *stage0 = smem_raw;                                   // [NB][TM + TN][128]
-    float *bias_s = reinterpret_cast<float *>(smem_raw + REGION);
-    int32_t *row_p = reinterpret_cast<int32_t *>(bias_s + TN);
+    int32_t *row_p = reinterpret_cast<int32_t *>(smem_raw + REGION);
     int32_t *row_base = row_p + TM;
     int32_t *row_img = row_base + TM;
     int32_t *row_hw = row_img + TM;
@@ -322,12 +331,18 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             row_hw[tid] = hw;
             row_bits[tid] = 0;
         }
-        // the bias is only needed by the epilogue: fetch it now, park it in LDS after the loop
-        float bias_v = 0.f;
-        if (tid < TN) {
-            const int co = co0 + tid;
-            bias_v = (bias && co < g.c_out) ? bias[co] : 0.f;
-        }
+        // The accumulators start from the bias (in the first K-split only), so the epilogue has
+        // nothing to add: every lane fetches the bias of its own channels now and the loads
+        // are long back when the set-up is done.
+        float4 bias_q[CB][4];
+#pragma unroll
+        for (int b = 0; b < CB; ++b)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int co = co0 + wave_n * WTN + b * 32 + q * 8 + (lane >> 5) * 4;
+                bias_q[b][q] = (bias && split == 0 && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
+                                                                    : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
         __syncthreads();
         bool use_halo = false;
         int ns = 0; // slots on this tile's pixel line
@@ -456,7 +471,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
             for (int b = 0; b < CB; ++b)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+                for (int q = 0; q < 4; ++q) {
+                    acc[a][b][q * 4 + 0] = bias_q[b][q].x;
+                    acc[a][b][q * 4 + 1] = bias_q[b][q].y;
+                    acc[a][b][q * 4 + 2] = bias_q[b][q].z;
+                    acc[a][b][q * 4 + 3] = bias_q[b][q].w;
+                }
 
         if (HALO && use_halo) {
             // ---------------- shared-halo loop ----------------
@@ -697,7 +717,6 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         // ---- epilogue: bias, ReLU, one rounding; the tile is transposed through LDS so that
         // every lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
         wait_vmcnt<0>();
-        if (tid < TN) bias_s[tid] = bias_v;
         __syncthreads();
         if (S > 1) {
             // Park this unit's fp32 partial tile (accumulator order, coalesced), then count
@@ -761,14 +780,25 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int cl = wave_n * WTN + b * 32 + q * 8 + (lane >> 5) * 4;
-                    const float4 bv = *reinterpret_cast<const float4 *>(bias_s + cl);
-                    float v0 = acc[a][b][q * 4 + 0] + bv.x, v1 = acc[a][b][q * 4 + 1] + bv.y;
-                    float v2 = acc[a][b][q * 4 + 2] + bv.z, v3 = acc[a][b][q * 4 + 3] + bv.w;
-                    if (g.flags & FC_RELU) {
-                        v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
-                        v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
+                    float v0 = acc[a][b][q * 4 + 0], v1 = acc[a][b][q * 4 + 1];
+                    float v2 = acc[a][b][q * 4 + 2], v3 = acc[a][b][q * 4 + 3];
+                    if constexpr (sizeof(TO) == 4) {
+                        if (g.flags & FC_RELU) {
+                            v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
+                            v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
+                        }
+                        store4<DT, TO>(reinterpret_cast<TO *>(Os + r * OP) + cl, v0, v1, v2, v3);
+                    } else {
+                        // 16-bit outputs: round first, then clear the values whose sign bit is set, two
+                        // at a time (rounding keeps the sign, so this is max(., 0) of the rounded value)
+                        uint2 pk;
+                        store4<DT, TO>(reinterpret_cast<TO *>(&pk), v0, v1, v2, v3);
+                        if (g.flags & FC_RELU) {
+                            pk.x = relu_packed16(pk.x);
+                            pk.y = relu_packed16(pk.y);
+                        }
+                        *reinterpret_cast<uint2 *>(Os + r * OP + cl * 2) = pk;
                     }
-                    store4<DT, TO>(reinterpret_cast<TO *>(Os + r * OP) + cl, v0, v1, v2, v3);
                 }
         }
         __syncthreads();
