@@ -223,6 +223,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     const int kwid = TAPC == 32 ? g.kw : (TAPC == 9 ? 3 : 1);
     const int cchunks = (g.c_in + kTK - 1) / kTK;
     const int stages = taps * cchunks;
+    const bool self_tap = TAPC == 1 && g.ph == 0 && g.pw == 0;
     const u32x4_t rsrc_x = make_rsrc_words(x, (uint32_t)g.n * g.h * g.w * g.c_in * 2u);
     const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * taps * g.c_in * 2u);
 
@@ -329,7 +330,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             row_base[tid] = base;
             row_img[tid] = b;
             row_hw[tid] = hw;
-            row_bits[tid] = 0;
+            // an unpadded 1x1 kernel reads exactly the pixel that decided to keep the position:
+            // inside the image and relevant by construction, nothing to look up
+            row_bits[tid] = (self_tap && p >= 0) ? 1u : 0u;
         }
         // The accumulators start from the bias (in the first K-split only), so the epilogue has
         // nothing to add: every lane fetches the bias of its own channels now and the loads
@@ -425,7 +428,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         // set-up B: one thread per (row, tap) decides "inside the image and relevant" (for a
         // masked layer it fetches the mask byte under the tap; all of a thread's bytes are in
         // flight together)
-        for (int i0 = 0; i0 < (use_halo ? 0 : PAIR_IT); i0 += PAIR_CH) {
+        for (int i0 = 0; i0 < ((use_halo || self_tap) ? 0 : PAIR_IT); i0 += PAIR_CH) {
             int prow_[PAIR_CH], ptap_[PAIR_CH], ppix_[PAIR_CH];
             bool pin_[PAIR_CH];
 #pragma unroll
