@@ -201,7 +201,10 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
                              partials, tile_counters, s);
         if (e != hipSuccess) return FC_ERR_HIP;
     } else {
-        e = launch_conv_direct(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s);
+        if (conv_stem_supported(g, desc->in_dtype, desc->out_dtype))
+            e = launch_conv_stem(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s);
+        else
+            e = launch_conv_direct(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s);
         if (e != hipSuccess) return FC_ERR_HIP;
         if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL)) {
             e = launch_zero_fill(g, mask_in, mask_out, out, desc->out_dtype, s);

@@ -118,6 +118,13 @@ hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const 
                               const uint8_t *mask_in, const void *w, const float *bias,
                               const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
+// Matrix-core path for layers with at most 4 input channels (RGB stems); the caller clears the
+// irrelevant rows with launch_zero_fill.
+bool conv_stem_supported(const Geom &g, int in_dtype, int out_dtype);
+hipError_t launch_conv_stem(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
+                            const void *w, const float *bias, const int32_t *idx, const int32_t *count,
+                            void *out, hipStream_t s);
+
 // Split-K scratch of the matrix-core path (optional): fp32 partial tiles and one counter
 // per tile.  Only layers with few tiles use it; for the others the sizes are zero.
 constexpr int kSplitGrid = 512;                          // workgroups launched when split-K may run

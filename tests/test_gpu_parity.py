@@ -199,6 +199,36 @@ def test_shared_halo_precomputed_list_and_16bit_output(layer):
     assert G.rel_err(G.to_f64(a), want, keep) <= TOL_F32_OUT
 
 
+# layers with at most 4 input channels run on the matrix cores through an element-wise gather
+STEM_LAYERS = [
+    # n, h, w, ci, co, k, s, p, d
+    (2, 37, 53, 3, 64, 3, 1, 1, 1),
+    (1, 64, 48, 3, 64, 7, 2, 3, 1),
+    (1, 33, 29, 1, 72, 5, 1, 2, 1),             # one channel, 25 taps, a partial channel tile
+    (2, 31, 40, 4, 16, 3, (2, 1), (2, 0), (2, 1)),
+    (1, 300, 200, 3, 128, 3, 1, 1, 1),          # many tiles per workgroup, two channel tiles
+]
+
+
+@pytest.mark.parametrize("layer", STEM_LAYERS)
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", None])
+def test_stem_layers_match_oracle(layer, mask_kind):
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=0.45, seed=211)
+    assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()
+
+
+def test_stem_16bit_output_and_precomputed_list():
+    torch = G.torch_mod()
+    layer = STEM_LAYERS[0]
+    a, want, keep = _run_layer(*layer, synth.F16, seed=212)
+    b, _, _ = _run_layer(*layer, synth.F16, seed=212, precomputed=True)
+    assert torch.equal(a, b)
+    c, _, _ = _run_layer(*layer, synth.F16, seed=212, out_dtype=synth.F16)
+    assert torch.equal(c, a.to(c.dtype))
+    assert G.rel_err(G.to_f64(a), want, keep) <= TOL_F32_OUT
+
+
 def test_dense_path_is_standard_convolution():
     out, want, keep = _run_layer(2, 21, 27, 64, 128, 3, 1, 1, 1, synth.BF16, mask_kind=None, seed=205)
     assert keep.all() and G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
