@@ -26,12 +26,15 @@
 //
 // The weights are the MFMA's A operand (rows = output channel) and the gathered
 // activations its B operand (columns = position), so a lane's accumulators hold 4
-// consecutive output channels of one position.  The epilogue adds bias, applies ReLU,
-// rounds once to the output type, transposes the tile through LDS and stores each
-// kept row as whole 16-byte pieces; the same kernel then clears the irrelevant rows.
+// consecutive output channels of one position.  The accumulators start from the bias;
+// the epilogue rounds once to the output type, applies ReLU, transposes the tile
+// through LDS and stores each kept row as whole 16-byte pieces.  The same kernel clears
+// the irrelevant rows (the workgroups that have no tile do it).
 //
 // The launch grid never depends on the kept count: workgroups stride over the tiles
-// and read the count on the device.
+// and read the count on the device.  Layers with few tiles split every tile's reduction
+// over several workgroups, which meet through fp32 partial tiles in the workspace; the
+// one that arrives last adds them in a fixed order and writes the tile.
 #include "fc_mfma_util.hpp"
 #include <cstdlib>
 
@@ -662,8 +665,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #undef FC_PREPARE_STAGE
         } // tap-by-tap loop
 
-        // ---- epilogue: bias, ReLU, one rounding; the tile is transposed through LDS so that
-        // every lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
+        // ---- epilogue: one rounding, ReLU; the tile is transposed through LDS so that every
+        // lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
         wait_vmcnt<0>();
         __syncthreads();
         if (S > 1) {
