@@ -117,6 +117,29 @@ int32_t fc_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t
 int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* Mask pyramid (Sec. III-B: one mask per image, rescaled to every layer's size).  Builds, for
+ * `levels` successive resolution changes, the mask and the kept-position list of every level
+ * from the input mask in two launches.  steps[l] is the window (kernel, stride, padding,
+ * dilation) of the layer that takes level l - 1 (the input mask for l = 0) to level l; level l
+ * equals fc_mask_downsample of level l - 1 with that window, and its list equals
+ * fc_active_index_compact of it (bit for bit).
+ *   mask_in   device, [n][h][w] bytes, read only
+ *   mask_out  host array of `levels` device pointers, [n][h_l][w_l] bytes each, overwritten
+ *   idx,count host arrays of `levels` device pointers (capacity n*h_l*w_l int32; one int32)
+ *   workspace device, >= fc_mask_pyramid_workspace_bytes
+ * fc_mask_pyramid_dims gives h_l, w_l (host only). */
+#define FC_MAX_PYRAMID_LEVELS 8
+typedef struct fc_mask_step {
+    int32_t kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} fc_mask_step;
+int32_t fc_mask_pyramid_dims(int32_t h, int32_t w, int32_t levels, const fc_mask_step *steps,
+                             int32_t *hs, int32_t *ws);
+int32_t fc_mask_pyramid_workspace_bytes(int32_t n, int32_t h, int32_t w, int32_t levels,
+                                        const fc_mask_step *steps, size_t *bytes);
+int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t levels,
+                        const fc_mask_step *steps, uint8_t *const *mask_out, int32_t *const *idx,
+                        int32_t *const *count, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The layer (Sec. III-A).  Gathers the receptive fields of the kept positions
  * (implicit im2col), multiplies by the unchanged weights on the matrix cores,
  * adds bias, applies ReLU if asked, writes each kept row, zero-fills the rest.

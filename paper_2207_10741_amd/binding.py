@@ -18,7 +18,9 @@ RELU, SKIP_ZERO_FILL, WORKSPACE_READY = 1, 2, 4
 WORKSPACE_COUNTER_BYTES = 2048
 
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
-             "fc_mask_downsample", "fc_active_index_compact", "fc_focused_conv2d", "fc_maxpool2d")
+             "fc_mask_downsample", "fc_active_index_compact", "fc_mask_pyramid_dims",
+             "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_maxpool2d")
+MAX_PYRAMID_LEVELS = 8
 
 
 class FcError(RuntimeError):
@@ -32,6 +34,11 @@ class ConvDesc(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int32) for k in (
         "n", "h", "w", "c_in", "c_out", "kh", "kw", "stride_h", "stride_w",
         "pad_h", "pad_w", "dil_h", "dil_w", "in_dtype", "out_dtype")] + [("flags", ctypes.c_uint32)]
+
+
+class MaskStep(ctypes.Structure):
+    """Mirror of fc_mask_step: the window that takes one pyramid level to the next."""
+    _fields_ = [(k, ctypes.c_int32) for k in ("kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w")]
 
 
 def conv_desc(n, h, w, c_in, c_out, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1),
@@ -65,6 +72,15 @@ def lib():
         L.fc_mask_downsample.argtypes = [vp] + [i32] * 11 + [vp, vp]
         L.fc_active_index_compact.restype = i32
         L.fc_active_index_compact.argtypes = [vp, i64, vp, vp, vp, ctypes.c_size_t, vp]
+        L.fc_mask_pyramid_dims.restype = i32
+        L.fc_mask_pyramid_dims.argtypes = [i32, i32, i32, ctypes.POINTER(MaskStep), ctypes.POINTER(i32),
+                                           ctypes.POINTER(i32)]
+        L.fc_mask_pyramid_workspace_bytes.restype = i32
+        L.fc_mask_pyramid_workspace_bytes.argtypes = [i32, i32, i32, i32, ctypes.POINTER(MaskStep),
+                                                      ctypes.POINTER(ctypes.c_size_t)]
+        L.fc_mask_pyramid.restype = i32
+        L.fc_mask_pyramid.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(MaskStep), ctypes.POINTER(vp),
+                                      ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
         L.fc_focused_conv2d.restype = i32
         L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_maxpool2d.restype = i32
@@ -140,6 +156,55 @@ def mask_downsample(mask_in, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1), ou
     _check(lib().fc_mask_downsample(_ptr(mask_in), n, h, w, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
                                     dil[0], dil[1], _ptr(out), _stream(stream)), "fc_mask_downsample")
     return out
+
+
+def _steps_array(steps):
+    arr = (MaskStep * len(steps))()
+    for i, (k, stride, pad, dil) in enumerate(steps):
+        arr[i] = MaskStep(k[0], k[1], stride[0], stride[1], pad[0], pad[1], dil[0], dil[1])
+    return arr
+
+
+def mask_pyramid_dims(h: int, w: int, steps):
+    """fc_mask_pyramid_dims: [(h_l, w_l)] for steps = [(k, stride, pad, dil), ...] (pairs each)."""
+    arr = _steps_array(steps)
+    hs, ws = (ctypes.c_int32 * len(steps))(), (ctypes.c_int32 * len(steps))()
+    _check(lib().fc_mask_pyramid_dims(h, w, len(steps), arr, hs, ws), "fc_mask_pyramid_dims")
+    return [(int(a), int(b)) for a, b in zip(hs, ws)]
+
+
+class PreparedPyramid:
+    """fc_mask_pyramid with its arguments marshalled once: all levels' masks and kept lists from
+    one input mask.  `levels` holds (mask_out, idx, count) per level."""
+
+    def __init__(self, mask_in, steps):
+        torch = _torch()
+        _require_cuda(mask_in)
+        n, h, w = mask_in.shape
+        self._steps = _steps_array(steps)
+        dims = mask_pyramid_dims(h, w, steps)
+        dev = mask_in.device
+        self.levels = [(torch.empty((n, hl, wl), dtype=torch.uint8, device=dev),
+                        torch.empty((n * hl * wl,), dtype=torch.int32, device=dev),
+                        torch.empty((1,), dtype=torch.int32, device=dev)) for hl, wl in dims]
+        b = ctypes.c_size_t()
+        _check(lib().fc_mask_pyramid_workspace_bytes(n, h, w, len(steps), self._steps, ctypes.byref(b)),
+               "fc_mask_pyramid_workspace_bytes")
+        self._ws = torch.empty((max(int(b.value), 16),), dtype=torch.uint8, device=dev)
+        vp = ctypes.c_void_p
+        nl = len(steps)
+        self._ptrs = tuple((vp * nl)(*[_ptr(lv[i]) for lv in self.levels]) for i in range(3))
+        self._args = (_ptr(mask_in), n, h, w, nl, self._steps, *self._ptrs, _ptr(self._ws), self._ws.numel())
+        self._keep = mask_in
+        self._fn = lib().fc_mask_pyramid
+        self._current_stream = torch.cuda.current_stream
+
+    def __call__(self, stream=None):
+        hnd = (self._current_stream() if stream is None else stream).cuda_stream
+        rc = self._fn(*self._args, ctypes.c_void_p(hnd))
+        if rc != 0:
+            raise FcError(rc, "fc_mask_pyramid")
+        return self.levels
 
 
 def active_index_compact(mask, idx=None, count=None, workspace=None, stream=None):

@@ -214,6 +214,91 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     return FC_OK;
 }
 
+// Fills the geometry part of the pyramid arguments; returns an fc_status.
+static int32_t pyramid_geometry(int32_t n, int32_t h, int32_t w, int32_t levels, const fc_mask_step *steps,
+                                PyramidArgs *a)
+{
+    if (!steps) return FC_ERR_NULL;
+    if (n <= 0 || h <= 0 || w <= 0 || levels <= 0 || levels > kMaxPyramidLevels) return FC_ERR_SHAPE;
+    if ((int64_t)n * h * w >= INT32_MAX) return FC_ERR_RANGE;
+    a->levels = levels;
+    a->n = n;
+    a->h[0] = h;
+    a->w[0] = w;
+    int64_t blocks = 0;
+    for (int l = 0; l < levels; ++l) {
+        const fc_mask_step &t = steps[l];
+        if (t.kh <= 0 || t.kw <= 0 || t.stride_h <= 0 || t.stride_w <= 0 || t.pad_h < 0 || t.pad_w < 0 ||
+            t.dil_h <= 0 || t.dil_w <= 0)
+            return FC_ERR_SHAPE;
+        const int32_t ho = out_dim(a->h[l], t.kh, t.stride_h, t.pad_h, t.dil_h);
+        const int32_t wo = out_dim(a->w[l], t.kw, t.stride_w, t.pad_w, t.dil_w);
+        if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
+        a->h[l + 1] = ho;
+        a->w[l + 1] = wo;
+        a->sh[l] = t.stride_h;
+        a->sw[l] = t.stride_w;
+        a->ch0[l] = -t.pad_h + t.dil_h * ((t.kh - 1) / 2);
+        a->cw0[l] = -t.pad_w + t.dil_w * ((t.kw - 1) / 2);
+        a->m[l] = (int64_t)n * ho * wo;
+        if (a->m[l] >= INT32_MAX) return FC_ERR_RANGE;
+        a->block0[l] = (int32_t)blocks;
+        blocks += compact_blocks(a->m[l]);
+    }
+    if (blocks >= INT32_MAX) return FC_ERR_RANGE;
+    a->block0[levels] = (int32_t)blocks;
+    a->identity0 = (a->sh[0] == 1 && a->sw[0] == 1 && a->ch0[0] == 0 && a->cw0[0] == 0 && a->h[1] == h && a->w[1] == w) ? 1 : 0;
+    return FC_OK;
+}
+
+int32_t fc_mask_pyramid_dims(int32_t h, int32_t w, int32_t levels, const fc_mask_step *steps, int32_t *hs,
+                             int32_t *ws)
+{
+    if (!hs || !ws) return FC_ERR_NULL;
+    PyramidArgs a;
+    const int32_t rc = pyramid_geometry(1, h, w, levels, steps, &a);
+    if (rc != FC_OK) return rc;
+    for (int l = 0; l < levels; ++l) {
+        hs[l] = a.h[l + 1];
+        ws[l] = a.w[l + 1];
+    }
+    return FC_OK;
+}
+
+int32_t fc_mask_pyramid_workspace_bytes(int32_t n, int32_t h, int32_t w, int32_t levels,
+                                        const fc_mask_step *steps, size_t *bytes)
+{
+    if (!bytes) return FC_ERR_NULL;
+    PyramidArgs a;
+    const int32_t rc = pyramid_geometry(n, h, w, levels, steps, &a);
+    if (rc != FC_OK) return rc;
+    *bytes = align_up((size_t)a.block0[levels] * sizeof(int32_t), 256);
+    return FC_OK;
+}
+
+int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t levels,
+                        const fc_mask_step *steps, uint8_t *const *mask_out, int32_t *const *idx,
+                        int32_t *const *count, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!mask_in || !mask_out || !idx || !count) return FC_ERR_NULL;
+    PyramidArgs a;
+    const int32_t rc = pyramid_geometry(n, h, w, levels, steps, &a);
+    if (rc != FC_OK) return rc;
+    for (int l = 0; l < levels; ++l) {
+        if (!mask_out[l] || !idx[l] || !count[l]) return FC_ERR_NULL;
+        if (!aligned16(mask_out[l]) || !aligned16(idx[l])) return FC_ERR_ALIGN;
+        a.mask_out[l] = mask_out[l];
+        a.idx[l] = idx[l];
+        a.count[l] = count[l];
+    }
+    if (!aligned16(mask_in)) a.identity0 = 0;
+    const size_t need = align_up((size_t)a.block0[levels] * sizeof(int32_t), 256);
+    if (!workspace || workspace_bytes < need) return FC_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FC_ERR_ALIGN;
+    const hipError_t e = launch_mask_pyramid(a, mask_in, (int32_t *)workspace, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
 int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,
                      int32_t stride, int32_t pad, void *out, void *stream)
 {

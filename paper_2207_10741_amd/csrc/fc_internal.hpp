@@ -108,6 +108,21 @@ struct CompactExtras {
 // may be NULL), the ascending index list and its length.
 hipError_t launch_compact(const MaskGeom &g, const uint8_t *mask_in, uint8_t *mask_out, int32_t *idx,
                           int32_t *count, int32_t *block_counts, const CompactExtras &extras, hipStream_t s);
+// Mask pyramid: level l (1-based here; index 0 of h/w is the input mask) is the centre-tap
+// rescaling of level l - 1 with vertical/horizontal step sh/sw and first-tap offset ch0/cw0.
+constexpr int kMaxPyramidLevels = 8;
+struct PyramidArgs {
+    int32_t levels, n;
+    int32_t identity0; // level 0 has the input's resolution, centred window, and the input is 16-byte aligned
+    int32_t h[kMaxPyramidLevels + 1], w[kMaxPyramidLevels + 1]; // [0] = input mask, [l + 1] = level l
+    int32_t sh[kMaxPyramidLevels], sw[kMaxPyramidLevels], ch0[kMaxPyramidLevels], cw0[kMaxPyramidLevels];
+    int64_t m[kMaxPyramidLevels];          // positions of level l
+    int32_t block0[kMaxPyramidLevels + 1]; // first block of level l; [levels] = total
+    uint8_t *mask_out[kMaxPyramidLevels];
+    int32_t *idx[kMaxPyramidLevels];
+    int32_t *count[kMaxPyramidLevels];
+};
+hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int32_t *block_counts, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,

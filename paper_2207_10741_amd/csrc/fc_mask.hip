@@ -215,6 +215,146 @@ hipError_t launch_compact(const MaskGeom &g_in, const uint8_t *mask_in, uint8_t 
 }
 
 // ---------------------------------------------------------------------------
+// Mask pyramid (Sec. III-B: one mask, rescaled to every layer's size): the masks and
+// the kept-position lists of all levels from the input mask, in two launches.
+// Level l is the centre-tap rescaling of level l - 1, so a position of level l reads
+// the input mask through the composition of the levels' index maps; no level waits for
+// another.  Launch 1 writes every level's 0/1 mask and per-block counts, launch 2 turns
+// the counts into offsets and writes the ordered lists.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int pyramid_level_of(const PyramidArgs &a, int block)
+{
+    int l = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxPyramidLevels; ++i)
+        if (i < a.levels && block >= a.block0[i]) l = i;
+    return l;
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_masks(PyramidArgs a,
+                                                                         const uint8_t *__restrict__ mask_in,
+                                                                         int32_t *__restrict__ block_counts)
+{
+    __shared__ int scratch[kCompactBlockThreads / 64];
+    const int l = pyramid_level_of(a, blockIdx.x);
+    const int64_t m = a.m[l];
+    const int64_t p0 = (int64_t)(blockIdx.x - a.block0[l]) * kCompactBlockElems +
+                       (int64_t)threadIdx.x * kCompactBytesPerThread;
+    uint32_t flags = 0;
+    if (l == 0 && a.identity0 && p0 + 16 <= m) {
+        // the first level keeps the resolution of an aligned input mask: one 128-bit load
+        const uint4 v = *reinterpret_cast<const uint4 *>(mask_in + p0);
+        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
+    } else if (p0 < m) {
+        const int wl = a.w[l + 1], hl = a.h[l + 1];
+        int ow = (int)(p0 % wl);
+        int64_t t = p0 / wl;
+        int oh = (int)(t % hl);
+        int b = (int)(t / hl);
+        // the row of the input mask this output row reads, through all levels down to the input
+        int ih = oh;
+        for (int j = l; j >= 0; --j) ih = min(max(ih * a.sh[j] + a.ch0[j], 0), a.h[j] - 1);
+        for (int j = 0; j < 16 && p0 + j < m; ++j) {
+            int iw = ow;
+            for (int q = l; q >= 0; --q) iw = min(max(iw * a.sw[q] + a.cw0[q], 0), a.w[q] - 1);
+            if (mask_in[((int64_t)b * a.h[0] + ih) * a.w[0] + iw]) flags |= 1u << j;
+            if (++ow == wl) {
+                ow = 0;
+                if (++oh == hl) {
+                    oh = 0;
+                    ++b;
+                }
+                ih = oh;
+                for (int q = l; q >= 0; --q) ih = min(max(ih * a.sh[q] + a.ch0[q], 0), a.h[q] - 1);
+            }
+        }
+    }
+    if (p0 < m) {
+        uint8_t *mo = a.mask_out[l];
+        if (p0 + 16 <= m && (reinterpret_cast<uintptr_t>(mo) & 15u) == 0) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                wds[q] = ((flags >> (4 * q)) & 1u) | (((flags >> (4 * q + 1)) & 1u) << 8) |
+                         (((flags >> (4 * q + 2)) & 1u) << 16) | (((flags >> (4 * q + 3)) & 1u) << 24);
+            *reinterpret_cast<uint4 *>(mo + p0) = make_uint4(wds[0], wds[1], wds[2], wds[3]);
+        } else {
+            for (int j = 0; j < 16 && p0 + j < m; ++j) mo[p0 + j] = (flags >> j) & 1u;
+        }
+    }
+    const int total = block_sum(__popc(flags), scratch);
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_lists(PyramidArgs a,
+                                                                         const int32_t *__restrict__ block_counts)
+{
+    __shared__ int wave_sum[kCompactBlockThreads / 64];
+    __shared__ int scratch[kCompactBlockThreads / 64];
+    __shared__ int32_t stage[kCompactBlockElems];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l = pyramid_level_of(a, blockIdx.x);
+    const int64_t m = a.m[l];
+    const int first = a.block0[l], last = a.block0[l + 1] - 1;
+
+    int part = 0;
+    for (int i = first + tid; i < (int)blockIdx.x; i += kCompactBlockThreads) part += block_counts[i];
+    const int block_base = block_sum(part, scratch);
+
+    // the level's own 0/1 mask, written by the first launch
+    const int64_t p0 = (int64_t)(blockIdx.x - first) * kCompactBlockElems + (int64_t)tid * kCompactBytesPerThread;
+    const uint8_t *mo = a.mask_out[l];
+    uint32_t flags = 0;
+    if (p0 + 16 <= m && (reinterpret_cast<uintptr_t>(mo) & 15u) == 0) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(mo + p0);
+        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
+    } else {
+        for (int j = 0; j < 16 && p0 + j < m; ++j)
+            if (mo[p0 + j]) flags |= 1u << j;
+    }
+    const int c = __popc(flags);
+    const int incl = wave_inclusive_scan(c);
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int before = 0, block_total = 0;
+#pragma unroll
+    for (int i = 0; i < kCompactBlockThreads / 64; ++i) {
+        if (i < wave) before += wave_sum[i];
+        block_total += wave_sum[i];
+    }
+    int pos = before + incl - c;
+    uint32_t f = flags;
+    while (f) {
+        const int j = __ffs(f) - 1;
+        f &= f - 1;
+        stage[pos++] = (int32_t)(p0 + j);
+    }
+    __syncthreads();
+    int32_t *idx = a.idx[l];
+    for (int i = tid; i < block_total; i += kCompactBlockThreads) idx[(int64_t)block_base + i] = stage[i];
+    if ((int)blockIdx.x == last && tid == 0) *a.count[l] = block_base + block_total;
+}
+
+hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int32_t *block_counts, hipStream_t s)
+{
+    const int nb = a.block0[a.levels];
+    hipLaunchKernelGGL(k_pyramid_masks, dim3(nb), dim3(kCompactBlockThreads), 0, s, a, mask_in, block_counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_pyramid_lists, dim3(nb), dim3(kCompactBlockThreads), 0, s, a,
+                       (const int32_t *)block_counts);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Zero-fill of the irrelevant output rows: a lane owns 16 bytes of one row.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ bool position_kept(const Geom &g, const uint8_t *__restrict__ mask_in,

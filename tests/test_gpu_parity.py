@@ -48,6 +48,38 @@ def test_active_index_compact_blobs_large():
     np.testing.assert_array_equal(idx[:want_cnt].cpu().numpy(), want_idx)
 
 
+@pytest.mark.parametrize("n,h,w,steps", [
+    (16, 128, 128, [((3, 3), (1, 1), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1)),
+                    ((3, 3), (2, 2), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1))]),
+    (3, 57, 83, [((7, 7), (2, 2), (3, 3), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1)), ((1, 1), (2, 2), (0, 0), (1, 1)),
+                 ((2, 2), (2, 2), (0, 0), (1, 1)), ((3, 3), (1, 1), (1, 1), (1, 1))]),
+    (1, 224, 224, [((7, 7), (2, 2), (3, 3), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1)),
+                   ((3, 3), (2, 2), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1))]),
+    (2, 33, 47, [((3, 5), (1, 2), (0, 4), (2, 1))]),
+    (2, 300, 500, [((3, 3), (1, 1), (1, 1), (1, 1)), ((5, 5), (3, 3), (0, 0), (1, 1))]),
+])
+@pytest.mark.parametrize("irr", [0.48, 0.0, 1.0])
+def test_mask_pyramid_matches_the_chain_of_rescalings(n, h, w, steps, irr):
+    """All levels' masks and lists from one launch pair equal, bit for bit, the oracle's
+    level-by-level rescaling and compaction."""
+    mask = synth.mask_objects(n, h, w, irr, 120, h) * np.uint8(3)        # any nonzero byte counts
+    md = G.mask_dev(mask)
+    pyr = B.PreparedPyramid(md, steps)
+    for m_out, idx, count in pyr.levels:
+        m_out.fill_(9)
+        idx.fill_(-7)
+        count.fill_(-1)
+    levels = pyr()
+    G.torch_mod().cuda.synchronize()
+    cur = mask
+    for (k, s_, p, d), (m_out, idx, count) in zip(steps, levels):
+        cur = O.mask_downsample(cur, k[0], k[1], s_, p, d)
+        np.testing.assert_array_equal(m_out.cpu().numpy(), cur)
+        want_idx, want_count = O.active_index_compact(cur)
+        assert int(count.item()) == want_count
+        np.testing.assert_array_equal(idx.cpu().numpy()[:want_count], want_idx[:want_count])
+
+
 # ------------------------------------------------------------- conv layers ----
 
 def _run_layer(n, h, w, ci, co, k, s, p, d, dtype, *, irr=0.48, relu=True, use_bias=True, out_dtype=B.F32,

@@ -115,3 +115,33 @@ def test_product_package_does_not_use_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "fc_oracle" not in src and "fco_" not in src and "import oracle" not in src, f
+
+
+def test_mask_pyramid_dims_and_argument_checks():
+    steps = [((3, 3), (1, 1), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1)), ((1, 1), (2, 2), (0, 0), (1, 1)),
+             ((2, 2), (2, 2), (0, 0), (1, 1)), ((7, 5), (2, 1), (3, 2), (1, 1))]
+    h, w = 135, 241
+    want = []
+    for k, s_, p, d in steps:
+        h, w = O.out_dim(h, k[0], s_[0], p[0], d[0]), O.out_dim(w, k[1], s_[1], p[1], d[1])
+        want.append((h, w))
+    assert B.mask_pyramid_dims(135, 241, steps) == want
+    L = B.lib()
+    arr = B._steps_array(steps[:2])
+    hs, ws = (ctypes.c_int32 * 2)(), (ctypes.c_int32 * 2)()
+    assert L.fc_mask_pyramid_dims(8, 8, 0, arr, hs, ws) == -2                      # no levels
+    assert L.fc_mask_pyramid_dims(8, 8, B.MAX_PYRAMID_LEVELS + 1, arr, hs, ws) == -2
+    assert L.fc_mask_pyramid_dims(8, 8, 2, None, hs, ws) == -1
+    bad = B._steps_array([((3, 3), (0, 1), (1, 1), (1, 1))])
+    assert L.fc_mask_pyramid_dims(8, 8, 1, bad, hs, ws) == -2                      # zero stride
+    tiny = B._steps_array([((3, 3), (1, 1), (0, 0), (1, 1))])
+    assert L.fc_mask_pyramid_dims(2, 2, 1, tiny, hs, ws) == -2                     # empty level
+    nbytes = ctypes.c_size_t()
+    assert L.fc_mask_pyramid_workspace_bytes(2, 64, 64, 2, arr, ctypes.byref(nbytes)) == 0 and nbytes.value >= 4 * 3
+    a = ctypes.c_void_p(0x1000)
+    ptrs = (ctypes.c_void_p * 2)(a, a)
+    none = (ctypes.c_void_p * 2)(a, None)
+    assert L.fc_mask_pyramid(None, 2, 64, 64, 2, arr, ptrs, ptrs, ptrs, a, 4096, None) == -1
+    assert L.fc_mask_pyramid(a, 2, 64, 64, 2, arr, none, ptrs, ptrs, a, 4096, None) == -1
+    assert L.fc_mask_pyramid(a, 2, 64, 64, 2, arr, ptrs, ptrs, ptrs, None, 0, None) == -5
+    assert L.fc_mask_pyramid(a, 2, 64, 64, 2, arr, ptrs, ptrs, ptrs, a, 4, None) == -5
