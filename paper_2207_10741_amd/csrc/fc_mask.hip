@@ -258,10 +258,13 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_masks(PyramidA
         // the row of the input mask this output row reads, through all levels down to the input
         int ih = oh;
         for (int j = l; j >= 0; --j) ih = min(max(ih * a.sh[j] + a.ch0[j], 0), a.h[j] - 1);
-        for (int j = 0; j < 16 && p0 + j < m; ++j) {
+        // addresses first, then all sixteen bytes in flight together
+        int64_t at[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
             int iw = ow;
             for (int q = l; q >= 0; --q) iw = min(max(iw * a.sw[q] + a.cw0[q], 0), a.w[q] - 1);
-            if (mask_in[((int64_t)b * a.h[0] + ih) * a.w[0] + iw]) flags |= 1u << j;
+            at[j] = p0 + j < m ? ((int64_t)b * a.h[0] + ih) * a.w[0] + iw : -1;
             if (++ow == wl) {
                 ow = 0;
                 if (++oh == hl) {
@@ -272,6 +275,11 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_masks(PyramidA
                 for (int q = l; q >= 0; --q) ih = min(max(ih * a.sh[q] + a.ch0[q], 0), a.h[q] - 1);
             }
         }
+        uint8_t got[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) got[j] = at[j] >= 0 ? mask_in[at[j]] : (uint8_t)0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) flags |= got[j] ? (1u << j) : 0u;
     }
     if (p0 < m) {
         uint8_t *mo = a.mask_out[l];
