@@ -94,6 +94,7 @@ def test_null_pointers_rejected_before_any_launch():
     assert conv(odd, None, a, None, None, None, None, o, None, 0, None) == -4
     assert conv(a, None, a, None, None, a, None, o, None, 0, None) == -1      # idx without count
     assert conv(a, None, a, None, None, a, a, o, None, 0, None) == -1         # idx without the input mask
+    assert conv(a, None, a, odd, None, None, None, o, None, 0, None) == -4    # misaligned bias
     assert conv(a, a, a, None, None, None, None, o, None, 0, None) == -5      # needs a workspace
     assert conv(a, a, a, None, None, None, None, o, a, 16, None) == -5        # workspace too small
     assert conv(a, None, a, None, None, None, None, a, None, 0, None) == -1   # out aliases x
