@@ -58,6 +58,11 @@ def lib():
         L.fco_focused_conv2d_at.restype = ctypes.c_int32
         L.fco_focused_conv2d_at.argtypes = ([ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
                                             + [ctypes.c_int64, ctypes.c_void_p])
+        L.fco_focused_dwconv2d.restype = ctypes.c_int32
+        L.fco_focused_dwconv2d.argtypes = [ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
+        L.fco_focused_dwconv2d_at.restype = ctypes.c_int32
+        L.fco_focused_dwconv2d_at.argtypes = ([ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
+                                              + [ctypes.c_int64, ctypes.c_void_p])
         _lib = L
     return _lib
 
@@ -173,4 +178,46 @@ def focused_conv2d_at(s: ConvShape, x, w, positions, bias=None, mask_in=None,
                                      _ptr(pos), pos.size, _ptr(out))
     if rc != 0:
         raise ValueError("fco_focused_conv2d_at rc=%d" % rc)
+    return out
+
+
+def _check_dw_operands(s: ConvShape, x, w, bias, mask_in, dtype):
+    if s.c_in != s.c_out:
+        raise ValueError("depthwise layer: c_in %d != c_out %d" % (s.c_in, s.c_out))
+    x = _storage(x, dtype)
+    w = _storage(w, dtype)
+    if x.shape != (s.n, s.h, s.w, s.c_in):
+        raise ValueError("x shape %s" % (x.shape,))
+    if w.shape != (s.c_out, s.kh, s.kw):
+        raise ValueError("w shape %s" % (w.shape,))
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if bias.shape != (s.c_out,):
+            raise ValueError("bias shape %s" % (bias.shape,))
+    return x, w, bias, _mask(mask_in, (s.n, s.h, s.w))
+
+
+def focused_dwconv2d(s: ConvShape, x, w, bias=None, mask_in=None, dtype: int = F32) -> np.ndarray:
+    """Depthwise layer (w is [C, KH, KW]); returns float64 [N, Ho, Wo, C]."""
+    x, w, bias, m = _check_dw_operands(s, x, w, bias, mask_in, dtype)
+    ho, wo = out_dims(s)
+    out = np.empty((s.n, ho, wo, s.c_out), dtype=np.float64)
+    c = _conv_struct(s, dtype)
+    rc = lib().fco_focused_dwconv2d(ctypes.byref(c), _ptr(x), _ptr(m), _ptr(w), _ptr(bias), _ptr(out))
+    if rc != 0:
+        raise ValueError("fco_focused_dwconv2d rc=%d" % rc)
+    return out
+
+
+def focused_dwconv2d_at(s: ConvShape, x, w, positions, bias=None, mask_in=None,
+                        dtype: int = F32) -> np.ndarray:
+    """Rows of the depthwise layer's output at the given flat positions; float64 [len, C]."""
+    x, w, bias, m = _check_dw_operands(s, x, w, bias, mask_in, dtype)
+    pos = np.ascontiguousarray(positions, dtype=np.int64).reshape(-1)
+    out = np.empty((pos.size, s.c_out), dtype=np.float64)
+    c = _conv_struct(s, dtype)
+    rc = lib().fco_focused_dwconv2d_at(ctypes.byref(c), _ptr(x), _ptr(m), _ptr(w), _ptr(bias),
+                                       _ptr(pos), pos.size, _ptr(out))
+    if rc != 0:
+        raise ValueError("fco_focused_dwconv2d_at rc=%d" % rc)
     return out

@@ -36,6 +36,10 @@
  * widened exactly and accumulated in double in the loop order
  * n, oh, ow, co, kh, kw, ci.  The result is left unrounded.
  *
+ * The depthwise layer at the end of this file (one filter per channel, the
+ * building block of the networks the paper evaluates in Sec. IV) follows the
+ * same definition with the sum over input channels removed.
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_pins.py
  * (figure counts, closed forms, hand-computed cases, an independently written
  * im2col+matmul, a library convolution, invariants).
@@ -219,6 +223,79 @@ int32_t fco_focused_conv2d_at(const fco_conv *c, const void *x, const uint8_t *m
         int32_t oh = (int32_t)((p / wo) % ho);
         int32_t b = (int32_t)(p / ((int64_t)wo * ho));
         conv_position(c, wd, x, mask_in, w, bias, b, oh, ow, out + (size_t)j * c->c_out);
+    }
+    return 0;
+}
+
+/* ---- depthwise layer -----------------------------------------------------
+ * Sec. IV replaces every convolutional layer of EfficientDet and SSD-Lite by
+ * its focused form; most of those layers are depthwise: channel c of the
+ * output sees channel c of the input only, through its own KH x KW filter.
+ * Everything else is Sec. III-A unchanged: a position whose centre-tap mask
+ * byte is zero produces no features (+0.0), a kept position sees zero at
+ * irrelevant input pixels and outside the image.
+ * Layouts: x[N][H][W][C], w[C][KH][KW], bias[C]; c_in must equal c_out.
+ * Loop order n, oh, ow, c, kh, kw; double accumulation; result unrounded. */
+static void dw_position(const fco_conv *c, widen_fn wd, const void *x, const uint8_t *mask_in,
+                        const void *w, const float *bias, int32_t b, int32_t oh, int32_t ow,
+                        double *out_row)
+{
+    int32_t ch = clampi(oh * c->stride_h - c->pad_h + c->dil_h * ((c->kh - 1) / 2), 0, c->h - 1);
+    int32_t cw = clampi(ow * c->stride_w - c->pad_w + c->dil_w * ((c->kw - 1) / 2), 0, c->w - 1);
+    if (mask_in && !mask_in[((size_t)b * c->h + ch) * c->w + cw]) {
+        for (int32_t k = 0; k < c->c_out; ++k) out_row[k] = 0.0;
+        return;
+    }
+    for (int32_t k = 0; k < c->c_out; ++k) {
+        double acc = bias ? (double)bias[k] : 0.0;
+        for (int32_t kh = 0; kh < c->kh; ++kh)
+            for (int32_t kw = 0; kw < c->kw; ++kw) {
+                int32_t ih = oh * c->stride_h - c->pad_h + kh * c->dil_h;
+                int32_t iw = ow * c->stride_w - c->pad_w + kw * c->dil_w;
+                if (ih < 0 || ih >= c->h || iw < 0 || iw >= c->w) continue;
+                size_t pix = ((size_t)b * c->h + ih) * c->w + iw;
+                if (mask_in && !mask_in[pix]) continue;
+                acc += wd(x, pix * c->c_in + k) * wd(w, ((size_t)k * c->kh + kh) * c->kw + kw);
+            }
+        if (c->relu && acc < 0.0) acc = 0.0;
+        out_row[k] = acc;
+    }
+}
+
+int32_t fco_focused_dwconv2d(const fco_conv *c, const void *x, const uint8_t *mask_in,
+                             const void *w, const float *bias, double *out)
+{
+    int32_t ho = fco_out_dim(c->h, c->kh, c->stride_h, c->pad_h, c->dil_h);
+    int32_t wo = fco_out_dim(c->w, c->kw, c->stride_w, c->pad_w, c->dil_w);
+    if (c->n <= 0 || ho <= 0 || wo <= 0 || c->c_in <= 0 || c->c_out != c->c_in) return -1;
+    widen_fn wd = pick_widen(c->dtype);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int32_t b = 0; b < c->n; ++b)
+        for (int32_t oh = 0; oh < ho; ++oh)
+            for (int32_t ow = 0; ow < wo; ++ow)
+                dw_position(c, wd, x, mask_in, w, bias, b, oh, ow,
+                            out + (((size_t)b * ho + oh) * wo + ow) * c->c_out);
+    return 0;
+}
+
+int32_t fco_focused_dwconv2d_at(const fco_conv *c, const void *x, const uint8_t *mask_in,
+                                const void *w, const float *bias, const int64_t *positions,
+                                int64_t npos, double *out)
+{
+    int32_t ho = fco_out_dim(c->h, c->kh, c->stride_h, c->pad_h, c->dil_h);
+    int32_t wo = fco_out_dim(c->w, c->kw, c->stride_w, c->pad_w, c->dil_w);
+    if (c->n <= 0 || ho <= 0 || wo <= 0 || c->c_in <= 0 || c->c_out != c->c_in) return -1;
+    int64_t m = (int64_t)c->n * ho * wo;
+    for (int64_t j = 0; j < npos; ++j)
+        if (positions[j] < 0 || positions[j] >= m) return -2;
+    widen_fn wd = pick_widen(c->dtype);
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t j = 0; j < npos; ++j) {
+        int64_t p = positions[j];
+        int32_t ow = (int32_t)(p % wo);
+        int32_t oh = (int32_t)((p / wo) % ho);
+        int32_t b = (int32_t)(p / ((int64_t)wo * ho));
+        dw_position(c, wd, x, mask_in, w, bias, b, oh, ow, out + (size_t)j * c->c_out);
     }
     return 0;
 }

@@ -399,3 +399,103 @@ def test_window_rules_would_not_keep_the_share():
         centre = O.mask_downsample(centre, 3, 3, (1, 1), (1, 1))
     assert centre[0].mean() == keep0
     assert any_m.mean() - keep0 > 0.05 and keep0 - all_m.mean() > 0.05
+
+
+# ---------------------------------------------------------- depthwise layer ----
+
+DW_CASES = [
+    # n, h, w, c, kh, kw, stride, pad, dil
+    (1, 7, 9, 5, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (2, 8, 8, 6, 3, 3, (2, 2), (1, 1), (1, 1)),
+    (1, 12, 10, 3, 5, 5, (1, 1), (2, 2), (1, 1)),
+    (1, 11, 13, 4, 3, 3, (1, 2), (2, 0), (2, 1)),
+    (2, 9, 7, 8, 5, 3, (2, 1), (0, 1), (1, 1)),
+]
+
+
+def _dw_inputs(case, seed):
+    n, h, w, c, kh, kw, st, pd, dl = case
+    x = synth.from_storage(synth.activations((n, h, w, c), synth.F32, seed, h, w) - 0.3, synth.F32)
+    wt = synth.he_weights(c, kh, kw, 1, synth.F32, seed + 1, h, w)[..., 0]
+    b = synth.bias(c, seed + 2, h)
+    return O.ConvShape(n, h, w, c, c, kh, kw, st, pd, dl), x, np.ascontiguousarray(wt), b
+
+
+def test_depthwise_hand_case():
+    """3x3 image, two channels with different 2x2 filters, written out by hand."""
+    x = np.zeros((1, 3, 3, 2), np.float32)
+    x[0, :, :, 0] = [[1, 2, 3], [4, 5, 6], [7, 8, 9]]
+    x[0, :, :, 1] = [[1, 0, -1], [2, 0, -2], [3, 0, -3]]
+    w = np.zeros((2, 2, 2), np.float32)
+    w[0] = [[1, 0], [0, -1]]          # x[r][c] - x[r+1][c+1]
+    w[1] = [[0, 2], [1, 0]]           # 2 x[r][c+1] + x[r+1][c]
+    s = O.ConvShape(1, 3, 3, 2, 2, 2, 2, (1, 1), (0, 0), (1, 1))
+    got = O.focused_dwconv2d(s, x, w, bias=np.array([0.5, -1.0], np.float32))
+    want0 = np.array([[1 - 5, 2 - 6], [4 - 8, 5 - 9]]) + 0.5
+    want1 = np.array([[2 * 0 + 2, 2 * -1 + 0], [2 * 0 + 3, 2 * -2 + 0]]) - 1.0
+    np.testing.assert_array_equal(got[0, :, :, 0], want0)
+    np.testing.assert_array_equal(got[0, :, :, 1], want1)
+    # centre tap of an even kernel is its top-left pixel: dropping pixel (1,1) drops output (1,1)
+    # and removes that pixel from the three other windows that contain it
+    m = np.ones((1, 3, 3), np.uint8)
+    m[0, 1, 1] = 0
+    gm = O.focused_dwconv2d(s, x, w, mask_in=m)
+    assert not gm[0, 1, 1].any()
+    np.testing.assert_array_equal(gm[0, 0, 0], [1 - 0, 2 * 0 + 2])
+    np.testing.assert_array_equal(gm[0, 0, 1], [2 - 6, 2 * -1 + 0])
+    np.testing.assert_array_equal(gm[0, 1, 0], [4 - 8, 2 * 0 + 3])
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+@pytest.mark.parametrize("masked", [False, True])
+def test_depthwise_is_the_full_layer_with_diagonal_weights(case, masked):
+    """A depthwise layer is the ordinary layer whose weight is zero off the channel diagonal;
+    the ordinary layer's oracle is pinned above by independent means."""
+    s, x, wt, b = _dw_inputs(case, 41)
+    mask = synth.mask_bernoulli(s.n, s.h, s.w, 0.4, 44, s.h, s.w) if masked else None
+    full = np.zeros((s.c_out, s.kh, s.kw, s.c_in), np.float32)
+    for k in range(s.c_out):
+        full[k, :, :, k] = wt[k]
+    s_relu = O.ConvShape(s.n, s.h, s.w, s.c_in, s.c_out, s.kh, s.kw, s.stride, s.pad, s.dil, relu=masked)
+    got = O.focused_dwconv2d(s_relu, x, wt, bias=b, mask_in=mask)
+    want = O.focused_conv2d(s_relu, x, full, bias=b, mask_in=mask)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+def test_depthwise_dense_matches_library_grouped_convolution(case):
+    torch = pytest.importorskip("torch")
+    s, x, wt, b = _dw_inputs(case, 51)
+    got = O.focused_dwconv2d(s, x, wt, bias=b)
+    ref = torch.nn.functional.conv2d(
+        torch.from_numpy(x).double().permute(0, 3, 1, 2), torch.from_numpy(wt).double()[:, None],
+        torch.from_numpy(b).double(), stride=s.stride, padding=s.pad, dilation=s.dil,
+        groups=s.c_in).permute(0, 2, 3, 1).numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_depthwise_invariants_and_sampled_positions():
+    s, x, wt, b = _dw_inputs((2, 14, 11, 6, 3, 3, (1, 1), (1, 1), (1, 1)), 61)
+    mask = synth.mask_objects(s.n, s.h, s.w, 0.48, 61, 4)
+    base = O.focused_dwconv2d(s, x, wt, bias=b, mask_in=mask)
+    keep = mask != 0
+    assert not base[~keep].view(np.uint8).any() and np.abs(base[keep]).max() > 0
+    assert not O.focused_dwconv2d(s, x, wt, bias=b, mask_in=np.zeros_like(mask)).view(np.uint8).any()
+    for poison in (1e6, np.nan):
+        xp = x.copy()
+        xp[~keep] = poison
+        np.testing.assert_array_equal(O.focused_dwconv2d(s, xp, wt, bias=b, mask_in=mask), base)
+    # channels do not mix: changing channel 2 of the input changes channel 2 of the output only
+    x2 = x.copy()
+    x2[..., 2] += 1.0
+    d = O.focused_dwconv2d(s, x2, wt, bias=b, mask_in=mask) - base
+    assert np.abs(d[..., 2]).max() > 0 and not np.delete(d, 2, axis=-1).any()
+    pos = np.array([0, 5, 17, s.h * s.w, 2 * s.h * s.w - 1])
+    np.testing.assert_array_equal(O.focused_dwconv2d_at(s, x, wt, pos, bias=b, mask_in=mask),
+                                  base.reshape(-1, s.c_out)[pos])
+    # 16-bit storage widens exactly
+    xb = synth.activations((s.n, s.h, s.w, s.c_in), synth.BF16, 62, 1)
+    wb = np.ascontiguousarray(synth.he_weights(s.c_out, s.kh, s.kw, 1, synth.BF16, 63, 2)[..., 0])
+    np.testing.assert_array_equal(
+        O.focused_dwconv2d(s, xb, wb, mask_in=mask, dtype=O.BF16),
+        O.focused_dwconv2d(s, synth.from_storage(xb, synth.BF16), synth.from_storage(wb, synth.BF16), mask_in=mask))
