@@ -234,6 +234,56 @@ def stack_bench(torch, B, synth, workloads, args):
     }))
 
 
+def depthwise_bench(torch, B, synth, workloads, args):
+    """The 3x3 depthwise layers of a MobileNetV2 backbone, batch 32, bf16, blob masks: per layer
+    the focused call and the same call without a mask, each as a HIP-graph replay of four
+    calls.  The layer is bound by memory traffic: algorithmic bytes = input mask + relevant
+    input pixels once + filters and bias + every output row once (kept rows and zero rows)."""
+    irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
+    n = workloads.DEPTHWISE_BATCH if args.batch is None else args.batch
+    dev = torch.device("cuda:0")
+    gen = synth.mask_bernoulli if args.mask == "bernoulli" else synth.mask_objects
+    rows, t_f, t_d, bytes_f, bytes_d = [], 0.0, 0.0, 0.0, 0.0
+    for li, (c, side, stride) in enumerate(workloads.mobilenetv2_depthwise()):
+        x = synth.activations((n, side, side, c), synth.BF16, 6, li, 1)
+        w = np.ascontiguousarray(synth.he_weights(c, 3, 3, 1, synth.BF16, 6, li, 2)[..., 0])
+        bias = synth.bias(c, 6, li, 3)
+        mask = gen(n, side, side, irr, 6, li, 4)
+        to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        desc = B.conv_desc(n, side, side, c, c, (3, 3), (stride, stride), (1, 1), (1, 1), B.BF16, B.BF16, B.RELU)
+        ho, wo = B.out_dims(desc)
+        xd, wd, bd, md = to_dev(x), to_dev(w), torch.from_numpy(bias).to(dev), torch.from_numpy(mask).to(dev)
+        out = torch.empty((n, ho, wo, c), dtype=torch.bfloat16, device=dev)
+        focused = B.PreparedDwConv(desc, xd, wd, bd, mask_in=md, out=out)
+        dense = B.PreparedDwConv(desc, xd, wd, bd, out=out)
+
+        def timed(call):
+            def fn():
+                for _ in range(4):
+                    call()
+            return time_loop(torch, capture(torch, fn).replay, args.steps, args.warmup) / 4
+
+        tf, td = timed(focused), timed(dense)
+        kept_in = float(np.count_nonzero(mask))
+        m = n * ho * wo
+        common = c * 9 * 2 + c * 4 + m * c * 2
+        bf = mask.size + kept_in * c * 2 + common
+        bd_ = mask.size * c * 2 + common
+        rows.append({"layer": "c%d@%d/s%d" % (c, side, stride), "focused_us": round(tf * 1e6, 2),
+                     "dense_us": round(td * 1e6, 2), "speedup": round(td / tf, 3),
+                     "focused_GBps": round(bf / tf / 1e9, 1), "dense_GBps": round(bd_ / td / 1e9, 1)})
+        t_f, t_d, bytes_f, bytes_d = t_f + tf, t_d + td, bytes_f + bf, bytes_d + bd_
+        del xd, out, focused, dense
+    print(json.dumps({
+        "depthwise": True, "workload": "MobileNetV2 3x3 depthwise layers, batch %d, 224x224 images, bf16, %s masks, "
+        "%d %% irrelevant" % (n, args.mask, round(irr * 100)), "launch": "HIP graph replay of four calls",
+        "steps": args.steps, "layers": rows, "focused_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
+        "speedup_vs_dense": round(t_d / t_f, 3),
+        "roofline": {"bound": "hbm", "achieved": round(bytes_f / t_f / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                     "frac": round(bytes_f / t_f / 8e12, 4), "traffic": None},
+        "dense_GBps": round(bytes_d / t_d / 1e9, 1)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -252,6 +302,9 @@ def main():
     ap.add_argument("--stack", choices=sorted(STACKS), default=None,
                     help="time a whole conv stack (dense / focused / focused without zero-fill between "
                          "convs) instead of the bench line")
+    ap.add_argument("--depthwise", action="store_true",
+                    help="time the depthwise layers of a MobileNetV2 backbone (focused and dense) "
+                         "instead of the bench line")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
@@ -274,6 +327,9 @@ def main():
         return
     if args.stack:
         stack_bench(torch, B, synth, workloads, args)
+        return
+    if args.depthwise:
+        depthwise_bench(torch, B, synth, workloads, args)
         return
     layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch)
 

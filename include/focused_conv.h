@@ -166,6 +166,26 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
                           const int32_t *idx, const int32_t *count, void *out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* The depthwise layer: one KH x KW filter per channel, the layer type most of
+ * the two networks of Sec. IV consist of (depthwise-separable blocks; their
+ * 1x1 halves are fc_focused_conv2d).  Sec. III-A unchanged otherwise: a
+ * position whose centre-tap mask byte is zero gets +0.0 in every channel (or is
+ * left untouched with FC_SKIP_ZERO_FILL), a kept position sees zero at
+ * irrelevant input pixels and outside the image; fp32 accumulation, taps in
+ * the order kh, kw, one rounding to out_dtype.
+ *   desc      c_out must equal c_in (else FC_ERR_SHAPE); flags FC_RELU and
+ *             FC_SKIP_ZERO_FILL apply
+ *   x         device, NHWC, in_dtype, read only; one image must stay below
+ *             0xF0000000 bytes and n below 65536 (else FC_ERR_RANGE)
+ *   mask_in   device [n][h][w] bytes, or NULL = every pixel relevant
+ *   w         device, [c][kh][kw], in_dtype, read only
+ *   bias      device, c floats, or NULL
+ *   out       device, NHWC [n][ho][wo][c], out_dtype; must not overlap x
+ * The label of a position is read from mask_in directly, so the call needs no
+ * kept-position list and no workspace; one kernel launch on `stream`. */
+int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in,
+                            const void *w, const float *bias, void *out, void *stream);
+
 /* Helper for conv stacks with pooling between layers (not part of the paper's
  * method): NHWC max-pool over the full tensor, window k, stride s, padding p
  * (padding never wins the max).  x/out device, dtype as given. */

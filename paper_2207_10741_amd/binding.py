@@ -19,7 +19,8 @@ WORKSPACE_COUNTER_BYTES = 2048
 
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
              "fc_mask_downsample", "fc_active_index_compact", "fc_mask_pyramid_dims",
-             "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_maxpool2d")
+             "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_dwconv2d",
+             "fc_maxpool2d")
 MAX_PYRAMID_LEVELS = 8
 
 
@@ -83,6 +84,8 @@ def lib():
                                       ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
         L.fc_focused_conv2d.restype = i32
         L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.fc_focused_dwconv2d.restype = i32
+        L.fc_focused_dwconv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 6
         L.fc_maxpool2d.restype = i32
         L.fc_maxpool2d.argtypes = [vp] + [i32] * 8 + [vp, vp]
         _lib = L
@@ -275,6 +278,41 @@ class PreparedConv:
         rc = self._fn(*self._args, ctypes.c_void_p(h))
         if rc != 0:
             raise FcError(rc, "fc_focused_conv2d")
+        return self.out
+
+
+def focused_dwconv2d(desc: ConvDesc, x, w, bias=None, mask_in=None, out=None, stream=None):
+    """fc_focused_dwconv2d.  x NHWC, w [C,KH,KW] (one filter per channel); returns out NHWC."""
+    torch = _torch()
+    _require_cuda(x, w, bias, mask_in, out)
+    ho, wo = out_dims(desc)
+    if out is None:
+        out = torch.empty((desc.n, ho, wo, desc.c_out), dtype=torch_dtype(desc.out_dtype), device=x.device)
+    _check(lib().fc_focused_dwconv2d(ctypes.byref(desc), _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias), _ptr(out),
+                                     _stream(stream)), "fc_focused_dwconv2d")
+    return out
+
+
+class PreparedDwConv:
+    """fc_focused_dwconv2d with its arguments marshalled once (see PreparedConv)."""
+
+    def __init__(self, desc: ConvDesc, x, w, bias=None, mask_in=None, out=None):
+        torch = _torch()
+        _require_cuda(x, w, bias, mask_in, out)
+        ho, wo = out_dims(desc)
+        if out is None:
+            out = torch.empty((desc.n, ho, wo, desc.c_out), dtype=torch_dtype(desc.out_dtype), device=x.device)
+        self.out = out
+        self._keep = (desc, x, w, bias, mask_in, out)
+        self._args = (ctypes.byref(desc), _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias), _ptr(out))
+        self._fn = lib().fc_focused_dwconv2d
+        self._current_stream = torch.cuda.current_stream
+
+    def __call__(self, stream=None):
+        h = (self._current_stream() if stream is None else stream).cuda_stream
+        rc = self._fn(*self._args, ctypes.c_void_p(h))
+        if rc != 0:
+            raise FcError(rc, "fc_focused_dwconv2d")
         return self.out
 
 

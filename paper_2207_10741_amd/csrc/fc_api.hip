@@ -214,6 +214,22 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     return FC_OK;
 }
 
+int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in, const void *w,
+                            const float *bias, void *out, void *stream)
+{
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != FC_OK) return rc;
+    if (g.c_in != g.c_out) return FC_ERR_SHAPE;
+    if (!x || !w || !out) return FC_ERR_NULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(bias)) return FC_ERR_ALIGN;
+    if (x == out) return FC_ERR_NULL;
+    if (!conv_depthwise_supported(g, desc->in_dtype)) return FC_ERR_RANGE;
+    const hipError_t e = launch_conv_depthwise(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, out,
+                                               (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
 // Fills the geometry part of the pyramid arguments; returns an fc_status.
 static int32_t pyramid_geometry(int32_t n, int32_t h, int32_t w, int32_t levels, const fc_mask_step *steps,
                                 PyramidArgs *a)

@@ -133,6 +133,12 @@ hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const 
                               const uint8_t *mask_in, const void *w, const float *bias,
                               const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
+// Depthwise layer (one filter per channel); labels positions from mask_in itself and clears
+// the irrelevant rows.
+bool conv_depthwise_supported(const Geom &g, int in_dtype);
+hipError_t launch_conv_depthwise(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
+                                 const void *w, const float *bias, void *out, hipStream_t s);
+
 // Matrix-core path for layers with at most 4 input channels (RGB stems); the caller clears the
 // irrelevant rows with launch_zero_fill.
 bool conv_stem_supported(const Geom &g, int in_dtype, int out_dtype);

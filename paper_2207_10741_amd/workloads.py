@@ -88,5 +88,13 @@ def sweep_shapes():
     return [(64, 128), (128, 64), (256, 32), (512, 16)]
 
 
+def mobilenetv2_depthwise():
+    """(channels, input side, stride) of the 3x3 depthwise layers of a MobileNetV2 backbone (the
+    backbone of SSD-Lite, Sec. IV) on 224 x 224 images; repeats of a shape listed once."""
+    return [(32, 112, 1), (96, 112, 2), (144, 56, 1), (144, 56, 2), (192, 28, 1), (192, 28, 2),
+            (384, 14, 1), (576, 14, 1), (576, 14, 2), (960, 7, 1)]
+
+
+DEPTHWISE_BATCH = 32
 SWEEP_BATCH = 16
 HEADLINE_IRRELEVANT = 0.48   # Sec. II-B: the paper's overall irrelevant-pixel share

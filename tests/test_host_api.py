@@ -98,6 +98,14 @@ def test_null_pointers_rejected_before_any_launch():
     assert conv(a, a, a, None, None, None, None, o, None, 0, None) == -5      # needs a workspace
     assert conv(a, a, a, None, None, None, None, o, a, 16, None) == -5        # workspace too small
     assert conv(a, None, a, None, None, None, None, a, None, 0, None) == -1   # out aliases x
+    dw = lambda desc, *args: L.fc_focused_dwconv2d(ctypes.byref(desc), *args)
+    #              x  mask_in w  bias out stream
+    assert dw(d, None, None, a, None, o, None) == -1
+    assert dw(d, odd, None, a, None, o, None) == -4
+    assert dw(d, a, None, a, odd, o, None) == -4
+    assert dw(d, a, None, a, None, a, None) == -1                             # out aliases x
+    assert dw(B.conv_desc(1, 8, 8, 8, 16), a, None, a, None, o, None) == -2   # not one filter per channel
+    assert dw(B.conv_desc(1, 40000, 40000, 8, 8, in_dtype=B.BF16), a, None, a, None, o, None) == -6
     assert L.fc_maxpool2d(a, 1, 8, 8, 8, 0, 2, 2, 2, a, None) == -2
     assert L.fc_maxpool2d(a, 1, 8, 8, 8, 9, 2, 2, 0, a, None) == -3
 
