@@ -71,6 +71,9 @@ DW_LAYERS = [
     (2, 19, 23, 20, 3, 1, 1, 1),               # channel count not a multiple of 8: one channel per lane
     (1, 17, 13, 7, (2, 3), (2, 1), 0, 1),      # even kernel height, odd channel count
     (1, 1, 1, 8, 3, 1, 1, 1),                  # a single position
+    (2, 70, 75, 32, 3, 1, 1, 1),               # several tiles each way, ragged last tiles
+    (1, 45, 50, 24, 5, 1, 2, 1),               # 5 x 5 over several tiles
+    (1, 64, 64, 128, 3, 1, 30, 30),            # dilation too wide for a staged patch: direct kernel
 ]
 
 
