@@ -19,6 +19,7 @@ _SRC = os.path.join(_HERE, "focused_conv_oracle.c")
 _LIB = os.path.join(_HERE, "libfc_oracle.so")
 
 F32, BF16, F16 = 0, 1, 2
+RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -58,6 +59,10 @@ def lib():
         L.fco_focused_conv2d_at.restype = ctypes.c_int32
         L.fco_focused_conv2d_at.argtypes = ([ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
                                             + [ctypes.c_int64, ctypes.c_void_p])
+        L.fco_mask_downsample_rule.restype = ctypes.c_int32
+        L.fco_mask_downsample_rule.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 12 + [ctypes.c_void_p]
+        L.fco_focused_conv2d_labelled.restype = ctypes.c_int32
+        L.fco_focused_conv2d_labelled.argtypes = [ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 6
         L.fco_focused_dwconv2d.restype = ctypes.c_int32
         L.fco_focused_dwconv2d.argtypes = [ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
         L.fco_focused_dwconv2d_at.restype = ctypes.c_int32
@@ -129,6 +134,20 @@ def mask_downsample(mask_in: np.ndarray, kh, kw, stride, pad, dil=(1, 1)) -> np.
     return out
 
 
+def mask_downsample_rule(mask_in: np.ndarray, kh, kw, stride, pad, dil=(1, 1), rule: int = RULE_CENTRE) -> np.ndarray:
+    """Labels of a layer's patches under the centre-tap, any-pixel or all-pixels rule."""
+    n, h, w = mask_in.shape
+    m = _mask(mask_in, (n, h, w))
+    ho = out_dim(h, kh, stride[0], pad[0], dil[0])
+    wo = out_dim(w, kw, stride[1], pad[1], dil[1])
+    out = np.empty((n, ho, wo), dtype=np.uint8)
+    rc = lib().fco_mask_downsample_rule(_ptr(m), n, h, w, kh, kw, stride[0], stride[1],
+                                        pad[0], pad[1], dil[0], dil[1], rule, _ptr(out))
+    if rc != 0:
+        raise ValueError("fco_mask_downsample_rule rc=%d" % rc)
+    return out
+
+
 def active_index_compact(mask: np.ndarray):
     m = np.ascontiguousarray(mask, dtype=np.uint8).reshape(-1)
     idx = np.empty(m.size, dtype=np.int32)
@@ -164,6 +183,20 @@ def focused_conv2d(s: ConvShape, x, w, bias=None, mask_in=None, dtype: int = F32
     rc = lib().fco_focused_conv2d(ctypes.byref(c), _ptr(x), _ptr(m), _ptr(w), _ptr(bias), _ptr(out))
     if rc != 0:
         raise ValueError("fco_focused_conv2d rc=%d" % rc)
+    return out
+
+
+def focused_conv2d_labelled(s: ConvShape, x, w, labels, bias=None, mask_in=None, dtype: int = F32) -> np.ndarray:
+    """Whole layer with the kept positions given as labels [N, Ho, Wo]; float64 [N, Ho, Wo, C_out]."""
+    x, w, bias, m = _check_operands(s, x, w, bias, mask_in, dtype)
+    ho, wo = out_dims(s)
+    lab = _mask(labels, (s.n, ho, wo))
+    out = np.empty((s.n, ho, wo, s.c_out), dtype=np.float64)
+    c = _conv_struct(s, dtype)
+    rc = lib().fco_focused_conv2d_labelled(ctypes.byref(c), _ptr(x), _ptr(m), _ptr(lab), _ptr(w), _ptr(bias),
+                                           _ptr(out))
+    if rc != 0:
+        raise ValueError("fco_focused_conv2d_labelled rc=%d" % rc)
     return out
 
 

@@ -141,6 +141,39 @@ int32_t fco_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_
     return 0;
 }
 
+/* ---- other ways to label a patch ---------------------------------------
+ * Sec. III-A only says "a patch labelled irrelevant"; the reading used everywhere
+ * else in this file is the centre tap (rule 0).  The two window rules are the other
+ * readings of that sentence: rule 1 keeps a patch if ANY pixel of its window is
+ * relevant, rule 2 only if ALL are.  Pixels outside the image are not part of the
+ * window; a window with no pixel inside the image is irrelevant under both. */
+int32_t fco_mask_downsample_rule(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
+                                 int32_t kh, int32_t kw, int32_t sh, int32_t sw,
+                                 int32_t ph, int32_t pw, int32_t dh, int32_t dw,
+                                 int32_t rule, uint8_t *mask_out)
+{
+    if (rule == 0)
+        return fco_mask_downsample(mask_in, n, h, w, kh, kw, sh, sw, ph, pw, dh, dw, mask_out);
+    if (rule != 1 && rule != 2) return -3;
+    int32_t ho = fco_out_dim(h, kh, sh, ph, dh), wo = fco_out_dim(w, kw, sw, pw, dw);
+    if (n <= 0 || ho <= 0 || wo <= 0 || !mask_in) return -1;
+    for (int32_t b = 0; b < n; ++b)
+        for (int32_t oh = 0; oh < ho; ++oh)
+            for (int32_t ow = 0; ow < wo; ++ow) {
+                int32_t inside = 0, relevant = 0;
+                for (int32_t i = 0; i < kh; ++i)
+                    for (int32_t j = 0; j < kw; ++j) {
+                        int32_t ih = oh * sh - ph + i * dh, iw = ow * sw - pw + j * dw;
+                        if (ih < 0 || ih >= h || iw < 0 || iw >= w) continue;
+                        ++inside;
+                        if (mask_in[((size_t)b * h + ih) * w + iw]) ++relevant;
+                    }
+                uint8_t v = rule == 1 ? (relevant > 0) : (inside > 0 && relevant == inside);
+                mask_out[((size_t)b * ho + oh) * wo + ow] = v;
+            }
+    return 0;
+}
+
 /* ---- which columns survive (Sec. III-A) --------------------------------
  * Ascending list of the flat positions whose mask byte is nonzero. */
 int64_t fco_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx)
@@ -297,5 +330,45 @@ int32_t fco_focused_dwconv2d_at(const fco_conv *c, const void *x, const uint8_t 
         int32_t b = (int32_t)(p / ((int64_t)wo * ho));
         dw_position(c, wd, x, mask_in, w, bias, b, oh, ow, out + (size_t)j * c->c_out);
     }
+    return 0;
+}
+
+/* ---- the layer with the labels given --------------------------------------
+ * labels[N][Ho][Wo] (nonzero = kept) say which patches become columns, however
+ * they were obtained (fco_mask_downsample_rule); a kept patch still sees zero at
+ * pixels the input mask marks irrelevant and outside the image.  Same loops and
+ * arithmetic as fco_focused_conv2d. */
+int32_t fco_focused_conv2d_labelled(const fco_conv *c, const void *x, const uint8_t *mask_in,
+                                    const uint8_t *labels, const void *w, const float *bias,
+                                    double *out)
+{
+    int32_t ho = fco_out_dim(c->h, c->kh, c->stride_h, c->pad_h, c->dil_h);
+    int32_t wo = fco_out_dim(c->w, c->kw, c->stride_w, c->pad_w, c->dil_w);
+    if (c->n <= 0 || ho <= 0 || wo <= 0 || c->c_in <= 0 || c->c_out <= 0 || !labels) return -1;
+    widen_fn wd = pick_widen(c->dtype);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int32_t b = 0; b < c->n; ++b)
+        for (int32_t oh = 0; oh < ho; ++oh)
+            for (int32_t ow = 0; ow < wo; ++ow) {
+                size_t p = ((size_t)b * ho + oh) * wo + ow;
+                double *out_row = out + p * c->c_out;
+                for (int32_t co = 0; co < c->c_out; ++co) {
+                    if (!labels[p]) { out_row[co] = 0.0; continue; }
+                    double acc = bias ? (double)bias[co] : 0.0;
+                    for (int32_t kh = 0; kh < c->kh; ++kh)
+                        for (int32_t kw = 0; kw < c->kw; ++kw) {
+                            int32_t ih = oh * c->stride_h - c->pad_h + kh * c->dil_h;
+                            int32_t iw = ow * c->stride_w - c->pad_w + kw * c->dil_w;
+                            if (ih < 0 || ih >= c->h || iw < 0 || iw >= c->w) continue;
+                            size_t pix = ((size_t)b * c->h + ih) * c->w + iw;
+                            if (mask_in && !mask_in[pix]) continue;
+                            for (int32_t ci = 0; ci < c->c_in; ++ci)
+                                acc += wd(x, pix * c->c_in + ci) *
+                                       wd(w, (((size_t)co * c->kh + kh) * c->kw + kw) * c->c_in + ci);
+                        }
+                    if (c->relu && acc < 0.0) acc = 0.0;
+                    out_row[co] = acc;
+                }
+            }
     return 0;
 }

@@ -499,3 +499,82 @@ def test_depthwise_invariants_and_sampled_positions():
     np.testing.assert_array_equal(
         O.focused_dwconv2d(s, xb, wb, mask_in=mask, dtype=O.BF16),
         O.focused_dwconv2d(s, synth.from_storage(xb, synth.BF16), synth.from_storage(wb, synth.BF16), mask_in=mask))
+
+
+# ----------------------------------------------------- window rules for labels ----
+
+def _window_labels_by_shifts(mask, kh, kw, st, pd, dl, rule):
+    """Independent formulation: pad with a marker, gather every tap as a strided view."""
+    n, h, w = mask.shape
+    ho = (h + 2 * pd[0] - dl[0] * (kh - 1) - 1) // st[0] + 1
+    wo = (w + 2 * pd[1] - dl[1] * (kw - 1) - 1) // st[1] + 1
+    rel = np.pad((mask != 0).astype(np.int8), ((0, 0), (pd[0], pd[0]), (pd[1], pd[1])), constant_values=-1)
+    taps = np.stack([rel[:, i * dl[0]: i * dl[0] + (ho - 1) * st[0] + 1: st[0],
+                         j * dl[1]: j * dl[1] + (wo - 1) * st[1] + 1: st[1]]
+                     for i in range(kh) for j in range(kw)])
+    inside = (taps >= 0).sum(0)
+    relevant = (taps == 1).sum(0)
+    return (relevant > 0) if rule == O.RULE_ANY else ((inside > 0) & (relevant == inside))
+
+
+RULE_CASES = [
+    # n, h, w, kh, kw, stride, pad, dil
+    (2, 9, 11, 3, 3, (1, 1), (1, 1), (1, 1)),
+    (1, 12, 10, 3, 3, (2, 2), (1, 1), (1, 1)),
+    (1, 10, 13, 5, 3, (1, 2), (2, 0), (1, 2)),
+    (2, 8, 8, 2, 2, (2, 2), (0, 0), (1, 1)),
+    (1, 7, 7, 3, 3, (1, 1), (4, 4), (1, 1)),      # windows that lie wholly outside the image
+    (1, 9, 9, 1, 1, (2, 2), (0, 0), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", RULE_CASES)
+@pytest.mark.parametrize("rule", [O.RULE_ANY, O.RULE_ALL])
+def test_window_rule_labels_match_shifted_views(case, rule):
+    n, h, w, kh, kw, st, pd, dl = case
+    mask = synth.mask_bernoulli(n, h, w, 0.5, 71, h, w) * np.uint8(5)
+    got = O.mask_downsample_rule(mask, kh, kw, st, pd, dl, rule)
+    np.testing.assert_array_equal(got != 0, _window_labels_by_shifts(mask, kh, kw, st, pd, dl, rule))
+    assert set(np.unique(got)) <= {0, 1}
+    # rule 0 is the centre tap
+    np.testing.assert_array_equal(O.mask_downsample_rule(mask, kh, kw, st, pd, dl, O.RULE_CENTRE),
+                                  O.mask_downsample(mask, kh, kw, st, pd, dl))
+
+
+def test_window_rules_against_library_morphology_and_closed_forms():
+    """3x3 / stride 1 / pad 1: ANY is a binary dilation, ALL (inside the image) an erosion whose
+    border treats outside pixels as relevant; a kept r x c rectangle away from the border becomes
+    (r + 2) x (c + 2) and (r - 2) x (c - 2); ALL <= centre <= ANY."""
+    ndi = pytest.importorskip("scipy.ndimage")
+    mask = synth.mask_objects(2, 40, 37, 0.48, 72, 4)
+    any_l = O.mask_downsample_rule(mask, 3, 3, (1, 1), (1, 1), (1, 1), O.RULE_ANY)
+    all_l = O.mask_downsample_rule(mask, 3, 3, (1, 1), (1, 1), (1, 1), O.RULE_ALL)
+    box = np.ones((3, 3), bool)
+    for b in range(2):
+        np.testing.assert_array_equal(any_l[b] != 0, ndi.binary_dilation(mask[b] != 0, structure=box))
+        np.testing.assert_array_equal(all_l[b] != 0, ndi.binary_erosion(mask[b] != 0, structure=box, border_value=1))
+    assert (all_l <= (mask != 0)).all() and ((mask != 0) <= any_l).all()
+    rect = np.zeros((1, 20, 20), np.uint8)
+    rect[0, 5:11, 4:13] = 1                                   # 6 x 9
+    assert O.mask_downsample_rule(rect, 3, 3, (1, 1), (1, 1), (1, 1), O.RULE_ANY).sum() == 8 * 11
+    assert O.mask_downsample_rule(rect, 3, 3, (1, 1), (1, 1), (1, 1), O.RULE_ALL).sum() == 4 * 7
+
+
+def test_labelled_layer_is_the_layer_when_labels_are_the_centre_taps_and_follows_any_labels():
+    n, h, w, ci, co = 2, 11, 13, 4, 5
+    x = synth.from_storage(synth.activations((n, h, w, ci), synth.F32, 73, 1) - 0.3, synth.F32)
+    wt = synth.he_weights(co, 3, 3, ci, synth.F32, 73, 2)
+    b = synth.bias(co, 73, 3)
+    mask = synth.mask_bernoulli(n, h, w, 0.5, 73, 4)
+    s = O.ConvShape(n, h, w, ci, co, 3, 3, (2, 1), (1, 1), (1, 1), relu=True)
+    centre = O.mask_downsample(mask, 3, 3, s.stride, s.pad, s.dil)
+    np.testing.assert_array_equal(O.focused_conv2d_labelled(s, x, wt, centre, bias=b, mask_in=mask),
+                                  O.focused_conv2d(s, x, wt, bias=b, mask_in=mask))
+    # any-pixel labels: kept rows equal the dense layer of the masked input, the rest is zero
+    lab = O.mask_downsample_rule(mask, 3, 3, s.stride, s.pad, s.dil, O.RULE_ANY)
+    got = O.focused_conv2d_labelled(s, x, wt, lab, bias=b, mask_in=mask)
+    xz = (x * (mask != 0)[..., None]).astype(np.float32)
+    dense = O.focused_conv2d(s, xz, wt, bias=b)
+    keep = lab != 0
+    np.testing.assert_array_equal(got[keep], dense[keep])
+    assert not got[~keep].view(np.uint8).any() and keep.sum() > (centre != 0).sum()
