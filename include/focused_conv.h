@@ -106,6 +106,23 @@ int32_t fc_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t
                            int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w,
                            uint8_t *mask_out, void *stream);
 
+/* Patch labels by another rule.  Sec. III-A speaks of "a patch labelled irrelevant"
+ * without saying how a per-pixel mask labels a patch; this library's reading is the
+ * centre tap (fc_mask_downsample, and what fc_focused_conv2d derives by itself).  The
+ * other two readings are offered here: FC_RULE_ANY keeps a patch if any pixel of its
+ * window is relevant (conservative: a margin of context around the relevant region),
+ * FC_RULE_ALL only if all are.  Pixels outside the image are not part of the window; a
+ * window wholly outside is irrelevant.  FC_RULE_CENTRE is fc_mask_downsample.
+ * To run a layer with such labels, compact them (fc_active_index_compact) and pass
+ * mask_out, idx and count to fc_focused_conv2d, with the geometry of that same layer:
+ * taps are still gated by mask_in, rows with label 0 are still zero-filled.
+ * Arguments as fc_mask_downsample; an unknown rule gives FC_ERR_DTYPE. */
+enum { FC_RULE_CENTRE = 0, FC_RULE_ANY = 1, FC_RULE_ALL = 2 };
+int32_t fc_mask_downsample_rule(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
+                                int32_t kh, int32_t kw, int32_t stride_h, int32_t stride_w,
+                                int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w,
+                                int32_t rule, uint8_t *mask_out, void *stream);
+
 /* Which patches become columns (Sec. III-A: an irrelevant patch is not
  * converted).  Writes the ascending list of flat positions p in [0,m) with
  * mask[p] != 0 and their number.  One list serves every layer at that
@@ -148,8 +165,9 @@ int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
  *             layer; idx/count/mask_out must then be NULL too)
  *   w         device, [c_out][kh][kw][c_in], in_dtype, read only
  *   bias      device, c_out floats, or NULL
- *   mask_out  device [n][ho][wo] 0/1 bytes as fc_mask_downsample writes them for
- *             this layer's geometry, or NULL (then derived from mask_in)
+ *   mask_out  device [n][ho][wo] 0/1 bytes as fc_mask_downsample (or
+ *             fc_mask_downsample_rule) writes them for this layer's geometry, or
+ *             NULL (then derived from mask_in by the centre tap)
  *   idx,count device, as fc_active_index_compact writes them from mask_out; both
  *             NULL = computed here into the workspace
  *   out       device, NHWC, out_dtype; must not overlap x

@@ -15,10 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libfocused_conv.so")
 
 F32, BF16, F16 = 0, 1, 2
 RELU, SKIP_ZERO_FILL, WORKSPACE_READY = 1, 2, 4
+RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 WORKSPACE_COUNTER_BYTES = 2048
 
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
-             "fc_mask_downsample", "fc_active_index_compact", "fc_mask_pyramid_dims",
+             "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_dwconv2d",
              "fc_maxpool2d")
 MAX_PYRAMID_LEVELS = 8
@@ -71,6 +72,8 @@ def lib():
         L.fc_compact_workspace_bytes.argtypes = [i64, ctypes.POINTER(ctypes.c_size_t)]
         L.fc_mask_downsample.restype = i32
         L.fc_mask_downsample.argtypes = [vp] + [i32] * 11 + [vp, vp]
+        L.fc_mask_downsample_rule.restype = i32
+        L.fc_mask_downsample_rule.argtypes = [vp] + [i32] * 12 + [vp, vp]
         L.fc_active_index_compact.restype = i32
         L.fc_active_index_compact.argtypes = [vp, i64, vp, vp, vp, ctypes.c_size_t, vp]
         L.fc_mask_pyramid_dims.restype = i32
@@ -158,6 +161,22 @@ def mask_downsample(mask_in, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1), ou
         out = torch.empty((n, ho, wo), dtype=torch.uint8, device=mask_in.device)
     _check(lib().fc_mask_downsample(_ptr(mask_in), n, h, w, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
                                     dil[0], dil[1], _ptr(out), _stream(stream)), "fc_mask_downsample")
+    return out
+
+
+def mask_downsample_rule(mask_in, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1), rule=RULE_CENTRE, out=None,
+                         stream=None):
+    """fc_mask_downsample_rule: patch labels by the centre tap, any pixel or all pixels of the window."""
+    torch = _torch()
+    _require_cuda(mask_in, out)
+    n, h, w = mask_in.shape
+    d = conv_desc(n, h, w, 1, 1, k, stride, pad, dil, F32)
+    ho, wo = out_dims(d)
+    if out is None:
+        out = torch.empty((n, ho, wo), dtype=torch.uint8, device=mask_in.device)
+    _check(lib().fc_mask_downsample_rule(_ptr(mask_in), n, h, w, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
+                                         dil[0], dil[1], rule, _ptr(out), _stream(stream)),
+           "fc_mask_downsample_rule")
     return out
 
 

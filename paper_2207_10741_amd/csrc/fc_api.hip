@@ -126,6 +126,26 @@ int32_t fc_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 
+int32_t fc_mask_downsample_rule(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                                int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t dil_h,
+                                int32_t dil_w, int32_t rule, uint8_t *mask_out, void *stream)
+{
+    if (rule == FC_RULE_CENTRE)
+        return fc_mask_downsample(mask_in, n, h, w, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, mask_out,
+                                  stream);
+    if (rule != FC_RULE_ANY && rule != FC_RULE_ALL) return FC_ERR_DTYPE;
+    if (!mask_in || !mask_out) return FC_ERR_NULL;
+    if (n <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0 || dil_h <= 0 || dil_w <= 0)
+        return FC_ERR_SHAPE;
+    const int32_t ho = out_dim(h, kh, stride_h, pad_h, dil_h), wo = out_dim(w, kw, stride_w, pad_w, dil_w);
+    if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
+    if ((int64_t)n * ho * wo >= INT32_MAX || (int64_t)n * h * w >= INT32_MAX) return FC_ERR_RANGE;
+    const hipError_t e = launch_mask_window(mask_in, n, h, w, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                                            ho, wo, rule == FC_RULE_ALL, mask_out, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
 int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count, void *workspace,
                                 size_t workspace_bytes, void *stream)
 {

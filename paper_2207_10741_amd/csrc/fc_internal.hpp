@@ -98,6 +98,10 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
 hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, int kh, int kw,
                                   int sh, int sw, int ph, int pw, int dh, int dw, int ho, int wo,
                                   uint8_t *mask_out, hipStream_t s);
+// Patch labels by a window rule: any pixel of the window relevant, or all of them.
+hipError_t launch_mask_window(const uint8_t *mask_in, int n, int h, int w, int kh, int kw, int sh, int sw,
+                              int ph, int pw, int dh, int dw, int ho, int wo, bool all, uint8_t *mask_out,
+                              hipStream_t s);
 // What the compaction can do on the side for the convolution that follows it.
 struct CompactExtras {
     int32_t *zero = nullptr; // zero_n ints to clear (the split-K tile counters)

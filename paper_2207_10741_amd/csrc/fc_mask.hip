@@ -40,6 +40,55 @@ hipError_t launch_mask_downsample(const uint8_t *mask_in, int n, int h, int w, i
 }
 
 // ---------------------------------------------------------------------------
+// Patch labels by a window rule (the other readings of "a patch labelled irrelevant",
+// Sec. III-A): kept if ANY pixel of the window is relevant, or only if ALL are.  Pixels
+// outside the image are not part of the window.  One thread per output byte; the
+// window's mask bytes come through the cache (neighbouring positions share them).
+// ---------------------------------------------------------------------------
+template <bool ALL>
+__global__ __launch_bounds__(256) void k_mask_window(const uint8_t *__restrict__ mask_in, int n, int h, int w,
+                                                     int kh, int kw, int sh, int sw, int ph, int pw, int dh,
+                                                     int dw, int ho, int wo, uint8_t *__restrict__ mask_out)
+{
+    const int64_t total = (int64_t)n * ho * wo;
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total;
+         p += (int64_t)gridDim.x * blockDim.x) {
+        const int ow = (int)(p % wo);
+        const int64_t t = p / wo;
+        const int oh = (int)(t % ho);
+        const uint8_t *img = mask_in + (t / ho) * ((int64_t)h * w);
+        int inside = 0, relevant = 0;
+        for (int i = 0; i < kh; ++i) {
+            const int ih = oh * sh - ph + i * dh;
+            if (ih < 0 || ih >= h) continue;
+            for (int j = 0; j < kw; ++j) {
+                const int iw = ow * sw - pw + j * dw;
+                if (iw < 0 || iw >= w) continue;
+                ++inside;
+                relevant += img[(int64_t)ih * w + iw] != 0;
+            }
+        }
+        mask_out[p] = ALL ? (inside > 0 && relevant == inside) : (relevant > 0);
+    }
+}
+
+hipError_t launch_mask_window(const uint8_t *mask_in, int n, int h, int w, int kh, int kw, int sh, int sw,
+                              int ph, int pw, int dh, int dw, int ho, int wo, bool all, uint8_t *mask_out,
+                              hipStream_t s)
+{
+    const int64_t total = (int64_t)n * ho * wo;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 65536) blocks = 65536;
+    if (all)
+        hipLaunchKernelGGL(k_mask_window<true>, dim3(blocks), dim3(256), 0, s, mask_in, n, h, w, kh, kw, sh, sw, ph,
+                           pw, dh, dw, ho, wo, mask_out);
+    else
+        hipLaunchKernelGGL(k_mask_window<false>, dim3(blocks), dim3(256), 0, s, mask_in, n, h, w, kh, kw, sh, sw, ph,
+                           pw, dh, dw, ho, wo, mask_out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Ordered compaction, fused with the mask propagation.  A block owns 4096
 // consecutive output positions, a lane 16 of them.  The output-resolution mask is
 // never needed as an input: every kernel recomputes a position's flag from the

@@ -29,6 +29,49 @@ def test_mask_downsample_bit_exact(n, h, w, k, s, p, d):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("n,h,w,k,s,p,d", [
+    (2, 57, 43, 3, 1, 1, 1), (1, 56, 56, 3, 2, 1, 1), (2, 33, 35, (5, 3), (1, 2), (2, 0), (1, 2)),
+    (1, 135, 241, 2, 2, 0, 1), (1, 7, 7, 3, 1, 4, 1), (1, 9, 300, 1, 2, 0, 1), (3, 224, 224, 7, 2, 3, 1),
+])
+@pytest.mark.parametrize("rule", [B.RULE_CENTRE, B.RULE_ANY, B.RULE_ALL])
+def test_window_rule_labels_bit_exact(n, h, w, k, s, p, d, rule):
+    pair = lambda v: tuple(v) if isinstance(v, (tuple, list)) else (v, v)
+    k, s, p, d = pair(k), pair(s), pair(p), pair(d)
+    mask = synth.mask_bernoulli(n, h, w, 0.5, 103, h, w) * np.uint8(7)
+    got = B.mask_downsample_rule(G.mask_dev(mask), k, s, p, d, rule).cpu().numpy()
+    np.testing.assert_array_equal(got, O.mask_downsample_rule(mask, k[0], k[1], s, p, d, rule))
+
+
+@pytest.mark.parametrize("rule", [B.RULE_ANY, B.RULE_ALL])
+@pytest.mark.parametrize("layer", [(2, 40, 56, 64, 128, 3, 1, 1, 1), (1, 19, 23, 64, 128, 3, 2, 1, 1),
+                                   (2, 30, 41, 24, 40, 3, 1, 1, 1)])
+def test_layer_with_window_rule_labels_matches_oracle(layer, rule):
+    """Labels from the any-pixel / all-pixels rule, compacted and handed to the layer."""
+    torch = G.torch_mod()
+    n, h, w, ci, co, k, s, p, d = layer
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 104, 1)
+    wt = synth.he_weights(co, k, k, ci, dtype, 104, 2)
+    bias = synth.bias(co, 104, 3)
+    mask = synth.mask_objects(n, h, w, 0.48, 104, 4)
+    md = G.mask_dev(mask)
+    labels = B.mask_downsample_rule(md, (k, k), (s, s), (p, p), (d, d), rule)
+    idx, count = B.active_index_compact(labels)
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s, s), (p, p), (d, d), dtype, B.F32, B.RELU)
+    ho, wo = B.out_dims(desc)
+    out = torch.full((n, ho, wo, co), 7.0, dtype=torch.float32, device=G.dev())
+    B.focused_conv2d(desc, G.to_dev(x, dtype), G.to_dev(wt, dtype), torch.from_numpy(bias).to(G.dev()), mask_in=md,
+                     mask_out=labels, idx=idx, count=count, out=out)
+    torch.cuda.synchronize()
+    want_labels = O.mask_downsample_rule(mask, k, k, (s, s), (p, p), (d, d), rule)
+    np.testing.assert_array_equal(labels.cpu().numpy(), want_labels)
+    want = O.focused_conv2d_labelled(O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=True), x, wt,
+                                     want_labels, bias=bias, mask_in=mask, dtype=dtype)
+    keep = want_labels != 0
+    assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()
+
+
 @pytest.mark.parametrize("m", [1, 15, 16, 17, 63, 64, 65, 4095, 4096, 4097, 8192, 12289, 100003, 1 << 20, 3000017])
 @pytest.mark.parametrize("irr", [0.48, 0.0, 1.0, 0.97])
 def test_active_index_compact_bit_exact(m, irr):

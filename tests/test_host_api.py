@@ -80,6 +80,11 @@ def test_null_pointers_rejected_before_any_launch():
     assert L.fc_focused_conv2d(ctypes.byref(d), None, None, None, None, None, None, None, None, None, 0, None) == -1
     assert L.fc_mask_downsample(None, 1, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, None, None) == -1
     assert L.fc_active_index_compact(None, 10, None, None, None, 0, None) == -1
+    assert L.fc_mask_downsample_rule(None, 1, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, 1, None, None) == -1
+    assert L.fc_mask_downsample_rule(ctypes.c_void_p(0x1000), 1, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, 7,
+                                     ctypes.c_void_p(0x2000), None) == -3     # unknown rule
+    assert L.fc_mask_downsample_rule(ctypes.c_void_p(0x1000), 1, 8, 8, 3, 3, 0, 1, 1, 1, 1, 1, 2,
+                                     ctypes.c_void_p(0x2000), None) == -2
     assert L.fc_maxpool2d(None, 1, 8, 8, 8, 0, 2, 2, 0, None, None) == -1
     # fake but well-formed addresses: the checks below fail before anything touches them
     a = ctypes.c_void_p(0x1000)
