@@ -168,6 +168,9 @@ STACKS = {
                  "ResNet-50 bottleneck convs on the post-stem activation of 480x640 images, batch 32, "
                  "per-image irrelevant share uniform in [0.3, 0.7]"),
     "vgg16": ("vgg16", 8, 1080, 1920, 3, "VGG-16 convs on 1080x1920 frames, batch 8, depth-ramp mask, 50 % irrelevant"),
+    "mobilenetv2": ("mobilenetv2", 32, 224, 224, 3,
+                    "MobileNetV2 backbone convs (1x1 / depthwise 3x3 / 1x1 blocks), batch 32, 224x224x3, boxes + sky "
+                    "band, 48 % irrelevant"),
 }
 
 
@@ -177,7 +180,9 @@ def stack_bench(torch, B, synth, workloads, args):
     outputs left unwritten at irrelevant rows.  One HIP graph replay per pass."""
     from paper_2207_10741_amd.stacks import ConvStack
     fn_name, n, h, w, c_in, what = STACKS[args.stack]
-    n = n if args.batch is None else args.batch
+    if args.batch is not None:
+        what = what.replace("batch %d" % n, "batch %d" % args.batch)
+        n = args.batch
     ops = getattr(workloads, fn_name)()
     if args.stack == "resnet50":
         shares = list(synth.rng(3, 0, 5).uniform(0.3, 0.7, size=n))
@@ -197,9 +202,9 @@ def stack_bench(torch, B, synth, workloads, args):
     torch.cuda.synchronize()
     dense_flops = kept_flops = 0.0
     for i, op in enumerate(ops):
-        if op.kind != "conv":
+        if op.kind not in ("conv", "dwconv"):
             continue
-        per_pos = 2.0 * op.k * op.k * op.c_in * op.c_out
+        per_pos = 2.0 * op.k * op.k * op.c_in * (op.c_out if op.kind == "conv" else 1)
         dense_flops += masks[i].numel() * per_pos
         kept_flops += float(torch.count_nonzero(masks[i]).item()) * per_pos
     del masks
@@ -223,7 +228,7 @@ def stack_bench(torch, B, synth, workloads, args):
     t_strict, _ = timed(mask=md)
     t_chain, _ = timed(mask=md, chain=True)
     print(json.dumps({
-        "stack": args.stack, "workload": what, "batch": n, "convs": sum(op.kind == "conv" for op in ops),
+        "stack": args.stack, "workload": what, "batch": n, "convs": sum(op.kind in ("conv", "dwconv") for op in ops),
         "launch": how, "steps": args.steps, "dtype": "bf16", "data": "synthetic",
         "kept_flop_share": round(kept_flops / dense_flops, 4),
         "dense_ms": round(t_dense * 1e3, 4), "dense_tflops": round(dense_flops / t_dense / 1e12, 2),

@@ -1,7 +1,8 @@
 """Runs a conv stack (workloads.Op list) through the library: mask propagation and
 kept-position lists are built once per (mask, window geometry) and shared by every
 layer that sees the same mask through the same geometry (Sec. III-B: one mask,
-rescaled per layer); each conv is one fc_focused_conv2d call.
+rescaled per layer); each conv is one fc_focused_conv2d call, each depthwise conv one
+fc_focused_dwconv2d call.
 
 Plumbing only: the order of library calls and which tensor feeds which.  Max-pools
 (not part of the paper's method) go through the library's helper.
@@ -29,9 +30,12 @@ class ConvStack:
         self.host_weights: Dict[int, np.ndarray] = {}
         self.host_biases: Dict[int, np.ndarray] = {}
         for i, op in enumerate(self.ops):
-            if op.kind != "conv":
+            if op.kind not in ("conv", "dwconv"):
                 continue
-            wt = synth.he_weights(op.c_out, op.k, op.k, op.c_in, dtype, seed, i, 2)
+            if op.kind == "dwconv":
+                wt = np.ascontiguousarray(synth.he_weights(op.c_out, op.k, op.k, 1, dtype, seed, i, 2)[..., 0])
+            else:
+                wt = synth.he_weights(op.c_out, op.k, op.k, op.c_in, dtype, seed, i, 2)
             bs = synth.bias(op.c_out, seed, i, 3)
             self.host_weights[i], self.host_biases[i] = wt, bs
             self.weights[i] = self._to_dev(wt)
@@ -103,8 +107,8 @@ class ConvStack:
                     m_out = B.mask_downsample(m_in, *geo)
                     idx, count = B.active_index_compact(m_out)
                     plan = plans[key] = produced[id(m_out)] = (m_out, idx, count)
-            if op.kind == "conv":
-                gated_readers_only = bool(readers.get(i)) and all(k == "conv" for k in readers[i])
+            if op.kind in ("conv", "dwconv"):
+                gated_readers_only = bool(readers.get(i)) and all(k in ("conv", "dwconv") for k in readers[i])
                 skip = chain and plan is not None and gated_readers_only
                 d = self.desc(i, flags_extra=B.WORKSPACE_READY | (B.SKIP_ZERO_FILL if skip else 0))
                 out = None
@@ -112,7 +116,12 @@ class ConvStack:
                     ho, wo = self.sizes[i]
                     out = self.torch.full((self.n, ho, wo, op.c_out), canary, dtype=B.torch_dtype(self.dtype),
                                           device=self.dev)
-                if plan is None:
+                if op.kind == "dwconv":
+                    # labels come from the input mask inside the call: no list, no workspace
+                    d.flags &= ~B.WORKSPACE_READY
+                    outs[i] = B.focused_dwconv2d(d, src, self.weights[i], self.biases[i],
+                                                 mask_in=m_in if plan is not None else None, out=out)
+                elif plan is None:
                     outs[i] = B.focused_conv2d(d, src, self.weights[i], self.biases[i], out=out,
                                                workspace=self.workspace)
                 else:
@@ -131,10 +140,10 @@ class ConvStack:
         """(dense FLOPs, kept FLOPs) of the stack; kept needs the host copies of the masks."""
         dense = kept = 0.0
         for i, op in enumerate(self.ops):
-            if op.kind != "conv":
+            if op.kind not in ("conv", "dwconv"):
                 continue
             ho, wo = self.sizes[i]
-            per_pos = 2.0 * op.k * op.k * op.c_in * op.c_out
+            per_pos = 2.0 * op.k * op.k * op.c_in * (op.c_out if op.kind == "conv" else 1)
             dense += self.n * ho * wo * per_pos
             if masks_host is not None:
                 kept += float(np.count_nonzero(masks_host[i])) * per_pos

@@ -15,7 +15,7 @@ from typing import List
 
 @dataclass(frozen=True)
 class Op:
-    kind: str      # "conv" or "maxpool"
+    kind: str      # "conv", "dwconv" (one filter per channel; c_out == c_in) or "maxpool"
     name: str
     c_in: int
     c_out: int
@@ -80,6 +80,27 @@ def vgg16() -> List[Op]:
             c_prev = c
         if i < 13:
             ops.append(Op("maxpool", "pool%d" % i, c, c, 2, 2, 0, len(ops) - 1))
+    return ops
+
+
+def mobilenetv2() -> List[Op]:
+    """The 52 convs of a MobileNetV2 backbone (SSD-Lite's backbone, Sec. IV): 3x3/2 stem, 17
+    inverted-residual blocks (1x1 expansion - none in the first block -, 3x3 depthwise, 1x1
+    projection), the final 1x1.  No residual adds; like the other stacks every conv is followed
+    by ReLU, the projections too, which keeps magnitudes steady under He-normal weights."""
+    ops: List[Op] = [Op("conv", "stem", 3, 32, 3, 2, 1, -1)]
+    c_prev = 32
+    settings = ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2),
+                (6, 320, 1, 1))
+    for bi, (t, c, reps, s) in enumerate(settings):
+        for r in range(reps):
+            mid = c_prev * t
+            if t != 1:
+                ops.append(Op("conv", "b%dr%d_expand" % (bi, r), c_prev, mid, 1, 1, 0, len(ops) - 1))
+            ops.append(Op("dwconv", "b%dr%d_dw" % (bi, r), mid, mid, 3, s if r == 0 else 1, 1, len(ops) - 1))
+            ops.append(Op("conv", "b%dr%d_project" % (bi, r), mid, c, 1, 1, 0, len(ops) - 1))
+            c_prev = c
+    ops.append(Op("conv", "head", c_prev, 1280, 1, 1, 0, len(ops) - 1))
     return ops
 
 

@@ -163,15 +163,22 @@ def _check_stack(ops, n, h, w, c_in, mask, seed):
             assert torch.equal(outs[i].float(), ref.permute(0, 2, 3, 1).contiguous()), op.name
             continue
         shape = O.ConvShape(n, hi, wi, op.c_in, op.c_out, op.k, op.k, (op.stride,) * 2, (op.pad,) * 2, (1, 1), relu=True)
-        want = O.focused_conv2d(shape, src, stack.host_weights[i], bias=stack.host_biases[i], mask_in=m_in, dtype=dtype)
         keep = m_out != 0
         # accumulation gate on an fp32-output call with the same device inputs
-        o32 = B.focused_conv2d(stack.desc(i, out_dtype=B.F32), outs[op.src], stack.weights[i], stack.biases[i],
-                               mask_in=masks[op.src])
+        if op.kind == "dwconv":
+            want = O.focused_dwconv2d(shape, src, stack.host_weights[i], bias=stack.host_biases[i], mask_in=m_in,
+                                      dtype=dtype)
+            o32 = B.focused_dwconv2d(stack.desc(i, out_dtype=B.F32), outs[op.src], stack.weights[i], stack.biases[i],
+                                     mask_in=masks[op.src])
+        else:
+            want = O.focused_conv2d(shape, src, stack.host_weights[i], bias=stack.host_biases[i], mask_in=m_in,
+                                    dtype=dtype)
+            o32 = B.focused_conv2d(stack.desc(i, out_dtype=B.F32), outs[op.src], stack.weights[i], stack.biases[i],
+                                   mask_in=masks[op.src])
         assert G.rel_err(G.to_f64(o32), want, keep) <= TOL_F32_OUT, op.name
         assert torch.equal(outs[i], o32.to(outs[i].dtype)), op.name
         assert not G.to_storage_np(outs[i], dtype)[~keep].any(), op.name
-        macs = op.k * op.k * op.c_in * op.c_out
+        macs = op.k * op.k * op.c_in * (op.c_out if op.kind == "conv" else 1)
         dense_macs += keep.size * macs
         kept_macs += int(keep.sum()) * macs
     return kept_macs / dense_macs
@@ -200,6 +207,16 @@ def test_resnet50_bottlenecks_small_batch():
     _check_stack(workloads.resnet50_bottlenecks(), n, h, w, 64, mask, 365)
 
 
+def test_mobilenetv2_stack_layer_by_layer():
+    """All 52 convs of the MobileNetV2-shaped stack (1x1 / depthwise 3x3 / 1x1 blocks) on small images."""
+    n, h, w = 2, 96, 128
+    mask = synth.mask_objects(n, h, w, [0.4, 0.55], 372)
+    ops = workloads.mobilenetv2()
+    assert sum(op.kind == "dwconv" for op in ops) == 17 and sum(op.kind == "conv" for op in ops) == 35
+    ratio = _check_stack(ops, n, h, w, 3, mask, 373)
+    assert abs(ratio - (1.0 - synth.irrelevant_fraction(mask))) < 0.07
+
+
 def test_chain_mode_never_reads_the_unwritten_rows():
     """Convs read only by convs leave their irrelevant rows unwritten; the readers gate their
     taps by the same mask, so every kept output is bit-identical to the zero-filled run even
@@ -209,6 +226,7 @@ def test_chain_mode_never_reads_the_unwritten_rows():
     for ops, (n, h, w, c_in), mask in (
         (workloads.resnet50_bottlenecks()[:13], (2, 48, 64, 64), synth.mask_objects(2, 48, 64, [0.4, 0.6], 366)),
         (workloads.vgg16()[:8], (1, 48, 64, 3), synth.mask_depth_ramp(1, 48, 64, 0.5, 367)),
+        (workloads.mobilenetv2()[:12], (2, 64, 96, 3), synth.mask_objects(2, 64, 96, [0.4, 0.6], 369)),
     ):
         stack = ConvStack(ops, n, h, w, dtype, seed=368)
         x = G.to_dev(synth.activations((n, h, w, c_in), dtype, 368, 1), dtype)
@@ -224,9 +242,9 @@ def test_chain_mode_never_reads_the_unwritten_rows():
             keep = masks[i].bool()
             a, b = strict[i], chained[i]
             assert torch.equal(a[keep].view(torch.int16), b[keep].view(torch.int16)), op.name
-            if op.kind != "conv":
+            if op.kind not in ("conv", "dwconv"):
                 continue
-            if readers.get(i) and all(k == "conv" for k in readers[i]):
+            if readers.get(i) and all(k in ("conv", "dwconv") for k in readers[i]):
                 assert torch.isnan(b[~keep].float()).all(), op.name      # untouched canary
                 skipped += 1
             else:
