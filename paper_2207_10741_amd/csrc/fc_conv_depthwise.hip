@@ -38,26 +38,6 @@ constexpr int kDwTargetBlocks = 1024;            // about four workgroups per CU
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// n / d for n < 2^31 as a multiply and a shift: s = ceil(log2 d), m = ceil(2^(31+s) / d);
-// m*d = 2^(31+s) + e with e < d <= 2^s, so the estimate is off by less than 1/d.
-struct FastDiv {
-    uint32_t m, s;
-};
-
-FastDiv make_fastdiv(uint32_t d)
-{
-    FastDiv f;
-    f.s = 0;
-    while ((1ull << f.s) < d) ++f.s;
-    f.m = (uint32_t)(((1ull << (31 + f.s)) + d - 1) / d);
-    return f;
-}
-
-__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f)
-{
-    return (uint32_t)(((uint64_t)n * f.m) >> (31 + f.s));
-}
-
 struct DwArgs {
     Geom g;
     int32_t lanes_per_pos; // channel chunks of one position handled by one workgroup

@@ -22,6 +22,10 @@ constexpr int kStemCo = 64;         // output channels per workgroup
 constexpr int kStemMaxK = 160;      // padded reduction length the tables are sized for (7x7x3 = 147)
 constexpr int kStemMaxTaps = 64;    // tap-valid bits live in one 64-bit word per position
 
+// bytes per weight row in LDS: the padded reduction plus one 16-byte piece, so that the 32
+// rows a wave reads together start in different banks
+__host__ __device__ static inline int stem_weight_pitch(int ksteps) { return ksteps * 32 + 16; }
+
 bool conv_stem_supported(const Geom &g, int in_dtype, int out_dtype)
 {
     if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
@@ -31,12 +35,18 @@ bool conv_stem_supported(const Geom &g, int in_dtype, int out_dtype)
     // element offset of the last tap from the first one, packed into 24 bits of a table entry
     const int64_t far = ((int64_t)(g.kh - 1) * g.dh * g.w + (int64_t)(g.kw - 1) * g.dw) * g.c_in + g.c_in;
     if (far >= (1 << 24)) return false;
+    if ((int64_t)(g.kh - 1) * g.dh >= 65536 || (int64_t)(g.kw - 1) * g.dw >= 65536) return false; // 16-bit tap offsets
     if ((int64_t)g.n * g.h * g.w * g.c_in >= INT32_MAX) return false; // 32-bit element indices
     return true;
 }
 
+// divisors of the position decode, prepared on the host
+struct StemDivs {
+    FastDiv wo, ho;
+};
+
 template <int DT, typename TO>
-__global__ __launch_bounds__(kStemThreads) void k_conv_stem(Geom g, const uint16_t *__restrict__ x,
+__global__ __launch_bounds__(kStemThreads, 5) void k_conv_stem(Geom g, StemDivs dv, const uint16_t *__restrict__ x,
                                                             const uint8_t *__restrict__ mask_in,
                                                             const uint16_t *__restrict__ w,
                                                             const float *__restrict__ bias,
@@ -44,18 +54,22 @@ __global__ __launch_bounds__(kStemThreads) void k_conv_stem(Geom g, const uint16
                                                             const int32_t *__restrict__ count,
                                                             TO *__restrict__ out)
 {
-    constexpr int WPITCH = kStemMaxK * 2 + 16;                 // bytes per weight row in LDS
     constexpr int OP = kStemCo * (int)sizeof(TO) + 16;         // bytes per output row in LDS
-    __shared__ __align__(16) unsigned char w_s[kStemCo * WPITCH];   // [channel][k] as stored
-    __shared__ __align__(16) unsigned char o_s[kStemRows * OP];
-    __shared__ __align__(16) uint32_t lut[kStemMaxK];               // tap << 24 | element offset
-    __shared__ int32_t row_p[kStemRows];
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int rows = idx ? *count : g.m;
     const int taps = g.kh * g.kw;
     const int K = taps * g.c_in;
     const int ksteps = (K + 15) / 16;
+    // LDS, sized by the launcher for this layer's reduction length (a 3x3x3 stem needs 24 KB,
+    // so six workgroups share a CU and hide each other's gather latency)
+    const int WPITCH = stem_weight_pitch(ksteps);                   // bytes per weight row
+    extern __shared__ __align__(16) unsigned char stem_lds[];
+    unsigned char *o_s = stem_lds;                                  // [rows][OP]
+    unsigned char *w_s = o_s + kStemRows * OP;                      // [channel][k] as stored
+    uint32_t *lut = reinterpret_cast<uint32_t *>(w_s + kStemCo * WPITCH); // tap << 24 | element offset
+    int32_t *row_p = reinterpret_cast<int32_t *>(lut + ksteps * 16);
+    float *bias_s = reinterpret_cast<float *>(row_p + kStemRows);   // [channel]
+    uint32_t *tap_s = reinterpret_cast<uint32_t *>(bias_s + kStemCo); // [tap] kh*dh | kw*dw << 16
     const int co0 = blockIdx.y * kStemCo;
 
     // ---- once per workgroup: weights and the reduction-index table ----
@@ -74,49 +88,100 @@ __global__ __launch_bounds__(kStemThreads) void k_conv_stem(Geom g, const uint16
         }
         lut[k] = e;
     }
+    if (tid < kStemCo) bias_s[tid] = (bias && co0 + tid < g.c_out) ? bias[co0 + tid] : 0.f;
+    if (tid < kStemMaxTaps) {
+        const int kh = tid / g.kw, kw = tid - kh * g.kw;
+        tap_s[tid] = tid < taps ? (uint32_t)(kh * g.dh) | ((uint32_t)(kw * g.dw) << 16) : 0u;
+    }
     __syncthreads();
-
-    // bias of this lane's channels (channel = cb*32 + (i/4)*8 + half*4 + i%4 of accumulator i)
-    float4 bias_q[2][4];
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int co = co0 + cb * 32 + q * 8 + half * 4;
-            bias_q[cb][q] = (bias && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
-                                                    : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+    const uint64_t all_taps = taps >= 64 ? ~0ull : ((1ull << taps) - 1ull);
+    const int reach_h = (g.kh - 1) * g.dh, reach_w = (g.kw - 1) * g.dw;
 
     const int ntiles = (rows + kStemRows - 1) / kStemRows;
-    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-        // ---- this lane's position and its tap-valid bits ----
+    // ---- locating a tile's rows, in pieces so that the memory round trips of the NEXT tile
+    // (position list, then mask bytes) run under the gathers, MFMAs and stores of the current
+    // one.  Piece 1: the list entry.  Piece 2: decode it and request the first sixteen taps'
+    // mask bytes (eight per half-wave).  Piece 3: tap-valid bits from those bytes, the remaining
+    // taps (kernels with more than sixteen) fetched on the spot, halves merged. ----
+    struct Located {
+        int p, base, ih0, iw0;
+        const uint8_t *mimg;
+        bool lookup;       // bits have to be built tap by tap
+        bool inside[8];
+        uint8_t mb[8];
+    };
+    auto fetch_entry = [&](int tile) -> int {
         const int r = tile * kStemRows + wave * 32 + (lane & 31);
-        int p = -1, base = 0;
-        uint64_t bits = 0;
-        if (r < rows) {
-            p = idx ? idx[r] : r;
-            const int ow = p % g.wo;
-            const int q = p / g.wo;
-            const int oh = q % g.ho;
-            const int b = q / g.ho;
-            const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
-            base = ((b * g.h + ih0) * g.w + iw0) * g.c_in; // may point before the image: only used with a valid tap
+        return r < rows ? (idx ? idx[r] : r) : -1;
+    };
+    auto request_taps = [&](const Located &L, int t0, bool (&inside)[8], uint8_t (&mb)[8]) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int t = t0 + 2 * u;
+            const uint32_t e = tap_s[t & (kStemMaxTaps - 1)];
+            const int ih = L.ih0 + (int)(e & 0xffffu), iw = L.iw0 + (int)(e >> 16);
+            inside[u] = t < taps && ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
+            mb[u] = 1;
+            // a tap outside the image reads the image's first pixel instead and is dropped afterwards
+            if (L.mimg) mb[u] = L.mimg[inside[u] ? ih * g.w + iw : 0];
+        }
+    };
+    auto decode = [&](int p, Located &L) {
+        L.p = p;
+        L.base = 0;
+        L.ih0 = L.iw0 = 0;
+        L.mimg = nullptr;
+        L.lookup = false;
+        if (p >= 0) {
+            const int q = (int)fast_div((uint32_t)p, dv.wo);
+            const int ow = p - q * g.wo;
+            const int b = (int)fast_div((uint32_t)q, dv.ho);
+            const int oh = q - b * g.ho;
+            L.ih0 = oh * g.sh - g.ph;
+            L.iw0 = ow * g.sw - g.pw;
+            L.base = ((b * g.h + L.ih0) * g.w + L.iw0) * g.c_in; // may point before the image: only used with a valid tap
+            L.mimg = mask_in ? mask_in + (int64_t)b * g.h * g.w : nullptr;
+            const bool interior = L.ih0 >= 0 && L.ih0 + reach_h < g.h && L.iw0 >= 0 && L.iw0 + reach_w < g.w;
+            L.lookup = mask_in || !interior; // else every tap is inside the image and nothing gates it
             // the two halves of the wave own the same positions: each looks at half of the taps
-            for (int t = half; t < taps; t += 2) {
-                const int kh = t / g.kw, kw = t - kh * g.kw;
-                const int ih = ih0 + kh * g.dh, iw = iw0 + kw * g.dw;
-                bool ok = ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
-                if (ok && mask_in) ok = mask_in[((int64_t)b * g.h + ih) * g.w + iw] != 0;
-                bits |= (uint64_t)ok << t;
+            if (L.lookup) request_taps(L, half, L.inside, L.mb);
+        }
+    };
+    auto finish = [&](const Located &L) -> uint64_t {
+        uint64_t bits = 0;
+        if (L.p >= 0) {
+            if (!L.lookup) {
+                bits = all_taps;
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) bits |= (uint64_t)(L.inside[u] && L.mb[u] != 0) << ((half + 2 * u) & 63);
+                for (int t0 = half + 16; t0 < taps; t0 += 16) {
+                    bool inside[8];
+                    uint8_t mb[8];
+                    request_taps(L, t0, inside, mb);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) bits |= (uint64_t)(inside[u] && mb[u] != 0) << ((t0 + 2 * u) & 63);
+                }
             }
         }
-        {
-            // merge the halves' bits
-            const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
-            const uint32_t lo2 = lo | (uint32_t)__shfl_xor((int)lo, 32, 64);
-            const uint32_t hi2 = hi | (uint32_t)__shfl_xor((int)hi, 32, 64);
-            bits = (uint64_t)lo2 | ((uint64_t)hi2 << 32);
-        }
+        // merge the halves' bits
+        const uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
+        const uint32_t lo2 = lo | (uint32_t)__shfl_xor((int)lo, 32, 64);
+        const uint32_t hi2 = hi | (uint32_t)__shfl_xor((int)hi, 32, 64);
+        return (uint64_t)lo2 | ((uint64_t)hi2 << 32);
+    };
+
+    Located nxt;
+    uint64_t bits_n = 0;
+    if ((int)blockIdx.x < ntiles) {
+        decode(fetch_entry(blockIdx.x), nxt);
+        bits_n = finish(nxt);
+    }
+    for (int tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int p = nxt.p, base = nxt.base;
+        const uint64_t bits = bits_n;
+        const bool more = tile + (int)gridDim.x < ntiles;
+        const int entry_n = more ? fetch_entry(tile + gridDim.x) : -1; // piece 1 of the next tile
         if (half == 0) row_p[wave * 32 + (lane & 31)] = p;
 
         f32x16_t acc[2];
@@ -124,10 +189,12 @@ __global__ __launch_bounds__(kStemThreads) void k_conv_stem(Geom g, const uint16
         for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                acc[cb][q * 4 + 0] = bias_q[cb][q].x;
-                acc[cb][q * 4 + 1] = bias_q[cb][q].y;
-                acc[cb][q * 4 + 2] = bias_q[cb][q].z;
-                acc[cb][q * 4 + 3] = bias_q[cb][q].w;
+                // channel = cb*32 + (i/4)*8 + half*4 + i%4 of accumulator i
+                const float4 bq = *reinterpret_cast<const float4 *>(bias_s + cb * 32 + q * 8 + half * 4);
+                acc[cb][q * 4 + 0] = bq.x;
+                acc[cb][q * 4 + 1] = bq.y;
+                acc[cb][q * 4 + 2] = bq.z;
+                acc[cb][q * 4 + 3] = bq.w;
             }
 
         for (int j = 0; j < ksteps; ++j) {
@@ -154,6 +221,8 @@ __global__ __launch_bounds__(kStemThreads) void k_conv_stem(Geom g, const uint16
                 acc[cb] = mfma32<DT>(wf, xf, acc[cb]);
             }
         }
+
+        if (more) decode(entry_n, nxt); // piece 2 of the next tile: its mask bytes travel during the epilogue
 
         // ---- epilogue: ReLU, one rounding, transposed through LDS, 16-byte row pieces ----
         __syncthreads(); // the previous tile's stores have read o_s; row_p is complete
@@ -192,6 +261,7 @@ __global__ __launch_bounds__(kStemThreads) void k_conv_stem(Geom g, const uint16
                 __builtin_nontemporal_store(*reinterpret_cast<const u32x4_t *>(o_s + rr * OP + pc * 16),
                                             reinterpret_cast<u32x4_t *>(out + (int64_t)pp * g.c_out + co));
         }
+        if (more) bits_n = finish(nxt); // piece 3
         __syncthreads(); // everyone is done with row_p and o_s before the next tile rewrites them
     }
 }
@@ -206,7 +276,13 @@ static hipError_t launch_stem_t(const Geom &g, const void *x, const uint8_t *mas
     const int64_t tiles = ((int64_t)g.m + kStemRows - 1) / kStemRows;
     const int gx = (int)(tiles > 2048 ? 2048 : tiles);
     const int gy = (g.c_out + kStemCo - 1) / kStemCo;
-    hipLaunchKernelGGL((k_conv_stem<DT, TO>), dim3(gx, gy), dim3(kStemThreads), 0, s, g, (const uint16_t *)x,
+    const int ksteps = (g.kh * g.kw * g.c_in + 15) / 16;
+    const size_t lds = (size_t)kStemRows * (kStemCo * sizeof(TO) + 16) + (size_t)kStemCo * stem_weight_pitch(ksteps) +
+                       (size_t)ksteps * 16 * sizeof(uint32_t) + (size_t)kStemRows * sizeof(int32_t) + (size_t)kStemCo * sizeof(float) + (size_t)kStemMaxTaps * sizeof(uint32_t);
+    StemDivs dv;
+    dv.wo = make_fastdiv((uint32_t)g.wo);
+    dv.ho = make_fastdiv((uint32_t)g.ho);
+    hipLaunchKernelGGL((k_conv_stem<DT, TO>), dim3(gx, gy), dim3(kStemThreads), lds, s, g, dv, (const uint16_t *)x,
                        mask_in, (const uint16_t *)w, bias, idx, count, (TO *)out);
     return hipGetLastError();
 }

@@ -49,6 +49,26 @@ __device__ __forceinline__ void from_float(float f, float *o) { *o = f; }
 __device__ __forceinline__ void from_float(float f, bf16_t *o) { o->bits = bf16_bits_rne(f); }
 __device__ __forceinline__ void from_float(float f, f16_t *o) { o->bits = f16_bits_rne(f); }
 
+// n / d for n < 2^31 as a multiply and a shift: s = ceil(log2 d), m = ceil(2^(31+s) / d);
+// m*d = 2^(31+s) + e with e < d <= 2^s, so the estimate is off by less than 1/d.
+struct FastDiv {
+    uint32_t m, s;
+};
+
+static inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.s = 0;
+    while ((1ull << f.s) < d) ++f.s;
+    f.m = (uint32_t)(((1ull << (31 + f.s)) + d - 1) / d);
+    return f;
+}
+
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f)
+{
+    return (uint32_t)(((uint64_t)n * f.m) >> (31 + f.s));
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 constexpr int kCompactBlockThreads = 256;

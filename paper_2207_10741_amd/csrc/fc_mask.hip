@@ -427,15 +427,36 @@ __device__ __forceinline__ bool position_kept(const Geom &g, const uint8_t *__re
     return mask_in[((int64_t)b * g.h + ih) * g.w + iw] != 0;
 }
 
+// Rows of whole 16-byte pieces: a wave looks at 64 positions at a time (one label each), lists
+// the irrelevant ones in LDS in order, and then all its lanes store 16-byte pieces of those
+// rows, so the stores are dense and none of them waits for a label.  The labels of the next 64
+// positions are requested before the stores of the current ones.
 __global__ __launch_bounds__(256) void k_zero_fill16(Geom g, const uint8_t *__restrict__ mask_in,
                                                      const uint8_t *__restrict__ mask_out,
                                                      uint4 *__restrict__ out, int chunks_per_row)
 {
-    const int64_t total = (int64_t)g.m * chunks_per_row;
-    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < total;
-         c += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t p = c / chunks_per_row;
-        if (!position_kept(g, mask_in, mask_out, p)) out[c] = make_uint4(0, 0, 0, 0);
+    __shared__ int32_t dropped_s[4][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t *dropped = dropped_s[wave];
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int64_t step = nwaves * 64;
+    typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+    const u32x4_nt zero4 = {0u, 0u, 0u, 0u};
+    u32x4_nt *o4 = reinterpret_cast<u32x4_nt *>(out);
+    int64_t p0 = ((int64_t)blockIdx.x * 4 + wave) * 64;
+    bool kept = p0 + lane >= g.m || position_kept(g, mask_in, mask_out, p0 + lane);
+    for (; p0 < g.m; p0 += step) {
+        const uint64_t drop = __ballot(!kept);
+        const int nd = __popcll(drop);
+        if (!kept) dropped[__popcll(drop & ((1ull << lane) - 1ull))] = (int32_t)(p0 + lane); // in position order
+        // (same wave wrote and reads the list: program order suffices)
+        const int64_t pn = p0 + step + lane;
+        kept = pn >= g.m || position_kept(g, mask_in, mask_out, pn);
+        const int total = nd * chunks_per_row;
+        for (int c = lane; c < total; c += 64) {
+            const int rk = c / chunks_per_row, pc = c - rk * chunks_per_row;
+            __builtin_nontemporal_store(zero4, o4 + (int64_t)dropped[rk] * chunks_per_row + pc);
+        }
     }
 }
 
@@ -458,8 +479,8 @@ hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t
     const int row_bytes = g.c_out * esz;
     if (row_bytes % 16 == 0) {
         const int cpr = row_bytes / 16;
-        int64_t total = (int64_t)g.m * cpr;
-        int blocks = (int)((total + 255) / 256 > 16384 ? 16384 : (total + 255) / 256);
+        const int64_t groups = ((int64_t)g.m + 255) / 256; // 64 positions per wave, 4 waves per workgroup
+        const int blocks = (int)(groups > 4096 ? 4096 : groups);
         hipLaunchKernelGGL(k_zero_fill16, dim3(blocks), dim3(256), 0, s, g, mask_in, mask_out, (uint4 *)out, cpr);
     } else {
         int64_t total = (int64_t)g.m * row_bytes;
