@@ -96,7 +96,9 @@ class ConvStack:
             if m_in is not None:
                 hi, wi = self.sizes[op.src]
                 same_view = (op.stride == 1 and self.sizes[i] == (hi, wi) and op.pad == (op.k - 1) // 2)
-                key = (id(m_in), op.k, op.stride, op.pad)
+                # two windows with the same stride, the same centre-tap offset and the same output
+                # size keep the same positions (a 3x3/2 pad 1 conv and the 1x1/2 projection beside it)
+                key = (id(m_in), op.stride, (op.k - 1) // 2 - op.pad, self.sizes[i])
                 if same_view and id(m_in) in produced:
                     # the window is centred and does not change the resolution: the mask this op
                     # keeps is the (already 0/1) mask it reads, and so is the kept list
