@@ -210,6 +210,15 @@ int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8
 int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype,
                      int32_t k, int32_t stride, int32_t pad, void *out, void *stream);
 
+/* The same helper for a stack that carries a mask: positions whose byte in `keep`
+ * ([n][ho][wo], as fc_mask_downsample writes it for the pool's window) is zero get
+ * +0.0 in every channel and their window is not read - no feature is computed at an
+ * irrelevant position (Sec. III-A), and a focused layer that reads the pooled tensor
+ * with that mask never looks at it.  keep == NULL is fc_maxpool2d. */
+int32_t fc_maxpool2d_masked(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype,
+                            int32_t k, int32_t stride, int32_t pad, const uint8_t *keep, void *out,
+                            void *stream);
+
 #ifdef __cplusplus
 }
 #endif

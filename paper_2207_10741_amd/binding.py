@@ -21,7 +21,7 @@ WORKSPACE_COUNTER_BYTES = 2048
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
              "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_dwconv2d",
-             "fc_maxpool2d")
+             "fc_maxpool2d", "fc_maxpool2d_masked")
 MAX_PYRAMID_LEVELS = 8
 
 
@@ -91,6 +91,8 @@ def lib():
         L.fc_focused_dwconv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 6
         L.fc_maxpool2d.restype = i32
         L.fc_maxpool2d.argtypes = [vp] + [i32] * 8 + [vp, vp]
+        L.fc_maxpool2d_masked.restype = i32
+        L.fc_maxpool2d_masked.argtypes = [vp] + [i32] * 8 + [vp, vp, vp]
         _lib = L
     return _lib
 
@@ -342,15 +344,22 @@ def ready_workspace(workspace):
     return workspace
 
 
-def maxpool2d(x, k: int, stride: int, pad: int, dtype: int, out=None, stream=None):
-    """fc_maxpool2d helper: NHWC max-pool of the whole tensor."""
+def maxpool2d(x, k: int, stride: int, pad: int, dtype: int, out=None, stream=None, keep=None):
+    """fc_maxpool2d / fc_maxpool2d_masked helper: NHWC max-pool; with `keep` ([N,Ho,Wo] bytes) only
+    the kept output positions are computed, the others are zero."""
     torch = _torch()
-    _require_cuda(x, out)
+    _require_cuda(x, out, keep)
     n, h, w, c = x.shape
     d = conv_desc(n, h, w, 1, 1, (k, k), (stride, stride), (pad, pad), (1, 1), F32)
     ho, wo = out_dims(d)
     if out is None:
         out = torch.empty((n, ho, wo, c), dtype=x.dtype, device=x.device)
-    _check(lib().fc_maxpool2d(_ptr(x), n, h, w, c, dtype, k, stride, pad, _ptr(out), _stream(stream)),
-           "fc_maxpool2d")
+    if keep is None:
+        _check(lib().fc_maxpool2d(_ptr(x), n, h, w, c, dtype, k, stride, pad, _ptr(out), _stream(stream)),
+               "fc_maxpool2d")
+    else:
+        if tuple(keep.shape) != (n, ho, wo):
+            raise ValueError("keep shape %s, expected %s" % (tuple(keep.shape), (n, ho, wo)))
+        _check(lib().fc_maxpool2d_masked(_ptr(x), n, h, w, c, dtype, k, stride, pad, _ptr(keep), _ptr(out),
+                                         _stream(stream)), "fc_maxpool2d_masked")
     return out

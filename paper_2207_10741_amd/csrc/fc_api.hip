@@ -338,13 +338,19 @@ int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
 int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,
                      int32_t stride, int32_t pad, void *out, void *stream)
 {
+    return fc_maxpool2d_masked(x, n, h, w, c, dtype, k, stride, pad, nullptr, out, stream);
+}
+
+int32_t fc_maxpool2d_masked(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,
+                            int32_t stride, int32_t pad, const uint8_t *keep, void *out, void *stream)
+{
     if (!x || !out) return FC_ERR_NULL;
     if (n <= 0 || h <= 0 || w <= 0 || c <= 0 || k <= 0 || stride <= 0 || pad < 0 || 2 * pad > k)
         return FC_ERR_SHAPE;
     if (dtype != FC_F32 && dtype != FC_BF16 && dtype != FC_F16) return FC_ERR_DTYPE;
     const int32_t ho = out_dim(h, k, stride, pad, 1), wo = out_dim(w, k, stride, pad, 1);
     if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
-    const hipError_t e = launch_maxpool(x, n, h, w, c, dtype, k, stride, pad, ho, wo, out, (hipStream_t)stream);
+    const hipError_t e = launch_maxpool(x, n, h, w, c, dtype, k, stride, pad, ho, wo, keep, out, (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 

@@ -149,8 +149,9 @@ struct PyramidArgs {
 hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int32_t *block_counts, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);
+// keep: [n][ho][wo] bytes or NULL; positions with a zero byte are written as +0 and not computed
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,
-                          int pad, int ho, int wo, void *out, hipStream_t s);
+                          int pad, int ho, int wo, const uint8_t *keep, void *out, hipStream_t s);
 
 // Direct convolution over the active rows; any shape, any dtype.
 hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const void *x,

@@ -509,7 +509,8 @@ hipError_t launch_zero_i32(int32_t *p, int n, hipStream_t s)
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void k_maxpool(const T *__restrict__ x, int n, int h, int w, int c, int k,
-                                                 int stride, int pad, int ho, int wo, T *__restrict__ out)
+                                                 int stride, int pad, int ho, int wo,
+                                                 const uint8_t *__restrict__ keep, T *__restrict__ out)
 {
     const int64_t total = (int64_t)n * ho * wo * c;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
@@ -520,6 +521,13 @@ __global__ __launch_bounds__(256) void k_maxpool(const T *__restrict__ x, int n,
         t /= wo;
         int oh = (int)(t % ho);
         int b = (int)(t / ho);
+        if (keep && !keep[((int64_t)b * ho + oh) * wo + ow]) {
+            // a position the mask drops: no feature is computed for it (Sec. III-A); its window is not read
+            T zero;
+            __builtin_memset(&zero, 0, sizeof(T));
+            out[i] = zero;
+            continue;
+        }
         bool have = false;
         float best = 0.f;
         T best_raw = x[0];
@@ -546,7 +554,8 @@ __global__ __launch_bounds__(256) void k_maxpool(const T *__restrict__ x, int n,
 // output position (16-byte loads and one 16-byte store).
 template <typename T>
 __global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int n, int h, int w, int c, int k,
-                                                    int stride, int pad, int ho, int wo, T *__restrict__ out)
+                                                    int stride, int pad, int ho, int wo,
+                                                    const uint8_t *__restrict__ keep, T *__restrict__ out)
 {
     const int cg = c / 8;
     const int64_t total = (int64_t)n * ho * wo * cg;
@@ -558,6 +567,10 @@ __global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int
         t /= wo;
         const int oh = (int)(t % ho);
         const int b = (int)(t / ho);
+        if (keep && !keep[((int64_t)b * ho + oh) * wo + ow]) {
+            *reinterpret_cast<uint4 *>(out + i * 8) = make_uint4(0, 0, 0, 0);
+            continue;
+        }
         bool have = false;
         float best[8];
         uint16_t raw[8];
@@ -597,30 +610,30 @@ __global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int
 }
 
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride, int pad,
-                          int ho, int wo, void *out, hipStream_t s)
+                          int ho, int wo, const uint8_t *keep, void *out, hipStream_t s)
 {
     if (dtype != FC_F32 && c % 8 == 0) {
         const int64_t total8 = (int64_t)n * ho * wo * (c / 8);
         const int blocks8 = (int)((total8 + 255) / 256 > 65536 ? 65536 : (total8 + 255) / 256);
         if (dtype == FC_BF16)
             hipLaunchKernelGGL(k_maxpool_x8<bf16_t>, dim3(blocks8), dim3(256), 0, s, (const bf16_t *)x, n, h, w, c, k,
-                               stride, pad, ho, wo, (bf16_t *)out);
+                               stride, pad, ho, wo, keep, (bf16_t *)out);
         else
             hipLaunchKernelGGL(k_maxpool_x8<f16_t>, dim3(blocks8), dim3(256), 0, s, (const f16_t *)x, n, h, w, c, k,
-                               stride, pad, ho, wo, (f16_t *)out);
+                               stride, pad, ho, wo, keep, (f16_t *)out);
         return hipGetLastError();
     }
     const int64_t total = (int64_t)n * ho * wo * c;
     int blocks = (int)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
     if (dtype == FC_F32)
         hipLaunchKernelGGL(k_maxpool<float>, dim3(blocks), dim3(256), 0, s, (const float *)x, n, h, w, c, k, stride,
-                           pad, ho, wo, (float *)out);
+                           pad, ho, wo, keep, (float *)out);
     else if (dtype == FC_BF16)
         hipLaunchKernelGGL(k_maxpool<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)x, n, h, w, c, k,
-                           stride, pad, ho, wo, (bf16_t *)out);
+                           stride, pad, ho, wo, keep, (bf16_t *)out);
     else
         hipLaunchKernelGGL(k_maxpool<f16_t>, dim3(blocks), dim3(256), 0, s, (const f16_t *)x, n, h, w, c, k, stride,
-                           pad, ho, wo, (f16_t *)out);
+                           pad, ho, wo, keep, (f16_t *)out);
     return hipGetLastError();
 }
 

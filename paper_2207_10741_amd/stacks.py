@@ -5,7 +5,8 @@ rescaled per layer); each conv is one fc_focused_conv2d call, each depthwise con
 fc_focused_dwconv2d call.
 
 Plumbing only: the order of library calls and which tensor feeds which.  Max-pools
-(not part of the paper's method) go through the library's helper.
+(not part of the paper's method) go through the library's helper, which with a mask
+computes only the pooled positions the mask keeps.
 """
 from __future__ import annotations
 
@@ -131,7 +132,9 @@ class ConvStack:
                                                mask_out=plan[0], idx=plan[1], count=plan[2], out=out,
                                                workspace=self.workspace)
             else:
-                outs[i] = B.maxpool2d(src, op.k, op.stride, op.pad, self.dtype)
+                # with a mask, only the pooled positions it keeps are computed; the rest is zero
+                outs[i] = B.maxpool2d(src, op.k, op.stride, op.pad, self.dtype,
+                                      keep=None if plan is None else plan[0])
             masks[i] = None if plan is None else plan[0]
             if not keep_outputs:
                 for j in [j for j in outs if j != i and last_use.get(j, -2) <= i and j != -1]:

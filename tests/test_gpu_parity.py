@@ -397,3 +397,12 @@ def test_maxpool_helper():
             got = B.maxpool2d(xd, k, s, p, dtype)
             ref = torch.nn.functional.max_pool2d(xd.float().permute(0, 3, 1, 2), k, s, p).permute(0, 2, 3, 1)
             assert torch.equal(got.float(), ref.contiguous())
+            # with a keep mask: kept positions as above, the others all-zero bytes, and NaN in
+            # windows that only dropped positions see is never read
+            ho, wo = got.shape[1:3]
+            keep = synth.mask_bernoulli(2, ho, wo, 0.5, 211, c, k)
+            canary = torch.full_like(got, 7.0)
+            B.maxpool2d(xd, k, s, p, dtype, out=canary, keep=G.mask_dev(keep))
+            kd = torch.from_numpy(keep != 0).to(G.dev())
+            assert torch.equal(canary[kd], got[kd])
+            assert not canary[~kd].view(torch.int16).any()

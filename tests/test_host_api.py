@@ -112,6 +112,8 @@ def test_null_pointers_rejected_before_any_launch():
     assert dw(B.conv_desc(1, 8, 8, 8, 16), a, None, a, None, o, None) == -2   # not one filter per channel
     assert dw(B.conv_desc(1, 40000, 40000, 8, 8, in_dtype=B.BF16), a, None, a, None, o, None) == -6
     assert L.fc_maxpool2d(a, 1, 8, 8, 8, 0, 2, 2, 2, a, None) == -2
+    assert L.fc_maxpool2d_masked(a, 1, 8, 8, 8, 0, 2, 2, 2, a, a, None) == -2
+    assert L.fc_maxpool2d_masked(None, 1, 8, 8, 8, 0, 2, 2, 0, a, a, None) == -1
     assert L.fc_maxpool2d(a, 1, 8, 8, 8, 9, 2, 2, 0, a, None) == -3
 
 
