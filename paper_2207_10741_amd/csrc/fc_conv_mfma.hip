@@ -875,10 +875,13 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
     // of adjacent kept positions; narrow layers with many tiles do better with three
     // workgroups per CU, see below)
     if constexpr (TAPC == 9) {
-        if (g.sw == 1 && g.dw == 1 && g.wo >= 32) {
+        if (g.sw == 1 && g.dw == 1 && g.wo >= 16) {
+            // (with many 128 x 128 tiles it pays down to 16-pixel rows: C512@16 at batch 128 is
+            // 13 % faster dense and 17 % faster focused than tap by tap)
             if (g.c_out > 64 && tiles128 >= 512)
                 return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
-            if (g.c_out > 64 || partials) return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+            if (g.wo >= 32 && (g.c_out > 64 || partials))
+                return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
         }
     }
     if (g.c_out > 64 && tiles128 >= 512)
