@@ -880,7 +880,10 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
             // 13 % faster dense and 17 % faster focused than tap by tap)
             if (g.c_out > 64 && tiles128 >= 512)
                 return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
-            if (g.wo >= 32 && (g.c_out > 64 || partials))
+            // narrow layers: only with many tiles (C64@128: -7 % focused, -4..8 % dense from batch 128
+            // on; at batch 16 three workgroups per CU, below, are as fast)
+            const bool many_narrow_tiles = (int64_t)((g.m + 127) / 128) >= 4096;
+            if (g.wo >= 32 && (g.c_out > 64 || partials || many_narrow_tiles))
                 return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
         }
     }
