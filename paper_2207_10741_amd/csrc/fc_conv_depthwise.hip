@@ -7,12 +7,13 @@
 // There is no contraction here (KH*KW multiply-adds per output value, 2 bytes in and 2 bytes
 // out), so the kernel is bound by memory traffic and vector ALU work, not by the matrix cores.
 //
-// Mapping.  A lane owns VEC consecutive channels (16 bytes of a pixel) for the whole launch, so
-// its filters (VEC x KH*KW values) and bias live in registers.  The lanes of a workgroup are
-// laid out [position][channel chunk]: consecutive lanes read and write consecutive 16-byte
-// pieces of a pixel, then the next pixel, and the workgroup walks the positions of one image
-// with a grid stride.  Nothing is staged in LDS and there is no barrier; taps shared by
-// neighbouring positions are served by the caches.
+// Mapping.  A lane owns VEC consecutive channels (16 bytes of a pixel) for the whole launch.
+// The lanes of a workgroup are laid out [position][channel chunk]: consecutive lanes read and
+// write consecutive 16-byte pieces of a pixel, then the next pixel, and the workgroup walks the
+// positions of one image with a grid stride.  Pixels are not staged in LDS; taps shared by
+// neighbouring positions are served by the caches.  The filters and the bias of a lane's
+// channels live in its registers, or, for 3 x 3 layers whose filters are small enough, in LDS
+// (which halves the register count and doubles the waves in flight).
 //
 // Gating without branches.  The image and its mask are addressed through buffer descriptors
 // that cover exactly one image: a tap outside the image or at an irrelevant pixel is given an
@@ -33,7 +34,7 @@ namespace {
 constexpr int kDwThreads = 256;
 constexpr uint32_t kDwBufferLimit = 0xF0000000u; // one image (and its mask) stays below this many bytes
 constexpr uint32_t kDwOutOfRange = kDwBufferLimit;
-constexpr int kDwTargetBlocks = 1024;            // about four workgroups per CU
+constexpr int kDwTargetBlocks = 1024;            // four workgroups per CU
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -121,8 +122,12 @@ __device__ __forceinline__ void store_piece(TO *dst, const float *v)
 
 // KS: compile-time square kernel size (filters in registers), or 0 for any KH x KW (filters
 // re-read through the cache at every tap).
-template <typename TI, typename TO, int VEC, int KS>
-__global__ __launch_bounds__(kDwThreads, (KS > 3 ? 2 : 4)) void k_dwconv(DwArgs a, const TI *__restrict__ x,
+// WLDS: the workgroup's filters and bias sit in LDS as fp32 [tap][channel] instead of in every
+// lane's registers; lanes with the same channel chunk read the same addresses.  The kernel then
+// needs about 60 registers instead of 128, twice as many waves fit a SIMD, and it is the number
+// of waves in flight that hides the dependent memory round trips of a position.
+template <typename TI, typename TO, int VEC, int KS, bool WLDS>
+__global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_dwconv(DwArgs a, const TI *__restrict__ x,
                                                        const uint8_t *__restrict__ mask_in,
                                                        const TI *__restrict__ w, const float *__restrict__ bias,
                                                        TO *__restrict__ out)
@@ -134,11 +139,23 @@ __global__ __launch_bounds__(kDwThreads, (KS > 3 ? 2 : 4)) void k_dwconv(DwArgs 
     const int j = threadIdx.x % a.lanes_per_pos;
     const int pp = threadIdx.x / a.lanes_per_pos;
     const int chunk = blockIdx.z * a.lanes_per_pos + j;
-    if (chunk >= a.chunks || pp >= a.pos_per_block) return; // no barrier below
-    const int c0 = chunk * VEC;
     const int C = g.c_in;
     const int kh_n = KS ? KS : g.kh, kw_n = KS ? KS : g.kw;
     const int taps = kh_n * kw_n;
+    extern __shared__ __align__(16) float dw_w[]; // WLDS only: [taps + 1][CT] filters, then bias
+    const int CT = a.lanes_per_pos * VEC;         // channels of this workgroup
+    if constexpr (WLDS) {
+        const int ch_first = blockIdx.z * CT;
+        for (int i = threadIdx.x; i < (TAPS_C + 1) * CT; i += kDwThreads) {
+            const int t = i / CT, ch = ch_first + (i - t * CT);
+            float v = 0.f;
+            if (ch < C) v = t < TAPS_C ? to_float(w[(int64_t)ch * TAPS_C + t]) : (bias ? bias[ch] : 0.f);
+            dw_w[i] = v;
+        }
+        __syncthreads();
+    }
+    if (chunk >= a.chunks || pp >= a.pos_per_block) return; // no barrier below
+    const int c0 = chunk * VEC;
 
     // one image and its mask per descriptor; offsets are bytes inside the image
     const uint32_t img_bytes = (uint32_t)g.h * g.w * C * (uint32_t)sizeof(TI);
@@ -154,8 +171,8 @@ __global__ __launch_bounds__(kDwThreads, (KS > 3 ? 2 : 4)) void k_dwconv(DwArgs 
     constexpr int WBYTES = KS ? VEC * TAPS_C * (int)sizeof(TI) : 4;
     constexpr int WWORDS = (WBYTES + 3) / 4;
     uint32_t wraw[WWORDS];
-    float wr[(KS && !WPACK) ? VEC * TAPS_C : 1];
-    if constexpr (KS != 0) {
+    float wr[(KS && !WPACK && !WLDS) ? VEC * TAPS_C : 1];
+    if constexpr (KS != 0 && !WLDS) {
         const TI *wp = w + (int64_t)c0 * TAPS_C;
         if constexpr (WBYTES % 16 == 0) {
 #pragma unroll
@@ -173,13 +190,17 @@ __global__ __launch_bounds__(kDwThreads, (KS > 3 ? 2 : 4)) void k_dwconv(DwArgs 
             for (int e = 0; e < VEC * TAPS_C; ++e) wr[e] = to_float(wp[e]);
         }
     }
+    const float *wl = dw_w + j * VEC; // WLDS: this lane's channels of tap 0
     auto filter = [&](int v, int t) -> float {
-        if constexpr (WPACK) return piece_elem<TI>(wraw, v * TAPS_C + t);
+        if constexpr (WLDS) return wl[t * CT + v];
+        else if constexpr (WPACK) return piece_elem<TI>(wraw, v * TAPS_C + t);
         else return wr[v * TAPS_C + t];
     };
-    float bv[VEC];
+    float bv[WLDS ? 1 : VEC];
+    if constexpr (!WLDS) {
 #pragma unroll
-    for (int v = 0; v < VEC; ++v) bv[v] = bias ? bias[c0 + v] : 0.f;
+        for (int v = 0; v < VEC; ++v) bv[v] = bias ? bias[c0 + v] : 0.f;
+    }
 
     const int hw_out = g.ho * g.wo;
     const int ch0 = -g.ph + g.dh * ((kh_n - 1) / 2), cw0 = -g.pw + g.dw * ((kw_n - 1) / 2);
@@ -215,7 +236,7 @@ __global__ __launch_bounds__(kDwThreads, (KS > 3 ? 2 : 4)) void k_dwconv(DwArgs 
         }
         float acc[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] = bv[v];
+        for (int v = 0; v < VEC; ++v) acc[v] = WLDS ? wl[TAPS_C * CT + v] : bv[WLDS ? 0 : v];
 
         if constexpr (KS != 0) {
             // 3 x 3: all nine taps in flight at once; larger kernels one kernel row at a time
@@ -284,6 +305,8 @@ __global__ __launch_bounds__(kDwThreads, (KS > 3 ? 2 : 4)) void k_dwconv(DwArgs 
     }
 }
 
+constexpr size_t kDwWldsBytes = 20 * 1024; // filters in LDS only while eight workgroups still fit a CU
+
 template <typename TI, typename TO, int VEC, int KS>
 hipError_t launch_k(const Geom &g, const void *x, const uint8_t *mask_in, const void *w, const float *bias,
                     void *out, hipStream_t s)
@@ -297,11 +320,23 @@ hipError_t launch_k(const Geom &g, const void *x, const uint8_t *mask_in, const 
     a.div_wo = make_fastdiv((uint32_t)g.wo);
     const int64_t hw_out = (int64_t)g.ho * g.wo;
     const int64_t need = (hw_out + a.pos_per_block - 1) / a.pos_per_block;
-    int64_t cap = kDwTargetBlocks / ((int64_t)g.n * ctiles);
+    const size_t wlds = (size_t)(KS * KS + 1) * a.lanes_per_pos * VEC * sizeof(float);
+    const bool use_wlds = KS == 3 && VEC > 1 && wlds <= kDwWldsBytes;
+    // eight workgroups per CU with the filters in LDS when every workgroup still has a few steps
+    // to do (its start-up is not free), else four
+    const bool wide_grid = use_wlds && need * g.n * ctiles >= 4 * kDwTargetBlocks;
+    int64_t cap = (wide_grid ? 2 : 1) * kDwTargetBlocks / ((int64_t)g.n * ctiles);
     if (cap < 1) cap = 1;
     const int gx = (int)(need < cap ? need : cap);
-    hipLaunchKernelGGL((k_dwconv<TI, TO, VEC, KS>), dim3(gx, g.n, ctiles), dim3(kDwThreads), 0, s, a, (const TI *)x,
-                       mask_in, (const TI *)w, bias, (TO *)out);
+    if constexpr (KS == 3 && VEC > 1) {
+        if (use_wlds) {
+            hipLaunchKernelGGL((k_dwconv<TI, TO, VEC, KS, true>), dim3(gx, g.n, ctiles), dim3(kDwThreads), wlds, s, a,
+                               (const TI *)x, mask_in, (const TI *)w, bias, (TO *)out);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((k_dwconv<TI, TO, VEC, KS, false>), dim3(gx, g.n, ctiles), dim3(kDwThreads), 0, s, a,
+                       (const TI *)x, mask_in, (const TI *)w, bias, (TO *)out);
     return hipGetLastError();
 }
 
