@@ -70,7 +70,12 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                 __syncthreads();
                 staged = nchunks == 1;
             }
-            for (int k = 0; k < kc; ++k) {
+            // four input channels at a time where the layout allows (fp32 storage, channel count
+            // a multiple of four: a group never straddles a tap or a staged chunk), so that a lane
+            // has one 16-byte load in flight per 4 x CO_T multiply-adds instead of four dependent
+            // 4-byte loads
+            const bool by4 = sizeof(TI) == 4 && g.c_in % 4 == 0;
+            for (int k = 0; k < kc; k += by4 ? 4 : 1) {
                 if (new_tap) {
                     const int ih = ih0 + kh * g.dh, iw = iw0 + kw * g.dw;
                     tap_ok = live && ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
@@ -82,11 +87,25 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                     new_tap = false;
                 }
                 if (tap_ok) {
-                    const float xv = to_float(xp[ci]);
-                    const float *wk = wt + k * CO_T;
+                    if (by4) {
+                        if constexpr (sizeof(TI) == 4) {
+                            const float4 xq = *reinterpret_cast<const float4 *>(xp + ci);
+                            const float xs[4] = {xq.x, xq.y, xq.z, xq.w};
 #pragma unroll
-                    for (int j = 0; j < CO_T; ++j) acc[j] = fmaf(xv, wk[j], acc[j]);
+                            for (int e = 0; e < 4; ++e) {
+                                const float *wk = wt + (k + e) * CO_T;
+#pragma unroll
+                                for (int j = 0; j < CO_T; ++j) acc[j] = fmaf(xs[e], wk[j], acc[j]);
+                            }
+                        }
+                    } else {
+                        const float xv = to_float(xp[ci]);
+                        const float *wk = wt + k * CO_T;
+#pragma unroll
+                        for (int j = 0; j < CO_T; ++j) acc[j] = fmaf(xv, wk[j], acc[j]);
+                    }
                 }
+                ci += by4 ? 3 : 0;
                 if (++ci == g.c_in) {
                     ci = 0;
                     new_tap = true;
@@ -143,8 +162,12 @@ static hipError_t launch_t(const Geom &g, const void *x, const uint8_t *mask_in,
                            const float *bias, const int32_t *idx, const int32_t *count, void *out,
                            hipStream_t s)
 {
-    // wide accumulator blocks when the layer is wide enough to use them
-    if (g.c_out > 32) return launch_rows<TI, TO, 64>(g, x, mask_in, w, bias, idx, count, out, s);
+    // wide accumulator blocks when the layer is wide enough to use them and has enough rows to
+    // fill the chip with them; a small layer is cut into narrow channel blocks instead (more
+    // workgroups, a four times shorter serial loop per lane; the input is re-read per block,
+    // which a small layer can afford)
+    const int64_t wide_blocks = (((int64_t)g.m + kRowsThreads - 1) / kRowsThreads) * ((g.c_out + 63) / 64);
+    if (g.c_out > 32 && wide_blocks >= 512) return launch_rows<TI, TO, 64>(g, x, mask_in, w, bias, idx, count, out, s);
     return launch_rows<TI, TO, 16>(g, x, mask_in, w, bias, idx, count, out, s);
 }
 
