@@ -196,18 +196,23 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
         uint8_t *ws = (uint8_t *)workspace;
         uint8_t *m_out = ws + l.mask_out;
         const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
-        CompactExtras ex;
-        if (tile_counters) {
-            ex.zero = tile_counters;
-            ex.zero_n = kSplitGrid;
-            counters_cleared = true;
+        // a small layer on the matrix-core path ranks its kept positions inside the convolution
+        // kernel (16 positions per thread): no compaction launch
+        const bool rank_in_kernel = mfma && g.m <= kInlineRankPositions;
+        if (!rank_in_kernel) {
+            CompactExtras ex;
+            if (tile_counters) {
+                ex.zero = tile_counters;
+                ex.zero_n = kSplitGrid;
+                counters_cleared = true;
+            }
+            const hipError_t ec = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx),
+                                                 (int32_t *)(ws + l.count), (int32_t *)(ws + l.scan), ex, s);
+            if (ec != hipSuccess) return FC_ERR_HIP;
+            mask_out = m_out;
+            idx = (const int32_t *)(ws + l.idx);
+            count = (const int32_t *)(ws + l.count);
         }
-        const hipError_t ec = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
-                                             (int32_t *)(ws + l.scan), ex, s);
-        if (ec != hipSuccess) return FC_ERR_HIP;
-        mask_out = m_out;
-        idx = (const int32_t *)(ws + l.idx);
-        count = (const int32_t *)(ws + l.count);
     }
 
     hipError_t e;

@@ -49,6 +49,7 @@ constexpr uint32_t kBufferLimit = 0xF0000000u; // tensors handled through one de
 constexpr uint32_t kOutOfRange = kBufferLimit; // offset that is out of range for every descriptor
 constexpr int kTK = 64;                        // reduction elements per stage (one 128-byte pixel chunk)
 constexpr int kMaxSplits = 16;                 // most K-splits of one tile
+constexpr int kMinSplitStages = 8;            // fewest stages a K-split is left with
 constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
 
 // Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
@@ -164,7 +165,37 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     const int wave_m = wave % WM, wave_n = wave / WM;
     const int slot = tid & 7, prow = tid >> 3;
 
-    const int rows = idx ? *count : g.m;
+    // Kept rows.  With a list they are given.  Without one but with a mask (the launcher does
+    // this only for layers of at most 16 positions per thread) the workgroup ranks the kept
+    // positions itself: thread t labels positions 16t .. 16t+15 (centre tap, Sec. III-B) and a
+    // prefix sum over the workgroup gives the rank of its first kept position; the set-up of a
+    // tile then has every thread drop its positions of that tile's rank range into row_p.  A
+    // small layer so needs no compaction launch before this one.
+    const bool inline_rank = !idx && mask_in;
+    uint32_t rank_flags = 0;
+    int rank_base = 0;
+    int rows = g.m;
+    if (inline_rank) {
+        MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
+        if (reinterpret_cast<uintptr_t>(mask_in) & 15u) mg.identity = 0; // the 128-bit path needs alignment
+        rank_flags = kept_flags16(mg, mask_in, (int64_t)tid * 16);
+        const int cnt = __popc(rank_flags);
+        const int incl = wave_inclusive_scan(cnt);
+        if (lane == 63) row_p[wave] = incl;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int v = 0; v < NT / 64; ++v) {
+            const int t = row_p[v];
+            before += v < wave ? t : 0;
+            total += t;
+        }
+        rank_base = before + incl - cnt;
+        rows = total;
+        __syncthreads(); // row_p is free again
+    } else if (idx) {
+        rows = *count;
+    }
     const int n_nt = (g.c_out + TN - 1) / TN;
     const int ntiles = ((rows + TM - 1) / TM) * n_nt;
     const int taps = TAPC == 32 ? g.kh * g.kw : TAPC;
@@ -197,6 +228,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         const int work = HALO ? g.kh * cchunks : stages; // (kernel row, chunk) groups or stages
         S = S < 1 ? 1 : (S > work ? work : S);
         if (S > kMaxSplits) S = kMaxSplits;
+        // the exchange of partial tiles costs about as much as twenty stages, so a unit keeps at
+        // least kMinSplitStages of them: short reductions are not split at all (a 3x3 layer with
+        // 64 input channels: 8.4 us unsplit against 19.3 us split three ways)
+        const int s_cap = stages / kMinSplitStages;
+        if (S > s_cap) S = s_cap < 1 ? 1 : s_cap;
     }
     const int nunits = ntiles * S;
     const int per_xcd = (nunits + 7) >> 3;
@@ -259,12 +295,29 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         const int co0 = nt * TN;
 
         __syncthreads(); // the previous tile's epilogue is done with LDS
+        if (inline_rank) {
+            // every thread drops its kept positions whose rank falls into this tile
+            if (tid < TM) row_p[tid] = -1;
+            __syncthreads();
+            const int lo = mt * TM;
+            int r = rank_base;
+            uint32_t f = rank_flags;
+            if (r < lo + TM && r + __popc(f) > lo) {
+                while (f) {
+                    const int j = __ffs((int)f) - 1;
+                    f &= f - 1;
+                    if (r >= lo && r < lo + TM) row_p[r - lo] = tid * 16 + j;
+                    ++r;
+                }
+            }
+            __syncthreads();
+        }
         int sa_p = -1, sa_ow = 0, sa_ih0 = 0, sa_iw0 = 0, sa_b = 0; // this thread's row (tid < TM)
         if (tid < TM) {
             const int m = mt * TM + tid;
             int p = -1, base = 0, b = 0, hw = 0;
             if (m < rows) {
-                p = idx ? idx[m] : m;
+                p = inline_rank ? row_p[tid] : (idx ? idx[m] : m);
                 const int ow = p % g.wo;
                 const int q = p / g.wo;
                 const int oh = q % g.ho;

@@ -86,7 +86,7 @@ struct MaskGeom {
     int64_t m;        // n*ho*wo
 };
 
-static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, int sw, int ph, int pw, int dh,
+__host__ __device__ static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, int sw, int ph, int pw, int dh,
                                  int dw, int ho, int wo)
 {
     MaskGeom g;
@@ -96,6 +96,41 @@ static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, in
     g.identity = (sh == 1 && sw == 1 && ho == h && wo == w && g.ch0 == 0 && g.cw0 == 0) ? 1 : 0;
     g.m = (int64_t)n * ho * wo;
     return g;
+}
+
+// bit j = output position p0 + j is kept (positions at or past g.m read as 0)
+__device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_t *__restrict__ mask_in,
+                                                 int64_t p0)
+{
+    uint32_t flags = 0;
+    if (p0 >= g.m) return 0;
+    if (g.identity && p0 + 16 <= g.m) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(mask_in + p0);
+        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
+        return flags;
+    }
+    int ow = (int)(p0 % g.wo);
+    int64_t t = p0 / g.wo;
+    int oh = (int)(t % g.ho);
+    int b = (int)(t / g.ho);
+    for (int j = 0; j < 16 && p0 + j < g.m; ++j) {
+        const int ih = min(max(oh * g.sh + g.ch0, 0), g.h - 1);
+        const int iw = min(max(ow * g.sw + g.cw0, 0), g.w - 1);
+        if (mask_in[((int64_t)b * g.h + ih) * g.w + iw]) flags |= 1u << j;
+        if (++ow == g.wo) {
+            ow = 0;
+            if (++oh == g.ho) {
+                oh = 0;
+                ++b;
+            }
+        }
+    }
+    return flags;
 }
 
 // inclusive prefix sum over the 64 lanes of a wave, on the cross-lane data path of the
@@ -173,6 +208,7 @@ hipError_t launch_conv_stem(const Geom &g, int in_dtype, int out_dtype, const vo
 
 // Split-K scratch of the matrix-core path (optional): fp32 partial tiles and one counter
 // per tile.  Only layers with few tiles use it; for the others the sizes are zero.
+constexpr int kInlineRankPositions = 4096;                  // layers up to this many positions rank their kept rows in the conv kernel (16 per thread of a 256-thread workgroup)
 constexpr int kSplitGrid = 512;                          // workgroups launched when split-K may run
 constexpr size_t kSplitTileFloats = 128 * 128;           // largest tile
 static inline bool split_k_possible(const Geom &g)

@@ -102,42 +102,6 @@ hipError_t launch_mask_window(const uint8_t *mask_in, int n, int h, int w, int k
 //   - larger inputs: two launches, per-block counts first, then prefix + scatter.
 // ---------------------------------------------------------------------------
 
-// bit j = output position p0 + j is kept (positions at or past g.m read as 0)
-__device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_t *__restrict__ mask_in,
-                                                 int64_t p0)
-{
-    uint32_t flags = 0;
-    if (p0 >= g.m) return 0;
-    if (g.identity && p0 + 16 <= g.m) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(mask_in + p0);
-        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
-        return flags;
-    }
-    int ow = (int)(p0 % g.wo);
-    int64_t t = p0 / g.wo;
-    int oh = (int)(t % g.ho);
-    int b = (int)(t / g.ho);
-    for (int j = 0; j < 16 && p0 + j < g.m; ++j) {
-        const int ih = min(max(oh * g.sh + g.ch0, 0), g.h - 1);
-        const int iw = min(max(ow * g.sw + g.cw0, 0), g.w - 1);
-        if (mask_in[((int64_t)b * g.h + ih) * g.w + iw]) flags |= 1u << j;
-        if (++ow == g.wo) {
-            ow = 0;
-            if (++oh == g.ho) {
-                oh = 0;
-                ++b;
-            }
-        }
-    }
-    return flags;
-}
-
-
 // sum of v over the block (all threads get it); scratch holds one int per wave
 __device__ __forceinline__ int block_sum(int v, int *scratch)
 {
