@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "focused_conv_oracle.c")
 _LIB = os.path.join(_HERE, "libfc_oracle.so")
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, FP8 = 0, 1, 2, 3
 RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 
 
@@ -54,6 +54,8 @@ def lib():
         L.fco_mask_downsample.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 11 + [ctypes.c_void_p]
         L.fco_active_index_compact.restype = ctypes.c_int64
         L.fco_active_index_compact.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        L.fco_widen.restype = ctypes.c_int32
+        L.fco_widen.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         L.fco_focused_conv2d.restype = ctypes.c_int32
         L.fco_focused_conv2d.argtypes = [ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
         L.fco_focused_conv2d_at.restype = ctypes.c_int32
@@ -105,11 +107,20 @@ def _ptr(a):
 
 
 def _storage(a: np.ndarray, dtype: int) -> np.ndarray:
-    """x / w arrive as float32 (dtype F32) or as raw uint16 bit patterns."""
-    want = np.float32 if dtype == F32 else np.uint16
+    """x / w arrive as float32 (dtype F32), as raw uint16 bit patterns, or as raw bytes (FP8)."""
+    want = np.float32 if dtype == F32 else np.uint8 if dtype == FP8 else np.uint16
     if a.dtype != want:
         raise TypeError("storage dtype %s does not match code %d" % (a.dtype, dtype))
     return np.ascontiguousarray(a)
+
+
+def widen(stored: np.ndarray, dtype: int) -> np.ndarray:
+    """The values a storage array holds, as float64 (exact)."""
+    a = _storage(stored, dtype)
+    out = np.empty(a.shape, dtype=np.float64)
+    if lib().fco_widen(dtype, _ptr(a), a.size, _ptr(out)) != 0:
+        raise ValueError("dtype %r" % (dtype,))
+    return out
 
 
 def _mask(m, shape):

@@ -32,8 +32,8 @@
  *
  * Layouts: x[N][H][W][C_in], w[C_out][KH][KW][C_in], bias[C_out] (float),
  * masks uint8 [N][H][W], out double [N][Ho][Wo][C_out].  Inputs arrive already
- * rounded to their storage type (float32, bfloat16 or IEEE half); they are
- * widened exactly and accumulated in double in the loop order
+ * rounded to their storage type (float32, bfloat16, IEEE half, or the 8-bit
+ * E4M3 format, one byte per value); they are widened exactly and accumulated in double in the loop order
  * n, oh, ow, co, kh, kw, ci.  The result is left unrounded.
  *
  * The depthwise layer at the end of this file (one filter per channel, the
@@ -51,7 +51,7 @@
 #include <omp.h>
 #endif
 
-enum { FCO_F32 = 0, FCO_BF16 = 1, FCO_F16 = 2 };
+enum { FCO_F32 = 0, FCO_BF16 = 1, FCO_F16 = 2, FCO_FP8 = 3 };
 
 typedef struct {
     int32_t n, h, w, c_in, c_out, kh, kw;
@@ -91,11 +91,43 @@ static double widen_f16(const void *p, size_t i)
     return sign ? -v : v;
 }
 
+/* 8-bit floating point, format E4M3 of the OCP 8-bit floating point specification
+ * (the variant without infinities): 1 sign bit, 4 exponent bits with bias 7, 3
+ * fraction bits.  Exponent field 0 holds the subnormals frac * 2^-9; exponent
+ * field 15 holds ordinary numbers (up to 1.75 * 2^8 = 448) except fraction 7,
+ * which is NaN. */
+static double widen_fp8(const void *p, size_t i)
+{
+    uint8_t bits = ((const uint8_t *)p)[i];
+    int sign = bits >> 7, e = (bits >> 3) & 15, frac = bits & 7;
+    double v;
+    if (e == 15 && frac == 7) return 0.0 / 0.0;
+    if (e == 0)
+        v = (double)frac / 512.0;
+    else {
+        v = 1.0 + (double)frac / 8.0;
+        int k = e - 7;
+        while (k > 0) { v *= 2.0; --k; }
+        while (k < 0) { v *= 0.5; ++k; }
+    }
+    return sign ? -v : v;
+}
+
+/* one stored value, widened (lets the tests pin the decoders one by one) */
 typedef double (*widen_fn)(const void *, size_t);
 
 static widen_fn pick_widen(int dtype)
 {
-    return dtype == FCO_BF16 ? widen_bf16 : dtype == FCO_F16 ? widen_f16 : widen_f32;
+    return dtype == FCO_BF16 ? widen_bf16 : dtype == FCO_F16 ? widen_f16 : dtype == FCO_FP8 ? widen_fp8 : widen_f32;
+}
+
+/* out[i] = value of the i-th stored element */
+int32_t fco_widen(int32_t dtype, const void *stored, int64_t count, double *out)
+{
+    if (dtype < FCO_F32 || dtype > FCO_FP8) return -1;
+    widen_fn wd = pick_widen(dtype);
+    for (int64_t i = 0; i < count; ++i) out[i] = wd(stored, (size_t)i);
+    return 0;
 }
 
 /* ---- output size (Sec. III-A operation count; Fig. 5 caption) ---------- */

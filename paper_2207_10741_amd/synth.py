@@ -16,8 +16,8 @@ import numpy as np
 
 BASE_SEED = 220710741
 
-F32, BF16, F16 = 0, 1, 2
-DTYPE_NAMES = {F32: "f32", BF16: "bf16", F16: "f16"}
+F32, BF16, F16, FP8 = 0, 1, 2, 3
+DTYPE_NAMES = {F32: "f32", BF16: "bf16", F16: "f16", FP8: "fp8"}
 
 
 def rng(*key: int) -> np.random.Generator:
@@ -46,14 +46,45 @@ def f16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
 
 
+def _fp8_table() -> np.ndarray:
+    """Values of the 127 non-negative finite E4M3 codes 0x00..0x7E, ascending
+    (OCP 8-bit floating point: bias 7, subnormals frac * 2^-9, no infinities,
+    0x7F = NaN)."""
+    codes = np.arange(127)
+    e, frac = codes >> 3, codes & 7
+    return np.where(e == 0, frac / 512.0, (1.0 + frac / 8.0) * np.exp2(e - 7.0)).astype(np.float32)
+
+
+def f32_to_fp8_bits(a: np.ndarray) -> np.ndarray:
+    """float32 -> E4M3 codes (uint8): nearest value, ties to the even code,
+    magnitudes beyond 448 clamp to 448, NaN -> 0x7F."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    table = _fp8_table().astype(np.float64)
+    mag = np.minimum(np.abs(a).astype(np.float64), table[-1])
+    hi = np.clip(np.searchsorted(table, mag, side="left"), 0, 126)
+    lo = np.maximum(hi - 1, 0)
+    d_lo, d_hi = mag - table[lo], table[hi] - mag
+    code = np.where(d_lo < d_hi, lo, np.where(d_hi < d_lo, hi, np.where(lo % 2 == 0, lo, hi)))
+    code = np.where(np.isnan(a), 0x7F, code).astype(np.uint8)
+    return code | (np.signbit(a).astype(np.uint8) << 7)
+
+
+def fp8_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    mag = np.append(_fp8_table(), np.float32(np.nan))[b & 0x7F]
+    return np.where(b >> 7, -mag, mag).astype(np.float32)
+
+
 def to_storage(a: np.ndarray, dtype: int) -> np.ndarray:
-    """Values -> the array both implementations read: float32, or uint16 bits."""
+    """Values -> the array both implementations read: float32, uint16 bits, or E4M3 bytes."""
     if dtype == F32:
         return np.ascontiguousarray(a, dtype=np.float32)
     if dtype == BF16:
         return f32_to_bf16_bits(a)
     if dtype == F16:
         return f32_to_f16_bits(a)
+    if dtype == FP8:
+        return f32_to_fp8_bits(a)
     raise ValueError("dtype %r" % (dtype,))
 
 
@@ -65,6 +96,8 @@ def from_storage(s: np.ndarray, dtype: int) -> np.ndarray:
         return bf16_bits_to_f32(s)
     if dtype == F16:
         return f16_bits_to_f32(s)
+    if dtype == FP8:
+        return fp8_bits_to_f32(s)
     raise ValueError("dtype %r" % (dtype,))
 
 

@@ -100,6 +100,8 @@ def test_active_index_compact_blobs_large():
                    ((3, 3), (2, 2), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1))]),
     (2, 33, 47, [((3, 5), (1, 2), (0, 4), (2, 1))]),
     (2, 300, 500, [((3, 3), (1, 1), (1, 1), (1, 1)), ((5, 5), (3, 3), (0, 0), (1, 1))]),
+    # many blocks of 4096 positions per level
+    (8, 256, 256, [((3, 3), (1, 1), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1))]),
 ])
 @pytest.mark.parametrize("irr", [0.48, 0.0, 1.0])
 def test_mask_pyramid_matches_the_chain_of_rescalings(n, h, w, steps, irr):

@@ -347,6 +347,45 @@ def test_16bit_storage_is_widened_exactly(dtype):
         np.testing.assert_array_equal(out.reshape(-1), bits.view(np.float16).astype(np.float64))
 
 
+def test_fp8_storage_decoder_and_encoder_against_the_format_and_a_library():
+    """E4M3 bytes (OCP 8-bit floating point, the variant without infinities): the oracle's
+    decoder against closed forms of the format and against torch's float8_e4m3fn for all 256
+    codes; the input generator's encoder against torch's conversion; the layer fed bytes equals
+    the layer fed the library-decoded values as float32."""
+    codes = np.arange(256, dtype=np.uint8)
+    vals = O.widen(codes, O.FP8)
+    # closed forms: one, the largest finite value, the smallest subnormal and normal, signed zero
+    assert vals[0x38] == 1.0 and vals[0x7E] == 448.0 and vals[0x01] == 2.0 ** -9 and vals[0x08] == 2.0 ** -6
+    assert vals[0x00] == 0.0 and vals[0x80] == 0.0 and np.signbit(vals[0x80]) and not np.signbit(vals[0x00])
+    assert np.isnan(vals[0x7F]) and np.isnan(vals[0xFF]) and np.isfinite(np.delete(vals, [0x7F, 0xFF])).all()
+    np.testing.assert_array_equal(vals[0x81:0xFF], -vals[0x01:0x7F])
+    assert (np.diff(vals[:0x7F]) > 0).all()                       # codes order like their values
+    # spacing: 8 values per binade, the subnormals continue the first binade's step
+    np.testing.assert_array_equal(np.diff(vals[0:16]), np.full(15, 2.0 ** -9))
+    np.testing.assert_array_equal(vals[0x40:0x48], 2.0 * (1 + np.arange(8) / 8.0))
+    torch = pytest.importorskip("torch")
+    lib_vals = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    np.testing.assert_array_equal(vals, lib_vals)                 # NaN positions compare equal here
+    np.testing.assert_array_equal(synth.fp8_bits_to_f32(codes).astype(np.float64), lib_vals)
+    # the encoder: exact values round-trip, everything else goes where the library puts it
+    np.testing.assert_array_equal(synth.f32_to_fp8_bits(lib_vals[:0x7F].astype(np.float32)), codes[:0x7F])
+    a = synth.rng(36, 8).standard_normal(20000).astype(np.float32) * np.float32(3.0)
+    a[:2000] *= np.float32(1e-2)                                  # into the subnormals
+    a[2000:2100] = np.linspace(-440, 440, 100, dtype=np.float32)
+    halfway = (lib_vals[1:0x7E] + lib_vals[2:0x7F]) / 2           # ties: to the even code
+    a = np.concatenate([a, halfway.astype(np.float32), -halfway.astype(np.float32)])
+    want = torch.from_numpy(a).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(synth.f32_to_fp8_bits(a), want)
+    # the layer on bytes = the layer on the same values held as float32
+    s, x, wt, b, mask = _setup(36, dtype=synth.FP8)
+    assert x.dtype == np.uint8 and wt.dtype == np.uint8
+    got = O.focused_conv2d(s, x, wt, bias=b, mask_in=mask, dtype=O.FP8)
+    xf = torch.from_numpy(x).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    wf = torch.from_numpy(wt).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    np.testing.assert_array_equal(got, O.focused_conv2d(s, xf, wf, bias=b, mask_in=mask))
+    assert np.count_nonzero(got) > got.size // 8
+
+
 # ------------------------------------------- Table I: multiply-adds follow the kept share ----
 
 def test_table1_ratio_is_kept_fraction():
