@@ -31,27 +31,33 @@ if ROOT not in sys.path:
 
 METRIC = "focused-conv effective TFLOP/s + speedup vs dense at 48% irrelevant pixels"
 BF16_MFMA_PEAK_TFLOPS = 2500.0
+FP8_MFMA_PEAK_TFLOPS = 5000.0
 # HBM bytes per launch of the conv kernel on the default workload (mean of the four layers),
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the counter read for a
 # 256 MiB streaming copy (x2.00 and x1.00): profiles/k_conv_dma_resnet50_3x3_b16_48pct.md
 TRAFFIC_BYTES_PER_LAUNCH = 41.0e6
 
 
-def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch):
-    """Device tensors for the four ResNet-50 3x3 shapes."""
+def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch, in_dtype=None):
+    """Device tensors for the four ResNet-50 3x3 shapes (bf16 storage, or E4M3 bytes with
+    bf16 outputs)."""
+    in_dtype = B.BF16 if in_dtype is None else in_dtype
     dev = torch.device("cuda:0")
     layers = []
     for li, (c, side) in enumerate(workloads.sweep_shapes()):
         key = (5, li)
-        x = synth.activations((batch, side, side, c), synth.BF16, *key, 1)
-        w = synth.he_weights(c, 3, 3, c, synth.BF16, *key, 2)
+        x = synth.activations((batch, side, side, c), in_dtype, *key, 1)
+        w = synth.he_weights(c, 3, 3, c, in_dtype, *key, 2)
         bias = synth.bias(c, *key, 3)
         if mask_kind == "bernoulli":
             mask = synth.mask_bernoulli(batch, side, side, irrelevant, *key, 4)
         else:
             mask = synth.mask_objects(batch, side, side, irrelevant, *key, 4)
-        desc = B.conv_desc(batch, side, side, c, c, in_dtype=B.BF16, out_dtype=B.BF16, flags=B.RELU)
-        to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        desc = B.conv_desc(batch, side, side, c, c, in_dtype=in_dtype, out_dtype=B.BF16, flags=B.RELU)
+        if in_dtype == B.FP8:
+            to_dev = lambda codes: torch.from_numpy(codes).to(dev).view(torch.float8_e4m3fn)
+        else:
+            to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
         L = dict(name="c%d@%d" % (c, side), desc=desc, c=c, side=side,
                  x=to_dev(x), w=to_dev(w), bias=torch.from_numpy(bias).to(dev),
                  mask=torch.from_numpy(mask).to(dev), host=(x, w, bias, mask),
@@ -101,7 +107,7 @@ def cpu_baseline(layers, images):
         c, side = L["c"], L["side"]
         s = O.ConvShape(images, side, side, c, c, relu=True)
         t0 = time.perf_counter()
-        O.focused_conv2d(s, x[:images], w, bias=bias, mask_in=mask[:images], dtype=O.BF16)
+        O.focused_conv2d(s, x[:images], w, bias=bias, mask_in=mask[:images], dtype=L["desc"].in_dtype)
         t += time.perf_counter() - t0
         flops += 2.0 * int(np.count_nonzero(mask[:images])) * L["k"] * c
     return flops / t / 1e12, O.num_threads(), t
@@ -299,6 +305,9 @@ def main():
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=16)
+    ap.add_argument("--in-dtype", choices=("bf16", "fp8"), default="bf16",
+                    help="storage type of activations and weights of the bench line (fp8 = E4M3 bytes, "
+                         "outputs bf16; the headline is bf16)")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel loop (for rocprofv3 --kernel-trace --stats)")
     ap.add_argument("--sweep", action="store_true",
@@ -336,7 +345,9 @@ def main():
     if args.depthwise:
         depthwise_bench(torch, B, synth, workloads, args)
         return
-    layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch)
+    in_dtype = B.FP8 if args.in_dtype == "fp8" else B.BF16
+    peak = FP8_MFMA_PEAK_TFLOPS if in_dtype == B.FP8 else BF16_MFMA_PEAK_TFLOPS
+    layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch, in_dtype)
 
     # The four shapes are the four resolutions of one network, so they see ONE mask, rescaled
     # (Sec. III-B): the mask of the first layer, subsampled by two per resolution change.
@@ -364,7 +375,7 @@ def main():
         L["call_dense"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"], workspace_ready=True)
         L["call_conv_only"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
                                              idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"], workspace_ready=True)
-        dk = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=B.BF16, out_dtype=B.BF16,
+        dk = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=in_dtype, out_dtype=B.BF16,
                          flags=B.RELU | B.SKIP_ZERO_FILL)
         L["call_kernel"] = B.PreparedConv(dk, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
                                           idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"], workspace_ready=True)
@@ -449,10 +460,11 @@ def main():
     flops_kept = sum(L["flops_kept"] for L in layers)
     kern_avg_s = sum(per_layer_ms) / 1e3 / len(layers)
     achieved = (flops_kept / len(layers)) / kern_avg_s / 1e12
-    default_workload = (args.irrelevant is None and args.mask == "blobs" and args.batch is None)
+    default_workload = (args.irrelevant is None and args.mask == "blobs" and args.batch is None and
+                        in_dtype == B.BF16)
     roofline = {
-        "bound": "mfma", "kernel": "k_conv_dma", "achieved": round(achieved, 3), "peak": BF16_MFMA_PEAK_TFLOPS,
-        "unit": "TFLOP/s", "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+        "bound": "mfma", "kernel": "k_conv_dma", "achieved": round(achieved, 3), "peak": peak,
+        "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
         "traffic": TRAFFIC_BYTES_PER_LAUNCH if default_workload else None,
         "avg_launch_us": round(kern_avg_s * 1e6, 3),
         "flops_per_launch": round(flops_kept / len(layers)),
@@ -475,10 +487,11 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": args.in_dtype,
         "data": "synthetic",
         "config": {
-            "workload": "ResNet-50 3x3 layer shapes (C64@128, C128@64, C256@32, C512@16), batch %d, "
+            "workload": ("" if in_dtype == B.BF16 else "E4M3 storage, bf16 outputs: ") +
+                        "ResNet-50 3x3 layer shapes (C64@128, C128@64, C256@32, C512@16), batch %d, "
                         "one %s mask per image with %.0f %% irrelevant, rescaled to the four resolutions; step = "
                         "mask pyramid (propagation + compaction for all four layers, two launches) + focused "
                         "conv + zero-fill per layer" % (batch, args.mask, 100 * irr),

@@ -58,7 +58,14 @@ typedef enum {
     FC_ERR_HIP = -7        /* the HIP runtime refused a launch */
 } fc_status;
 
-typedef enum { FC_F32 = 0, FC_BF16 = 1, FC_F16 = 2 } fc_dtype;
+/* FC_FP8 is the 8-bit E4M3 format of the OCP 8-bit floating point specification (the
+ * variant without infinities; bias 7, largest value 448, 0x7F/0xFF = NaN), one byte per
+ * value, as the gfx950 matrix cores read it.  The paper's method does not depend on the
+ * storage type (Sec. III-A keeps the layer's weights and arithmetic unchanged); the 8-bit
+ * form halves the gathered bytes.  Values are used as stored: a caller that quantises with
+ * per-tensor scales folds their product into the bias (divide it) and into whatever reads
+ * the output (ReLU commutes with a positive scale). */
+typedef enum { FC_F32 = 0, FC_BF16 = 1, FC_F16 = 2, FC_FP8 = 3 } fc_dtype;
 
 enum {
     FC_RELU = 1u,           /* max(.,0) at kept positions */
@@ -73,7 +80,9 @@ enum {
 enum { FC_WORKSPACE_COUNTER_BYTES = 2048 };
 
 /* One convolution layer.  in_dtype is the storage type of x and w; out_dtype is
- * in_dtype or FC_F32. */
+ * in_dtype or FC_F32 (for FC_FP8 inputs: FC_BF16 or FC_F32).  FC_FP8 is served by
+ * fc_focused_conv2d only, and only for layers with c_in a multiple of 16, c_out a multiple
+ * of 8 and at most 32 taps; anything else gives FC_ERR_DTYPE. */
 typedef struct fc_conv_desc {
     int32_t n, h, w, c_in, c_out, kh, kw;
     int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;

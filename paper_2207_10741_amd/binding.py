@@ -13,7 +13,7 @@ from dataclasses import dataclass
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfocused_conv.so")
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, FP8 = 0, 1, 2, 3
 RELU, SKIP_ZERO_FILL, WORKSPACE_READY = 1, 2, 4
 RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 WORKSPACE_COUNTER_BYTES = 2048
@@ -46,7 +46,8 @@ class MaskStep(ctypes.Structure):
 def conv_desc(n, h, w, c_in, c_out, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1),
               in_dtype=BF16, out_dtype=None, flags=0) -> ConvDesc:
     return ConvDesc(n, h, w, c_in, c_out, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
-                    dil[0], dil[1], in_dtype, in_dtype if out_dtype is None else out_dtype, flags)
+                    dil[0], dil[1], in_dtype,
+                    (BF16 if in_dtype == FP8 else in_dtype) if out_dtype is None else out_dtype, flags)
 
 
 _lib = None
@@ -143,7 +144,7 @@ def _stream(stream):
 
 def torch_dtype(code: int):
     torch = _torch()
-    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[code]
+    return {F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16, FP8: torch.float8_e4m3fn}[code]
 
 
 def _require_cuda(*tensors):

@@ -21,8 +21,11 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
     if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c_in <= 0 || d->c_out <= 0 || d->kh <= 0 || d->kw <= 0 ||
         d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0 || d->dil_h <= 0 || d->dil_w <= 0)
         return FC_ERR_SHAPE;
-    if (d->in_dtype != FC_F32 && d->in_dtype != FC_BF16 && d->in_dtype != FC_F16) return FC_ERR_DTYPE;
-    if (d->out_dtype != d->in_dtype && d->out_dtype != FC_F32) return FC_ERR_DTYPE;
+    if (d->in_dtype != FC_F32 && d->in_dtype != FC_BF16 && d->in_dtype != FC_F16 && d->in_dtype != FC_FP8)
+        return FC_ERR_DTYPE;
+    // 8-bit inputs round to bfloat16 (or stay fp32); every other type to itself or fp32
+    if (d->out_dtype != (d->in_dtype == FC_FP8 ? FC_BF16 : d->in_dtype) && d->out_dtype != FC_F32)
+        return FC_ERR_DTYPE;
     if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY)) return FC_ERR_DTYPE;
     const int32_t ho = out_dim(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
     const int32_t wo = out_dim(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
@@ -178,6 +181,8 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     hipStream_t s = (hipStream_t)stream;
 
     const bool mfma = conv_mfma_supported(g, desc->in_dtype, desc->out_dtype);
+    // 8-bit layers exist on the matrix cores only (16 | c_in, 8 | c_out, at most 32 taps)
+    if (desc->in_dtype == FC_FP8 && !mfma) return FC_ERR_DTYPE;
     const ConvWorkspace l = conv_ws_layout(g);
     // split-K scratch of the matrix-core path, when the layer is small enough to want it and
     // the caller gave room
@@ -249,6 +254,7 @@ int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8
     if (!x || !w || !out) return FC_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(bias)) return FC_ERR_ALIGN;
     if (x == out) return FC_ERR_NULL;
+    if (desc->in_dtype == FC_FP8) return FC_ERR_DTYPE; // no 8-bit depthwise layer
     if (!conv_depthwise_supported(g, desc->in_dtype)) return FC_ERR_RANGE;
     const hipError_t e = launch_conv_depthwise(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, out,
                                                (hipStream_t)stream);

@@ -3,11 +3,15 @@
 //
 // GEMM view: rows = kept output positions (from the index list), reduction
 // K = (tap, input channel), columns = output channels.  The patch matrix is never
-// stored: for every (tap, 64-channel chunk) = one pipeline stage, the workgroup
+// stored: for every (tap, 128-byte chunk of channels) = one pipeline stage, the workgroup
 // gathers, for each of its TM positions, the 128 contiguous bytes of that tap's NHWC
 // pixel into LDS (zeros where the tap falls outside the image or on an irrelevant
-// input pixel), next to the TN x 64 slab of weights for the same tap, and feeds both
-// to v_mfma_f32_32x32x16 with fp32 accumulators.
+// input pixel), next to the TN x 128-byte slab of weights for the same tap, and feeds
+// both to the matrix cores with fp32 accumulators: v_mfma_f32_32x32x16 for bf16 / f16
+// storage (64 channels per stage, four instructions per 32 x 32 block), and
+// v_mfma_f32_32x32x64_f8f6f4 for 8-bit E4M3 storage (128 channels per stage, two
+// instructions of twice the length).  Everything outside the multiply itself - gather,
+// swizzle, pipeline, epilogue - moves bytes and is the same code for both.
 //
 // Data path.  The gathers go straight from global memory into LDS ("buffer_load ...
 // lds", 16 bytes per lane) without passing through registers: measured on this chip a
@@ -47,9 +51,10 @@ namespace fc {
 
 constexpr uint32_t kBufferLimit = 0xF0000000u; // tensors handled through one descriptor stay below this
 constexpr uint32_t kOutOfRange = kBufferLimit; // offset that is out of range for every descriptor
-constexpr int kTK = 64;                        // reduction elements per stage (one 128-byte pixel chunk)
+constexpr int kStageBytes = 128;               // bytes of one pixel a stage gathers (64 16-bit or 128 8-bit channels)
 constexpr int kMaxSplits = 16;                 // most K-splits of one tile
 constexpr int kMinSplitStages = 8;            // fewest stages a K-split is left with
+constexpr int kBusySplitStages = 64;          // shortest reduction that is split on a busy chip
 constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
 
 // Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
@@ -133,7 +138,16 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     constexpr int L = XR + WR;         // loads per thread per stage
     constexpr int WTM = TM / WM, WTN = TN / WN;
     constexpr int PB = WTM / 32, CB = WTN / 32;
-    constexpr int KK = kTK / 16;
+    constexpr int ES = DT == FC_FP8 ? 1 : 2;               // bytes per stored element
+    constexpr int TK = kStageBytes / ES;                   // reduction elements per stage
+    constexpr int EPP = 16 / ES;                           // elements per 16-byte piece
+    constexpr uint32_t KSTEP = kStepBytes<DT>;             // bytes of a row per matrix instruction
+    constexpr int KK = kStageBytes / (int)KSTEP;           // matrix instructions per stage and block pair
+    constexpr int ODT = DT == FC_FP8 ? FC_BF16 : DT;       // 16-bit output format
+    // register sets of operand fragments: the 16-bit types fetch step kk + 1 while step kk is
+    // multiplied; fp8 fragments are twice as large and its instructions twice as long, so one set,
+    // refilled behind the multiplies of a step, keeps the kernel inside the register file
+    constexpr int FB = (DT == FC_FP8 && TM * TN >= 128 * 128) ? 1 : 2;
     constexpr int PAIR_IT = (TM * TAPC + NT - 1) / NT;
     constexpr int PAIR_CH = PAIR_IT < 5 ? PAIR_IT : 5;
     constexpr int STAGE_BYTES = (TM + TN) * 128;
@@ -200,17 +214,19 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     const int ntiles = ((rows + TM - 1) / TM) * n_nt;
     const int taps = TAPC == 32 ? g.kh * g.kw : TAPC;
     const int kwid = TAPC == 32 ? g.kw : (TAPC == 9 ? 3 : 1);
-    const int cchunks = (g.c_in + kTK - 1) / kTK;
+    const int cchunks = (g.c_in + TK - 1) / TK;
     const int stages = taps * cchunks;
     const bool self_tap = TAPC == 1 && g.ph == 0 && g.pw == 0;
-    const u32x4_t rsrc_x = make_rsrc_words(x, (uint32_t)g.n * g.h * g.w * g.c_in * 2u);
-    const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * taps * g.c_in * 2u);
+    const u32x4_t rsrc_x = make_rsrc_words(x, (uint32_t)g.n * g.h * g.w * g.c_in * (uint32_t)ES);
+    const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * taps * g.c_in * (uint32_t)ES);
 
-    // fragment addressing: lane reads row (lane & 31) of a 32-row block, 16-byte piece
-    // 2*kk + (lane >> 5), stored at slot piece ^ ((row >> 1) & 7); all block bases are
-    // multiples of 32 rows, so the swizzle term depends on the lane only
+    // fragment addressing: lane reads row (lane & 31) of a 32-row block; in step kk that is
+    // the 16-byte piece 2*kk + (lane >> 5) (fp8: the pieces 4*kk + 2*(lane >> 5) and the one
+    // after it), stored at slot piece ^ ((row >> 1) & 7); all block bases are multiples of 32
+    // rows, so the swizzle term depends on the lane only
+    constexpr uint32_t HALF = KSTEP / 32u; // piece index of the upper half-wave within a step
     const uint32_t frag_row = (uint32_t)(lane & 31) * 128u;
-    const uint32_t frag_t16 = (uint32_t)((lane >> 5) ^ FC_SWZ(lane & 31)) * 16u;
+    const uint32_t frag_t16 = (uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(lane & 31)) * 16u;
 
     // Tile order: all row tiles of channel tile 0, then of channel tile 1, ...  Workgroups
     // are dispatched round-robin over the 8 XCDs, each with its own L2, so XCD j takes the
@@ -233,6 +249,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         // 64 input channels: 8.4 us unsplit against 19.3 us split three ways)
         const int s_cap = stages / kMinSplitStages;
         if (S > s_cap) S = s_cap < 1 ? 1 : s_cap;
+        // when the tiles alone already fill more than a quarter of the grid, the exchange also
+        // competes with the other tiles' traffic and only long reductions gain (512 channels at
+        // 16 x 16, batch 16: 72 stages split three ways 31 -> 26 us, 36 stages 20 -> 28 us)
+        if (ntiles * 4 > (int)gridDim.x && stages < kBusySplitStages) S = 1;
     }
     const int nunits = ntiles * S;
     const int per_xcd = (nunits + 7) >> 3;
@@ -465,7 +485,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             const int r = prow + j * RPP;
             const int co = co0 + r;
             wgp[j] = slot ^ FC_SWZ(r);
-            woff[j] = co < g.c_out ? ((uint32_t)co * (uint32_t)(taps * g.c_in) + (uint32_t)wgp[j] * 8u) * 2u
+            woff[j] = co < g.c_out ? ((uint32_t)co * (uint32_t)(taps * g.c_in) + (uint32_t)wgp[j] * EPP) * ES
                                    : kOutOfRange;
         }
 
@@ -498,7 +518,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             for (int j = 0; j < XL; ++j) {
                 const int sl = prow + j * RPP;
                 hxgp[j] = slot ^ FC_SWZ(sl);
-                hxoff[j] = ((uint32_t)slot_pix[sl] * (uint32_t)g.c_in + (uint32_t)hxgp[j] * 8u) * 2u;
+                hxoff[j] = ((uint32_t)slot_pix[sl] * (uint32_t)g.c_in + (uint32_t)hxgp[j] * EPP) * ES;
                 hxbits[j] = slot_bits[sl];
             }
             // fragment addressing: the three slots of this lane's rows
@@ -509,7 +529,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
                     const int sl = cs + t - 1;
-                    xfa[a][t] = (uint32_t)sl * 128u + (uint32_t)((lane >> 5) ^ FC_SWZ(sl)) * 16u;
+                    xfa[a][t] = (uint32_t)sl * 128u + (uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(sl)) * 16u;
                 }
             }
             const int groups = g.kh * cchunks;
@@ -521,13 +541,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             uint32_t ld_off[WR + XL], ld_lds[WR + XL];
 #define FC_HALO_PREP_X(at)                                                                                \
     {                                                                                                     \
-        const uint32_t sx = (uint32_t)((xkh * g.dh) * g.w * g.c_in + xcc * kTK) * 2u;                     \
+        const uint32_t sx = (uint32_t)((xkh * g.dh) * g.w * g.c_in + xcc * TK) * ES;                      \
         const uint32_t l0 = lds0 + (uint32_t)xbuf_i * XB + (uint32_t)wave * 1024u;                        \
         const bool in_k = xleft > 0;                                                                      \
         --xleft;                                                                                          \
         _Pragma("unroll") for (int j = 0; j < XL; ++j)                                                    \
         {                                                                                                 \
-            const bool ok = in_k && xcc * kTK + hxgp[j] * 8 < g.c_in && ((hxbits[j] >> (xkh & 31)) & 1u); \
+            const bool ok = in_k && xcc * TK + hxgp[j] * EPP < g.c_in && ((hxbits[j] >> (xkh & 31)) & 1u); \
             ld_off[(at) + j] = ok ? hxoff[j] + sx : kOutOfRange;                                          \
             ld_lds[(at) + j] = l0 + (uint32_t)j * (RPP * 128);                                            \
         }                                                                                                 \
@@ -538,13 +558,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     }
 #define FC_HALO_PREP_W()                                                                                  \
     {                                                                                                     \
-        const uint32_t sw = (uint32_t)((wkh * 3 + wkw) * g.c_in + wcc * kTK) * 2u;                        \
+        const uint32_t sw = (uint32_t)((wkh * 3 + wkw) * g.c_in + wcc * TK) * ES;                         \
         const uint32_t l0 = lds0 + 2u * XB + (uint32_t)wbuf_i * WB + (uint32_t)wave * 1024u;              \
         const bool in_k = wleft > 0;                                                                      \
         --wleft;                                                                                          \
         _Pragma("unroll") for (int j = 0; j < WR; ++j)                                                    \
         {                                                                                                 \
-            const bool ok = in_k && wcc * kTK + wgp[j] * 8 < g.c_in;                                      \
+            const bool ok = in_k && wcc * TK + wgp[j] * EPP < g.c_in;                                     \
             ld_off[j] = ok ? woff[j] + sw : kOutOfRange;                                                  \
             ld_lds[j] = l0 + (uint32_t)j * (RPP * 128);                                                   \
         }                                                                                                 \
@@ -587,23 +607,20 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                         stage0 + 2u * XB + (uint32_t)cwb * WB + (wave_n * WTN) * 128 + frag_row;
                     const int nld = t == 0 ? WR + XL : WR;
                     const int lpk = t == 0 ? (WR + XL + KK - 1) / KK : (WR + KK - 1) / KK;
-                    uint4 wf[2][CB], xf[2][PB];
+                    Frag<DT> wf[FB][CB], xf[FB][PB];
 #pragma unroll
-                    for (int b = 0; b < CB; ++b)
-                        wf[0][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + frag_t16);
+                    for (int b = 0; b < CB; ++b) wf[0][b].load(ws + b * 4096, frag_t16);
 #pragma unroll
-                    for (int a = 0; a < PB; ++a) xf[0][a] = *reinterpret_cast<const uint4 *>(xs + xfa[a][t]);
+                    for (int a = 0; a < PB; ++a) xf[0][a].load(xs, xfa[a][t]);
 #pragma unroll
                     for (int kk = 0; kk < KK; ++kk) {
-                        if (kk + 1 < KK) {
-                            const uint32_t o = ((uint32_t)(kk + 1) * 32u) ^ frag_t16;
+                        if (FB == 2 && kk + 1 < KK) {
+                            const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
-                            for (int b = 0; b < CB; ++b)
-                                wf[(kk + 1) & 1][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + o);
+                            for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
 #pragma unroll
                             for (int a = 0; a < PB; ++a)
-                                xf[(kk + 1) & 1][a] = *reinterpret_cast<const uint4 *>(
-                                    xs + (xfa[a][t] ^ ((uint32_t)(kk + 1) * 32u)));
+                                xf[(kk + 1) & 1][a].load(xs, xfa[a][t] ^ ((uint32_t)(kk + 1) * KSTEP));
                         }
                         __builtin_amdgcn_sched_barrier(0);
                         FC_HALO_ISSUE(kk * lpk, (kk + 1) * lpk, nld)
@@ -611,7 +628,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                         for (int a = 0; a < PB; ++a)
 #pragma unroll
                             for (int b = 0; b < CB; ++b)
-                                acc[a][b] = mfma32<DT>(wf[kk & 1][b], xf[kk & 1][a], acc[a][b]);
+                                acc[a][b] = mfma32<DT>(wf[kk % FB][b], xf[kk % FB][a], acc[a][b]);
+                        if (FB == 1 && kk + 1 < KK) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
+#pragma unroll
+                            for (int b = 0; b < CB; ++b) wf[0][b].load(ws + b * 4096, o);
+#pragma unroll
+                            for (int a = 0; a < PB; ++a) xf[0][a].load(xs, xfa[a][t] ^ ((uint32_t)(kk + 1) * KSTEP));
+                        }
                     }
                     cwb = (cwb + 1 == NBW) ? 0 : cwb + 1;
                 }
@@ -628,7 +653,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         for (int j = 0; j < XR; ++j) {
             const int r = prow + j * RPP;
             xgp[j] = slot ^ FC_SWZ(r);
-            xoff[j] = ((uint32_t)row_base[r] * (uint32_t)g.c_in + (uint32_t)xgp[j] * 8u) * 2u;
+            xoff[j] = ((uint32_t)row_base[r] * (uint32_t)g.c_in + (uint32_t)xgp[j] * EPP) * ES;
             xbits[j] = row_bits[r];
         }
         // cursor: the next stage to be issued (starts at this unit's first stage)
@@ -641,20 +666,20 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         uint32_t ld_off[L], ld_lds[L];
 #define FC_PREPARE_STAGE()                                                                                \
     {                                                                                                     \
-        const uint32_t sx = (uint32_t)(((kh * g.dh) * g.w + kw * g.dw) * g.c_in + cc * kTK) * 2u;         \
-        const uint32_t sw = (uint32_t)(tap * g.c_in + cc * kTK) * 2u;                                     \
+        const uint32_t sx = (uint32_t)(((kh * g.dh) * g.w + kw * g.dw) * g.c_in + cc * TK) * ES;          \
+        const uint32_t sw = (uint32_t)(tap * g.c_in + cc * TK) * ES;                                      \
         const uint32_t ldsx = lds0 + (uint32_t)ibuf * STAGE_BYTES + (uint32_t)wave * 1024u;               \
         const bool in_k = to_issue > 0;                                                                   \
         --to_issue;                                                                                       \
         _Pragma("unroll") for (int j = 0; j < XR; ++j)                                                    \
         {                                                                                                 \
-            const bool ok = in_k && cc * kTK + xgp[j] * 8 < g.c_in && ((xbits[j] >> (tap & 31)) & 1u);    \
+            const bool ok = in_k && cc * TK + xgp[j] * EPP < g.c_in && ((xbits[j] >> (tap & 31)) & 1u);   \
             ld_off[j] = ok ? xoff[j] + sx : kOutOfRange;                                                  \
             ld_lds[j] = ldsx + (uint32_t)j * (RPP * 128);                                                 \
         }                                                                                                 \
         _Pragma("unroll") for (int j = 0; j < WR; ++j)                                                    \
         {                                                                                                 \
-            const bool ok = in_k && cc * kTK + wgp[j] * 8 < g.c_in;                                       \
+            const bool ok = in_k && cc * TK + wgp[j] * EPP < g.c_in;                                      \
             ld_off[XR + j] = ok ? woff[j] + sw : kOutOfRange;                                             \
             ld_lds[XR + j] = ldsx + (uint32_t)(TM * 128 + j * (RPP * 128));                               \
         }                                                                                                 \
@@ -685,21 +710,19 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             __syncthreads();            // ... and everyone else's; buffer (s-1) % NB is free
             const unsigned char *xs = stage0 + cbuf * STAGE_BYTES + (wave_m * WTM) * 128 + frag_row;
             const unsigned char *ws = stage0 + cbuf * STAGE_BYTES + (TM + wave_n * WTN) * 128 + frag_row;
-            uint4 wf[2][CB], xf[2][PB];
+            Frag<DT> wf[FB][CB], xf[FB][PB];
 #pragma unroll
-            for (int b = 0; b < CB; ++b) wf[0][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + frag_t16);
+            for (int b = 0; b < CB; ++b) wf[0][b].load(ws + b * 4096, frag_t16);
 #pragma unroll
-            for (int a = 0; a < PB; ++a) xf[0][a] = *reinterpret_cast<const uint4 *>(xs + a * 4096 + frag_t16);
+            for (int a = 0; a < PB; ++a) xf[0][a].load(xs + a * 4096, frag_t16);
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk) {
-                if (kk + 1 < KK) {
-                    const uint32_t o = ((uint32_t)(kk + 1) * 32u) ^ frag_t16;
+                if (FB == 2 && kk + 1 < KK) {
+                    const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
-                    for (int b = 0; b < CB; ++b)
-                        wf[(kk + 1) & 1][b] = *reinterpret_cast<const uint4 *>(ws + b * 4096 + o);
+                    for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
 #pragma unroll
-                    for (int a = 0; a < PB; ++a)
-                        xf[(kk + 1) & 1][a] = *reinterpret_cast<const uint4 *>(xs + a * 4096 + o);
+                    for (int a = 0; a < PB; ++a) xf[(kk + 1) & 1][a].load(xs + a * 4096, o);
                 }
                 // keep the order "fetch step kk+1, then multiply step kk": the LDS latency
                 // then hides under the MFMAs
@@ -710,7 +733,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                 for (int a = 0; a < PB; ++a)
 #pragma unroll
-                    for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[kk & 1][b], xf[kk & 1][a], acc[a][b]);
+                    for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[kk % FB][b], xf[kk % FB][a], acc[a][b]);
+                if (FB == 1 && kk + 1 < KK) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
+#pragma unroll
+                    for (int b = 0; b < CB; ++b) wf[0][b].load(ws + b * 4096, o);
+#pragma unroll
+                    for (int a = 0; a < PB; ++a) xf[0][a].load(xs + a * 4096, o);
+                }
             }
             cbuf = (cbuf + 1 == NB) ? 0 : cbuf + 1;
         }
@@ -791,12 +822,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                             v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
                             v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
                         }
-                        store4<DT, TO>(reinterpret_cast<TO *>(Os + r * OP) + cl, v0, v1, v2, v3);
+                        store4<ODT, TO>(reinterpret_cast<TO *>(Os + r * OP) + cl, v0, v1, v2, v3);
                     } else {
                         // 16-bit outputs: round first, then clear the values whose sign bit is set, two
                         // at a time (rounding keeps the sign, so this is max(., 0) of the rounded value)
                         uint2 pk;
-                        store4<DT, TO>(reinterpret_cast<TO *>(&pk), v0, v1, v2, v3);
+                        store4<ODT, TO>(reinterpret_cast<TO *>(&pk), v0, v1, v2, v3);
                         if (g.flags & FC_RELU) {
                             pk.x = relu_packed16(pk.x);
                             pk.y = relu_packed16(pk.y);
@@ -838,15 +869,17 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 
 bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 {
-    if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
-    if (out_dtype != in_dtype && out_dtype != FC_F32) return false;
-    if (g.c_in % 8 != 0 || g.c_out % 8 != 0) return false; // 16-byte gathers, 4-channel stores
+    if (in_dtype != FC_BF16 && in_dtype != FC_F16 && in_dtype != FC_FP8) return false;
+    // fp8 layers round to bfloat16 (or stay fp32); the 16-bit types keep their own format
+    if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32) return false;
+    const uint64_t es = in_dtype == FC_FP8 ? 1u : 2u;
+    if ((g.c_in * es) % 16 != 0 || g.c_out % 8 != 0) return false; // 16-byte gathers, 4-channel stores
     if (g.kh * g.kw > kMaxTaps) return false;
     // row origins are packed into signed 16-bit halves
     if (g.h > 16384 || g.w > 16384 || g.ph > 8192 || g.pw > 8192) return false;
     // x and w are each addressed through one buffer descriptor with 32-bit byte offsets
-    if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
-    if ((uint64_t)g.c_out * g.kh * g.kw * g.c_in * 2u >= kBufferLimit) return false;
+    if ((uint64_t)g.n * g.h * g.w * g.c_in * es >= kBufferLimit) return false;
+    if ((uint64_t)g.c_out * g.kh * g.kw * g.c_in * es >= kBufferLimit) return false;
     return true;
 }
 
@@ -970,6 +1003,11 @@ hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const vo
         if (out_dtype == FC_F32)
             return launch_dt<FC_BF16, float>(FC_ARGS2);
         return launch_dt<FC_BF16, uint16_t>(FC_ARGS2);
+    }
+    if (in_dtype == FC_FP8) {
+        if (out_dtype == FC_F32)
+            return launch_dt<FC_FP8, float>(FC_ARGS2);
+        return launch_dt<FC_FP8, uint16_t>(FC_ARGS2);
     }
     if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(FC_ARGS2);
     return launch_dt<FC_F16, uint16_t>(FC_ARGS2);

@@ -14,10 +14,12 @@ def dev():
 
 
 def to_dev(storage: np.ndarray, dtype: int):
-    """Storage array (float32, or uint16 bit patterns) -> device tensor of that dtype."""
+    """Storage array (float32, uint16 bit patterns or E4M3 bytes) -> device tensor of that dtype."""
     torch = torch_mod()
     if dtype == synth.F32:
         return torch.from_numpy(np.ascontiguousarray(storage, dtype=np.float32)).to(dev())
+    if dtype == synth.FP8:
+        return torch.from_numpy(np.ascontiguousarray(storage, dtype=np.uint8)).to(dev()).view(torch.float8_e4m3fn)
     t = torch.from_numpy(np.ascontiguousarray(storage).view(np.int16)).to(dev())
     return t.view(torch.bfloat16 if dtype == synth.BF16 else torch.float16)
 
@@ -27,6 +29,8 @@ def to_storage_np(t, dtype: int) -> np.ndarray:
     torch = torch_mod()
     if dtype == synth.F32:
         return t.detach().cpu().numpy()
+    if dtype == synth.FP8:
+        return t.detach().view(torch.uint8).cpu().numpy()
     return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
 
 

@@ -53,6 +53,8 @@ def test_descriptor_errors():
     assert rc(h=2, pad=(0, 0)) == -2                      # empty output
     assert rc(in_dtype=7) == -3
     assert rc(in_dtype=B.F32, out_dtype=B.BF16) == -3     # output narrower than the input type
+    assert rc(in_dtype=B.FP8, out_dtype=B.BF16) == 0 and rc(in_dtype=B.FP8, out_dtype=B.F32) == 0
+    assert rc(in_dtype=B.FP8, out_dtype=B.FP8) == -3 and rc(in_dtype=B.FP8, out_dtype=B.F16) == -3
     assert rc(flags=64) == -3
     assert rc(flags=B.RELU | B.SKIP_ZERO_FILL | B.WORKSPACE_READY) == 0
     assert B.WORKSPACE_COUNTER_BYTES == int(re.search(r"FC_WORKSPACE_COUNTER_BYTES\s*=\s*(\d+)", HEADER_TEXT).group(1))
@@ -103,7 +105,13 @@ def test_null_pointers_rejected_before_any_launch():
     assert conv(a, a, a, None, None, None, None, o, None, 0, None) == -5      # needs a workspace
     assert conv(a, a, a, None, None, None, None, o, a, 16, None) == -5        # workspace too small
     assert conv(a, None, a, None, None, None, None, a, None, 0, None) == -1   # out aliases x
+    # 8-bit layers: only what the matrix-core path takes (16 | c_in, 8 | c_out, at most 32 taps)
+    fp8 = lambda ci, co, k=(3, 3): L.fc_focused_conv2d(
+        ctypes.byref(B.conv_desc(1, 8, 8, ci, co, k, pad=(k[0] // 2, k[1] // 2), in_dtype=B.FP8, out_dtype=B.F32)),
+        a, None, a, None, None, None, None, o, None, 0, None)
+    assert fp8(24, 64) == -3 and fp8(64, 20) == -3 and fp8(3, 64, (7, 7)) == -3 and fp8(16, 16, (7, 7)) == -3
     dw = lambda desc, *args: L.fc_focused_dwconv2d(ctypes.byref(desc), *args)
+    assert dw(B.conv_desc(1, 8, 8, 16, 16, in_dtype=B.FP8), a, None, a, None, o, None) == -3
     #              x  mask_in w  bias out stream
     assert dw(d, None, None, a, None, o, None) == -1
     assert dw(d, odd, None, a, None, o, None) == -4
