@@ -72,6 +72,32 @@ def test_layer_with_window_rule_labels_matches_oracle(layer, rule):
     assert not out.cpu().numpy()[~keep].view(np.uint32).any()
 
 
+@pytest.mark.parametrize("margin", [1, 2, 4])
+def test_context_margin_is_the_any_rule_with_a_wider_window(margin):
+    """A mask grown by a margin of context pixels (every pixel within `margin` of a relevant
+    one, Chebyshev distance) is the any-pixel rule over a (2*margin+1)^2 window at stride 1:
+    bit-exact against the oracle and against a library dilation; a layer run with the grown
+    mask as its input mask matches the oracle run with the same mask."""
+    ndimage = pytest.importorskip("scipy.ndimage")
+    torch = G.torch_mod()
+    n, h, w, ci, co = 2, 45, 61, 32, 48
+    mask = synth.mask_objects(n, h, w, 0.6, 105, margin)
+    k = 2 * margin + 1
+    grown = B.mask_downsample_rule(G.mask_dev(mask), (k, k), (1, 1), (margin, margin), (1, 1), B.RULE_ANY)
+    got = grown.cpu().numpy()
+    np.testing.assert_array_equal(got, O.mask_downsample_rule(mask, k, k, (1, 1), (margin, margin), (1, 1), O.RULE_ANY))
+    lib = np.stack([ndimage.binary_dilation(m != 0, structure=np.ones((k, k), bool)) for m in mask])
+    np.testing.assert_array_equal(got != 0, lib)
+    assert got.sum() > np.count_nonzero(mask)
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 105, 1)
+    wt = synth.he_weights(co, 3, 3, ci, dtype, 105, 2)
+    desc = B.conv_desc(n, h, w, ci, co, in_dtype=dtype, out_dtype=B.F32, flags=B.RELU)
+    out = B.focused_conv2d(desc, G.to_dev(x, dtype), G.to_dev(wt, dtype), None, mask_in=grown)
+    want = O.focused_conv2d(O.ConvShape(n, h, w, ci, co, relu=True), x, wt, mask_in=got, dtype=dtype)
+    assert G.rel_err(G.to_f64(out), want, got != 0) <= TOL_F32_OUT
+
+
 @pytest.mark.parametrize("m", [1, 15, 16, 17, 63, 64, 65, 4095, 4096, 4097, 8192, 12289, 100003, 1 << 20, 3000017])
 @pytest.mark.parametrize("irr", [0.48, 0.0, 1.0, 0.97])
 def test_active_index_compact_bit_exact(m, irr):
