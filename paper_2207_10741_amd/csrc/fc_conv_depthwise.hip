@@ -120,6 +120,28 @@ __device__ __forceinline__ void store_piece(TO *dst, const float *v)
     }
 }
 
+// a.lo * b.lo + a.hi * b.hi + c for two packed 16-bit floats per operand, summed in fp32
+// (v_dot2c_f32_bf16 / v_dot2c_f32_f16)
+typedef __bf16 bf16x2_native __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_native __attribute__((ext_vector_type(2)));
+template <typename TI>
+__device__ __forceinline__ float dot2_acc(uint32_t a, uint32_t b, float c)
+{
+    if constexpr (__is_same(TI, bf16_t))
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_native, a),
+                                               __builtin_bit_cast(bf16x2_native, b), c, false);
+    else
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_native, a), __builtin_bit_cast(f16x2_native, b), c,
+                                      false);
+}
+
+// 3 x 3 layers of the 16-bit types pair their taps: (0,1) (2,3) (4,5) (6,7) and tap 8 with a
+// zero.  The two pixels of a pair are interleaved channel by channel (one byte permute per
+// output channel) and multiplied against the packed pair of filter values by one 2-element dot
+// product, instead of two unpacks and two multiply-adds; the filters take 5 words per channel
+// instead of 9.
+constexpr int kDwPairRows = 5;
+
 // KS: compile-time square kernel size (filters in registers), or 0 for any KH x KW (filters
 // re-read through the cache at every tap).
 // WLDS: the workgroup's filters and bias sit in LDS as fp32 [tap][channel] instead of in every
@@ -134,6 +156,8 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
 {
     constexpr int PIECE = VEC * (int)sizeof(TI); // bytes of a pixel one lane owns
     constexpr int TAPS_C = KS * KS;
+    constexpr bool PAIR = KS == 3 && sizeof(TI) == 2 && VEC == 8;
+    constexpr int WROWS = PAIR ? kDwPairRows : TAPS_C; // filter words per channel (LDS rows before the bias)
     const Geom &g = a.g;
     const int b = blockIdx.y;
     const int j = threadIdx.x % a.lanes_per_pos;
@@ -142,14 +166,25 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
     const int C = g.c_in;
     const int kh_n = KS ? KS : g.kh, kw_n = KS ? KS : g.kw;
     const int taps = kh_n * kw_n;
-    extern __shared__ __align__(16) float dw_w[]; // WLDS only: [taps + 1][CT] filters, then bias
-    const int CT = a.lanes_per_pos * VEC;         // channels of this workgroup
+    // WLDS only: [WROWS + 1][CT]: the filters (fp32 per tap, or packed pairs of taps), then the bias
+    extern __shared__ __align__(16) float dw_w[];
+    const int CT = a.lanes_per_pos * VEC; // channels of this workgroup
     if constexpr (WLDS) {
         const int ch_first = blockIdx.z * CT;
-        for (int i = threadIdx.x; i < (TAPS_C + 1) * CT; i += kDwThreads) {
+        for (int i = threadIdx.x; i < (WROWS + 1) * CT; i += kDwThreads) {
             const int t = i / CT, ch = ch_first + (i - t * CT);
             float v = 0.f;
-            if (ch < C) v = t < TAPS_C ? to_float(w[(int64_t)ch * TAPS_C + t]) : (bias ? bias[ch] : 0.f);
+            if (ch < C) {
+                if (t == WROWS) {
+                    v = bias ? bias[ch] : 0.f;
+                } else if constexpr (PAIR) {
+                    const uint32_t lo = w[(int64_t)ch * TAPS_C + 2 * t].bits;
+                    const uint32_t hi = 2 * t + 1 < TAPS_C ? (uint32_t)w[(int64_t)ch * TAPS_C + 2 * t + 1].bits : 0u;
+                    v = __uint_as_float(lo | (hi << 16));
+                } else {
+                    v = to_float(w[(int64_t)ch * TAPS_C + t]);
+                }
+            }
             dw_w[i] = v;
         }
         __syncthreads();
@@ -171,7 +206,8 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
     constexpr int WBYTES = KS ? VEC * TAPS_C * (int)sizeof(TI) : 4;
     constexpr int WWORDS = (WBYTES + 3) / 4;
     uint32_t wraw[WWORDS];
-    float wr[(KS && !WPACK && !WLDS) ? VEC * TAPS_C : 1];
+    float wr[(KS && !WPACK && !WLDS && !PAIR) ? VEC * TAPS_C : 1];
+    uint32_t wpr[(PAIR && !WLDS) ? VEC * kDwPairRows : 1]; // [row][channel] packed pairs of taps
     if constexpr (KS != 0 && !WLDS) {
         const TI *wp = w + (int64_t)c0 * TAPS_C;
         if constexpr (WBYTES % 16 == 0) {
@@ -180,7 +216,17 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
                 const u32x4 t = reinterpret_cast<const u32x4 *>(wp)[k];
                 wraw[4 * k] = t.x; wraw[4 * k + 1] = t.y; wraw[4 * k + 2] = t.z; wraw[4 * k + 3] = t.w;
             }
-            if constexpr (!WPACK) {
+            if constexpr (PAIR) {
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+#pragma unroll
+                    for (int r = 0; r < kDwPairRows; ++r) {
+                        const int e0 = v * TAPS_C + 2 * r, e1 = e0 + 1;
+                        const uint32_t lo = (wraw[e0 >> 1] >> (16 * (e0 & 1))) & 0xffffu;
+                        const uint32_t hi = 2 * r + 1 < TAPS_C ? (wraw[e1 >> 1] >> (16 * (e1 & 1))) & 0xffffu : 0u;
+                        wpr[r * VEC + v] = lo | (hi << 16);
+                    }
+            } else if constexpr (!WPACK) {
 #pragma unroll
                 for (int e = 0; e < VEC * TAPS_C; ++e) wr[e] = piece_elem<TI>(wraw, e);
             }
@@ -191,6 +237,10 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
         }
     }
     const float *wl = dw_w + j * VEC; // WLDS: this lane's channels of tap 0
+    auto filter_pair = [&](int v, int r) -> uint32_t { // taps 2r and 2r + 1 of channel v
+        if constexpr (WLDS) return __float_as_uint(wl[r * CT + v]);
+        else return wpr[r * VEC + v];
+    };
     auto filter = [&](int v, int t) -> float {
         if constexpr (WLDS) return wl[t * CT + v];
         else if constexpr (WPACK) return piece_elem<TI>(wraw, v * TAPS_C + t);
@@ -236,7 +286,7 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
         }
         float acc[VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[v] = WLDS ? wl[TAPS_C * CT + v] : bv[WLDS ? 0 : v];
+        for (int v = 0; v < VEC; ++v) acc[v] = WLDS ? wl[WROWS * CT + v] : bv[WLDS ? 0 : v];
 
         if constexpr (KS != 0) {
             // 3 x 3: all nine taps in flight at once; larger kernels one kernel row at a time
@@ -272,11 +322,26 @@ __global__ __launch_bounds__(kDwThreads, (WLDS ? 8 : (KS > 3 ? 2 : 4))) void k_d
                                              : pix[t] * (uint32_t)(C * (int)sizeof(TI)) + (uint32_t)(c0 * (int)sizeof(TI));
                     xv[t] = buffer_load<PIECE>(rx, off);
                 }
+                if constexpr (PAIR) {
 #pragma unroll
-                for (int t = 0; t < GT; ++t)
+                    for (int r = 0; r < kDwPairRows; ++r)
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v)
-                        acc[v] = fmaf(piece_elem<TI>(xv[t].v, v), filter(v, kh0 * KS + t), acc[v]);
+                        for (int q = 0; q < VEC / 2; ++q) {
+                            const uint32_t x0 = xv[2 * r].v[q];
+                            const uint32_t x1 = 2 * r + 1 < GT ? xv[2 * r + 1 < GT ? 2 * r + 1 : 0].v[q] : 0u;
+                            // channel 2q of both taps, channel 2q + 1 of both taps
+                            const uint32_t even = __builtin_amdgcn_perm(x1, x0, 0x05040100u);
+                            const uint32_t odd = __builtin_amdgcn_perm(x1, x0, 0x07060302u);
+                            acc[2 * q] = dot2_acc<TI>(even, filter_pair(2 * q, r), acc[2 * q]);
+                            acc[2 * q + 1] = dot2_acc<TI>(odd, filter_pair(2 * q + 1, r), acc[2 * q + 1]);
+                        }
+                } else {
+#pragma unroll
+                    for (int t = 0; t < GT; ++t)
+#pragma unroll
+                        for (int v = 0; v < VEC; ++v)
+                            acc[v] = fmaf(piece_elem<TI>(xv[t].v, v), filter(v, kh0 * KS + t), acc[v]);
+                }
             }
         } else {
             for (int kh = 0; kh < kh_n; ++kh) {
@@ -320,7 +385,8 @@ hipError_t launch_k(const Geom &g, const void *x, const uint8_t *mask_in, const 
     a.div_wo = make_fastdiv((uint32_t)g.wo);
     const int64_t hw_out = (int64_t)g.ho * g.wo;
     const int64_t need = (hw_out + a.pos_per_block - 1) / a.pos_per_block;
-    const size_t wlds = (size_t)(KS * KS + 1) * a.lanes_per_pos * VEC * sizeof(float);
+    constexpr bool pair = KS == 3 && sizeof(TI) == 2 && VEC == 8; // as in the kernel
+    const size_t wlds = (size_t)((pair ? kDwPairRows : KS * KS) + 1) * a.lanes_per_pos * VEC * sizeof(float);
     const bool use_wlds = KS == 3 && VEC > 1 && wlds <= kDwWldsBytes;
     // eight workgroups per CU with the filters in LDS when every workgroup still has a few steps
     // to do (its start-up is not free), else four
