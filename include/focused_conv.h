@@ -198,8 +198,9 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
  * 1x1 halves are fc_focused_conv2d).  Sec. III-A unchanged otherwise: a
  * position whose centre-tap mask byte is zero gets +0.0 in every channel (or is
  * left untouched with FC_SKIP_ZERO_FILL), a kept position sees zero at
- * irrelevant input pixels and outside the image; fp32 accumulation, taps in
- * the order kh, kw, one rounding to out_dtype.
+ * irrelevant input pixels and outside the image; exact products, fp32
+ * accumulation over the taps in the order kh, kw (16-bit 3x3 layers add the
+ * taps two at a time), one rounding to out_dtype.
  *   desc      c_out must equal c_in (else FC_ERR_SHAPE); flags FC_RELU and
  *             FC_SKIP_ZERO_FILL apply
  *   x         device, NHWC, in_dtype, read only; one image must stay below

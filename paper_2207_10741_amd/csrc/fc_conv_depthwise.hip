@@ -19,8 +19,8 @@
 // that cover exactly one image: a tap outside the image or at an irrelevant pixel is given an
 // out-of-range offset, for which the hardware returns zero and touches no memory, so NaN at an
 // irrelevant pixel is never loaded.  The mask bytes of all taps are requested first, then the
-// pixels of the taps that survive, then the arithmetic (fp32, taps in the order kh, kw; one
-// rounding to the output type).
+// pixels of the taps that survive, then the arithmetic (fp32 sums over the taps in the order
+// kh, kw, two taps at a time for 16-bit 3 x 3 layers; one rounding to the output type).
 //
 // The position's own label is read from the input mask under the centre tap (Sec. III-B), so
 // no kept-position list is needed, and irrelevant positions are cleared by the lanes that
