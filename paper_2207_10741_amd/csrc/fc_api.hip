@@ -288,6 +288,8 @@ static int32_t pyramid_geometry(int32_t n, int32_t h, int32_t w, int32_t levels,
         a->ch0[l] = -t.pad_h + t.dil_h * ((t.kh - 1) / 2);
         a->cw0[l] = -t.pad_w + t.dil_w * ((t.kw - 1) / 2);
         a->m[l] = (int64_t)n * ho * wo;
+        a->div_w[l] = make_fastdiv((uint32_t)wo);
+        a->div_h[l] = make_fastdiv((uint32_t)ho);
         if (a->m[l] >= INT32_MAX) return FC_ERR_RANGE;
         a->block0[l] = (int32_t)blocks;
         blocks += compact_blocks(a->m[l]);

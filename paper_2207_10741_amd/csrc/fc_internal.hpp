@@ -176,6 +176,7 @@ struct PyramidArgs {
     int32_t h[kMaxPyramidLevels + 1], w[kMaxPyramidLevels + 1]; // [0] = input mask, [l + 1] = level l
     int32_t sh[kMaxPyramidLevels], sw[kMaxPyramidLevels], ch0[kMaxPyramidLevels], cw0[kMaxPyramidLevels];
     int64_t m[kMaxPyramidLevels];          // positions of level l
+    FastDiv div_w[kMaxPyramidLevels], div_h[kMaxPyramidLevels]; // by the level's width and height
     int32_t block0[kMaxPyramidLevels + 1]; // first block of level l; [levels] = total
     uint8_t *mask_out[kMaxPyramidLevels];
     int32_t *idx[kMaxPyramidLevels];

@@ -263,29 +263,39 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_masks(PyramidA
 #pragma unroll
             for (int b = 0; b < 4; ++b) flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
     } else if (p0 < m) {
+        // (positions fit 31 bits; the level's parameters are read with constant indices, so they
+        // sit in scalar registers instead of being fetched again for every position)
         const int wl = a.w[l + 1], hl = a.h[l + 1];
-        int ow = (int)(p0 % wl);
-        int64_t t = p0 / wl;
-        int oh = (int)(t % hl);
-        int b = (int)(t / hl);
-        // the row of the input mask this output row reads, through all levels down to the input
-        int ih = oh;
-        for (int j = l; j >= 0; --j) ih = min(max(ih * a.sh[j] + a.ch0[j], 0), a.h[j] - 1);
+        const uint32_t t = fast_div((uint32_t)p0, a.div_w[l]);
+        int ow = (int)((uint32_t)p0 - t * (uint32_t)wl);
+        int b = (int)fast_div(t, a.div_h[l]);
+        int oh = (int)(t - (uint32_t)b * (uint32_t)hl);
+        // a row / column of level l seen through all levels down to the input mask
+        auto row_in = [&](int v) {
+#pragma unroll
+            for (int q = kMaxPyramidLevels - 1; q >= 0; --q)
+                if (q <= l) v = min(max(v * a.sh[q] + a.ch0[q], 0), a.h[q] - 1);
+            return v;
+        };
+        auto col_in = [&](int v) {
+#pragma unroll
+            for (int q = kMaxPyramidLevels - 1; q >= 0; --q)
+                if (q <= l) v = min(max(v * a.sw[q] + a.cw0[q], 0), a.w[q] - 1);
+            return v;
+        };
+        int row_at = (b * a.h[0] + row_in(oh)) * a.w[0];
         // addresses first, then all sixteen bytes in flight together
-        int64_t at[16];
+        int at[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            int iw = ow;
-            for (int q = l; q >= 0; --q) iw = min(max(iw * a.sw[q] + a.cw0[q], 0), a.w[q] - 1);
-            at[j] = p0 + j < m ? ((int64_t)b * a.h[0] + ih) * a.w[0] + iw : -1;
+            at[j] = p0 + j < m ? row_at + col_in(ow) : -1;
             if (++ow == wl) {
                 ow = 0;
                 if (++oh == hl) {
                     oh = 0;
                     ++b;
                 }
-                ih = oh;
-                for (int q = l; q >= 0; --q) ih = min(max(ih * a.sh[q] + a.ch0[q], 0), a.h[q] - 1);
+                row_at = (b * a.h[0] + row_in(oh)) * a.w[0];
             }
         }
         uint8_t got[16];
