@@ -114,22 +114,31 @@ __device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_
                 flags |= ((wds[q] >> (8 * b)) & 0xffu) ? (1u << (4 * q + b)) : 0u;
         return flags;
     }
-    int ow = (int)(p0 % g.wo);
-    int64_t t = p0 / g.wo;
-    int oh = (int)(t % g.ho);
-    int b = (int)(t / g.ho);
-    for (int j = 0; j < 16 && p0 + j < g.m; ++j) {
-        const int ih = min(max(oh * g.sh + g.ch0, 0), g.h - 1);
-        const int iw = min(max(ow * g.sw + g.cw0, 0), g.w - 1);
-        if (mask_in[((int64_t)b * g.h + ih) * g.w + iw]) flags |= 1u << j;
+    // (positions fit 31 bits: 32-bit divisions; addresses first, then all sixteen bytes in
+    // flight together)
+    const uint32_t t = (uint32_t)p0 / (uint32_t)g.wo;
+    int ow = (int)((uint32_t)p0 - t * (uint32_t)g.wo);
+    int b = (int)(t / (uint32_t)g.ho);
+    int oh = (int)(t - (uint32_t)b * (uint32_t)g.ho);
+    int row_at = (b * g.h + min(max(oh * g.sh + g.ch0, 0), g.h - 1)) * g.w;
+    int at[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        at[j] = p0 + j < g.m ? row_at + min(max(ow * g.sw + g.cw0, 0), g.w - 1) : -1;
         if (++ow == g.wo) {
             ow = 0;
             if (++oh == g.ho) {
                 oh = 0;
                 ++b;
             }
+            row_at = (b * g.h + min(max(oh * g.sh + g.ch0, 0), g.h - 1)) * g.w;
         }
     }
+    uint8_t got[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) got[j] = at[j] >= 0 ? mask_in[at[j]] : (uint8_t)0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) flags |= got[j] ? (1u << j) : 0u;
     return flags;
 }
 

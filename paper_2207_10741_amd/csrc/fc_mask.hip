@@ -16,13 +16,14 @@ __global__ __launch_bounds__(256) void k_mask_downsample(const uint8_t *__restri
     const int64_t total = (int64_t)n * ho * wo;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total;
          p += (int64_t)gridDim.x * blockDim.x) {
-        int ow = (int)(p % wo);
-        int64_t t = p / wo;
-        int oh = (int)(t % ho);
-        int b = (int)(t / ho);
+        // (position counts fit 31 bits: 32-bit divisions)
+        const uint32_t t = (uint32_t)p / (uint32_t)wo;
+        const int ow = (int)((uint32_t)p - t * (uint32_t)wo);
+        const int b = (int)(t / (uint32_t)ho);
+        const int oh = (int)(t - (uint32_t)b * (uint32_t)ho);
         int ih = min(max(oh * sh + ch0, 0), h - 1);
         int iw = min(max(ow * sw + cw0, 0), w - 1);
-        mask_out[p] = mask_in[((int64_t)b * h + ih) * w + iw] ? 1 : 0;
+        mask_out[p] = mask_in[(b * h + ih) * w + iw] ? 1 : 0;
     }
 }
 
@@ -53,10 +54,11 @@ __global__ __launch_bounds__(256) void k_mask_window(const uint8_t *__restrict__
     const int64_t total = (int64_t)n * ho * wo;
     for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < total;
          p += (int64_t)gridDim.x * blockDim.x) {
-        const int ow = (int)(p % wo);
-        const int64_t t = p / wo;
-        const int oh = (int)(t % ho);
-        const uint8_t *img = mask_in + (t / ho) * ((int64_t)h * w);
+        const uint32_t t = (uint32_t)p / (uint32_t)wo; // (position counts fit 31 bits)
+        const int ow = (int)((uint32_t)p - t * (uint32_t)wo);
+        const uint32_t b = t / (uint32_t)ho;
+        const int oh = (int)(t - b * (uint32_t)ho);
+        const uint8_t *img = mask_in + (int64_t)b * ((int64_t)h * w);
         int inside = 0, relevant = 0;
         for (int i = 0; i < kh; ++i) {
             const int ih = oh * sh - ph + i * dh;
@@ -392,13 +394,13 @@ __device__ __forceinline__ bool position_kept(const Geom &g, const uint8_t *__re
                                               const uint8_t *__restrict__ mask_out, int64_t p)
 {
     if (mask_out) return mask_out[p] != 0;
-    int ow = (int)(p % g.wo);
-    int64_t t = p / g.wo;
-    int oh = (int)(t % g.ho);
-    int b = (int)(t / g.ho);
+    const uint32_t t = (uint32_t)p / (uint32_t)g.wo; // (position counts fit 31 bits)
+    const int ow = (int)((uint32_t)p - t * (uint32_t)g.wo);
+    const int b = (int)(t / (uint32_t)g.ho);
+    const int oh = (int)(t - (uint32_t)b * (uint32_t)g.ho);
     int ih = min(max(oh * g.sh - g.ph + g.dh * ((g.kh - 1) / 2), 0), g.h - 1);
     int iw = min(max(ow * g.sw - g.pw + g.dw * ((g.kw - 1) / 2), 0), g.w - 1);
-    return mask_in[((int64_t)b * g.h + ih) * g.w + iw] != 0;
+    return mask_in[(b * g.h + ih) * g.w + iw] != 0;
 }
 
 // Rows of whole 16-byte pieces: a wave looks at 64 positions at a time (one label each), lists
@@ -525,8 +527,9 @@ __global__ __launch_bounds__(256) void k_maxpool(const T *__restrict__ x, int n,
 }
 
 // 16-bit types, channel count a multiple of 8: one lane owns 8 consecutive channels of an
-// output position (16-byte loads and one 16-byte store).
-template <typename T>
+// output position (16-byte loads and one 16-byte store).  IDX: the type the flat index is split
+// in (32 bits whenever the tensor allows: the three divisions are most of the arithmetic).
+template <typename T, typename IDX>
 __global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int n, int h, int w, int c, int k,
                                                     int stride, int pad, int ho, int wo,
                                                     const uint8_t *__restrict__ keep, T *__restrict__ out)
@@ -535,13 +538,14 @@ __global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int
     const int64_t total = (int64_t)n * ho * wo * cg;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (int64_t)gridDim.x * blockDim.x) {
-        const int g8 = (int)(i % cg);
-        int64_t t = i / cg;
-        const int ow = (int)(t % wo);
-        t /= wo;
-        const int oh = (int)(t % ho);
-        const int b = (int)(t / ho);
-        if (keep && !keep[((int64_t)b * ho + oh) * wo + ow]) {
+        IDX t = (IDX)i / (IDX)cg;
+        const int g8 = (int)((IDX)i - t * (IDX)cg);
+        const IDX pos = t; // (b * ho + oh) * wo + ow
+        const IDX t2 = t / (IDX)wo;
+        const int ow = (int)(t - t2 * (IDX)wo);
+        const int b = (int)(t2 / (IDX)ho);
+        const int oh = (int)(t2 - (IDX)b * (IDX)ho);
+        if (keep && !keep[pos]) {
             *reinterpret_cast<uint4 *>(out + i * 8) = make_uint4(0, 0, 0, 0);
             continue;
         }
@@ -589,12 +593,22 @@ hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, 
     if (dtype != FC_F32 && c % 8 == 0) {
         const int64_t total8 = (int64_t)n * ho * wo * (c / 8);
         const int blocks8 = (int)((total8 + 255) / 256 > 65536 ? 65536 : (total8 + 255) / 256);
-        if (dtype == FC_BF16)
-            hipLaunchKernelGGL(k_maxpool_x8<bf16_t>, dim3(blocks8), dim3(256), 0, s, (const bf16_t *)x, n, h, w, c, k,
-                               stride, pad, ho, wo, keep, (bf16_t *)out);
-        else
-            hipLaunchKernelGGL(k_maxpool_x8<f16_t>, dim3(blocks8), dim3(256), 0, s, (const f16_t *)x, n, h, w, c, k,
-                               stride, pad, ho, wo, keep, (f16_t *)out);
+        const bool small = total8 < (int64_t)INT32_MAX;
+        if (dtype == FC_BF16) {
+            if (small)
+                hipLaunchKernelGGL((k_maxpool_x8<bf16_t, uint32_t>), dim3(blocks8), dim3(256), 0, s, (const bf16_t *)x, n,
+                                   h, w, c, k, stride, pad, ho, wo, keep, (bf16_t *)out);
+            else
+                hipLaunchKernelGGL((k_maxpool_x8<bf16_t, int64_t>), dim3(blocks8), dim3(256), 0, s, (const bf16_t *)x, n,
+                                   h, w, c, k, stride, pad, ho, wo, keep, (bf16_t *)out);
+        } else {
+            if (small)
+                hipLaunchKernelGGL((k_maxpool_x8<f16_t, uint32_t>), dim3(blocks8), dim3(256), 0, s, (const f16_t *)x, n, h,
+                                   w, c, k, stride, pad, ho, wo, keep, (f16_t *)out);
+            else
+                hipLaunchKernelGGL((k_maxpool_x8<f16_t, int64_t>), dim3(blocks8), dim3(256), 0, s, (const f16_t *)x, n, h,
+                                   w, c, k, stride, pad, ho, wo, keep, (f16_t *)out);
+        }
         return hipGetLastError();
     }
     const int64_t total = (int64_t)n * ho * wo * c;
