@@ -220,7 +220,7 @@ class PreparedPyramid:
         nl = len(steps)
         self._ptrs = tuple((vp * nl)(*[_ptr(lv[i]) for lv in self.levels]) for i in range(3))
         self._args = (_ptr(mask_in), n, h, w, nl, self._steps, *self._ptrs, _ptr(self._ws), self._ws.numel())
-        self._keep = mask_in
+        self.mask_in = mask_in   # (kept alive: the call reads it)
         self._fn = lib().fc_mask_pyramid
         self._current_stream = torch.cuda.current_stream
 

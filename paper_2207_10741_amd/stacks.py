@@ -1,8 +1,9 @@
 """Runs a conv stack (workloads.Op list) through the library: mask propagation and
 kept-position lists are built once per (mask, window geometry) and shared by every
 layer that sees the same mask through the same geometry (Sec. III-B: one mask,
-rescaled per layer); each conv is one fc_focused_conv2d call, each depthwise conv one
-fc_focused_dwconv2d call.
+rescaled per layer) - by one fc_mask_pyramid call per pass when the mask levels form
+a chain, as they do in a feed-forward network; each conv is one fc_focused_conv2d
+call, each depthwise conv one fc_focused_dwconv2d call.
 
 Plumbing only: the order of library calls and which tensor feeds which.  Max-pools
 (not part of the paper's method) go through the library's helper, which with a mask
@@ -54,6 +55,36 @@ class ConvStack:
         # its arrival counters are cleared once here; every library call leaves them at zero,
         # so the calls carry FC_WORKSPACE_READY and none of them launches a clear
         B.ready_workspace(self.workspace)
+        # the mask levels the ops need, when they form one chain (input -> level 0 -> level 1 ...):
+        # then one fc_mask_pyramid call per pass builds all of them
+        self.pyramid_steps = self._pyramid_steps()
+        self._pyramids: Dict[int, object] = {}
+
+    def _same_view(self, i: int) -> bool:
+        op = self.ops[i]
+        return op.stride == 1 and self.sizes[i] == self.sizes[op.src] and op.pad == (op.k - 1) // 2
+
+    def _pyramid_steps(self):
+        """The windows that take each mask level to the next, in the order the ops first need them,
+        or None when the levels do not form a single chain (then every level is built by its own
+        fc_mask_downsample + fc_active_index_compact calls)."""
+        level_of = {-1: -1}       # op -> level its output mask is (-1: the input mask)
+        plans: Dict[tuple, int] = {}
+        steps = []
+        for i, op in enumerate(self.ops):
+            src_level = level_of[op.src]
+            key = (src_level, op.stride, (op.k - 1) // 2 - op.pad, self.sizes[i])
+            if self._same_view(i) and src_level >= 0:
+                level = src_level
+            elif key in plans:
+                level = plans[key]
+            else:
+                if src_level != len(steps) - 1:
+                    return None
+                steps.append(((op.k, op.k), (op.stride, op.stride), (op.pad, op.pad), (1, 1)))
+                level = plans[key] = len(steps) - 1
+            level_of[i] = level
+        return steps if 0 < len(steps) <= B.MAX_PYRAMID_LEVELS else None
 
     def _to_dev(self, storage: np.ndarray):
         torch = self.torch
@@ -87,6 +118,12 @@ class ConvStack:
         masks: Dict[int, object] = {-1: mask}
         plans: Dict[tuple, tuple] = {}
         produced: Dict[int, tuple] = {}   # 0/1 masks this run wrote, with their kept lists
+        levels = None                     # all mask levels from one call, taken in order
+        if mask is not None and self.pyramid_steps is not None:
+            pyr = self._pyramids.get(mask.data_ptr())
+            if pyr is None or pyr.mask_in is not mask:
+                pyr = self._pyramids[mask.data_ptr()] = B.PreparedPyramid(mask, self.pyramid_steps)
+            levels = list(pyr())
         last_use = {}
         for i, op in enumerate(self.ops):
             last_use[op.src] = i
@@ -96,7 +133,7 @@ class ConvStack:
             plan = None
             if m_in is not None:
                 hi, wi = self.sizes[op.src]
-                same_view = (op.stride == 1 and self.sizes[i] == (hi, wi) and op.pad == (op.k - 1) // 2)
+                same_view = self._same_view(i)
                 # two windows with the same stride, the same centre-tap offset and the same output
                 # size keep the same positions (a 3x3/2 pad 1 conv and the 1x1/2 projection beside it)
                 key = (id(m_in), op.stride, (op.k - 1) // 2 - op.pad, self.sizes[i])
@@ -106,6 +143,9 @@ class ConvStack:
                     plan = produced[id(m_in)]
                 elif key in plans:
                     plan = plans[key]
+                elif levels is not None:
+                    m_out, idx, count = levels.pop(0)
+                    plan = plans[key] = produced[id(m_out)] = (m_out, idx, count)
                 else:
                     m_out = B.mask_downsample(m_in, *geo)
                     idx, count = B.active_index_compact(m_out)
