@@ -169,3 +169,14 @@ def test_mask_pyramid_dims_and_argument_checks():
     assert L.fc_mask_pyramid(a, 2, 64, 64, 2, arr, none, ptrs, ptrs, a, 4096, None) == -1
     assert L.fc_mask_pyramid(a, 2, 64, 64, 2, arr, ptrs, ptrs, ptrs, None, 0, None) == -5
     assert L.fc_mask_pyramid(a, 2, 64, 64, 2, arr, ptrs, ptrs, ptrs, a, 4, None) == -5
+
+
+def test_bench_refuses_more_than_one_gpu_with_a_message():
+    """bench.py --gpus N > 1 exits with a message before touching a GPU (this build is one GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120)
+    assert res.returncode != 0
+    assert "one GPU" in res.stderr and not res.stdout.strip()
