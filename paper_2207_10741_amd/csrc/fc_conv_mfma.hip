@@ -56,6 +56,7 @@ constexpr int kMaxSplits = 16;                 // most K-splits of one tile
 constexpr int kMinSplitStages = 8;            // fewest stages a K-split is left with
 constexpr int kBusySplitStages = 64;          // shortest reduction that is split on a busy chip
 constexpr int kSmallLayerTiles = 64;  // layers with at most this many 128 x 64 tiles use 64 x 64 tiles
+constexpr int kDeviceScope = 16;                // cache-policy bit sc1: the access is coherent across the XCDs' L2s
 constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
 
 // Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
@@ -761,17 +762,24 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             // tile.  Nobody waits for anybody.  The partials and the counter are written and
             // read with device-scope accesses, which go through to the memory side of the
             // per-XCD L2s, so no cache-wide write-back or invalidate is needed.
-            uint64_t *mine = reinterpret_cast<uint64_t *>(partials + (size_t)unit * (TM * TN));
+            // (16 bytes per access with the device-scope cache policy, the form a relaxed
+            // agent-scope atomic store / load of 8 bytes compiles to, at twice the width)
+            const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+                partials, 0, (uint32_t)((size_t)kSplitGrid * kSplitTileFloats * sizeof(float)), 0x00020000);
+            const uint32_t mine = (uint32_t)unit * (uint32_t)(TM * TN * 4);
 #pragma unroll
             for (int a = 0; a < PB; ++a)
 #pragma unroll
                 for (int b = 0; b < CB; ++b)
 #pragma unroll
-                    for (int h = 0; h < 8; ++h) {
-                        const uint64_t v = (uint64_t)__float_as_uint(acc[a][b][2 * h]) |
-                                           ((uint64_t)__float_as_uint(acc[a][b][2 * h + 1]) << 32);
-                        __hip_atomic_store(mine + ((a * CB + b) * 8 + h) * NT + tid, v, __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_AGENT);
+                    for (int h = 0; h < 4; ++h) {
+                        u32x4_t v;
+                        v.x = __float_as_uint(acc[a][b][4 * h]);
+                        v.y = __float_as_uint(acc[a][b][4 * h + 1]);
+                        v.z = __float_as_uint(acc[a][b][4 * h + 2]);
+                        v.w = __float_as_uint(acc[a][b][4 * h + 3]);
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            v, rp, mine + (uint32_t)(((a * CB + b) * 4 + h) * NT + tid) * 16u, 0, kDeviceScope);
                     }
             wait_vmcnt<0>(); // this thread's partial stores have been acknowledged
             __syncthreads(); // ... and every other thread's
@@ -790,18 +798,19 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
             for (int sp = 0; sp < S; ++sp) {
-                const uint64_t *theirs =
-                    reinterpret_cast<const uint64_t *>(partials + (size_t)(tile * S + sp) * (TM * TN));
+                const uint32_t theirs = (uint32_t)(tile * S + sp) * (uint32_t)(TM * TN * 4);
 #pragma unroll
                 for (int a = 0; a < PB; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b)
 #pragma unroll
-                        for (int h = 0; h < 8; ++h) {
-                            const uint64_t v = __hip_atomic_load(theirs + ((a * CB + b) * 8 + h) * NT + tid,
-                                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            acc[a][b][2 * h] += __uint_as_float((uint32_t)v);
-                            acc[a][b][2 * h + 1] += __uint_as_float((uint32_t)(v >> 32));
+                        for (int h = 0; h < 4; ++h) {
+                            const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(
+                                rp, theirs + (uint32_t)(((a * CB + b) * 4 + h) * NT + tid) * 16u, 0, kDeviceScope);
+                            acc[a][b][4 * h] += __uint_as_float(v.x);
+                            acc[a][b][4 * h + 1] += __uint_as_float(v.y);
+                            acc[a][b][4 * h + 2] += __uint_as_float(v.z);
+                            acc[a][b][4 * h + 3] += __uint_as_float(v.w);
                         }
             }
         }
