@@ -111,6 +111,32 @@ def test_resnet50_layers_full_batch_sampled(layer):
     _check_sampled(n, h, w, ci, co, k, s, p, mask, 332 + ci + co, samples=2000)
 
 
+@pytest.mark.parametrize("layer", [
+    # layers with enough tiles for each of the large-tile instances (small layers run 64 x 64 tiles)
+    (8, 96, 96, 64, 128, 3, 1, 1),      # many 128 x 128 tiles, shared pixel line
+    (4, 64, 64, 128, 128, 3, 1, 1),     # fewer tiles: 128 x 64, shared pixel line, reduction may be split
+    (6, 80, 80, 64, 64, 3, 1, 1),       # 64 output channels
+    (4, 72, 72, 96, 192, 3, 2, 1),      # stride 2: tap by tap
+    (4, 60, 64, 256, 320, 1, 1, 0),     # 1x1
+    (2, 48, 160, 32, 64, 5, 1, 2),      # 25 taps
+])
+@pytest.mark.parametrize("mask_kind,irr", [("bernoulli", 0.5), ("mixed", 0.5), ("band", 0.48), ("objects", 0.9),
+                                           ("objects", 0.0), ("objects", 1.0)])
+def test_large_tile_instances_mask_structures_sampled(layer, mask_kind, irr):
+    n, h, w, ci, co, k, s, p = layer
+    if mask_kind == "bernoulli":
+        mask = synth.mask_bernoulli(n, h, w, irr, 345, h, ci)
+    elif mask_kind == "band":
+        mask = synth.mask_band_and_boxes(n, h, w, irr, 345, h, ci)
+    elif mask_kind == "mixed":
+        mask = synth.mask_bernoulli(n, h, w, irr, 345, h, ci)
+        mask[:, :, w // 3:] = 1
+        mask[:, ::7, :] = 0
+    else:
+        mask = synth.mask_objects(n, h, w, irr, 345, h, ci)
+    _check_sampled(n, h, w, ci, co, k, s, p, mask, 346 + ci + co, samples=1500)
+
+
 def test_hd_frame_first_layers_sampled():
     """VGG-16's first two convs on full-HD frames (batch 2 here), depth-ramp mask."""
     n, h, w = 2, 1080, 1920
