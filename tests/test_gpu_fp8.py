@@ -163,6 +163,39 @@ def test_fp8_large_layer_on_sampled_positions():
     assert float(np.abs(got[pos] - want).max()) / rms <= TOL_FP8
 
 
+@pytest.mark.parametrize("layer", [
+    (8, 96, 96, 64, 128, 3, 1, 1),      # many 128 x 128 tiles (one set of operand fragments), shared pixel line
+    (8, 96, 96, 256, 256, 3, 1, 1),     # the same with two stages per tap
+    (4, 64, 64, 128, 128, 3, 1, 1),     # 128 x 64, shared pixel line
+    (6, 80, 80, 64, 64, 3, 1, 1),       # 64 output channels
+    (4, 72, 72, 96, 192, 3, 2, 1),      # stride 2: tap by tap
+    (4, 96, 96, 256, 320, 1, 1, 0),     # 1x1, 128 x 128 tiles
+])
+@pytest.mark.parametrize("mask_kind,irr", [("objects", 0.48), ("bernoulli", 0.5), ("objects", 0.0)])
+def test_fp8_large_tile_instances_sampled(layer, mask_kind, irr):
+    """Layers with enough tiles for the large-tile instances, on sampled positions (half of them
+    near a mask edge or the image border) plus all-zero irrelevant rows."""
+    from tests.test_gpu_stacks import _sample_positions
+    torch = G.torch_mod()
+    n, h, w, ci, co, k, s_, p = layer
+    x = synth.activations((n, h, w, ci), synth.FP8, 217, 1)
+    wt = synth.he_weights(co, k, k, ci, synth.FP8, 217, 2)
+    bias = synth.bias(co, 217, 3)
+    mask = (synth.mask_bernoulli if mask_kind == "bernoulli" else synth.mask_objects)(n, h, w, irr, 217, h, ci)
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s_, s_), (p, p), (1, 1), B.FP8, B.F32, B.RELU)
+    out = B.focused_conv2d(desc, G.to_dev(x, synth.FP8), G.to_dev(wt, synth.FP8),
+                           torch.from_numpy(bias).to(G.dev()), mask_in=G.mask_dev(mask))
+    m_out = O.mask_downsample(mask, k, k, (s_, s_), (p, p))
+    got = out.cpu().numpy().reshape(-1, co)
+    assert not got[m_out.reshape(-1) == 0].view(np.uint32).any()
+    pos = _sample_positions(m_out, 1500, 218)
+    want = O.focused_conv2d_at(O.ConvShape(n, h, w, ci, co, k, k, (s_, s_), (p, p), (1, 1), relu=True), x, wt, pos,
+                               bias=bias, mask_in=mask, dtype=O.FP8)
+    kept = m_out.reshape(-1)[pos] != 0
+    rms = float(np.sqrt(np.mean(want[kept] ** 2)))
+    assert float(np.abs(got[pos] - want).max()) / rms <= TOL_FP8
+
+
 def test_fp8_layers_the_matrix_path_cannot_take_are_refused():
     torch = G.torch_mod()
     a = torch.zeros((1 << 16,), dtype=torch.uint8, device=G.dev())
