@@ -54,6 +54,8 @@ def lib():
         L.fco_mask_downsample.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 11 + [ctypes.c_void_p]
         L.fco_active_index_compact.restype = ctypes.c_int64
         L.fco_active_index_compact.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        L.fco_active_index_compact_tiled.restype = ctypes.c_int64
+        L.fco_active_index_compact_tiled.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p]
         L.fco_widen.restype = ctypes.c_int32
         L.fco_widen.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         L.fco_focused_conv2d.restype = ctypes.c_int32
@@ -163,6 +165,18 @@ def active_index_compact(mask: np.ndarray):
     m = np.ascontiguousarray(mask, dtype=np.uint8).reshape(-1)
     idx = np.empty(m.size, dtype=np.int32)
     cnt = int(lib().fco_active_index_compact(_ptr(m), m.size, _ptr(idx)))
+    return idx[:cnt].copy(), cnt
+
+
+def active_index_compact_tiled(mask, tile_h: int, tile_w: int):
+    """(idx, count): the kept positions of a [n, ho, wo] mask in tile order (tiles row-major,
+    positions row-major inside a tile)."""
+    m = np.ascontiguousarray(mask, dtype=np.uint8)
+    n, ho, wo = m.shape
+    idx = np.empty(m.size, dtype=np.int32)
+    cnt = int(lib().fco_active_index_compact_tiled(_ptr(m), n, ho, wo, tile_h, tile_w, _ptr(idx)))
+    if cnt < 0:
+        raise ValueError("bad sizes")
     return idx[:cnt].copy(), cnt
 
 

@@ -248,6 +248,28 @@ static void conv_position(const fco_conv *c, widen_fn wd, const void *x, const u
     }
 }
 
+/* ---- kept-position list in tile order -----------------------------------
+ * Sec. III-A only says which patches become columns, not in which order; any
+ * order gives the same features.  This order walks an image tile by tile
+ * (tiles of tile_h x tile_w positions, row-major over the tiles, row-major
+ * inside a tile), so that consecutive entries are neighbours in both
+ * directions.  mask: [n][ho][wo] bytes.  Returns the count, or -1. */
+int64_t fco_active_index_compact_tiled(const uint8_t *mask, int32_t n, int32_t ho, int32_t wo,
+                                       int32_t tile_h, int32_t tile_w, int32_t *idx)
+{
+    if (n <= 0 || ho <= 0 || wo <= 0 || tile_h <= 0 || tile_w <= 0) return -1;
+    int64_t count = 0;
+    for (int32_t b = 0; b < n; ++b)
+        for (int32_t y0 = 0; y0 < ho; y0 += tile_h)
+            for (int32_t x0 = 0; x0 < wo; x0 += tile_w)
+                for (int32_t y = y0; y < y0 + tile_h && y < ho; ++y)
+                    for (int32_t x = x0; x < x0 + tile_w && x < wo; ++x) {
+                        int64_t p = ((int64_t)b * ho + y) * wo + x;
+                        if (mask[p]) idx[count++] = (int32_t)p;
+                    }
+    return count;
+}
+
 /* ---- the whole layer ----------------------------------------------------
  * out[N][Ho][Wo][C_out] in double.  mask_in NULL = every pixel relevant (the
  * standard convolution, Sec. III-A last paragraph).  bias NULL = no bias. */

@@ -347,6 +347,29 @@ def test_16bit_storage_is_widened_exactly(dtype):
         np.testing.assert_array_equal(out.reshape(-1), bits.view(np.float16).astype(np.float64))
 
 
+def test_tile_ordered_list_is_a_reordering_sorted_by_tile():
+    """The tile-ordered list holds exactly the ascending list's positions, sorted by (image, tile
+    row, tile column, row, column) - checked with numpy's lexsort, on ragged sizes - and a hand
+    case."""
+    hand = np.array([[[1, 0, 1, 1, 0],
+                      [0, 1, 1, 0, 1],
+                      [1, 1, 0, 0, 1]]], np.uint8)
+    idx, cnt = O.active_index_compact_tiled(hand, 2, 2)
+    # tiles of 2x2: (rows 0-1, cols 0-1): 0, 6; (cols 2-3): 2, 3, 7; (col 4): 9; (row 2, cols 0-1): 10, 11; (col 4): 14
+    assert cnt == 9 and idx.tolist() == [0, 6, 2, 3, 7, 9, 10, 11, 14]
+    for (n, h, w, th, tw) in ((2, 13, 37, 8, 16), (1, 16, 32, 8, 16), (3, 7, 5, 3, 4), (1, 1, 9, 8, 16), (2, 9, 16, 1, 16)):
+        mask = synth.mask_bernoulli(n, h, w, 0.4, 37, h, w) * np.uint8(5)
+        idx, cnt = O.active_index_compact_tiled(mask, th, tw)
+        plain, pcnt = O.active_index_compact(mask.reshape(-1))
+        assert cnt == pcnt and np.array_equal(np.sort(idx), plain[:pcnt])
+        b, y, x = np.unravel_index(plain[:pcnt], (n, h, w))
+        order = np.lexsort((x % tw, y % th, x // tw, y // th, b))      # last key is the primary one
+        np.testing.assert_array_equal(idx, plain[:pcnt][order])
+    # one tile as large as the image is the ascending order
+    mask = synth.mask_objects(2, 11, 14, 0.5, 38)
+    np.testing.assert_array_equal(O.active_index_compact_tiled(mask, 11, 14)[0], O.active_index_compact(mask.reshape(-1))[0][:int(np.count_nonzero(mask))])
+
+
 def test_fp8_storage_decoder_and_encoder_against_the_format_and_a_library():
     """E4M3 bytes (OCP 8-bit floating point, the variant without infinities): the oracle's
     decoder against closed forms of the format and against torch's float8_e4m3fn for all 256
