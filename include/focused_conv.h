@@ -143,6 +143,21 @@ int32_t fc_mask_downsample_rule(const uint8_t *mask_in, int32_t n, int32_t h, in
 int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, int32_t *count,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same positions in tile order.  Sec. III-A fixes WHICH patches become columns, not their
+ * order, and fc_focused_conv2d takes the kept positions in any order (each exactly once): every
+ * output row gets the same terms, only the order of its fp32 sum may differ.  This list walks every image tile by tile - tiles of
+ * tile_h x tile_w positions, row-major over the tiles, row-major inside a tile - so that
+ * the rows of one GEMM tile are neighbours in both directions.
+ *   mask      device, [n][ho][wo] bytes (a layer's output-resolution mask), read only
+ *   tile_w    1..32; tile_h >= 1
+ *   idx,count as fc_active_index_compact
+ *   workspace device, >= fc_compact_tiled_workspace_bytes(...) */
+int32_t fc_compact_tiled_workspace_bytes(int32_t n, int32_t ho, int32_t wo, int32_t tile_h,
+                                         int32_t tile_w, size_t *bytes);
+int32_t fc_active_index_compact_tiled(const uint8_t *mask, int32_t n, int32_t ho, int32_t wo,
+                                      int32_t tile_h, int32_t tile_w, int32_t *idx, int32_t *count,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
 /* Mask pyramid (Sec. III-B: one mask per image, rescaled to every layer's size).  Builds, for
  * `levels` successive resolution changes, the mask and the kept-position list of every level
  * from the input mask in two launches.  steps[l] is the window (kernel, stride, padding,

@@ -19,7 +19,8 @@ RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 WORKSPACE_COUNTER_BYTES = 2048
 
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
-             "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact", "fc_mask_pyramid_dims",
+             "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact",
+             "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_dwconv2d",
              "fc_maxpool2d", "fc_maxpool2d_masked")
 MAX_PYRAMID_LEVELS = 8
@@ -77,6 +78,10 @@ def lib():
         L.fc_mask_downsample_rule.argtypes = [vp] + [i32] * 12 + [vp, vp]
         L.fc_active_index_compact.restype = i32
         L.fc_active_index_compact.argtypes = [vp, i64, vp, vp, vp, ctypes.c_size_t, vp]
+        L.fc_compact_tiled_workspace_bytes.restype = i32
+        L.fc_compact_tiled_workspace_bytes.argtypes = [i32] * 5 + [ctypes.POINTER(ctypes.c_size_t)]
+        L.fc_active_index_compact_tiled.restype = i32
+        L.fc_active_index_compact_tiled.argtypes = [vp] + [i32] * 5 + [vp, vp, vp, ctypes.c_size_t, vp]
         L.fc_mask_pyramid_dims.restype = i32
         L.fc_mask_pyramid_dims.argtypes = [i32, i32, i32, ctypes.POINTER(MaskStep), ctypes.POINTER(i32),
                                            ctypes.POINTER(i32)]
@@ -246,6 +251,25 @@ def active_index_compact(mask, idx=None, count=None, workspace=None, stream=None
     _check(lib().fc_active_index_compact(_ptr(mask), m, _ptr(idx), _ptr(count), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream(stream)),
            "fc_active_index_compact")
+    return idx, count
+
+
+def active_index_compact_tiled(mask, tile_h: int = 8, tile_w: int = 16, idx=None, count=None, stream=None):
+    """fc_active_index_compact_tiled: (idx, count) of a [n, ho, wo] mask in tile order."""
+    torch = _torch()
+    _require_cuda(mask, idx, count)
+    n, ho, wo = mask.shape
+    if idx is None:
+        idx = torch.empty((n * ho * wo,), dtype=torch.int32, device=mask.device)
+    if count is None:
+        count = torch.empty((1,), dtype=torch.int32, device=mask.device)
+    b = ctypes.c_size_t()
+    _check(lib().fc_compact_tiled_workspace_bytes(n, ho, wo, tile_h, tile_w, ctypes.byref(b)),
+           "fc_compact_tiled_workspace_bytes")
+    ws = torch.empty((max(int(b.value), 16),), dtype=torch.uint8, device=mask.device)
+    _check(lib().fc_active_index_compact_tiled(_ptr(mask), n, ho, wo, tile_h, tile_w, _ptr(idx), _ptr(count),
+                                               _ptr(ws), ws.numel(), _stream(stream)),
+           "fc_active_index_compact_tiled")
     return idx, count
 
 

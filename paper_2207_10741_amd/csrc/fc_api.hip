@@ -166,6 +166,44 @@ int32_t fc_active_index_compact(const uint8_t *mask, int64_t m, int32_t *idx, in
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 
+static int32_t tiled_check(int32_t n, int32_t ho, int32_t wo, int32_t tile_h, int32_t tile_w, int64_t *rows)
+{
+    if (n <= 0 || ho <= 0 || wo <= 0 || tile_h <= 0 || tile_w <= 0 || tile_w > kMaxListTileWidth) return FC_ERR_SHAPE;
+    if ((int64_t)n * ho * wo >= INT32_MAX) return FC_ERR_RANGE;
+    if (tile_h > ho) tile_h = ho; // (a taller tile is the same order)
+    *rows = tiled_rows(n, ho, wo, tile_h, tile_w);
+    if (*rows >= INT32_MAX) return FC_ERR_RANGE;
+    return FC_OK;
+}
+
+int32_t fc_compact_tiled_workspace_bytes(int32_t n, int32_t ho, int32_t wo, int32_t tile_h, int32_t tile_w,
+                                         size_t *bytes)
+{
+    if (!bytes) return FC_ERR_NULL;
+    int64_t rows;
+    const int32_t rc = tiled_check(n, ho, wo, tile_h, tile_w, &rows);
+    if (rc != FC_OK) return rc;
+    *bytes = align_up((size_t)((rows + kCompactBlockThreads - 1) / kCompactBlockThreads) * sizeof(int32_t), 256);
+    return FC_OK;
+}
+
+int32_t fc_active_index_compact_tiled(const uint8_t *mask, int32_t n, int32_t ho, int32_t wo, int32_t tile_h,
+                                      int32_t tile_w, int32_t *idx, int32_t *count, void *workspace,
+                                      size_t workspace_bytes, void *stream)
+{
+    if (!mask || !idx || !count) return FC_ERR_NULL;
+    int64_t rows;
+    const int32_t rc = tiled_check(n, ho, wo, tile_h, tile_w, &rows);
+    if (rc != FC_OK) return rc;
+    if (tile_h > ho) tile_h = ho;
+    const size_t need = align_up((size_t)((rows + kCompactBlockThreads - 1) / kCompactBlockThreads) * sizeof(int32_t), 256);
+    if (!workspace || workspace_bytes < need) return FC_ERR_WORKSPACE;
+    if (!aligned16(idx) || !aligned16(workspace)) return FC_ERR_ALIGN;
+    const hipError_t e = launch_compact_tiled(mask, n, ho, wo, tile_h, tile_w, idx, count, (int32_t *)workspace,
+                                              (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
 int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in, const void *w,
                           const float *bias, const uint8_t *mask_out, const int32_t *idx, const int32_t *count,
                           void *out, void *workspace, size_t workspace_bytes, void *stream)

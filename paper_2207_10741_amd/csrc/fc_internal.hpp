@@ -191,6 +191,14 @@ struct PyramidArgs {
     int32_t *idx[kMaxPyramidLevels];
     int32_t *count[kMaxPyramidLevels];
 };
+// kept positions of a [n][ho][wo] mask in tile order; block_counts: one int per 256 tile rows
+hipError_t launch_compact_tiled(const uint8_t *mask, int n, int ho, int wo, int tile_h, int tile_w, int32_t *idx,
+                                int32_t *count, int32_t *block_counts, hipStream_t s);
+constexpr int kMaxListTileWidth = 32; // a tile row's labels are one 32-bit word
+static inline int64_t tiled_rows(int n, int ho, int wo, int tile_h, int tile_w)
+{
+    return (int64_t)n * ((ho + tile_h - 1) / tile_h) * ((wo + tile_w - 1) / tile_w) * tile_h;
+}
 hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int32_t *block_counts, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);

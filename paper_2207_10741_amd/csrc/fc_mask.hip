@@ -230,6 +230,115 @@ hipError_t launch_compact(const MaskGeom &g_in, const uint8_t *mask_in, uint8_t 
 }
 
 // ---------------------------------------------------------------------------
+// Kept positions in tile order (Sec. III-A fixes which patches become columns, not their
+// order): tiles of tile_h x tile_w positions, row-major over the tiles of an image, row-major
+// inside a tile.  A thread owns one row of one tile (up to 32 positions), a block 256 such rows
+// in list order; two launches: per-block counts, then offsets + ordered scatter.
+// ---------------------------------------------------------------------------
+struct TiledGeom {
+    int32_t n, ho, wo, th, tw, tiles_y, tiles_x;
+    int32_t rows; // n * tiles_y * tiles_x * th tile rows (those below the image are empty)
+};
+
+// bit j = position (row of a tile, column j) is kept; *first = flat position of column 0
+__device__ __forceinline__ uint32_t tiled_row_flags(const TiledGeom &g, const uint8_t *__restrict__ mask, int r,
+                                                    int *first)
+{
+    *first = 0;
+    if (r >= g.rows) return 0;
+    const uint32_t t = (uint32_t)r / (uint32_t)g.th;
+    const int dy = (int)((uint32_t)r - t * (uint32_t)g.th);
+    const uint32_t t2 = t / (uint32_t)g.tiles_x;
+    const int tx = (int)(t - t2 * (uint32_t)g.tiles_x);
+    const int b = (int)(t2 / (uint32_t)g.tiles_y);
+    const int ty = (int)(t2 - (uint32_t)b * (uint32_t)g.tiles_y);
+    const int y = ty * g.th + dy, x0 = tx * g.tw;
+    if (y >= g.ho) return 0;
+    const int p = (b * g.ho + y) * g.wo + x0;
+    *first = p;
+    const int nx = min(g.tw, g.wo - x0);
+    uint32_t flags = 0;
+    if (nx == 16 && ((reinterpret_cast<uintptr_t>(mask) + (uintptr_t)p) & 15u) == 0) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(mask + p);
+        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) flags |= ((wds[q] >> (8 * bb)) & 0xffu) ? (1u << (4 * q + bb)) : 0u;
+    } else {
+        uint8_t got[32];
+#pragma unroll
+        for (int j = 0; j < 32; ++j) got[j] = j < nx ? mask[p + j] : (uint8_t)0;
+#pragma unroll
+        for (int j = 0; j < 32; ++j) flags |= got[j] ? (1u << j) : 0u;
+    }
+    return flags;
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_tiled_count(TiledGeom g, const uint8_t *__restrict__ mask,
+                                                                       int32_t *__restrict__ block_counts)
+{
+    __shared__ int scratch[kCompactBlockThreads / 64];
+    int first;
+    const uint32_t flags = tiled_row_flags(g, mask, (int)(blockIdx.x * kCompactBlockThreads + threadIdx.x), &first);
+    const int total = block_sum(__popc(flags), scratch);
+    if (threadIdx.x == 0) block_counts[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(kCompactBlockThreads) void k_tiled_scatter(TiledGeom g, const uint8_t *__restrict__ mask,
+                                                                         const int32_t *__restrict__ block_counts,
+                                                                         int32_t *__restrict__ idx,
+                                                                         int32_t *__restrict__ count)
+{
+    __shared__ int wave_sum[kCompactBlockThreads / 64];
+    __shared__ int scratch[kCompactBlockThreads / 64];
+    __shared__ int32_t stage[kCompactBlockThreads * 32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int part = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += kCompactBlockThreads) part += block_counts[i];
+    const int block_base = block_sum(part, scratch);
+    int first;
+    const uint32_t flags = tiled_row_flags(g, mask, (int)(blockIdx.x * kCompactBlockThreads + tid), &first);
+    const int c = __popc(flags);
+    const int incl = wave_inclusive_scan(c);
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int before = 0, block_total = 0;
+#pragma unroll
+    for (int i = 0; i < kCompactBlockThreads / 64; ++i) {
+        if (i < wave) before += wave_sum[i];
+        block_total += wave_sum[i];
+    }
+    int pos = before + incl - c;
+    uint32_t f = flags;
+    while (f) {
+        const int j = __ffs(f) - 1;
+        f &= f - 1;
+        stage[pos++] = first + j;
+    }
+    __syncthreads();
+    for (int i = tid; i < block_total; i += kCompactBlockThreads) idx[(int64_t)block_base + i] = stage[i];
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) *count = block_base + block_total;
+}
+
+hipError_t launch_compact_tiled(const uint8_t *mask, int n, int ho, int wo, int tile_h, int tile_w, int32_t *idx,
+                                int32_t *count, int32_t *block_counts, hipStream_t s)
+{
+    TiledGeom g;
+    g.n = n; g.ho = ho; g.wo = wo; g.th = tile_h; g.tw = tile_w;
+    g.tiles_y = (ho + tile_h - 1) / tile_h;
+    g.tiles_x = (wo + tile_w - 1) / tile_w;
+    g.rows = n * g.tiles_y * g.tiles_x * tile_h;
+    const int nb = (g.rows + kCompactBlockThreads - 1) / kCompactBlockThreads;
+    hipLaunchKernelGGL(k_tiled_count, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask, block_counts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_tiled_scatter, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask,
+                       (const int32_t *)block_counts, idx, count);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Mask pyramid (Sec. III-B: one mask, rescaled to every layer's size): the masks and
 // the kept-position lists of all levels from the input mask, in two launches.
 // Level l is the centre-tap rescaling of level l - 1, so a position of level l reads

@@ -109,6 +109,55 @@ def test_active_index_compact_bit_exact(m, irr):
     np.testing.assert_array_equal(idx[:cnt].cpu().numpy(), want_idx)
 
 
+@pytest.mark.parametrize("n,h,w,th,tw", [(2, 13, 37, 8, 16), (1, 16, 32, 8, 16), (3, 7, 5, 3, 4), (1, 1, 9, 8, 16),
+                                        (2, 9, 16, 1, 16), (16, 128, 128, 8, 16), (3, 120, 160, 8, 16), (2, 57, 83, 4, 32),
+                                        (1, 300, 500, 16, 8), (2, 33, 64, 40, 16)])
+@pytest.mark.parametrize("irr", [0.48, 0.0, 1.0])
+def test_tile_ordered_list_bit_exact(n, h, w, th, tw, irr):
+    mask = synth.mask_bernoulli(n, h, w, irr, 106, h, w) * np.uint8(9)
+    idx, count = B.active_index_compact_tiled(G.mask_dev(mask), th, tw)
+    want_idx, want_cnt = O.active_index_compact_tiled(mask, th, tw)
+    assert int(count.cpu().item()) == want_cnt
+    np.testing.assert_array_equal(idx[:want_cnt].cpu().numpy(), want_idx)
+
+
+@pytest.mark.parametrize("layer", [(2, 40, 56, 64, 128, 3, 1, 1, 1), (1, 19, 23, 64, 128, 3, 2, 1, 1),
+                                   (4, 64, 64, 128, 128, 3, 1, 1, 1), (2, 30, 41, 24, 40, 3, 1, 1, 1),
+                                   (2, 20, 24, 64, 256, 1, 1, 0, 1)])
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli"])
+def test_layer_with_tile_ordered_list_matches(layer, mask_kind):
+    """The layer takes the kept positions in any order: with the tile-ordered list every output
+    row gets the same terms; only the order of its fp32 sum can differ (a tile whose pixel line is
+    too long for the shared-line loop goes tap by tap), so the result equals the ascending list's
+    to fp32 rounding of the sum, and the oracle within the bar."""
+    torch = G.torch_mod()
+    n, h, w, ci, co, k, s, p, d = layer
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 107, 1)
+    wt = synth.he_weights(co, k, k, ci, dtype, 107, 2)
+    bias = synth.bias(co, 107, 3)
+    mask = (synth.mask_objects if mask_kind == "objects" else synth.mask_bernoulli)(n, h, w, 0.48, 107, 4)
+    md = G.mask_dev(mask)
+    m_out = B.mask_downsample(md, (k, k), (s, s), (p, p), (d, d))
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s, s), (p, p), (d, d), dtype, B.F32, B.RELU)
+    ho, wo = B.out_dims(desc)
+    outs = []
+    for tiled in (False, True):
+        idx, count = B.active_index_compact_tiled(m_out, 8, 16) if tiled else B.active_index_compact(m_out)
+        out = torch.full((n, ho, wo, co), 7.0, dtype=torch.float32, device=G.dev())
+        ws = torch.zeros((B.workspace_bytes(desc),), dtype=torch.uint8, device=G.dev())
+        B.focused_conv2d(desc, G.to_dev(x, dtype), G.to_dev(wt, dtype), torch.from_numpy(bias).to(G.dev()), mask_in=md,
+                         mask_out=m_out, idx=idx, count=count, out=out, workspace=ws)
+        outs.append(out)
+    torch.cuda.synchronize()
+    want = O.focused_conv2d(O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=True), x, wt, bias=bias,
+                            mask_in=mask, dtype=dtype)
+    keep = O.mask_downsample(mask, k, k, (s, s), (p, p), (d, d)) != 0
+    assert G.rel_err(G.to_f64(outs[1]), G.to_f64(outs[0]), keep) <= 1e-5
+    assert G.rel_err(G.to_f64(outs[1]), want, keep) <= TOL_F32_OUT
+    assert not outs[1].cpu().numpy()[~keep].view(np.uint32).any()
+
+
 def test_active_index_compact_blobs_large():
     mask = synth.mask_objects(3, 480, 640, [0.3, 0.5, 0.7], 103)
     idx, count = B.active_index_compact(G.mask_dev(mask))

@@ -95,6 +95,15 @@ def test_null_pointers_rejected_before_any_launch():
     assert L.fc_active_index_compact(a, 10, a, a, a, 1, None) == -5
     assert L.fc_active_index_compact(odd, 10, a, a, a, 4096, None) == -4
     assert L.fc_active_index_compact(a, 0, a, a, a, 4096, None) == -2
+    nb = ctypes.c_size_t()
+    assert L.fc_compact_tiled_workspace_bytes(2, 64, 64, 8, 16, ctypes.byref(nb)) == 0 and nb.value >= 4 * 2
+    assert L.fc_compact_tiled_workspace_bytes(2, 64, 64, 8, 33, ctypes.byref(nb)) == -2       # tile wider than 32
+    assert L.fc_compact_tiled_workspace_bytes(2, 64, 64, 0, 16, ctypes.byref(nb)) == -2
+    assert L.fc_compact_tiled_workspace_bytes(2, 64, 64, 8, 16, None) == -1
+    assert L.fc_active_index_compact_tiled(None, 2, 64, 64, 8, 16, a, a, a, 4096, None) == -1
+    assert L.fc_active_index_compact_tiled(a, 2, 64, 64, 8, 16, a, a, None, 0, None) == -5
+    assert L.fc_active_index_compact_tiled(a, 2, 64, 64, 8, 16, odd, a, a, 4096, None) == -4
+    assert L.fc_active_index_compact_tiled(a, 40000, 1000, 1000, 8, 16, a, a, a, 4096, None) == -6
     o = ctypes.c_void_p(0x2000)
     conv = lambda *args: L.fc_focused_conv2d(ctypes.byref(d), *args)
     #            x    mask_in w  bias  mask_out idx  count out ws    ws_bytes stream
