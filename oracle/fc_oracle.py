@@ -54,6 +54,8 @@ def lib():
         L.fco_mask_downsample.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 11 + [ctypes.c_void_p]
         L.fco_active_index_compact.restype = ctypes.c_int64
         L.fco_active_index_compact.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        L.fco_focused_gconv2d.restype = ctypes.c_int32
+        L.fco_focused_gconv2d.argtypes = [ctypes.POINTER(_Conv), ctypes.c_int32] + [ctypes.c_void_p] * 5
         L.fco_active_index_compact_tiled.restype = ctypes.c_int64
         L.fco_active_index_compact_tiled.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p]
         L.fco_widen.restype = ctypes.c_int32
@@ -236,6 +238,26 @@ def focused_conv2d_at(s: ConvShape, x, w, positions, bias=None, mask_in=None,
                                      _ptr(pos), pos.size, _ptr(out))
     if rc != 0:
         raise ValueError("fco_focused_conv2d_at rc=%d" % rc)
+    return out
+
+
+def focused_gconv2d(s: ConvShape, groups: int, x, w, bias=None, mask_in=None, dtype: int = F32) -> np.ndarray:
+    """The grouped layer: w is [C_out, KH, KW, C_in / groups]; out float64 NHWC."""
+    x = _storage(x, dtype)
+    w = _storage(w, dtype)
+    if groups <= 0 or s.c_in % groups or s.c_out % groups:
+        raise ValueError("channel counts are not multiples of groups")
+    if x.shape != (s.n, s.h, s.w, s.c_in) or w.shape != (s.c_out, s.kh, s.kw, s.c_in // groups):
+        raise ValueError("operand shapes")
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    m = _mask(mask_in, (s.n, s.h, s.w))
+    ho, wo = out_dims(s)
+    out = np.empty((s.n, ho, wo, s.c_out), dtype=np.float64)
+    c = _conv_struct(s, dtype)
+    rc = lib().fco_focused_gconv2d(ctypes.byref(c), groups, _ptr(x), _ptr(m), _ptr(w), _ptr(bias), _ptr(out))
+    if rc != 0:
+        raise ValueError("fco_focused_gconv2d failed: %d" % rc)
     return out
 
 

@@ -314,6 +314,54 @@ int32_t fco_focused_conv2d_at(const fco_conv *c, const void *x, const uint8_t *m
     return 0;
 }
 
+/* ---- grouped layer --------------------------------------------------------
+ * The layer type between the full layer and the depthwise one: the channels are
+ * cut into `groups` equal slices, output slice g sees input slice g only.
+ * Everything else is Sec. III-A unchanged (labels, zero at irrelevant inputs,
+ * +0.0 at irrelevant positions).  Layouts: x[N][H][W][C_in],
+ * w[C_out][KH][KW][C_in/groups], bias[C_out].  Returns -3 when the channel
+ * counts are not multiples of groups. */
+int32_t fco_focused_gconv2d(const fco_conv *c, int32_t groups, const void *x, const uint8_t *mask_in,
+                            const void *w, const float *bias, double *out)
+{
+    int32_t ho = fco_out_dim(c->h, c->kh, c->stride_h, c->pad_h, c->dil_h);
+    int32_t wo = fco_out_dim(c->w, c->kw, c->stride_w, c->pad_w, c->dil_w);
+    if (c->n <= 0 || ho <= 0 || wo <= 0 || c->c_in <= 0 || c->c_out <= 0) return -1;
+    if (groups <= 0 || c->c_in % groups || c->c_out % groups) return -3;
+    int32_t cig = c->c_in / groups, cog = c->c_out / groups;
+    widen_fn wd = pick_widen(c->dtype);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int32_t b = 0; b < c->n; ++b)
+        for (int32_t oh = 0; oh < ho; ++oh)
+            for (int32_t ow = 0; ow < wo; ++ow) {
+                double *out_row = out + (((size_t)b * ho + oh) * wo + ow) * c->c_out;
+                int32_t ch = clampi(oh * c->stride_h - c->pad_h + c->dil_h * ((c->kh - 1) / 2), 0, c->h - 1);
+                int32_t cw = clampi(ow * c->stride_w - c->pad_w + c->dil_w * ((c->kw - 1) / 2), 0, c->w - 1);
+                if (mask_in && !mask_in[((size_t)b * c->h + ch) * c->w + cw]) {
+                    for (int32_t co = 0; co < c->c_out; ++co) out_row[co] = 0.0;
+                    continue;
+                }
+                for (int32_t co = 0; co < c->c_out; ++co) {
+                    int32_t g = co / cog; /* the slice this output channel belongs to */
+                    double acc = bias ? (double)bias[co] : 0.0;
+                    for (int32_t kh = 0; kh < c->kh; ++kh)
+                        for (int32_t kw = 0; kw < c->kw; ++kw) {
+                            int32_t ih = oh * c->stride_h - c->pad_h + kh * c->dil_h;
+                            int32_t iw = ow * c->stride_w - c->pad_w + kw * c->dil_w;
+                            if (ih < 0 || ih >= c->h || iw < 0 || iw >= c->w) continue;
+                            size_t pix = ((size_t)b * c->h + ih) * c->w + iw;
+                            if (mask_in && !mask_in[pix]) continue;
+                            size_t xo = pix * c->c_in + (size_t)g * cig;
+                            size_t wo_ = (((size_t)co * c->kh + kh) * c->kw + kw) * cig;
+                            for (int32_t ci = 0; ci < cig; ++ci) acc += wd(x, xo + ci) * wd(w, wo_ + ci);
+                        }
+                    if (c->relu && acc < 0.0) acc = 0.0;
+                    out_row[co] = acc;
+                }
+            }
+    return 0;
+}
+
 /* ---- depthwise layer -----------------------------------------------------
  * Sec. IV replaces every convolutional layer of EfficientDet and SSD-Lite by
  * its focused form; most of those layers are depthwise: channel c of the

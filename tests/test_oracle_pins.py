@@ -347,6 +347,41 @@ def test_16bit_storage_is_widened_exactly(dtype):
         np.testing.assert_array_equal(out.reshape(-1), bits.view(np.float16).astype(np.float64))
 
 
+@pytest.mark.parametrize("case", [(2, 9, 11, 8, 12, 3, (1, 1), (1, 1), 4), (1, 10, 8, 6, 6, 3, (2, 2), (1, 1), 3),
+                                  (2, 7, 9, 12, 4, 1, (1, 1), (0, 0), 2), (1, 8, 8, 4, 8, 5, (1, 1), (2, 2), 4)])
+@pytest.mark.parametrize("masked", [False, True])
+def test_grouped_layer_against_the_full_layer_a_library_and_its_limits(case, masked):
+    """groups = 1 is the full layer; groups = C is the depthwise layer; any groups equals the full
+    layer with block-diagonal weights (exactly: the extra terms are zeros) and, dense, torch's
+    grouped conv2d in float64."""
+    n, h, w, ci, co, k, st, pd, groups = case
+    x = synth.from_storage(synth.activations((n, h, w, ci), synth.F32, 39, h, w) - 0.3, synth.F32)
+    wt = synth.he_weights(co, k, k, ci // groups, synth.F32, 39, h, 2)
+    b = synth.bias(co, 39, 3)
+    mask = synth.mask_bernoulli(n, h, w, 0.4, 39, h, 4) if masked else None
+    s = O.ConvShape(n, h, w, ci, co, k, k, st, pd, (1, 1), relu=masked)
+    got = O.focused_gconv2d(s, groups, x, wt, bias=b, mask_in=mask)
+    cig, cog = ci // groups, co // groups
+    full = np.zeros((co, k, k, ci), np.float32)
+    for g in range(groups):
+        full[g * cog:(g + 1) * cog, :, :, g * cig:(g + 1) * cig] = wt[g * cog:(g + 1) * cog]
+    np.testing.assert_allclose(got, O.focused_conv2d(s, x, full, bias=b, mask_in=mask), rtol=1e-13, atol=1e-13)
+    np.testing.assert_array_equal(O.focused_gconv2d(s, 1, x, full, bias=b, mask_in=mask),
+                                  O.focused_conv2d(s, x, full, bias=b, mask_in=mask))
+    if not masked:
+        torch = pytest.importorskip("torch")
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2),
+                                         torch.from_numpy(wt.astype(np.float64)).permute(0, 3, 1, 2),
+                                         torch.from_numpy(b.astype(np.float64)), stride=st, padding=pd, groups=groups)
+        np.testing.assert_allclose(got, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-11, atol=1e-11)
+    if ci == co:
+        wd = synth.he_weights(ci, k, k, 1, synth.F32, 39, 5)
+        np.testing.assert_array_equal(O.focused_gconv2d(s, ci, x, wd, bias=b, mask_in=mask),
+                                      O.focused_dwconv2d(s, x, np.ascontiguousarray(wd[..., 0]), bias=b, mask_in=mask))
+    with pytest.raises(ValueError):
+        O.focused_gconv2d(s, 5, x, wt, bias=b, mask_in=mask)
+
+
 def test_tile_ordered_list_is_a_reordering_sorted_by_tile():
     """The tile-ordered list holds exactly the ascending list's positions, sorted by (image, tile
     row, tile column, row, column) - checked with numpy's lexsort, on ragged sizes - and a hand
