@@ -208,6 +208,20 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
                           const int32_t *idx, const int32_t *count, void *out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* The grouped layer: channels cut into `groups` equal slices, output slice g sees input slice
+ * g only (the layer type between fc_focused_conv2d, groups = 1, and fc_focused_dwconv2d, one
+ * channel per group; both are what this call runs in those two cases).  Sec. III-A unchanged
+ * otherwise.  Arguments as fc_focused_conv2d, with
+ *   desc      c_in and c_out are the totals; both must be multiples of groups (FC_ERR_SHAPE)
+ *   w         device, [c_out][kh][kw][c_in / groups]
+ *   workspace needed (>= fc_workspace_bytes(desc)) only when mask_in is given without a list
+ * Layers with more than one channel per group run on the vector ALUs, not on the matrix
+ * cores, and take the 32- and 16-bit storage types only (FC_FP8: FC_ERR_DTYPE). */
+int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void *x,
+                           const uint8_t *mask_in, const void *w, const float *bias,
+                           const uint8_t *mask_out, const int32_t *idx, const int32_t *count,
+                           void *out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The depthwise layer: one KH x KW filter per channel, the layer type most of
  * the two networks of Sec. IV consist of (depthwise-separable blocks; their
  * 1x1 halves are fc_focused_conv2d).  Sec. III-A unchanged otherwise: a

@@ -21,7 +21,8 @@ WORKSPACE_COUNTER_BYTES = 2048
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
              "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact",
              "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
-             "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_dwconv2d",
+             "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_gconv2d",
+             "fc_focused_dwconv2d",
              "fc_maxpool2d", "fc_maxpool2d_masked")
 MAX_PYRAMID_LEVELS = 8
 
@@ -93,6 +94,8 @@ def lib():
                                       ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
         L.fc_focused_conv2d.restype = i32
         L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.fc_focused_gconv2d.restype = i32
+        L.fc_focused_gconv2d.argtypes = [ctypes.POINTER(ConvDesc), i32] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_focused_dwconv2d.restype = i32
         L.fc_focused_dwconv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 6
         L.fc_maxpool2d.restype = i32
@@ -325,6 +328,23 @@ class PreparedConv:
         if rc != 0:
             raise FcError(rc, "fc_focused_conv2d")
         return self.out
+
+
+def focused_gconv2d(desc: ConvDesc, groups: int, x, w, bias=None, mask_in=None, mask_out=None, idx=None,
+                    count=None, out=None, workspace=None, stream=None):
+    """fc_focused_gconv2d.  x NHWC, w [C_out,KH,KW,C_in/groups]; returns out NHWC."""
+    torch = _torch()
+    _require_cuda(x, w, bias, mask_in, mask_out, idx, count, out, workspace)
+    ho, wo = out_dims(desc)
+    if out is None:
+        out = torch.empty((desc.n, ho, wo, desc.c_out), dtype=torch_dtype(desc.out_dtype), device=x.device)
+    if workspace is None and mask_in is not None and idx is None:
+        workspace = torch.empty((workspace_bytes(desc),), dtype=torch.uint8, device=x.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().fc_focused_gconv2d(ctypes.byref(desc), groups, _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias),
+                                    _ptr(mask_out), _ptr(idx), _ptr(count), _ptr(out), _ptr(workspace),
+                                    ws_bytes, _stream(stream)), "fc_focused_gconv2d")
+    return out
 
 
 def focused_dwconv2d(desc: ConvDesc, x, w, bias=None, mask_in=None, out=None, stream=None):

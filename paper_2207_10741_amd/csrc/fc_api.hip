@@ -282,6 +282,53 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     return FC_OK;
 }
 
+int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void *x, const uint8_t *mask_in,
+                           const void *w, const float *bias, const uint8_t *mask_out, const int32_t *idx,
+                           const int32_t *count, void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (groups == 1)
+        return fc_focused_conv2d(desc, x, mask_in, w, bias, mask_out, idx, count, out, workspace, workspace_bytes,
+                                 stream);
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != FC_OK) return rc;
+    if (groups <= 0 || g.c_in % groups != 0 || g.c_out % groups != 0) return FC_ERR_SHAPE;
+    // one channel per group with the labels of the input mask: the depthwise kernel
+    if (groups == g.c_in && g.c_in == g.c_out && !idx && !mask_out)
+        return fc_focused_dwconv2d(desc, x, mask_in, w, bias, out, stream);
+    if (desc->in_dtype == FC_FP8) return FC_ERR_DTYPE;
+    if (!x || !w || !out) return FC_ERR_NULL;
+    if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
+    if (!mask_in && (idx || mask_out)) return FC_ERR_NULL;
+    if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(idx) || !aligned16(bias)) return FC_ERR_ALIGN;
+    if (x == out) return FC_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (mask_in && !idx) {
+        const ConvWorkspace l = conv_ws_layout(g);
+        if (!workspace || workspace_bytes < l.total) return FC_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return FC_ERR_ALIGN;
+        uint8_t *ws = (uint8_t *)workspace;
+        const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
+        const hipError_t ec = launch_compact(mg, mask_in, ws + l.mask_out, (int32_t *)(ws + l.idx),
+                                             (int32_t *)(ws + l.count), (int32_t *)(ws + l.scan), CompactExtras(), s);
+        if (ec != hipSuccess) return FC_ERR_HIP;
+        mask_out = ws + l.mask_out;
+        idx = (const int32_t *)(ws + l.idx);
+        count = (const int32_t *)(ws + l.count);
+    }
+    Geom one = g; // the geometry of one group
+    one.c_in = g.c_in / groups;
+    one.c_out = g.c_out / groups;
+    hipError_t e = launch_conv_direct(one, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, idx, count, out, s,
+                                      groups);
+    if (e != hipSuccess) return FC_ERR_HIP;
+    if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL)) {
+        e = launch_zero_fill(g, mask_in, mask_out, out, desc->out_dtype, s);
+        if (e != hipSuccess) return FC_ERR_HIP;
+    }
+    return FC_OK;
+}
+
 int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in, const void *w,
                             const float *bias, void *out, void *stream)
 {

@@ -24,8 +24,17 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                                                             const float *__restrict__ bias,
                                                             const int32_t *__restrict__ idx,
                                                             const int32_t *__restrict__ count,
-                                                            TO *__restrict__ out)
+                                                            TO *__restrict__ out, int groups)
 {
+    // Grouped layers: g.c_in and g.c_out are the channels of ONE group, blockIdx.z is the group;
+    // a pixel of x holds groups * g.c_in channels and a row of out groups * g.c_out, group by
+    // group; w is [groups * g.c_out][kh][kw][g.c_in].  groups = 1 is the plain layer.
+    const int grp = blockIdx.z;
+    const int x_pitch = groups * g.c_in, out_pitch = groups * g.c_out;
+    x += grp * g.c_in;
+    w += (int64_t)grp * g.c_out * (g.kh * g.kw * g.c_in);
+    if (bias) bias += grp * g.c_out;
+    out += grp * g.c_out;
     constexpr int KC = kRowsLdsFloats / CO_T; // reduction elements staged at a time
     __shared__ float wt[KC * CO_T];           // [k][channel]
     const int tid = threadIdx.x;
@@ -82,7 +91,7 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                     if (tap_ok) {
                         const int64_t pix = ((int64_t)b * g.h + ih) * g.w + iw;
                         tap_ok = !mask_in || mask_in[pix] != 0;
-                        xp = x + pix * g.c_in;
+                        xp = x + pix * x_pitch;
                     }
                     new_tap = false;
                 }
@@ -117,7 +126,7 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
             }
         }
         if (live) {
-            TO *orow = out + (int64_t)p * g.c_out + co0;
+            TO *orow = out + (int64_t)p * out_pitch + co0;
             constexpr int EPV = 16 / (int)sizeof(TO); // elements per 16-byte store
             const bool whole_pieces = g.c_out % EPV == 0;
 #pragma unroll
@@ -146,42 +155,42 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
 template <typename TI, typename TO, int CO_T>
 static hipError_t launch_rows(const Geom &g, const void *x, const uint8_t *mask_in, const void *w,
                               const float *bias, const int32_t *idx, const int32_t *count, void *out,
-                              hipStream_t s)
+                              int groups, hipStream_t s)
 {
     // grid sized for the dense row count: the kept count is only known on the device
     const int64_t row_blocks = ((int64_t)g.m + kRowsThreads - 1) / kRowsThreads;
     const int gx = (int)(row_blocks > 8192 ? 8192 : row_blocks);
     const int gy = (g.c_out + CO_T - 1) / CO_T;
-    hipLaunchKernelGGL((k_conv_rows<TI, TO, CO_T>), dim3(gx, gy), dim3(kRowsThreads), 0, s, g, (const TI *)x,
-                       mask_in, (const TI *)w, bias, idx, count, (TO *)out);
+    hipLaunchKernelGGL((k_conv_rows<TI, TO, CO_T>), dim3(gx, gy, groups), dim3(kRowsThreads), 0, s, g, (const TI *)x,
+                       mask_in, (const TI *)w, bias, idx, count, (TO *)out, groups);
     return hipGetLastError();
 }
 
 template <typename TI, typename TO>
 static hipError_t launch_t(const Geom &g, const void *x, const uint8_t *mask_in, const void *w,
                            const float *bias, const int32_t *idx, const int32_t *count, void *out,
-                           hipStream_t s)
+                           int groups, hipStream_t s)
 {
     // wide accumulator blocks when the layer is wide enough to use them and has enough rows to
     // fill the chip with them; a small layer is cut into narrow channel blocks instead (more
     // workgroups, a four times shorter serial loop per lane; the input is re-read per block,
     // which a small layer can afford)
-    const int64_t wide_blocks = (((int64_t)g.m + kRowsThreads - 1) / kRowsThreads) * ((g.c_out + 63) / 64);
-    if (g.c_out > 32 && wide_blocks >= 512) return launch_rows<TI, TO, 64>(g, x, mask_in, w, bias, idx, count, out, s);
-    return launch_rows<TI, TO, 16>(g, x, mask_in, w, bias, idx, count, out, s);
+    const int64_t wide_blocks = (((int64_t)g.m + kRowsThreads - 1) / kRowsThreads) * ((g.c_out + 63) / 64) * groups;
+    if (g.c_out > 32 && wide_blocks >= 512) return launch_rows<TI, TO, 64>(g, x, mask_in, w, bias, idx, count, out, groups, s);
+    return launch_rows<TI, TO, 16>(g, x, mask_in, w, bias, idx, count, out, groups, s);
 }
 
 hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const void *x,
                               const uint8_t *mask_in, const void *w, const float *bias, const int32_t *idx,
-                              const int32_t *count, void *out, hipStream_t s)
+                              const int32_t *count, void *out, hipStream_t s, int groups)
 {
-    if (in_dtype == FC_F32) return launch_t<float, float>(g, x, mask_in, w, bias, idx, count, out, s);
+    if (in_dtype == FC_F32) return launch_t<float, float>(g, x, mask_in, w, bias, idx, count, out, groups, s);
     if (in_dtype == FC_BF16) {
-        if (out_dtype == FC_F32) return launch_t<bf16_t, float>(g, x, mask_in, w, bias, idx, count, out, s);
-        return launch_t<bf16_t, bf16_t>(g, x, mask_in, w, bias, idx, count, out, s);
+        if (out_dtype == FC_F32) return launch_t<bf16_t, float>(g, x, mask_in, w, bias, idx, count, out, groups, s);
+        return launch_t<bf16_t, bf16_t>(g, x, mask_in, w, bias, idx, count, out, groups, s);
     }
-    if (out_dtype == FC_F32) return launch_t<f16_t, float>(g, x, mask_in, w, bias, idx, count, out, s);
-    return launch_t<f16_t, f16_t>(g, x, mask_in, w, bias, idx, count, out, s);
+    if (out_dtype == FC_F32) return launch_t<f16_t, float>(g, x, mask_in, w, bias, idx, count, out, groups, s);
+    return launch_t<f16_t, f16_t>(g, x, mask_in, w, bias, idx, count, out, groups, s);
 }
 
 } // namespace fc

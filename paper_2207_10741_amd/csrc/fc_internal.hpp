@@ -206,10 +206,11 @@ hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,
                           int pad, int ho, int wo, const uint8_t *keep, void *out, hipStream_t s);
 
-// Direct convolution over the active rows; any shape, any dtype.
+// Direct convolution over the active rows; any shape, any dtype.  groups > 1: g.c_in / g.c_out
+// are the channels of one group, x and out hold all groups side by side.
 hipError_t launch_conv_direct(const Geom &g, int in_dtype, int out_dtype, const void *x,
                               const uint8_t *mask_in, const void *w, const float *bias,
-                              const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
+                              const int32_t *idx, const int32_t *count, void *out, hipStream_t s, int groups = 1);
 
 // Depthwise layer (one filter per channel); labels positions from mask_in itself and clears
 // the irrelevant rows.
