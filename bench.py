@@ -295,6 +295,55 @@ def depthwise_bench(torch, B, synth, workloads, args):
         "dense_GBps": round(bytes_d / t_d / 1e9, 1)}))
 
 
+def grouped_bench(torch, B, synth, workloads, args):
+    """The 3x3 grouped layers of a ResNeXt-50 (32 groups of 4 to 32 channels), bf16, blob masks:
+    per layer the focused call (list given) and the dense call, each as a HIP-graph replay of four
+    calls.  These layers run on the vector ALUs (fp32 multiply-adds), so the bound quoted is the
+    fp32 vector peak; their arithmetic intensity (a few dozen FLOP per byte) puts the memory
+    roofline far above what they reach."""
+    irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
+    n = 16 if args.batch is None else args.batch
+    dev = torch.device("cuda:0")
+    gen = synth.mask_bernoulli if args.mask == "bernoulli" else synth.mask_objects
+    rows, t_f, t_d, fl_f, fl_d = [], 0.0, 0.0, 0.0, 0.0
+    for li, (c, side) in enumerate(((128, 56), (256, 28), (512, 14), (1024, 7))):
+        groups = 32
+        x = synth.activations((n, side, side, c), synth.BF16, 8, li, 1)
+        w = synth.he_weights(c, 3, 3, c // groups, synth.BF16, 8, li, 2)
+        bias = synth.bias(c, 8, li, 3)
+        mask = gen(n, side, side, irr, 8, li, 4)
+        to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+        desc = B.conv_desc(n, side, side, c, c, in_dtype=B.BF16, out_dtype=B.BF16, flags=B.RELU)
+        xd, wd, bd, md = to_dev(x), to_dev(w), torch.from_numpy(bias).to(dev), torch.from_numpy(mask).to(dev)
+        out = torch.empty((n, side, side, c), dtype=torch.bfloat16, device=dev)
+        m_out = B.mask_downsample(md)
+        idx, count = B.active_index_compact(m_out)
+
+        def timed(**kw):
+            def fn():
+                for _ in range(4):
+                    B.focused_gconv2d(desc, groups, xd, wd, bd, out=out, **kw)
+            return time_loop(torch, capture(torch, fn).replay, args.steps, args.warmup) / 4
+
+        tf = timed(mask_in=md, mask_out=m_out, idx=idx, count=count)
+        td = timed()
+        per_pos = 2.0 * 9 * (c // groups) * c
+        ff, fd = float(np.count_nonzero(mask)) * per_pos, float(mask.size) * per_pos
+        rows.append({"layer": "c%d@%d/g%d" % (c, side, groups), "focused_us": round(tf * 1e6, 2),
+                     "dense_us": round(td * 1e6, 2), "speedup": round(td / tf, 3),
+                     "focused_TFLOPs": round(ff / tf / 1e12, 2), "dense_TFLOPs": round(fd / td / 1e12, 2)})
+        t_f, t_d, fl_f, fl_d = t_f + tf, t_d + td, fl_f + ff, fl_d + fd
+        del xd, out
+    print(json.dumps({
+        "grouped": True, "workload": "ResNeXt-50 (32x4d) 3x3 grouped layers, batch %d, 224x224 images, bf16, %s masks, "
+        "%d %% irrelevant" % (n, args.mask, round(irr * 100)), "launch": "HIP graph replay of four calls",
+        "steps": args.steps, "layers": rows, "focused_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
+        "speedup_vs_dense": round(t_d / t_f, 3),
+        "roofline": {"bound": "alu", "achieved": round(fl_f / t_f / 1e12, 3), "peak": 157.3, "unit": "TFLOP/s",
+                     "frac": round(fl_f / t_f / 157.3e12, 4), "traffic": None},
+        "dense_TFLOPs": round(fl_d / t_d / 1e12, 2)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -319,6 +368,8 @@ def main():
     ap.add_argument("--depthwise", action="store_true",
                     help="time the depthwise layers of a MobileNetV2 backbone (focused and dense) "
                          "instead of the bench line")
+    ap.add_argument("--grouped", action="store_true",
+                    help="time the 3x3 grouped layers of a ResNeXt-50 (focused and dense) instead of the bench line")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
@@ -344,6 +395,9 @@ def main():
         return
     if args.depthwise:
         depthwise_bench(torch, B, synth, workloads, args)
+        return
+    if args.grouped:
+        grouped_bench(torch, B, synth, workloads, args)
         return
     in_dtype = B.FP8 if args.in_dtype == "fp8" else B.BF16
     peak = FP8_MFMA_PEAK_TFLOPS if in_dtype == B.FP8 else BF16_MFMA_PEAK_TFLOPS

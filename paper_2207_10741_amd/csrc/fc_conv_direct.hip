@@ -79,11 +79,11 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                 __syncthreads();
                 staged = nchunks == 1;
             }
-            // four input channels at a time where the layout allows (fp32 storage, channel count
-            // a multiple of four: a group never straddles a tap or a staged chunk), so that a lane
-            // has one 16-byte load in flight per 4 x CO_T multiply-adds instead of four dependent
-            // 4-byte loads
-            const bool by4 = sizeof(TI) == 4 && g.c_in % 4 == 0;
+            // four input channels at a time where the layout allows (channel count a multiple of
+            // four: a group of four never straddles a tap or a staged chunk), so that a lane has one
+            // 16-byte (fp32) or 8-byte (16-bit types) load in flight per 4 x CO_T multiply-adds
+            // instead of four dependent narrow loads
+            const bool by4 = g.c_in % 4 == 0;
             for (int k = 0; k < kc; k += by4 ? 4 : 1) {
                 if (new_tap) {
                     const int ih = ih0 + kh * g.dh, iw = iw0 + kw * g.dw;
@@ -97,15 +97,23 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                 }
                 if (tap_ok) {
                     if (by4) {
+                        float xs[4];
                         if constexpr (sizeof(TI) == 4) {
                             const float4 xq = *reinterpret_cast<const float4 *>(xp + ci);
-                            const float xs[4] = {xq.x, xq.y, xq.z, xq.w};
+                            xs[0] = xq.x; xs[1] = xq.y; xs[2] = xq.z; xs[3] = xq.w;
+                        } else {
+                            const uint2 xq = *reinterpret_cast<const uint2 *>(xp + ci);
+                            TI t;
+                            t.bits = (uint16_t)(xq.x & 0xffffu); xs[0] = to_float(t);
+                            t.bits = (uint16_t)(xq.x >> 16);     xs[1] = to_float(t);
+                            t.bits = (uint16_t)(xq.y & 0xffffu); xs[2] = to_float(t);
+                            t.bits = (uint16_t)(xq.y >> 16);     xs[3] = to_float(t);
+                        }
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float *wk = wt + (k + e) * CO_T;
+                        for (int e = 0; e < 4; ++e) {
+                            const float *wk = wt + (k + e) * CO_T;
 #pragma unroll
-                                for (int j = 0; j < CO_T; ++j) acc[j] = fmaf(xs[e], wk[j], acc[j]);
-                            }
+                            for (int j = 0; j < CO_T; ++j) acc[j] = fmaf(xs[e], wk[j], acc[j]);
                         }
                     } else {
                         const float xv = to_float(xp[ci]);
@@ -127,7 +135,9 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
         }
         if (live) {
             TO *orow = out + (int64_t)p * out_pitch + co0;
-            constexpr int EPV = 16 / (int)sizeof(TO); // elements per 16-byte store
+            // elements per store: 16 bytes' worth, or the whole (narrow) channel block
+            constexpr int EPV = 16 / (int)sizeof(TO) < CO_T ? 16 / (int)sizeof(TO) : CO_T;
+            constexpr int PIECE_BYTES = EPV * (int)sizeof(TO);
             const bool whole_pieces = g.c_out % EPV == 0;
 #pragma unroll
             for (int j0 = 0; j0 < CO_T; j0 += EPV) {
@@ -141,7 +151,12 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                     from_float(v, &piece[e]);
                 }
                 if (whole_pieces) {
-                    *reinterpret_cast<uint4 *>(orow + j0) = *reinterpret_cast<const uint4 *>(piece);
+                    if constexpr (PIECE_BYTES == 16)
+                        *reinterpret_cast<uint4 *>(orow + j0) = *reinterpret_cast<const uint4 *>(piece);
+                    else if constexpr (PIECE_BYTES == 8)
+                        *reinterpret_cast<uint2 *>(orow + j0) = *reinterpret_cast<const uint2 *>(piece);
+                    else
+                        *reinterpret_cast<uint32_t *>(orow + j0) = *reinterpret_cast<const uint32_t *>(piece);
                 } else {
 #pragma unroll
                     for (int e = 0; e < EPV; ++e)
@@ -177,6 +192,9 @@ static hipError_t launch_t(const Geom &g, const void *x, const uint8_t *mask_in,
     // which a small layer can afford)
     const int64_t wide_blocks = (((int64_t)g.m + kRowsThreads - 1) / kRowsThreads) * ((g.c_out + 63) / 64) * groups;
     if (g.c_out > 32 && wide_blocks >= 512) return launch_rows<TI, TO, 64>(g, x, mask_in, w, bias, idx, count, out, groups, s);
+    // few output channels (per group): accumulator blocks no wider than the layer
+    if (g.c_out <= 4) return launch_rows<TI, TO, 4>(g, x, mask_in, w, bias, idx, count, out, groups, s);
+    if (g.c_out <= 8) return launch_rows<TI, TO, 8>(g, x, mask_in, w, bias, idx, count, out, groups, s);
     return launch_rows<TI, TO, 16>(g, x, mask_in, w, bias, idx, count, out, groups, s);
 }
 
