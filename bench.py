@@ -306,6 +306,7 @@ def grouped_bench(torch, B, synth, workloads, args):
     dev = torch.device("cuda:0")
     gen = synth.mask_bernoulli if args.mask == "bernoulli" else synth.mask_objects
     rows, t_f, t_d, fl_f, fl_d = [], 0.0, 0.0, 0.0, 0.0
+    t_mf = t_md = 0.0
     for li, (c, side) in enumerate(((128, 56), (256, 28), (512, 14), (1024, 7))):
         groups = 32
         x = synth.activations((n, side, side, c), synth.BF16, 8, li, 1)
@@ -327,18 +328,37 @@ def grouped_bench(torch, B, synth, workloads, args):
 
         tf = timed(mask_in=md, mask_out=m_out, idx=idx, count=count)
         td = timed()
+        # the same layer as a full layer with block-diagonal weights, on the matrix cores
+        w_full = B.expand_group_weights(wd, groups, B.BF16)
+        ws = B.ready_workspace(torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=dev))
+        on_mfma_f = B.PreparedConv(desc, xd, w_full, bd, mask_in=md, mask_out=m_out, idx=idx, count=count, out=out,
+                                   workspace=ws, workspace_ready=True)
+        on_mfma_d = B.PreparedConv(desc, xd, w_full, bd, out=out, workspace=ws, workspace_ready=True)
+
+        def timed_call(call):
+            def fn():
+                for _ in range(4):
+                    call()
+            return time_loop(torch, capture(torch, fn).replay, args.steps, args.warmup) / 4
+
+        tmf, tmd = timed_call(on_mfma_f), timed_call(on_mfma_d)
         per_pos = 2.0 * 9 * (c // groups) * c
         ff, fd = float(np.count_nonzero(mask)) * per_pos, float(mask.size) * per_pos
         rows.append({"layer": "c%d@%d/g%d" % (c, side, groups), "focused_us": round(tf * 1e6, 2),
                      "dense_us": round(td * 1e6, 2), "speedup": round(td / tf, 3),
-                     "focused_TFLOPs": round(ff / tf / 1e12, 2), "dense_TFLOPs": round(fd / td / 1e12, 2)})
+                     "focused_TFLOPs": round(ff / tf / 1e12, 2), "dense_TFLOPs": round(fd / td / 1e12, 2),
+                     "block_diagonal_on_matrix_cores_focused_us": round(tmf * 1e6, 2),
+                     "block_diagonal_on_matrix_cores_dense_us": round(tmd * 1e6, 2)})
         t_f, t_d, fl_f, fl_d = t_f + tf, t_d + td, fl_f + ff, fl_d + fd
-        del xd, out
+        t_mf, t_md = t_mf + tmf, t_md + tmd
+        del xd, out, on_mfma_f, on_mfma_d
     print(json.dumps({
         "grouped": True, "workload": "ResNeXt-50 (32x4d) 3x3 grouped layers, batch %d, 224x224 images, bf16, %s masks, "
         "%d %% irrelevant" % (n, args.mask, round(irr * 100)), "launch": "HIP graph replay of four calls",
         "steps": args.steps, "layers": rows, "focused_ms": round(t_f * 1e3, 4), "dense_ms": round(t_d * 1e3, 4),
         "speedup_vs_dense": round(t_d / t_f, 3),
+        "block_diagonal_on_matrix_cores": {"focused_ms": round(t_mf * 1e3, 4), "dense_ms": round(t_md * 1e3, 4),
+                                           "speedup_vs_dense": round(t_md / t_mf, 3)},
         "roofline": {"bound": "alu", "achieved": round(fl_f / t_f / 1e12, 3), "peak": 157.3, "unit": "TFLOP/s",
                      "frac": round(fl_f / t_f / 157.3e12, 4), "traffic": None},
         "dense_TFLOPs": round(fl_d / t_d / 1e12, 2)}))

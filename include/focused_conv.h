@@ -222,6 +222,16 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
                            const uint8_t *mask_out, const int32_t *idx, const int32_t *count,
                            void *out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* A grouped layer is the full layer with block-diagonal weights (the terms outside the blocks
+ * are zeros and change no sum).  This writes those weights: w_full[c_out][kh][kw][c_in] from
+ * w_grouped[c_out][kh][kw][c_in / groups], any storage type, both device.  With them
+ * fc_focused_conv2d runs the grouped layer on the matrix cores, which for the group counts of
+ * common networks is several times faster than fc_focused_gconv2d in spite of the `groups`
+ * times larger multiply count (and is the only way to run a grouped layer in FC_FP8).  Expand
+ * once when the weights are loaded. */
+int32_t fc_expand_group_weights(int32_t c_in, int32_t c_out, int32_t kh, int32_t kw, int32_t groups,
+                                int32_t dtype, const void *w_grouped, void *w_full, void *stream);
+
 /* The depthwise layer: one KH x KW filter per channel, the layer type most of
  * the two networks of Sec. IV consist of (depthwise-separable blocks; their
  * 1x1 halves are fc_focused_conv2d).  Sec. III-A unchanged otherwise: a

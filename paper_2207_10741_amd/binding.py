@@ -22,6 +22,7 @@ FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compac
              "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact",
              "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_gconv2d",
+             "fc_expand_group_weights",
              "fc_focused_dwconv2d",
              "fc_maxpool2d", "fc_maxpool2d_masked")
 MAX_PYRAMID_LEVELS = 8
@@ -96,6 +97,8 @@ def lib():
         L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_focused_gconv2d.restype = i32
         L.fc_focused_gconv2d.argtypes = [ctypes.POINTER(ConvDesc), i32] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.fc_expand_group_weights.restype = i32
+        L.fc_expand_group_weights.argtypes = [i32] * 6 + [vp, vp, vp]
         L.fc_focused_dwconv2d.restype = i32
         L.fc_focused_dwconv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 6
         L.fc_maxpool2d.restype = i32
@@ -345,6 +348,17 @@ def focused_gconv2d(desc: ConvDesc, groups: int, x, w, bias=None, mask_in=None, 
                                     _ptr(mask_out), _ptr(idx), _ptr(count), _ptr(out), _ptr(workspace),
                                     ws_bytes, _stream(stream)), "fc_focused_gconv2d")
     return out
+
+
+def expand_group_weights(w, groups: int, dtype: int, stream=None):
+    """fc_expand_group_weights: [C_out,KH,KW,C_in/groups] -> block-diagonal [C_out,KH,KW,C_in]."""
+    torch = _torch()
+    _require_cuda(w)
+    c_out, kh, kw, cig = w.shape
+    full = torch.empty((c_out, kh, kw, cig * groups), dtype=w.dtype, device=w.device)
+    _check(lib().fc_expand_group_weights(cig * groups, c_out, kh, kw, groups, dtype, _ptr(w), _ptr(full),
+                                         _stream(stream)), "fc_expand_group_weights")
+    return full
 
 
 def focused_dwconv2d(desc: ConvDesc, x, w, bias=None, mask_in=None, out=None, stream=None):

@@ -329,6 +329,20 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
     return FC_OK;
 }
 
+int32_t fc_expand_group_weights(int32_t c_in, int32_t c_out, int32_t kh, int32_t kw, int32_t groups, int32_t dtype,
+                                const void *w_grouped, void *w_full, void *stream)
+{
+    if (!w_grouped || !w_full) return FC_ERR_NULL;
+    if (c_in <= 0 || c_out <= 0 || kh <= 0 || kw <= 0 || groups <= 0 || c_in % groups != 0 || c_out % groups != 0)
+        return FC_ERR_SHAPE;
+    if (dtype != FC_F32 && dtype != FC_BF16 && dtype != FC_F16 && dtype != FC_FP8) return FC_ERR_DTYPE;
+    if ((int64_t)c_out * kh * kw * c_in >= INT32_MAX) return FC_ERR_RANGE;
+    const int esize = dtype == FC_F32 ? 4 : (dtype == FC_FP8 ? 1 : 2);
+    const hipError_t e =
+        launch_expand_group_weights(w_grouped, c_in, c_out, kh * kw, groups, esize, w_full, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
 int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in, const void *w,
                             const float *bias, void *out, void *stream)
 {

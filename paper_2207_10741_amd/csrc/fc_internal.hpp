@@ -202,6 +202,8 @@ static inline int64_t tiled_rows(int n, int ho, int wo, int tile_h, int tile_w)
 hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int32_t *block_counts, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);
+hipError_t launch_expand_group_weights(const void *wg, int c_in, int c_out, int taps, int groups, int esize,
+                                       void *wd, hipStream_t s);
 // keep: [n][ho][wo] bytes or NULL; positions with a zero byte are written as +0 and not computed
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride,
                           int pad, int ho, int wo, const uint8_t *keep, void *out, hipStream_t s);

@@ -696,6 +696,37 @@ __global__ __launch_bounds__(256) void k_maxpool_x8(const T *__restrict__ x, int
     }
 }
 
+// Grouped weights [c_out][taps][c_in / groups] written as the block-diagonal weights
+// [c_out][taps][c_in] of the full layer that computes the same thing (zeros outside the
+// blocks); esize = bytes per value.  One thread per output value.
+__global__ __launch_bounds__(256) void k_expand_group_weights(const uint8_t *__restrict__ wg, int c_in, int c_out,
+                                                              int taps, int groups, int esize,
+                                                              uint8_t *__restrict__ wd)
+{
+    const int cig = c_in / groups, cog = c_out / groups;
+    const int64_t total = (int64_t)c_out * taps * c_in;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int ci = (int)(i % c_in);
+        const int64_t ct = i / c_in; // co * taps + tap
+        const int co = (int)(ct / taps);
+        const int grp = co / cog;
+        const int cl = ci - grp * cig;
+        const bool inside = cl >= 0 && cl < cig;
+        for (int b = 0; b < esize; ++b) wd[i * esize + b] = inside ? wg[(ct * cig + cl) * esize + b] : (uint8_t)0;
+    }
+}
+
+hipError_t launch_expand_group_weights(const void *wg, int c_in, int c_out, int taps, int groups, int esize,
+                                       void *wd, hipStream_t s)
+{
+    const int64_t total = (int64_t)c_out * taps * c_in;
+    const int blocks = (int)((total + 255) / 256 > 65536 ? 65536 : (total + 255) / 256);
+    hipLaunchKernelGGL(k_expand_group_weights, dim3(blocks), dim3(256), 0, s, (const uint8_t *)wg, c_in, c_out, taps,
+                       groups, esize, (uint8_t *)wd);
+    return hipGetLastError();
+}
+
 hipError_t launch_maxpool(const void *x, int n, int h, int w, int c, int dtype, int k, int stride, int pad,
                           int ho, int wo, const uint8_t *keep, void *out, hipStream_t s)
 {

@@ -94,3 +94,30 @@ def test_grouped_layer_argument_errors():
     with pytest.raises(B.FcError) as e:
         B.focused_gconv2d(d8, 2, a, a, None, out=o.view(torch.float32))
     assert e.value.status == -3
+
+
+@pytest.mark.parametrize("layer", [GROUPED_LAYERS[0], GROUPED_LAYERS[1], GROUPED_LAYERS[5], (1, 20, 20, 64, 96, 1, 1, 0, 4)])
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F32, synth.FP8])
+def test_expanded_group_weights_run_the_grouped_layer_on_the_full_layer_path(layer, dtype):
+    """Block-diagonal weights: bit-exact expansion (against numpy), and the full layer run with
+    them matches the oracle's grouped layer."""
+    torch = G.torch_mod()
+    n, h, w, ci, co, k, s_, p, groups = layer
+    if dtype == synth.FP8 and (ci % 16 or co % 8):
+        pytest.skip("not an 8-bit matrix-core shape")
+    x = synth.activations((n, h, w, ci), dtype, 401, 1)
+    wt = synth.he_weights(co, k, k, ci // groups, dtype, 401, 2)
+    bias = synth.bias(co, 401, 3)
+    mask = synth.mask_objects(n, h, w, 0.48, 401, 4)
+    full = B.expand_group_weights(G.to_dev(wt, dtype), groups, dtype)
+    cig, cog = ci // groups, co // groups
+    want_w = np.zeros((co, k, k, ci), wt.dtype)
+    for g in range(groups):
+        want_w[g * cog:(g + 1) * cog, :, :, g * cig:(g + 1) * cig] = wt[g * cog:(g + 1) * cog]
+    np.testing.assert_array_equal(G.to_storage_np(full, dtype), want_w)
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s_, s_), (p, p), (1, 1), dtype, B.F32, B.RELU)
+    out = B.focused_conv2d(desc, G.to_dev(x, dtype), full, torch.from_numpy(bias).to(G.dev()), mask_in=G.mask_dev(mask))
+    want = O.focused_gconv2d(O.ConvShape(n, h, w, ci, co, k, k, (s_, s_), (p, p), (1, 1), relu=True), groups, x, wt,
+                             bias=bias, mask_in=mask, dtype=dtype)
+    keep = O.mask_downsample(mask, k, k, (s_, s_), (p, p)) != 0
+    assert G.rel_err(G.to_f64(out), want, keep) <= (5e-4 if dtype == synth.FP8 else TOL_F32_OUT)
