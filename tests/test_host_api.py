@@ -119,6 +119,13 @@ def test_null_pointers_rejected_before_any_launch():
         ctypes.byref(B.conv_desc(1, 8, 8, ci, co, k, pad=(k[0] // 2, k[1] // 2), in_dtype=B.FP8, out_dtype=B.F32)),
         a, None, a, None, None, None, None, o, None, 0, None)
     assert fp8(24, 64) == -3 and fp8(64, 20) == -3 and fp8(3, 64, (7, 7)) == -3 and fp8(16, 16, (7, 7)) == -3
+    assert L.fc_expand_group_weights(64, 64, 3, 3, 4, B.BF16, None, a, None) == -1
+    assert L.fc_expand_group_weights(64, 64, 3, 3, 5, B.BF16, a, a, None) == -2       # channels not multiples of groups
+    assert L.fc_expand_group_weights(64, 64, 3, 3, 4, 9, a, a, None) == -3
+    gc = lambda groups, *args: L.fc_focused_gconv2d(ctypes.byref(B.conv_desc(1, 8, 8, 24, 36)), groups, *args)
+    assert gc(5, a, None, a, None, None, None, None, o, None, 0, None) == -2
+    assert gc(3, None, None, a, None, None, None, None, o, None, 0, None) == -1
+    assert gc(3, a, a, a, None, None, None, None, o, None, 0, None) == -5              # mask without a list needs a workspace
     dw = lambda desc, *args: L.fc_focused_dwconv2d(ctypes.byref(desc), *args)
     assert dw(B.conv_desc(1, 8, 8, 16, 16, in_dtype=B.FP8), a, None, a, None, o, None) == -3
     #              x  mask_in w  bias out stream
