@@ -36,6 +36,11 @@
  *   - the return value is an fc_status.  Argument errors are found on the host
  *     before anything is launched and leave every output untouched.
  *   - device base pointers must be 16-byte aligned.
+ *   - every call enqueues kernel launches only (no memsets, no copies, no
+ *     allocation), so calls can be recorded into a HIP graph.  The first call
+ *     that uses a given kernel variant also raises that kernel's dynamic LDS
+ *     limit, once per process and on the host: run a call once eagerly before
+ *     capturing it.
  */
 #ifndef FOCUSED_CONV_H
 #define FOCUSED_CONV_H
