@@ -217,7 +217,8 @@ def stack_bench(torch, B, synth, workloads, args):
 
     def timed(**kw):
         def one():
-            stack.run(x, kw.get("mask"), keep_outputs=False, chain=kw.get("chain", False))
+            stack.run(x, kw.get("mask"), keep_outputs=False, chain=kw.get("chain", False),
+                      compact=kw.get("compact", False))
         try:
             graph = capture(torch, one)
             t = time_loop(torch, graph.replay, args.steps, args.warmup)
@@ -233,6 +234,7 @@ def stack_bench(torch, B, synth, workloads, args):
     t_dense, how = timed()
     t_strict, _ = timed(mask=md)
     t_chain, _ = timed(mask=md, chain=True)
+    t_compact, _ = timed(mask=md, chain=True, compact=True)
     print(json.dumps({
         "stack": args.stack, "workload": what, "batch": n, "convs": sum(op.kind in ("conv", "dwconv") for op in ops),
         "launch": how, "steps": args.steps, "dtype": "bf16", "data": "synthetic",
@@ -241,6 +243,7 @@ def stack_bench(torch, B, synth, workloads, args):
         "focused_ms": round(t_strict * 1e3, 4), "focused_effective_tflops": round(kept_flops / t_strict / 1e12, 2),
         "speedup_vs_dense": round(t_dense / t_strict, 3),
         "focused_chain_ms": round(t_chain * 1e3, 4), "speedup_chain_vs_dense": round(t_dense / t_chain, 3),
+        "focused_compact_ms": round(t_compact * 1e3, 4), "speedup_compact_vs_dense": round(t_dense / t_compact, 3),
         "ms_per_image": round(t_strict * 1e3 / n, 5),
     }))
 

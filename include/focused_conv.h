@@ -75,10 +75,16 @@ typedef enum { FC_F32 = 0, FC_BF16 = 1, FC_F16 = 2, FC_FP8 = 3 } fc_dtype;
 enum {
     FC_RELU = 1u,           /* max(.,0) at kept positions */
     FC_SKIP_ZERO_FILL = 2u, /* leave irrelevant output positions untouched */
-    FC_WORKSPACE_READY = 4u /* the caller vouches that the counters at the start of `workspace` are
+    FC_WORKSPACE_READY = 4u, /* the caller vouches that the counters at the start of `workspace` are
                                zero: true for a workspace that was zeroed once, and from then on
                                after every completed fc_focused_conv2d call that was given it (the
                                library leaves them zero).  Saves the launch that clears them. */
+    /* Compacted activations (fc_focused_conv2d with a kept list only, matrix-core layers only,
+       else FC_ERR_DTYPE): rows stored in list order, row j = list entry j, nothing for the
+       irrelevant positions.  Layers that see the same list can hand each other such tensors. */
+    FC_COMPACT_OUT = 8u,     /* out is [count][c_out] (capacity n*ho*wo rows); no zero-fill */
+    FC_COMPACT_IN = 16u      /* x is [count][c_in]; 1x1 kernels with unit stride and no padding only
+                               (else FC_ERR_SHAPE): row j of x is the pixel list entry j reads */
 };
 
 /* The arrival counters of FC_WORKSPACE_READY live in this many leading bytes of the workspace. */

@@ -26,7 +26,8 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
     // 8-bit inputs round to bfloat16 (or stay fp32); every other type to itself or fp32
     if (d->out_dtype != (d->in_dtype == FC_FP8 ? FC_BF16 : d->in_dtype) && d->out_dtype != FC_F32)
         return FC_ERR_DTYPE;
-    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY)) return FC_ERR_DTYPE;
+    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY | FC_COMPACT_OUT | FC_COMPACT_IN))
+        return FC_ERR_DTYPE;
     const int32_t ho = out_dim(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
     const int32_t wo = out_dim(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
     if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
@@ -221,6 +222,15 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     const bool mfma = conv_mfma_supported(g, desc->in_dtype, desc->out_dtype);
     // 8-bit layers exist on the matrix cores only (16 | c_in, 8 | c_out, at most 32 taps)
     if (desc->in_dtype == FC_FP8 && !mfma) return FC_ERR_DTYPE;
+    if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN)) {
+        // compacted activations: rows in list order, so the list must be given
+        if (!idx) return FC_ERR_NULL;
+        if (!mfma) return FC_ERR_DTYPE;
+        if ((g.flags & FC_COMPACT_IN) &&
+            !(g.kh == 1 && g.kw == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0))
+            return FC_ERR_SHAPE;
+        if (g.flags & FC_COMPACT_OUT) g.flags |= FC_SKIP_ZERO_FILL; // there are no irrelevant rows to clear
+    }
     const ConvWorkspace l = conv_ws_layout(g);
     // split-K scratch of the matrix-core path, when the layer is small enough to want it and
     // the caller gave room
@@ -293,6 +303,7 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
     const int32_t rc = make_geom(desc, &g);
     if (rc != FC_OK) return rc;
     if (groups <= 0 || g.c_in % groups != 0 || g.c_out % groups != 0) return FC_ERR_SHAPE;
+    if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN)) return FC_ERR_DTYPE; // full layers only
     // one channel per group with the labels of the input mask: the depthwise kernel
     if (groups == g.c_in && g.c_in == g.c_out && !idx && !mask_out)
         return fc_focused_dwconv2d(desc, x, mask_in, w, bias, out, stream);
@@ -350,6 +361,7 @@ int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8
     const int32_t rc = make_geom(desc, &g);
     if (rc != FC_OK) return rc;
     if (g.c_in != g.c_out) return FC_ERR_SHAPE;
+    if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN)) return FC_ERR_DTYPE; // full layers only
     if (!x || !w || !out) return FC_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(bias)) return FC_ERR_ALIGN;
     if (x == out) return FC_ERR_NULL;

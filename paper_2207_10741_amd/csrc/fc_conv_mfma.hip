@@ -347,6 +347,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                 const int ih0 = oh * g.sh - g.ph, iw0 = ow * g.sw - g.pw;
                 sa_p = p; sa_ow = ow; sa_ih0 = ih0; sa_iw0 = iw0; sa_b = b;
                 base = (b * g.h + ih0) * g.w + iw0;
+                // compacted input (1x1, unit stride, no padding): the row's pixel is row m of x
+                if (g.flags & FC_COMPACT_IN) base = m;
                 hw = (int)(((uint32_t)ih0 & 0xffffu) | ((uint32_t)iw0 << 16));
             }
             row_p[tid] = p;
@@ -868,8 +870,11 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             // streaming stores: the output is not read again by this kernel
 #pragma unroll
             for (int k = 0; k < NPASS; ++k)
-                if (pp[k] >= 0 && co < g.c_out)
-                    __builtin_nontemporal_store(pv[k], reinterpret_cast<u32x4_t *>(out + (int64_t)pp[k] * g.c_out + co));
+                if (pp[k] >= 0 && co < g.c_out) {
+                    // compacted output: row = place in the list, else the position itself
+                    const int64_t orow = (g.flags & FC_COMPACT_OUT) ? (int64_t)mt * TM + r0 + k * RPI : (int64_t)pp[k];
+                    __builtin_nontemporal_store(pv[k], reinterpret_cast<u32x4_t *>(out + orow * g.c_out + co));
+                }
         }
     }
 

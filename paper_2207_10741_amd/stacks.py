@@ -100,7 +100,16 @@ class ConvStack:
         return B.conv_desc(self.n, hi, wi, op.c_in, op.c_out, (op.k, op.k), (op.stride, op.stride),
                            (op.pad, op.pad), (1, 1), self.dtype, out_dtype, flags)
 
-    def run(self, x, mask=None, keep_outputs: bool = True, chain: bool = False, canary=None):
+    def _pointwise(self, i: int) -> bool:
+        op = self.ops[i]
+        return op.kind == "conv" and op.k == 1 and op.stride == 1 and op.pad == 0
+
+    def _matrix_core_shape(self, i: int) -> bool:
+        op = self.ops[i]
+        return (op.kind == "conv" and self.dtype in (B.BF16, B.F16) and op.c_in % 8 == 0 and op.c_out % 8 == 0
+                and op.k * op.k <= 32)
+
+    def run(self, x, mask=None, keep_outputs: bool = True, chain: bool = False, canary=None, compact: bool = False):
         """x: device NHWC tensor; mask: device uint8 [N,H,W] or None (dense).
         Returns (outputs, masks): per-op output tensors and per-op output masks
         (index -1 = the stack's input).
@@ -110,10 +119,16 @@ class ConvStack:
         rows are never looked at (Sec. III-A: irrelevant pixels are excluded from the
         product; Sec. III-B: the mask is the same all the way).  Outputs that a pooling
         layer or nobody reads are still zero-filled.
+        compact (with chain): a conv read only by 1x1 convs of unit stride writes its kept rows
+        compacted, in list order (FC_COMPACT_OUT), and those readers read them that way
+        (FC_COMPACT_IN): they see the same mask through the same geometry, hence the same list.
         canary: value every conv output buffer is pre-filled with (tests)."""
         readers: Dict[int, List[str]] = {}
-        for op in self.ops:
+        reader_ops: Dict[int, List[int]] = {}
+        for j, op in enumerate(self.ops):
             readers.setdefault(op.src, []).append(op.kind)
+            reader_ops.setdefault(op.src, []).append(j)
+        compacted: Dict[int, bool] = {}   # op -> its output is stored compacted
         outs: Dict[int, object] = {-1: x}
         masks: Dict[int, object] = {-1: mask}
         plans: Dict[tuple, tuple] = {}
@@ -153,12 +168,22 @@ class ConvStack:
             if op.kind in ("conv", "dwconv"):
                 gated_readers_only = bool(readers.get(i)) and all(k in ("conv", "dwconv") for k in readers[i])
                 skip = chain and plan is not None and gated_readers_only
-                d = self.desc(i, flags_extra=B.WORKSPACE_READY | (B.SKIP_ZERO_FILL if skip else 0))
+                extra = B.WORKSPACE_READY | (B.SKIP_ZERO_FILL if skip else 0)
                 out = None
-                if canary is not None:
-                    ho, wo = self.sizes[i]
+                ho, wo = self.sizes[i]
+                if compacted.get(op.src, False):
+                    extra |= B.COMPACT_IN
+                if (compact and skip and op.kind == "conv" and self._matrix_core_shape(i)
+                        and all(self._pointwise(j) and self._matrix_core_shape(j) for j in reader_ops[i])):
+                    extra |= B.COMPACT_OUT
+                    compacted[i] = True
+                    out = (self.torch.empty if canary is None else
+                           (lambda *a, **k: self.torch.full(*a, canary, **k)))(
+                        (self.n * ho * wo, op.c_out), dtype=B.torch_dtype(self.dtype), device=self.dev)
+                elif canary is not None:
                     out = self.torch.full((self.n, ho, wo, op.c_out), canary, dtype=B.torch_dtype(self.dtype),
                                           device=self.dev)
+                d = self.desc(i, flags_extra=extra)
                 if op.kind == "dwconv":
                     # labels come from the input mask inside the call: no list, no workspace
                     d.flags &= ~B.WORKSPACE_READY

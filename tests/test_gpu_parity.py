@@ -158,6 +158,81 @@ def test_layer_with_tile_ordered_list_matches(layer, mask_kind):
     assert not outs[1].cpu().numpy()[~keep].view(np.uint32).any()
 
 
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.FP8])
+@pytest.mark.parametrize("irr", [0.48, 0.0, 0.97])
+def test_compacted_activations_through_a_bottleneck(dtype, irr):
+    """1x1 -> 3x3 -> 1x1 with the activations between the last two layers, and the block's output,
+    stored compacted (rows in list order): the 3x3 writes compact rows (FC_COMPACT_OUT), the second
+    1x1 reads and writes them (FC_COMPACT_IN | FC_COMPACT_OUT).  Every compact row equals, bit for
+    bit, the row the spatial layout holds at that list entry; rows past the count stay untouched;
+    the oracle checks the values."""
+    torch = G.torch_mod()
+    n, h, w, c_mid, c_out = 2, 36, 44, 64, 256
+    x = synth.activations((n, h, w, c_mid), dtype, 108, 1)
+    w3 = synth.he_weights(c_mid, 3, 3, c_mid, dtype, 108, 2)
+    w1 = synth.he_weights(c_out, 1, 1, c_mid, dtype, 108, 3)
+    b3, b1 = synth.bias(c_mid, 108, 4), synth.bias(c_out, 108, 5)
+    mask = synth.mask_objects(n, h, w, irr, 108, 6)
+    md = G.mask_dev(mask)
+    m_out = B.mask_downsample(md)
+    idx, count = B.active_index_compact(m_out)
+    cnt = int(count.item())
+    act = B.BF16 if dtype == synth.FP8 else dtype            # 8-bit layers write bf16
+    d3 = B.conv_desc(n, h, w, c_mid, c_mid, in_dtype=dtype, out_dtype=act, flags=B.RELU)
+    d3c = B.conv_desc(n, h, w, c_mid, c_mid, in_dtype=dtype, out_dtype=act, flags=B.RELU | B.COMPACT_OUT)
+    xd, w3d, b3d = G.to_dev(x, dtype), G.to_dev(w3, dtype), torch.from_numpy(b3).to(G.dev())
+    lists = dict(mask_in=md, mask_out=m_out, idx=idx, count=count)
+    y_spatial = B.focused_conv2d(d3, xd, w3d, b3d, **lists)
+    y_compact = torch.full((n * h * w, c_mid), 7.0, dtype=B.torch_dtype(act), device=G.dev())
+    B.focused_conv2d(d3c, xd, w3d, b3d, out=y_compact, **lists)
+    li = idx[:cnt].long()
+    assert torch.equal(y_compact[:cnt], y_spatial.reshape(-1, c_mid)[li])
+    assert bool((y_compact[cnt:] == 7.0).all())
+    if dtype == synth.FP8:
+        return                                               # (the next layer would mix storage types)
+    # second layer: compact in, compact out, against spatial in / spatial out
+    w1d, b1d = G.to_dev(w1, dtype), torch.from_numpy(b1).to(G.dev())
+    d1 = B.conv_desc(n, h, w, c_mid, c_out, (1, 1), (1, 1), (0, 0), (1, 1), dtype, B.F32, B.RELU)
+    d1c = B.conv_desc(n, h, w, c_mid, c_out, (1, 1), (1, 1), (0, 0), (1, 1), dtype, B.F32,
+                      B.RELU | B.COMPACT_IN | B.COMPACT_OUT)
+    z_spatial = B.focused_conv2d(d1, y_spatial, w1d, b1d, **lists)
+    z_compact = torch.full((n * h * w, c_out), 7.0, dtype=torch.float32, device=G.dev())
+    B.focused_conv2d(d1c, y_compact, w1d, b1d, out=z_compact, **lists)
+    assert torch.equal(z_compact[:cnt], z_spatial.reshape(-1, c_out)[li])
+    assert bool((z_compact[cnt:] == 7.0).all())
+    # and the oracle on the second layer, fed the GPU's own (spatial) input
+    y_host = G.to_storage_np(y_spatial, dtype)
+    want = O.focused_conv2d(O.ConvShape(n, h, w, c_mid, c_out, 1, 1, pad=(0, 0), relu=True), y_host, w1, bias=b1,
+                            mask_in=mask, dtype=dtype)
+    keep = mask != 0
+    assert G.rel_err(G.to_f64(z_spatial), want, keep) <= TOL_F32_OUT
+    if cnt:
+        got = z_compact[:cnt].to(torch.float64).cpu().numpy()
+        rms = float(np.sqrt(np.mean(want[keep] ** 2)))
+        assert float(np.abs(got - want.reshape(-1, c_out)[idx[:cnt].cpu().numpy()]).max()) / rms <= TOL_F32_OUT
+
+
+def test_compacted_activations_argument_checks():
+    torch = G.torch_mod()
+    a = torch.zeros((1 << 18,), dtype=torch.uint8, device=G.dev())
+    o = torch.zeros((1 << 18,), dtype=torch.uint8, device=G.dev())
+    i32 = torch.zeros((64,), dtype=torch.int32, device=G.dev())
+    d = B.conv_desc(1, 8, 8, 64, 64, in_dtype=B.BF16, out_dtype=B.BF16, flags=B.COMPACT_OUT)
+    with pytest.raises(B.FcError) as e:                       # no list
+        B.focused_conv2d(d, a.view(torch.bfloat16), a.view(torch.bfloat16), None, mask_in=a, out=o.view(torch.bfloat16))
+    assert e.value.status == -1
+    d = B.conv_desc(1, 8, 8, 64, 64, in_dtype=B.BF16, out_dtype=B.BF16, flags=B.COMPACT_IN)   # 3x3 cannot read compact rows
+    with pytest.raises(B.FcError) as e:
+        B.focused_conv2d(d, a.view(torch.bfloat16), a.view(torch.bfloat16), None, mask_in=a, mask_out=a, idx=i32,
+                         count=i32, out=o.view(torch.bfloat16))
+    assert e.value.status == -2
+    d = B.conv_desc(1, 8, 8, 5, 7, (1, 1), (1, 1), (0, 0), in_dtype=B.F32, flags=B.COMPACT_OUT)     # not a matrix-core layer
+    with pytest.raises(B.FcError) as e:
+        B.focused_conv2d(d, a.view(torch.float32), a.view(torch.float32), None, mask_in=a, mask_out=a, idx=i32,
+                         count=i32, out=o.view(torch.float32))
+    assert e.value.status == -3
+
+
 def test_active_index_compact_blobs_large():
     mask = synth.mask_objects(3, 480, 640, [0.3, 0.5, 0.7], 103)
     idx, count = B.active_index_compact(G.mask_dev(mask))

@@ -281,6 +281,35 @@ def test_chain_mode_never_reads_the_unwritten_rows():
         assert skipped >= 3
 
 
+def test_compact_mode_holds_the_same_rows_as_the_spatial_layout():
+    """With compacted activations (rows in list order between a conv and the 1x1 convs that read
+    it) every layer's kept rows are, bit for bit, those of the chained spatial run, wherever they
+    are stored; rows past the kept count keep the canary."""
+    torch = G.torch_mod()
+    dtype = synth.BF16
+    ops = workloads.resnet50_bottlenecks()[:23]
+    n, h, w, c_in = 2, 48, 64, 64
+    mask = synth.mask_objects(n, h, w, [0.4, 0.6], 371)
+    stack = ConvStack(ops, n, h, w, dtype, seed=372)
+    x = G.to_dev(synth.activations((n, h, w, c_in), dtype, 372, 1), dtype)
+    md = G.mask_dev(mask)
+    chained, masks = stack.run(x, md, chain=True)
+    compact, _ = stack.run(x, md, chain=True, compact=True, canary=float("nan"))
+    torch.cuda.synchronize()
+    n_compact = 0
+    for i, op in enumerate(ops):
+        keep = masks[i].bool()
+        a, b = chained[i], compact[i]
+        if b.dim() == 2:                               # stored compacted: [positions, channels]
+            cnt = int(keep.sum().item())
+            assert torch.equal(b[:cnt].view(torch.int16), a[keep].view(torch.int16)), op.name
+            assert torch.isnan(b[cnt:].float()).all(), op.name
+            n_compact += 1
+        else:
+            assert torch.equal(a[keep].view(torch.int16), b[keep].view(torch.int16)), op.name
+    assert n_compact >= 8
+
+
 # ------------------------------------------------------- graph capture ----
 
 def test_graph_replays_match_eager():
