@@ -121,7 +121,11 @@ constexpr size_t dma_lds_bytes()
 // against the weights of another horizontal tap, which cuts the gathered bytes by up to three.
 // A tile whose line would need more than SL slots (a fragmented mask) runs the tap-by-tap
 // loop instead.  NBW: LDS buffers for the per-tap weight slabs of the shared-halo loop.
-template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW>
+//
+// CMP: the instances that serve compacted activations (FC_COMPACT_IN / FC_COMPACT_OUT: rows
+// stored in list order).  Separate instances, so that the ordinary ones do not change by a
+// register: the 128 x 64 three-buffer instance loses 20 % with a handful more.
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW, bool CMP>
 __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
                                                                  const uint8_t *__restrict__ mask_in,
                                                                  const uint8_t *__restrict__ mask_out,
@@ -348,7 +352,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                 sa_p = p; sa_ow = ow; sa_ih0 = ih0; sa_iw0 = iw0; sa_b = b;
                 base = (b * g.h + ih0) * g.w + iw0;
                 // compacted input (1x1, unit stride, no padding): the row's pixel is row m of x
-                if (g.flags & FC_COMPACT_IN) base = m;
+                if constexpr (CMP) {
+                    if (g.flags & FC_COMPACT_IN) base = m;
+                }
                 hw = (int)(((uint32_t)ih0 & 0xffffu) | ((uint32_t)iw0 << 16));
             }
             row_p[tid] = p;
@@ -872,7 +878,10 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             for (int k = 0; k < NPASS; ++k)
                 if (pp[k] >= 0 && co < g.c_out) {
                     // compacted output: row = place in the list, else the position itself
-                    const int64_t orow = (g.flags & FC_COMPACT_OUT) ? (int64_t)mt * TM + r0 + k * RPI : (int64_t)pp[k];
+                    int64_t orow = (int64_t)pp[k];
+                    if constexpr (CMP) {
+                        if (g.flags & FC_COMPACT_OUT) orow = (int64_t)mt * TM + r0 + k * RPI;
+                    }
                     __builtin_nontemporal_store(pv[k], reinterpret_cast<u32x4_t *>(out + orow * g.c_out + co));
                 }
         }
@@ -898,12 +907,12 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
     return true;
 }
 
-template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2>
+template <int DT, typename TO, bool CMP, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2>
 static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                              const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                              void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW>;
+    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW, CMP>;
     constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW>();
     static bool attr_set = false;
     if (!attr_set) {
@@ -923,46 +932,46 @@ static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_i
 
 #define FC_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, partials, tile_counters, s
 
-template <int DT, typename TO, int TAPC>
+template <int DT, typename TO, int TAPC, bool CMP>
 static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                               const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                               void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
 #ifdef FC_TUNE
     // tuning builds only: pick a tile configuration by number (bf16 in/out, 3x3 only)
-    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 9) {
+    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 9 && !CMP) {
         static const int cfg = getenv("FC_TILE_CONFIG") ? atoi(getenv("FC_TILE_CONFIG")) : 0;
         switch (cfg) {
-        case 20: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 4, 1>(FC_ARGS);
-        case 21: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
-        case 22: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
-        case 23: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
-        case 24: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 4, 1>(FC_ARGS);
-        case 25: return launch_dma<DT, TO, 256, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
-        case 26: return launch_dma<DT, TO, 256, 128, 4, 1, TAPC, 3, 1>(FC_ARGS);
-        case 27: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
-        case 28: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
-        case 29: return launch_dma<DT, TO, 256, 64, 4, 1, TAPC, 2, 1>(FC_ARGS);
-        case 30: return launch_dma<DT, TO, 128, 64, 4, 1, TAPC, 2, 3>(FC_ARGS);
-        case 31: return launch_dma<DT, TO, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
-        case 41: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
-        case 44: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
-        case 45: return launch_dma<DT, TO, 256, 128, 4, 2, TAPC, 2, 2, 320, 3>(FC_ARGS);
-        case 46: return launch_dma<DT, TO, 256, 128, 4, 2, TAPC, 2, 2, 320, 2>(FC_ARGS);
+        case 20: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 4, 1>(FC_ARGS);
+        case 21: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
+        case 22: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
+        case 23: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
+        case 24: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 4, 1>(FC_ARGS);
+        case 25: return launch_dma<DT, TO, CMP, 256, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
+        case 26: return launch_dma<DT, TO, CMP, 256, 128, 4, 1, TAPC, 3, 1>(FC_ARGS);
+        case 27: return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
+        case 28: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
+        case 29: return launch_dma<DT, TO, CMP, 256, 64, 4, 1, TAPC, 2, 1>(FC_ARGS);
+        case 30: return launch_dma<DT, TO, CMP, 128, 64, 4, 1, TAPC, 2, 3>(FC_ARGS);
+        case 31: return launch_dma<DT, TO, CMP, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
+        case 41: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
+        case 44: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+        case 45: return launch_dma<DT, TO, CMP, 256, 128, 4, 2, TAPC, 2, 2, 320, 3>(FC_ARGS);
+        case 46: return launch_dma<DT, TO, CMP, 256, 128, 4, 2, TAPC, 2, 2, 320, 2>(FC_ARGS);
         default: break;
         }
     }
-    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 1) {
+    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 1 && !CMP) {
         static const int cfg1 = getenv("FC_TILE_CONFIG_1X1") ? atoi(getenv("FC_TILE_CONFIG_1X1")) : 0;
         switch (cfg1) {
-        case 22: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
-        case 23: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
-        case 28: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
-        case 27: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
-        case 50: return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 4>(FC_ARGS);
-        case 51: return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 2, 5>(FC_ARGS);
-        case 52: return launch_dma<DT, TO, 256, 64, 4, 1, TAPC, 2, 2>(FC_ARGS);
-        case 53: return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 3>(FC_ARGS);
+        case 22: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
+        case 23: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
+        case 28: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
+        case 27: return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
+        case 50: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 4>(FC_ARGS);
+        case 51: return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 2, 5>(FC_ARGS);
+        case 52: return launch_dma<DT, TO, CMP, 256, 64, 4, 1, TAPC, 2, 2>(FC_ARGS);
+        case 53: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 3>(FC_ARGS);
         default: break;
         }
     }
@@ -976,7 +985,7 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
     // flight (a ResNet-18 stack at batch 1: 0.243 -> 0.221 ms dense, 0.266 -> 0.245 ms focused)
     if constexpr (TAPC != 32) {
         const int64_t tiles64w = (int64_t)((g.m + 127) / 128) * ((g.c_out + 63) / 64);
-        if (tiles64w <= kSmallLayerTiles) return launch_dma<DT, TO, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
+        if (tiles64w <= kSmallLayerTiles) return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
     }
     // 3x3 kernels that step one pixel at a time horizontally share the gathered pixels
     // between their three horizontal taps (worth it when image rows are long enough for runs
@@ -987,33 +996,42 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
             // (with many 128 x 128 tiles it pays down to 16-pixel rows: C512@16 at batch 128 is
             // 13 % faster dense and 17 % faster focused than tap by tap)
             if (g.c_out > 64 && tiles128 >= 512)
-                return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
+                return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
             // narrow layers: only with many tiles (C64@128: -7 % focused, -4..8 % dense from batch 128
             // on; at batch 16 three workgroups per CU, below, are as fast)
             const bool many_narrow_tiles = (int64_t)((g.m + 127) / 128) >= 4096;
             if (g.wo >= 32 && (g.c_out > 64 || partials || many_narrow_tiles))
-                return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+                return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
         }
     }
     if (g.c_out > 64 && tiles128 >= 512)
-        return launch_dma<DT, TO, 128, 128, 2, 2, TAPC, (sizeof(TO) == 4 ? 3 : 2), 2>(FC_ARGS);
+        return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, (sizeof(TO) == 4 ? 3 : 2), 2>(FC_ARGS);
     // narrow layers with many tiles: two stage buffers, so that three workgroups fit a CU
     // and overlap each other's set-up and epilogue
-    if (g.c_out <= 64 && !partials) return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
-    return launch_dma<DT, TO, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
+    if (g.c_out <= 64 && !partials) return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
+    return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
 }
 #undef FC_ARGS
 
 #define FC_ARGS2 g, x, mask_in, mask_out, w, bias, idx, count, out, partials, tile_counters, s
+
+template <int DT, typename TO, bool CMP>
+static hipError_t launch_cmp(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
+                            const void *w, const float *bias, const int32_t *idx, const int32_t *count,
+                            void *out, float *partials, int32_t *tile_counters, hipStream_t s)
+{
+    if (g.kh == 1 && g.kw == 1) return launch_tile<DT, TO, 1, CMP>(FC_ARGS2);
+    if (g.kh == 3 && g.kw == 3) return launch_tile<DT, TO, 9, CMP>(FC_ARGS2);
+    return launch_tile<DT, TO, 32, CMP>(FC_ARGS2);
+}
 
 template <int DT, typename TO>
 static hipError_t launch_dt(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                             const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                             void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-    if (g.kh == 1 && g.kw == 1) return launch_tile<DT, TO, 1>(FC_ARGS2);
-    if (g.kh == 3 && g.kw == 3) return launch_tile<DT, TO, 9>(FC_ARGS2);
-    return launch_tile<DT, TO, 32>(FC_ARGS2);
+    if (g.flags & (FC_COMPACT_IN | FC_COMPACT_OUT)) return launch_cmp<DT, TO, true>(FC_ARGS2);
+    return launch_cmp<DT, TO, false>(FC_ARGS2);
 }
 
 hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
