@@ -60,6 +60,8 @@ def lib():
         L.fco_active_index_compact_tiled.argtypes = [ctypes.c_void_p] + [ctypes.c_int32] * 5 + [ctypes.c_void_p]
         L.fco_widen.restype = ctypes.c_int32
         L.fco_widen.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        L.fco_narrow_fp8.restype = ctypes.c_int32
+        L.fco_narrow_fp8.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
         L.fco_focused_conv2d.restype = ctypes.c_int32
         L.fco_focused_conv2d.argtypes = [ctypes.POINTER(_Conv)] + [ctypes.c_void_p] * 5
         L.fco_focused_conv2d_at.restype = ctypes.c_int32
@@ -124,6 +126,16 @@ def widen(stored: np.ndarray, dtype: int) -> np.ndarray:
     out = np.empty(a.shape, dtype=np.float64)
     if lib().fco_widen(dtype, _ptr(a), a.size, _ptr(out)) != 0:
         raise ValueError("dtype %r" % (dtype,))
+    return out
+
+
+def narrow_fp8(values: np.ndarray) -> np.ndarray:
+    """The 8-bit (E4M3) codes a layer with 8-bit output stores for these values: nearest value,
+    ties to the even code, saturating at 448."""
+    v = np.ascontiguousarray(values, dtype=np.float64)
+    out = np.empty(v.shape, dtype=np.uint8)
+    if lib().fco_narrow_fp8(_ptr(v), v.size, _ptr(out)) != 0:
+        raise ValueError("narrow_fp8")
     return out
 
 

@@ -47,6 +47,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string.h>
+#include <math.h>
 #ifdef _OPENMP
 #include <omp.h>
 #endif
@@ -127,6 +128,36 @@ int32_t fco_widen(int32_t dtype, const void *stored, int64_t count, double *out)
     if (dtype < FCO_F32 || dtype > FCO_FP8) return -1;
     widen_fn wd = pick_widen(dtype);
     for (int64_t i = 0; i < count; ++i) out[i] = wd(stored, (size_t)i);
+    return 0;
+}
+
+/* The 8-bit code an output value is stored as when a layer writes FCO_FP8 (an extension
+ * beyond the paper, which stores fp32): the nearest of the format's values, a tie going to
+ * the code with the even fraction; magnitudes beyond the largest value (448) store that
+ * value; NaN stores code 0x7F with the sign.  Written as the definition: the value's
+ * binade fixes the spacing of the candidates, nearbyint (round-half-even in the default
+ * rounding mode) picks among them. */
+static uint8_t narrow_fp8(double v)
+{
+    uint8_t sign = signbit(v) ? 0x80 : 0x00;
+    double a = fabs(v);
+    if (isnan(v)) return (uint8_t)(sign | 0x7F);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7E);
+    if (a < 1.0 / 64.0) /* subnormals and the first ordinary value: multiples of 2^-9, codes 0..8 */
+        return (uint8_t)(sign | (uint8_t)nearbyint(a * 512.0));
+    int e;
+    double m = frexp(a, &e); /* a = m * 2^e, m in [0.5, 1) */
+    int q = (int)nearbyint((2.0 * m - 1.0) * 8.0); /* eighths above 2^(e-1): 0..8 */
+    int ex = e - 1;
+    if (q == 8) { q = 0; ++ex; }
+    return (uint8_t)(sign | ((ex + 7) << 3) | q);
+}
+
+/* codes[i] = the 8-bit code of values[i] */
+int32_t fco_narrow_fp8(const double *values, int64_t count, uint8_t *codes)
+{
+    if (!values || !codes) return -1;
+    for (int64_t i = 0; i < count; ++i) codes[i] = narrow_fp8(values[i]);
     return 0;
 }
 

@@ -444,6 +444,41 @@ def test_fp8_storage_decoder_and_encoder_against_the_format_and_a_library():
     assert np.count_nonzero(got) > got.size // 8
 
 
+def test_fp8_output_narrowing_against_the_format_and_a_library():
+    """The code an 8-bit output is stored as: every value of the format is its own code, a value
+    between two neighbours goes to the nearer one (brute force over the table of all values), a
+    midpoint to the even code, magnitudes past 448 stay at 448, NaN keeps its sign; in range it
+    agrees with torch's float8_e4m3fn conversion."""
+    codes = np.arange(256, dtype=np.uint8)
+    vals = O.widen(codes, O.FP8)
+    finite = np.delete(codes, [0x7F, 0xFF])
+    np.testing.assert_array_equal(O.narrow_fp8(vals[finite]), finite)        # fixed points, -0 included
+    np.testing.assert_array_equal(O.narrow_fp8(np.array([np.nan, -np.nan])) & 0x7F, [0x7F, 0x7F])
+    np.testing.assert_array_equal(O.narrow_fp8(np.array([449.0, 464.0, 1e9, np.inf, -470.0, -np.inf])),
+                                  [0x7E, 0x7E, 0x7E, 0x7E, 0xFE, 0xFE])
+    pos = vals[:0x7F]                                                         # ascending, 0 .. 448
+    mid = (pos[:-1] + pos[1:]) / 2
+    even = np.where(codes[:0x7E] % 2 == 0, codes[:0x7E], codes[1:0x7F])
+    np.testing.assert_array_equal(O.narrow_fp8(mid), even)                    # ties
+    np.testing.assert_array_equal(O.narrow_fp8(-mid), even | 0x80)
+    np.testing.assert_array_equal(O.narrow_fp8(np.nextafter(mid, 0)), codes[:0x7E])      # just below
+    np.testing.assert_array_equal(O.narrow_fp8(np.nextafter(mid, np.inf)), codes[1:0x7F])  # just above
+    # brute force: nearest table value for random magnitudes over all binades
+    r = synth.rng(37, 1)
+    a = np.concatenate([np.ldexp(r.uniform(0.5, 1.0, 40000), r.integers(-12, 10, 40000)),
+                        r.uniform(0, 2.0 ** -6, 4000)])
+    a = a[a < 448.0]
+    near = np.abs(a[:, None] - pos[None, :]).argmin(axis=1)
+    got = O.narrow_fp8(a)
+    dist = np.abs(pos[got] - a)
+    assert (dist <= np.abs(pos[near] - a)).all()
+    np.testing.assert_array_equal(O.narrow_fp8(-a), got | 0x80)
+    torch = pytest.importorskip("torch")
+    a32 = a.astype(np.float32)
+    want = torch.from_numpy(a32).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    np.testing.assert_array_equal(O.narrow_fp8(a32.astype(np.float64)), want)
+
+
 # ------------------------------------------- Table I: multiply-adds follow the kept share ----
 
 def test_table1_ratio_is_kept_fraction():
