@@ -38,10 +38,11 @@ FP8_MFMA_PEAK_TFLOPS = 5000.0
 TRAFFIC_BYTES_PER_LAUNCH = 41.0e6
 
 
-def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch, in_dtype=None):
+def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch, in_dtype=None, out_dtype=None):
     """Device tensors for the four ResNet-50 3x3 shapes (bf16 storage, or E4M3 bytes with
-    bf16 outputs)."""
+    bf16 or E4M3 outputs)."""
     in_dtype = B.BF16 if in_dtype is None else in_dtype
+    out_dtype = B.BF16 if out_dtype is None else out_dtype
     dev = torch.device("cuda:0")
     layers = []
     for li, (c, side) in enumerate(workloads.sweep_shapes()):
@@ -53,7 +54,7 @@ def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch,
             mask = synth.mask_bernoulli(batch, side, side, irrelevant, *key, 4)
         else:
             mask = synth.mask_objects(batch, side, side, irrelevant, *key, 4)
-        desc = B.conv_desc(batch, side, side, c, c, in_dtype=in_dtype, out_dtype=B.BF16, flags=B.RELU)
+        desc = B.conv_desc(batch, side, side, c, c, in_dtype=in_dtype, out_dtype=out_dtype, flags=B.RELU)
         if in_dtype == B.FP8:
             to_dev = lambda codes: torch.from_numpy(codes).to(dev).view(torch.float8_e4m3fn)
         else:
@@ -62,7 +63,7 @@ def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch,
                  x=to_dev(x), w=to_dev(w), bias=torch.from_numpy(bias).to(dev),
                  mask=torch.from_numpy(mask).to(dev), host=(x, w, bias, mask),
                  kept=int(np.count_nonzero(mask)), m=mask.size, k=9 * c)
-        L["out"] = torch.empty((batch, side, side, c), dtype=torch.bfloat16, device=dev)
+        L["out"] = torch.empty((batch, side, side, c), dtype=B.torch_dtype(out_dtype), device=dev)
         # one workspace per layer, counters cleared once: the timed calls carry FC_WORKSPACE_READY
         L["ws"] = B.ready_workspace(torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=dev))
         L["flops_kept"] = 2.0 * L["kept"] * L["k"] * c
@@ -380,6 +381,8 @@ def main():
     ap.add_argument("--in-dtype", choices=("bf16", "fp8"), default="bf16",
                     help="storage type of activations and weights of the bench line (fp8 = E4M3 bytes, "
                          "outputs bf16; the headline is bf16)")
+    ap.add_argument("--out-dtype", choices=("bf16", "fp8"), default="bf16",
+                    help="with --in-dtype fp8: store the outputs as E4M3 bytes too")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant-kernel loop (for rocprofv3 --kernel-trace --stats)")
     ap.add_argument("--sweep", action="store_true",
@@ -424,7 +427,10 @@ def main():
         return
     in_dtype = B.FP8 if args.in_dtype == "fp8" else B.BF16
     peak = FP8_MFMA_PEAK_TFLOPS if in_dtype == B.FP8 else BF16_MFMA_PEAK_TFLOPS
-    layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch, in_dtype)
+    if args.out_dtype == "fp8" and in_dtype != B.FP8:
+        sys.exit("bench.py: --out-dtype fp8 needs --in-dtype fp8")
+    out_dtype = B.FP8 if args.out_dtype == "fp8" else B.BF16
+    layers = build_sweep_layers(torch, B, synth, workloads, irr, args.mask, batch, in_dtype, out_dtype)
 
     # The four shapes are the four resolutions of one network, so they see ONE mask, rescaled
     # (Sec. III-B): the mask of the first layer, subsampled by two per resolution change.
@@ -452,7 +458,7 @@ def main():
         L["call_dense"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], out=L["out"], workspace=L["ws"], workspace_ready=True)
         L["call_conv_only"] = B.PreparedConv(d, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
                                              idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"], workspace_ready=True)
-        dk = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=in_dtype, out_dtype=B.BF16,
+        dk = B.conv_desc(batch, L["side"], L["side"], L["c"], L["c"], in_dtype=in_dtype, out_dtype=out_dtype,
                          flags=B.RELU | B.SKIP_ZERO_FILL)
         L["call_kernel"] = B.PreparedConv(dk, L["x"], L["w"], L["bias"], mask_in=L["mask"], mask_out=L["m_out"],
                                           idx=L["idx"], count=L["count"], out=L["out"], workspace=L["ws"], workspace_ready=True)
@@ -567,7 +573,7 @@ def main():
         "dtype": args.in_dtype,
         "data": "synthetic",
         "config": {
-            "workload": ("" if in_dtype == B.BF16 else "E4M3 storage, bf16 outputs: ") +
+            "workload": ("" if in_dtype == B.BF16 else "E4M3 storage, %s outputs: " % ("E4M3" if out_dtype == B.FP8 else "bf16")) +
                         "ResNet-50 3x3 layer shapes (C64@128, C128@64, C256@32, C512@16), batch %d, "
                         "one %s mask per image with %.0f %% irrelevant, rescaled to the four resolutions; step = "
                         "mask pyramid (propagation + compaction for all four layers, two launches) + focused "

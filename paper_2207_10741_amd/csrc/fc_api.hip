@@ -23,8 +23,9 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
         return FC_ERR_SHAPE;
     if (d->in_dtype != FC_F32 && d->in_dtype != FC_BF16 && d->in_dtype != FC_F16 && d->in_dtype != FC_FP8)
         return FC_ERR_DTYPE;
-    // 8-bit inputs round to bfloat16 (or stay fp32); every other type to itself or fp32
-    if (d->out_dtype != (d->in_dtype == FC_FP8 ? FC_BF16 : d->in_dtype) && d->out_dtype != FC_F32)
+    // 8-bit inputs round to bfloat16 or to 8 bits (or stay fp32); every other type to itself or fp32
+    if (d->out_dtype != (d->in_dtype == FC_FP8 ? FC_BF16 : d->in_dtype) && d->out_dtype != FC_F32 &&
+        !(d->in_dtype == FC_FP8 && d->out_dtype == FC_FP8))
         return FC_ERR_DTYPE;
     if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY | FC_COMPACT_OUT | FC_COMPACT_IN))
         return FC_ERR_DTYPE;

@@ -841,6 +841,12 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                             v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
                         }
                         store4<ODT, TO>(reinterpret_cast<TO *>(Os + r * OP) + cl, v0, v1, v2, v3);
+                    } else if constexpr (sizeof(TO) == 1) {
+                        // 8-bit outputs: four codes per word, the same sign-bit rule
+                        uint32_t pk;
+                        store4<ODT, TO>(reinterpret_cast<TO *>(&pk), v0, v1, v2, v3);
+                        if (g.flags & FC_RELU) pk = relu_packed8(pk);
+                        *reinterpret_cast<uint32_t *>(Os + r * OP + cl) = pk;
                     } else {
                         // 16-bit outputs: round first, then clear the values whose sign bit is set, two
                         // at a time (rounding keeps the sign, so this is max(., 0) of the rounded value)
@@ -894,10 +900,13 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 {
     if (in_dtype != FC_BF16 && in_dtype != FC_F16 && in_dtype != FC_FP8) return false;
-    // fp8 layers round to bfloat16 (or stay fp32); the 16-bit types keep their own format
-    if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32) return false;
+    // fp8 layers round to bfloat16 or to fp8 (or stay fp32); the 16-bit types keep their own format
+    if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32 &&
+        !(in_dtype == FC_FP8 && out_dtype == FC_FP8))
+        return false;
     const uint64_t es = in_dtype == FC_FP8 ? 1u : 2u;
     if ((g.c_in * es) % 16 != 0 || g.c_out % 8 != 0) return false; // 16-byte gathers, 4-channel stores
+    if (out_dtype == FC_FP8 && g.c_out % 16 != 0) return false;     // rows are stored in 16-byte pieces
     if (g.kh * g.kw > kMaxTaps) return false;
     // row origins are packed into signed 16-bit halves
     if (g.h > 16384 || g.w > 16384 || g.ph > 8192 || g.pw > 8192) return false;
@@ -1047,6 +1056,8 @@ hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const vo
     if (in_dtype == FC_FP8) {
         if (out_dtype == FC_F32)
             return launch_dt<FC_FP8, float>(FC_ARGS2);
+        if (out_dtype == FC_FP8)
+            return launch_dt<FC_FP8, uint8_t>(FC_ARGS2);
         return launch_dt<FC_FP8, uint16_t>(FC_ARGS2);
     }
     if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(FC_ARGS2);

@@ -560,7 +560,7 @@ __global__ __launch_bounds__(256) void k_zero_fill_bytes(Geom g, const uint8_t *
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s)
 {
-    const int esz = out_dtype == FC_F32 ? 4 : 2;
+    const int esz = out_dtype == FC_F32 ? 4 : (out_dtype == FC_FP8 ? 1 : 2);
     const int row_bytes = g.c_out * esz;
     if (row_bytes % 16 == 0) {
         const int cpr = row_bytes / 16;

@@ -75,11 +75,24 @@ typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
 // Four fp32 values -> four stored values; the narrowing is the hardware's
 // round-to-nearest-even conversion (v_cvt_pk_bf16_f32 / v_cvt_f16_f32).
+// a value held to the E4M3 range; NaN stays NaN
+__device__ __forceinline__ float sat_e4m3(float v)
+{
+    return v != v ? v : __builtin_amdgcn_fmed3f(v, -448.f, 448.f);
+}
+
 template <int DT, typename TO>
 __device__ __forceinline__ void store4(TO *dst, float a, float b, float c, float d)
 {
     if constexpr (sizeof(TO) == 4) {
         *reinterpret_cast<float4 *>(dst) = make_float4(a, b, c, d);
+    } else if constexpr (sizeof(TO) == 1) {
+        // v_cvt_pk_fp8_f32 rounds two values to nearest even (E4M3 on gfx950); magnitudes are
+        // held at 448 first so that the result does not depend on its overflow behaviour
+        a = sat_e4m3(a); b = sat_e4m3(b); c = sat_e4m3(c); d = sat_e4m3(d);
+        int r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
+        *reinterpret_cast<uint32_t *>(dst) = (uint32_t)r;
     } else if constexpr (DT == FC_BF16) {
         const f32x2_t lo = {a, b}, hi = {c, d};
         uint2 v;
@@ -106,6 +119,12 @@ __device__ __forceinline__ uint32_t relu_packed16(uint32_t two)
 {
     const i16x2_t zero = {0, 0};
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2_t, two), zero));
+}
+
+// ReLU of four packed 8-bit floats: a code with the sign bit set becomes +0.
+__device__ __forceinline__ uint32_t relu_packed8(uint32_t four)
+{
+    return four & ~(((four >> 7) & 0x01010101u) * 0xFFu);
 }
 
 } // namespace fc

@@ -13,7 +13,15 @@ test_fp8_error_stays_inside_the_bound_of_the_instruction checks element by eleme
 of two 4-bit significands has 8 bits, so only products below 2^-6 of their run's largest lose
 anything, and the typical error is far below the bound: 2e-6 of the output RMS on average,
 2e-4 at worst over the layers below.  The bar for fp32 output is 5e-4 of the RMS of the kept
-outputs; bf16 output must equal the round-to-nearest-even of the fp32 output bit for bit."""
+outputs; bf16 output must equal the round-to-nearest-even of the fp32 output bit for bit.
+
+8-bit output.  The stored code is a rounding decision taken on the fp32 result, so it is checked
+three ways: (1) where every sum is a small integer the fp32 result is exact on both sides and the
+codes must equal the oracle's, ties and saturation included; (2) on ordinary inputs the codes must
+equal the oracle's narrowing of the kernel's own fp32 output bit for bit (the decision in the
+kernel's precision); (3) against the oracle end to end, a stored value v may be off the exact
+result y by the distance from y to the nearest E4M3 value plus twice the fp32 tolerance, which is
+what a correct rounding of a result within that tolerance gives."""
 
 import numpy as np
 import pytest
@@ -205,9 +213,137 @@ def test_fp8_layers_the_matrix_path_cannot_take_are_refused():
         with pytest.raises(B.FcError) as e:
             B.focused_conv2d(d, a, a, None, out=o.view(torch.float32))
         assert e.value.status == -3
-    d = B.conv_desc(1, 8, 8, 64, 64, in_dtype=B.FP8, out_dtype=B.F16)           # fp8 rounds to bf16 or fp32 only
+    d = B.conv_desc(1, 8, 8, 64, 64, in_dtype=B.FP8, out_dtype=B.F16)           # fp8 rounds to bf16, fp8 or fp32 only
     with pytest.raises(B.FcError):
         B.focused_conv2d(d, a, a, None, out=o.view(torch.float16))
     d = B.conv_desc(1, 8, 8, 64, 64, in_dtype=B.FP8, out_dtype=B.BF16)
     with pytest.raises(B.FcError):
         B.focused_dwconv2d(d, a, a, None, out=o.view(torch.bfloat16))
+
+
+# ---- 8-bit outputs --------------------------------------------------------------------------
+
+def _codes(t):
+    return t.view(G.torch_mod().uint8).cpu().numpy()
+
+
+def test_fp8_out_integer_sums_equal_the_oracle_codes():
+    """Inputs 0..3 and weights -2..2 (exact E4M3 values), bias a multiple of 1/2: every partial sum
+    is exact in fp32 in any order, so the codes must be the oracle's: integers between two E4M3
+    values, exact midpoints (17, 34, 36, ...: ties to the even code) and sums past 448."""
+    torch = G.torch_mod()
+    n, h, w, ci, co = 2, 19, 22, 32, 48
+    r = synth.rng(220, 1)
+    xv = r.integers(0, 4, (n, h, w, ci)).astype(np.float32)
+    wv = r.integers(-2, 3, (co, 3, 3, ci)).astype(np.float32)
+    wv[:8] = np.abs(wv[:8])                                    # some channels run past 448
+    bias = (r.integers(-40, 41, co) / 2.0).astype(np.float32)
+    x8, w8 = synth.f32_to_fp8_bits(xv), synth.f32_to_fp8_bits(wv)
+    mask = synth.mask_objects(n, h, w, 0.4, 220, 4)
+    for relu in (False, True):
+        desc = B.conv_desc(n, h, w, ci, co, (3, 3), (1, 1), (1, 1), (1, 1), B.FP8, B.FP8, B.RELU if relu else 0)
+        out = B.focused_conv2d(desc, G.to_dev(x8, synth.FP8), G.to_dev(w8, synth.FP8),
+                               torch.from_numpy(bias).to(G.dev()), mask_in=G.mask_dev(mask))
+        torch.cuda.synchronize()
+        shape = O.ConvShape(n, h, w, ci, co, 3, 3, (1, 1), (1, 1), (1, 1), relu=relu)
+        y = O.focused_conv2d(shape, x8, w8, bias=bias, mask_in=mask, dtype=O.FP8)
+        want = O.narrow_fp8(y)
+        keep = mask != 0
+        got = _codes(out)
+        # ReLU of a negative sum is +0 here; the oracle's max(y, 0) agrees (no -0 from integers)
+        np.testing.assert_array_equal(got[keep], want[keep])
+        assert not got[~keep].any()                            # irrelevant rows: the code of +0.0
+        if not relu:
+            yk = y[keep]
+            assert (np.abs(yk) > 448).mean() > 0.01 and (np.abs(yk) < 16).mean() > 0.05
+            grid = O.widen(np.arange(0x7F, dtype=np.uint8), O.FP8)
+            mids = (grid[:-1] + grid[1:]) / 2
+            assert np.isin(np.abs(yk), mids).mean() > 0.02     # ties are among the cases
+
+
+def test_fp8_out_stores_a_nan_code_for_a_nan_result():
+    """One NaN byte in a kept pixel of x: every output whose window holds it is NaN in the oracle
+    and one of the two NaN codes in the stored bytes; all other codes are the oracle's."""
+    torch = G.torch_mod()
+    n, h, w, ci, co = 1, 12, 12, 16, 16
+    r = synth.rng(224, 1)
+    x8 = synth.f32_to_fp8_bits(r.integers(0, 3, (n, h, w, ci)).astype(np.float32))
+    w8 = synth.f32_to_fp8_bits(r.integers(-1, 2, (co, 3, 3, ci)).astype(np.float32))
+    w8[w8 == 0x00] = 0x38                                      # no zero weights: the NaN reaches every channel
+    x8[0, 5, 6, 3] = 0x7F
+    mask = np.ones((n, h, w), np.uint8)
+    mask[0, :2] = 0
+    desc = B.conv_desc(n, h, w, ci, co, (3, 3), (1, 1), (1, 1), (1, 1), B.FP8, B.FP8, 0)
+    out = B.focused_conv2d(desc, G.to_dev(x8, synth.FP8), G.to_dev(w8, synth.FP8), None, mask_in=G.mask_dev(mask))
+    torch.cuda.synchronize()
+    y = O.focused_conv2d(O.ConvShape(n, h, w, ci, co, 3, 3, (1, 1), (1, 1), (1, 1), relu=False), x8, w8,
+                         bias=None, mask_in=mask, dtype=O.FP8)
+    got = _codes(out)
+    nan = np.isnan(y)
+    assert nan.sum() == 9 * co
+    assert ((got[nan] & 0x7F) == 0x7F).all()
+    np.testing.assert_array_equal(got[~nan], O.narrow_fp8(y)[~nan])
+
+
+@pytest.mark.parametrize("layer", [FP8_LAYERS[0], FP8_LAYERS[1], FP8_LAYERS[3], FP8_LAYERS[4], FP8_LAYERS[6],
+                                   FP8_LAYERS[7], FP8_LAYERS[8], FP8_LAYERS[2], FP8_LAYERS[13]])
+@pytest.mark.parametrize("relu", [True, False])
+def test_fp8_out_is_the_narrowed_fp32_out_and_within_rounding_of_the_oracle(layer, relu):
+    out32, want, keep = _run_layer(*layer, synth.FP8, seed=221, relu=relu)
+    out8, _, _ = _run_layer(*layer, synth.FP8, seed=221, relu=relu, out_dtype=B.FP8)
+    got = _codes(out8)
+    f32 = out32.cpu().numpy()
+    expect = O.narrow_fp8(f32.astype(np.float64))
+    if relu:
+        expect[f32 == 0] = 0            # the sign-bit rule stores +0 for -0
+    np.testing.assert_array_equal(got[keep], expect[keep])
+    assert not got[~keep].any()
+    # end to end: v within (distance of y to the grid) + 2 tol of y
+    grid = O.widen(np.arange(0x7F, dtype=np.uint8), O.FP8)
+    grid = np.concatenate([-grid[:0:-1], grid])
+    v = O.widen(got, O.FP8)
+    rms = float(np.sqrt(np.mean(np.square(want[keep]))))
+    yk, vk = want[keep], v[keep]
+    j = np.searchsorted(grid, np.clip(yk, grid[0], grid[-1]))
+    lo, hi = grid[np.maximum(j - 1, 0)], grid[np.minimum(j, grid.size - 1)]
+    dist = np.minimum(np.abs(yk - lo), np.abs(hi - yk))
+    assert (np.abs(vk - yk) <= dist + 2 * TOL_FP8 * rms).all()
+    # and the codes mostly are the oracle's own (they differ only next to a rounding boundary)
+    assert (got[keep] != O.narrow_fp8(want)[keep]).mean() < 0.01
+
+
+def test_fp8_out_list_path_split_reduction_and_chain_of_two_layers():
+    """The precomputed-list call (split reduction for this small layer) stores the same codes as
+    the mask-only call; a second 8-bit layer fed the first one's bytes matches the oracle fed the
+    same bytes."""
+    torch = G.torch_mod()
+    layer = FP8_LAYERS[7]
+    a, _, keep = _run_layer(*layer, synth.FP8, seed=222, out_dtype=B.FP8)
+    b, _, _ = _run_layer(*layer, synth.FP8, seed=222, out_dtype=B.FP8, precomputed=True)
+    np.testing.assert_array_equal(_codes(a), _codes(b))
+    n, h, w, ci, co = 2, 24, 20, 64, 64
+    x = synth.activations((n, h, w, ci), synth.FP8, 223, 1)
+    w1 = synth.he_weights(co, 3, 3, ci, synth.FP8, 223, 2)
+    w2 = synth.he_weights(co, 1, 1, co, synth.FP8, 223, 3)
+    mask = synth.mask_objects(n, h, w, 0.48, 223, 4)
+    md = G.mask_dev(mask)
+    d1 = B.conv_desc(n, h, w, ci, co, (3, 3), (1, 1), (1, 1), (1, 1), B.FP8, B.FP8, B.RELU)
+    d2 = B.conv_desc(n, h, w, co, co, (1, 1), (1, 1), (0, 0), (1, 1), B.FP8, B.F32, 0)
+    y1 = B.focused_conv2d(d1, G.to_dev(x, synth.FP8), G.to_dev(w1, synth.FP8), None, mask_in=md)
+    y2 = B.focused_conv2d(d2, y1, G.to_dev(w2, synth.FP8), None, mask_in=md)
+    torch.cuda.synchronize()
+    s2 = O.ConvShape(n, h, w, co, co, 1, 1, (1, 1), (0, 0), (1, 1), relu=False)
+    want = O.focused_conv2d(s2, _codes(y1), w2, bias=None, mask_in=mask, dtype=O.FP8)
+    assert G.rel_err(G.to_f64(y2), want, mask != 0) <= TOL_FP8
+
+
+def test_fp8_out_refusals():
+    torch = G.torch_mod()
+    # 8-bit output needs 8-bit input and whole 16-byte rows
+    for in_dt, co in ((B.BF16, 64), (B.FP8, 40)):
+        desc = B.conv_desc(1, 8, 8, 64, co, (3, 3), (1, 1), (1, 1), (1, 1), in_dt, B.FP8, 0)
+        x = torch.zeros((1, 8, 8, 64), dtype=B.torch_dtype(in_dt), device=G.dev())
+        w = torch.zeros((co, 3, 3, 64), dtype=B.torch_dtype(in_dt), device=G.dev())
+        with pytest.raises(B.FcError) as e:
+            B.focused_conv2d(desc, x, w, None)
+        assert e.value.status == -3

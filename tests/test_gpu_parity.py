@@ -314,7 +314,10 @@ def _run_layer(n, h, w, ci, co, k, s, p, d, dtype, *, irr=0.48, relu=True, use_b
         kw = dict(mask_out=m_out, idx=idx, count=count, workspace=ws)
     # the output buffer starts full of a canary, so a row nobody writes cannot pass as zero
     ho, wo = B.out_dims(desc)
-    out = torch.full((n, ho, wo, co), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
+    if out_dtype == B.FP8:       # the code of 7.0
+        out = torch.full((n, ho, wo, co), 0x4E, dtype=torch.uint8, device=G.dev()).view(B.torch_dtype(out_dtype))
+    else:
+        out = torch.full((n, ho, wo, co), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
     B.focused_conv2d(desc, xd, wd, bd, mask_in=md, out=out, **kw)
     torch.cuda.synchronize()
     shape = O.ConvShape(n, h, w, ci, co, k, k, s, p, d, relu=relu)
