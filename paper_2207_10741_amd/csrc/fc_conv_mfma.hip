@@ -57,7 +57,7 @@ constexpr int kMinSplitStages = 8;            // fewest stages a K-split is left
 constexpr int kBusySplitStages = 64;          // shortest reduction that is split on a busy chip
 constexpr int kSmallLayerTiles = 64;  // layers with at most this many 128 x 64 tiles use 64 x 64 tiles
 constexpr int kDeviceScope = 16;                // cache-policy bit sc1: the access is coherent across the XCDs' L2s
-constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
+[[maybe_unused]] constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
 
 // Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
 // plain byte offsets and anything at or beyond `bytes` reads as zero.
@@ -897,6 +897,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 
 // ---------------------------------------------------------------------------
 
+#if !defined(FC_MFMA_PART) || FC_MFMA_PART == 0
 bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 {
     if (in_dtype != FC_BF16 && in_dtype != FC_F16 && in_dtype != FC_FP8) return false;
@@ -915,6 +916,7 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
     if ((uint64_t)g.c_out * g.kh * g.kw * g.c_in * es >= kBufferLimit) return false;
     return true;
 }
+#endif
 
 template <int DT, typename TO, bool CMP, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2>
 static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
@@ -1034,34 +1036,71 @@ static hipError_t launch_cmp(const Geom &g, const void *x, const uint8_t *mask_i
     return launch_tile<DT, TO, 32, CMP>(FC_ARGS2);
 }
 
-template <int DT, typename TO>
-static hipError_t launch_dt(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
-                            const void *w, const float *bias, const int32_t *idx, const int32_t *count,
-                            void *out, float *partials, int32_t *tile_counters, hipStream_t s)
+// The instances of one storage type, with or without compacted activations.
+template <int DT, bool CMP>
+static hipError_t launch_part(const Geom &g, int out_dtype, const void *x, const uint8_t *mask_in,
+                              const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
+                              const int32_t *count, void *out, float *partials, int32_t *tile_counters,
+                              hipStream_t s)
 {
-    if (g.flags & (FC_COMPACT_IN | FC_COMPACT_OUT)) return launch_cmp<DT, TO, true>(FC_ARGS2);
-    return launch_cmp<DT, TO, false>(FC_ARGS2);
+    if (out_dtype == FC_F32) return launch_cmp<DT, float, CMP>(FC_ARGS2);
+    if constexpr (DT == FC_FP8) {
+        if (out_dtype == FC_FP8) return launch_cmp<DT, uint8_t, CMP>(FC_ARGS2);
+    }
+    return launch_cmp<DT, uint16_t, CMP>(FC_ARGS2);
 }
 
+// The kernel instances are spread over six translation units so that a build can compile them
+// side by side: a unit compiled with -DFC_MFMA_PART=p (p = 2 * storage type index + compacted)
+// holds the instances of part p, part 0 also the two entry points below; without the macro
+// this file is one unit that holds everything.
+#define FC_PART_PARAMS                                                                                     \
+    const Geom &g, int out_dtype, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,         \
+        const void *w, const float *bias, const int32_t *idx, const int32_t *count, void *out,             \
+        float *partials, int32_t *tile_counters, hipStream_t s
+#define FC_PART_ARGS g, out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, partials, tile_counters, s
+hipError_t launch_mfma_bf16(FC_PART_PARAMS);
+hipError_t launch_mfma_bf16_compact(FC_PART_PARAMS);
+hipError_t launch_mfma_f16(FC_PART_PARAMS);
+hipError_t launch_mfma_f16_compact(FC_PART_PARAMS);
+hipError_t launch_mfma_fp8(FC_PART_PARAMS);
+hipError_t launch_mfma_fp8_compact(FC_PART_PARAMS);
+
+#ifndef FC_MFMA_PART
+#define FC_MFMA_PART -1
+#endif
+#define FC_IN_PART(p) (FC_MFMA_PART < 0 || FC_MFMA_PART == (p))
+
+#if FC_IN_PART(0)
+hipError_t launch_mfma_bf16(FC_PART_PARAMS) { return launch_part<FC_BF16, false>(FC_PART_ARGS); }
+#endif
+#if FC_IN_PART(1)
+hipError_t launch_mfma_bf16_compact(FC_PART_PARAMS) { return launch_part<FC_BF16, true>(FC_PART_ARGS); }
+#endif
+#if FC_IN_PART(2)
+hipError_t launch_mfma_f16(FC_PART_PARAMS) { return launch_part<FC_F16, false>(FC_PART_ARGS); }
+#endif
+#if FC_IN_PART(3)
+hipError_t launch_mfma_f16_compact(FC_PART_PARAMS) { return launch_part<FC_F16, true>(FC_PART_ARGS); }
+#endif
+#if FC_IN_PART(4)
+hipError_t launch_mfma_fp8(FC_PART_PARAMS) { return launch_part<FC_FP8, false>(FC_PART_ARGS); }
+#endif
+#if FC_IN_PART(5)
+hipError_t launch_mfma_fp8_compact(FC_PART_PARAMS) { return launch_part<FC_FP8, true>(FC_PART_ARGS); }
+#endif
+
+#if FC_IN_PART(0)
 hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
                             const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
                             const int32_t *count, void *out, float *partials, int32_t *tile_counters,
                             hipStream_t s)
 {
-    if (in_dtype == FC_BF16) {
-        if (out_dtype == FC_F32)
-            return launch_dt<FC_BF16, float>(FC_ARGS2);
-        return launch_dt<FC_BF16, uint16_t>(FC_ARGS2);
-    }
-    if (in_dtype == FC_FP8) {
-        if (out_dtype == FC_F32)
-            return launch_dt<FC_FP8, float>(FC_ARGS2);
-        if (out_dtype == FC_FP8)
-            return launch_dt<FC_FP8, uint8_t>(FC_ARGS2);
-        return launch_dt<FC_FP8, uint16_t>(FC_ARGS2);
-    }
-    if (out_dtype == FC_F32) return launch_dt<FC_F16, float>(FC_ARGS2);
-    return launch_dt<FC_F16, uint16_t>(FC_ARGS2);
+    const bool compact = (g.flags & (FC_COMPACT_IN | FC_COMPACT_OUT)) != 0;
+    if (in_dtype == FC_BF16) return compact ? launch_mfma_bf16_compact(FC_PART_ARGS) : launch_mfma_bf16(FC_PART_ARGS);
+    if (in_dtype == FC_FP8) return compact ? launch_mfma_fp8_compact(FC_PART_ARGS) : launch_mfma_fp8(FC_PART_ARGS);
+    return compact ? launch_mfma_f16_compact(FC_PART_ARGS) : launch_mfma_f16(FC_PART_ARGS);
 }
+#endif
 
 } // namespace fc
