@@ -91,9 +91,12 @@ enum {
 enum { FC_WORKSPACE_COUNTER_BYTES = 2048 };
 
 /* One convolution layer.  in_dtype is the storage type of x and w; out_dtype is
- * in_dtype or FC_F32 (for FC_FP8 inputs: FC_BF16, FC_FP8 or FC_F32).  FC_FP8 is served by
- * fc_focused_conv2d only, and only for layers with c_in a multiple of 16, c_out a multiple
- * of 8 (of 16 for FC_FP8 outputs) and at most 32 taps; anything else gives FC_ERR_DTYPE.
+ * in_dtype or FC_F32 (for FC_FP8 inputs: FC_BF16 or FC_F32), or FC_FP8 for any in_dtype but
+ * FC_F32.  FC_FP8 inputs are served by fc_focused_conv2d only, and only for layers with c_in a
+ * multiple of 16, c_out a multiple of 8 and at most 32 taps; FC_FP8 outputs by
+ * fc_focused_conv2d only, for c_out a multiple of 16 and the layers its matrix-core kernels
+ * take (16-bit storage: c_in a multiple of 8 and at most 32 taps, or c_in <= 4); anything
+ * else gives FC_ERR_DTYPE.
  * An FC_FP8 output is the fp32 result (bias and ReLU applied) rounded once to the nearest
  * E4M3 value, ties to the even code; magnitudes beyond 448 are stored as 448 with their
  * sign, NaN as one of the two NaN codes: what the next 8-bit layer reads, so that a chain of such layers moves

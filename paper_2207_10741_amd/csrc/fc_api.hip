@@ -23,9 +23,10 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
         return FC_ERR_SHAPE;
     if (d->in_dtype != FC_F32 && d->in_dtype != FC_BF16 && d->in_dtype != FC_F16 && d->in_dtype != FC_FP8)
         return FC_ERR_DTYPE;
-    // 8-bit inputs round to bfloat16 or to 8 bits (or stay fp32); every other type to itself or fp32
+    // 8-bit inputs round to bfloat16 (or stay fp32); every other type to itself or fp32; all but
+    // fp32 storage can also round to 8 bits
     if (d->out_dtype != (d->in_dtype == FC_FP8 ? FC_BF16 : d->in_dtype) && d->out_dtype != FC_F32 &&
-        !(d->in_dtype == FC_FP8 && d->out_dtype == FC_FP8))
+        !(d->in_dtype != FC_F32 && d->out_dtype == FC_FP8))
         return FC_ERR_DTYPE;
     if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY | FC_COMPACT_OUT | FC_COMPACT_IN))
         return FC_ERR_DTYPE;
@@ -223,6 +224,9 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     const bool mfma = conv_mfma_supported(g, desc->in_dtype, desc->out_dtype);
     // 8-bit layers exist on the matrix cores only (16 | c_in, 8 | c_out, at most 32 taps)
     if (desc->in_dtype == FC_FP8 && !mfma) return FC_ERR_DTYPE;
+    // 8-bit outputs: the matrix-core kernels round to them, the direct kernel does not
+    if (desc->out_dtype == FC_FP8 && !mfma && !conv_stem_supported(g, desc->in_dtype, desc->out_dtype))
+        return FC_ERR_DTYPE;
     if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN)) {
         // compacted activations: rows in list order, so the list must be given
         if (!idx) return FC_ERR_NULL;
@@ -308,7 +312,7 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
     // one channel per group with the labels of the input mask: the depthwise kernel
     if (groups == g.c_in && g.c_in == g.c_out && !idx && !mask_out)
         return fc_focused_dwconv2d(desc, x, mask_in, w, bias, out, stream);
-    if (desc->in_dtype == FC_FP8) return FC_ERR_DTYPE;
+    if (desc->in_dtype == FC_FP8 || desc->out_dtype == FC_FP8) return FC_ERR_DTYPE;
     if (!x || !w || !out) return FC_ERR_NULL;
     if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
     if (!mask_in && (idx || mask_out)) return FC_ERR_NULL;
@@ -366,7 +370,7 @@ int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8
     if (!x || !w || !out) return FC_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(bias)) return FC_ERR_ALIGN;
     if (x == out) return FC_ERR_NULL;
-    if (desc->in_dtype == FC_FP8) return FC_ERR_DTYPE; // no 8-bit depthwise layer
+    if (desc->in_dtype == FC_FP8 || desc->out_dtype == FC_FP8) return FC_ERR_DTYPE; // no 8-bit depthwise layer
     if (!conv_depthwise_supported(g, desc->in_dtype)) return FC_ERR_RANGE;
     const hipError_t e = launch_conv_depthwise(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, out,
                                                (hipStream_t)stream);

@@ -901,9 +901,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 {
     if (in_dtype != FC_BF16 && in_dtype != FC_F16 && in_dtype != FC_FP8) return false;
-    // fp8 layers round to bfloat16 or to fp8 (or stay fp32); the 16-bit types keep their own format
-    if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32 &&
-        !(in_dtype == FC_FP8 && out_dtype == FC_FP8))
+    // fp8 layers round to bfloat16 (or stay fp32), the 16-bit types keep their own format; all can
+    // round to fp8
+    if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32 && out_dtype != FC_FP8)
         return false;
     const uint64_t es = in_dtype == FC_FP8 ? 1u : 2u;
     if ((g.c_in * es) % 16 != 0 || g.c_out % 8 != 0) return false; // 16-byte gathers, 4-channel stores
@@ -1044,9 +1044,7 @@ static hipError_t launch_part(const Geom &g, int out_dtype, const void *x, const
                               hipStream_t s)
 {
     if (out_dtype == FC_F32) return launch_cmp<DT, float, CMP>(FC_ARGS2);
-    if constexpr (DT == FC_FP8) {
-        if (out_dtype == FC_FP8) return launch_cmp<DT, uint8_t, CMP>(FC_ARGS2);
-    }
+    if (out_dtype == FC_FP8) return launch_cmp<DT, uint8_t, CMP>(FC_ARGS2);
     return launch_cmp<DT, uint16_t, CMP>(FC_ARGS2);
 }
 

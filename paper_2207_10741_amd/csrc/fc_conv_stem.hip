@@ -29,8 +29,9 @@ __host__ __device__ static inline int stem_weight_pitch(int ksteps) { return kst
 bool conv_stem_supported(const Geom &g, int in_dtype, int out_dtype)
 {
     if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
-    if (out_dtype != in_dtype && out_dtype != FC_F32) return false;
+    if (out_dtype != in_dtype && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
     if (g.c_in > 4 || g.c_out % 8 != 0) return false;
+    if (out_dtype == FC_FP8 && g.c_out % 16 != 0) return false; // rows are stored in 16-byte pieces
     if (g.kh * g.kw > kStemMaxTaps || (g.kh * g.kw * g.c_in + 15) / 16 * 16 > kStemMaxK) return false;
     // element offset of the last tap from the first one, packed into 24 bits of a table entry
     const int64_t far = ((int64_t)(g.kh - 1) * g.dh * g.w + (int64_t)(g.kw - 1) * g.dw) * g.c_in + g.c_in;
@@ -240,6 +241,11 @@ __global__ __launch_bounds__(kStemThreads, 5) void k_conv_stem(Geom g, StemDivs 
                         v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
                     }
                     store4<DT, TO>(reinterpret_cast<TO *>(o_s + rl * OP) + cl, v0, v1, v2, v3);
+                } else if constexpr (sizeof(TO) == 1) {
+                    uint32_t pk;
+                    store4<DT, TO>(reinterpret_cast<TO *>(&pk), v0, v1, v2, v3);
+                    if (g.flags & FC_RELU) pk = relu_packed8(pk);
+                    *reinterpret_cast<uint32_t *>(o_s + rl * OP + cl) = pk;
                 } else {
                     uint2 pk;
                     store4<DT, TO>(reinterpret_cast<TO *>(&pk), v0, v1, v2, v3);
@@ -293,9 +299,11 @@ hipError_t launch_conv_stem(const Geom &g, int in_dtype, int out_dtype, const vo
 {
     if (in_dtype == FC_BF16) {
         if (out_dtype == FC_F32) return launch_stem_t<FC_BF16, float>(g, x, mask_in, w, bias, idx, count, out, s);
+        if (out_dtype == FC_FP8) return launch_stem_t<FC_BF16, uint8_t>(g, x, mask_in, w, bias, idx, count, out, s);
         return launch_stem_t<FC_BF16, uint16_t>(g, x, mask_in, w, bias, idx, count, out, s);
     }
     if (out_dtype == FC_F32) return launch_stem_t<FC_F16, float>(g, x, mask_in, w, bias, idx, count, out, s);
+    if (out_dtype == FC_FP8) return launch_stem_t<FC_F16, uint8_t>(g, x, mask_in, w, bias, idx, count, out, s);
     return launch_stem_t<FC_F16, uint16_t>(g, x, mask_in, w, bias, idx, count, out, s);
 }
 

@@ -337,13 +337,38 @@ def test_fp8_out_list_path_split_reduction_and_chain_of_two_layers():
     assert G.rel_err(G.to_f64(y2), want, mask != 0) <= TOL_FP8
 
 
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16])
+@pytest.mark.parametrize("layer", [
+    (1, 56, 56, 64, 64, 3, 1, 1, 1), (2, 20, 24, 64, 256, 1, 1, 0, 1), (1, 7, 9, 512, 512, 3, 1, 1, 1),
+    (1, 64, 48, 3, 64, 7, 2, 3, 1),         # RGB stem
+    (1, 40, 40, 3, 64, 3, 1, 1, 1),         # VGG first layer
+    (1, 17, 13, 24, 48, 3, 1, 1, 1),
+])
+def test_fp8_out_from_16_bit_storage(layer, dtype):
+    """16-bit activations and weights, 8-bit output (where an 8-bit chain starts): the codes are
+    the oracle's narrowing of the kernel's own fp32 output, and within rounding of the oracle."""
+    out32, want, keep = _run_layer(*layer, dtype, seed=225)
+    out8, _, _ = _run_layer(*layer, dtype, seed=225, out_dtype=B.FP8)
+    got = _codes(out8)
+    f32 = out32.cpu().numpy()
+    expect = O.narrow_fp8(f32.astype(np.float64))
+    expect[f32 == 0] = 0
+    np.testing.assert_array_equal(got[keep], expect[keep])
+    assert not got[~keep].any()
+    assert (got[keep] != O.narrow_fp8(want)[keep]).mean() < 0.01
+    v = O.widen(got, O.FP8)
+    rms = float(np.sqrt(np.mean(np.square(want[keep]))))
+    # half the spacing of E4M3 values (2^-4 relative, 2^-10 absolute below 2^-6) + the fp32 tolerance
+    assert (np.abs(v[keep] - want[keep]) <= np.maximum(np.abs(want[keep]) / 16, 2.0 ** -10) + 2e-4 * rms).all()
+
+
 def test_fp8_out_refusals():
     torch = G.torch_mod()
-    # 8-bit output needs 8-bit input and whole 16-byte rows
-    for in_dt, co in ((B.BF16, 64), (B.FP8, 40)):
-        desc = B.conv_desc(1, 8, 8, 64, co, (3, 3), (1, 1), (1, 1), (1, 1), in_dt, B.FP8, 0)
-        x = torch.zeros((1, 8, 8, 64), dtype=B.torch_dtype(in_dt), device=G.dev())
-        w = torch.zeros((co, 3, 3, 64), dtype=B.torch_dtype(in_dt), device=G.dev())
+    # 8-bit output needs a matrix-core layer (not fp32 storage, not odd channel counts) and whole 16-byte rows
+    for in_dt, ci, co in ((B.F32, 64, 64), (B.FP8, 64, 40), (B.BF16, 64, 40), (B.BF16, 12, 64)):
+        desc = B.conv_desc(1, 8, 8, ci, co, (3, 3), (1, 1), (1, 1), (1, 1), in_dt, B.FP8, 0)
+        x = torch.zeros((1, 8, 8, ci), dtype=B.torch_dtype(in_dt), device=G.dev())
+        w = torch.zeros((co, 3, 3, ci), dtype=B.torch_dtype(in_dt), device=G.dev())
         with pytest.raises(B.FcError) as e:
             B.focused_conv2d(desc, x, w, None)
         assert e.value.status == -3

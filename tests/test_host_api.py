@@ -55,7 +55,7 @@ def test_descriptor_errors():
     assert rc(in_dtype=B.F32, out_dtype=B.BF16) == -3     # output narrower than the input type
     assert rc(in_dtype=B.FP8, out_dtype=B.BF16) == 0 and rc(in_dtype=B.FP8, out_dtype=B.F32) == 0
     assert rc(in_dtype=B.FP8, out_dtype=B.FP8) == 0 and rc(in_dtype=B.FP8, out_dtype=B.F16) == -3
-    assert rc(in_dtype=B.BF16, out_dtype=B.FP8) == -3 and rc(in_dtype=B.F32, out_dtype=B.FP8) == -3
+    assert rc(in_dtype=B.BF16, out_dtype=B.FP8) == 0 and rc(in_dtype=B.F32, out_dtype=B.FP8) == -3
     assert rc(flags=64) == -3
     assert rc(flags=B.RELU | B.SKIP_ZERO_FILL | B.WORKSPACE_READY) == 0
     assert B.WORKSPACE_COUNTER_BYTES == int(re.search(r"FC_WORKSPACE_COUNTER_BYTES\s*=\s*(\d+)", HEADER_TEXT).group(1))
