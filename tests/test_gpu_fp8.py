@@ -202,6 +202,14 @@ def test_fp8_large_tile_instances_sampled(layer, mask_kind, irr):
     kept = m_out.reshape(-1)[pos] != 0
     rms = float(np.sqrt(np.mean(want[kept] ** 2)))
     assert float(np.abs(got[pos] - want).max()) / rms <= TOL_FP8
+    # the same instances with 8-bit output: the codes are the narrowing of the values above
+    if co % 16 == 0 and mask_kind == "objects":
+        desc8 = B.conv_desc(n, h, w, ci, co, (k, k), (s_, s_), (p, p), (1, 1), B.FP8, B.FP8, B.RELU)
+        out8 = B.focused_conv2d(desc8, G.to_dev(x, synth.FP8), G.to_dev(wt, synth.FP8),
+                                torch.from_numpy(bias).to(G.dev()), mask_in=G.mask_dev(mask))
+        expect = O.narrow_fp8(got.astype(np.float64))
+        expect[got == 0] = 0
+        np.testing.assert_array_equal(_codes(out8).reshape(-1, co), expect)
 
 
 def test_fp8_layers_the_matrix_path_cannot_take_are_refused():
