@@ -41,6 +41,7 @@
 // one that arrives last adds them in a fixed order and writes the tile.
 #include "fc_mfma_util.hpp"
 #include <cstdlib>
+#include <atomic>
 
 namespace fc {
 
@@ -925,12 +926,18 @@ static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_i
 {
     auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW, CMP>;
     constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW>();
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // more than 64 KB of dynamic LDS has to be allowed once per function and device; two
+    // threads that both find the bit clear both set the attribute, which is harmless
+    static std::atomic<uint64_t> attr_devices{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t dev_bit = 1ull << (dev & 63);
+    if (!(attr_devices.load(std::memory_order_acquire) & dev_bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_devices.fetch_or(dev_bit, std::memory_order_release);
     }
     const int64_t max_tiles = (int64_t)((g.m + TM - 1) / TM) * ((g.c_out + TN - 1) / TN);
     const int64_t cap = 256 * 8;
