@@ -198,9 +198,13 @@ def stack_bench(torch, B, synth, workloads, args):
         mask = synth.mask_depth_ramp(n, h, w, 0.5, 4, 0, 4)
     else:
         mask = synth.mask_objects(n, h, w, workloads.HEADLINE_IRRELEVANT, 2, 0, 4)
-    stack = ConvStack(ops, n, h, w, B.BF16, seed=len(args.stack))
-    x_host = synth.activations((n, h, w, c_in), synth.BF16, 9, 0, 1)
-    x = torch.from_numpy(x_host.view(np.int16)).to("cuda:0").view(torch.bfloat16)
+    fp8 = args.in_dtype == "fp8"    # 8-bit activations and weights all the way (stacks of matrix-core convs only)
+    stack = ConvStack(ops, n, h, w, B.FP8 if fp8 else B.BF16, seed=len(args.stack))
+    x_host = synth.activations((n, h, w, c_in), synth.FP8 if fp8 else synth.BF16, 9, 0, 1)
+    if fp8:
+        x = torch.from_numpy(x_host).to("cuda:0").view(torch.float8_e4m3fn)
+    else:
+        x = torch.from_numpy(x_host.view(np.int16)).to("cuda:0").view(torch.bfloat16)
     md = torch.from_numpy(mask).to("cuda:0")
     del x_host
 
@@ -238,7 +242,7 @@ def stack_bench(torch, B, synth, workloads, args):
     t_compact, _ = timed(mask=md, chain=True, compact=True)
     print(json.dumps({
         "stack": args.stack, "workload": what, "batch": n, "convs": sum(op.kind in ("conv", "dwconv") for op in ops),
-        "launch": how, "steps": args.steps, "dtype": "bf16", "data": "synthetic",
+        "launch": how, "steps": args.steps, "dtype": args.in_dtype, "data": "synthetic",
         "kept_flop_share": round(kept_flops / dense_flops, 4),
         "dense_ms": round(t_dense * 1e3, 4), "dense_tflops": round(dense_flops / t_dense / 1e12, 2),
         "focused_ms": round(t_strict * 1e3, 4), "focused_effective_tflops": round(kept_flops / t_strict / 1e12, 2),

@@ -27,6 +27,8 @@ class ConvStack:
         self.n, self.h, self.w, self.dtype = n, h, w, dtype
         self.dev = torch.device("cuda:0")
         self.relu = relu
+        if dtype == B.FP8 and not all(op.kind == "conv" and op.c_in % 16 == 0 and op.c_out % 16 == 0 for op in self.ops):
+            raise ValueError("an 8-bit stack takes convolutions with multiples of 16 channels only")
         self.weights: Dict[int, object] = {}
         self.biases: Dict[int, object] = {}
         self.host_weights: Dict[int, np.ndarray] = {}
@@ -90,6 +92,8 @@ class ConvStack:
         torch = self.torch
         if self.dtype == B.F32:
             return torch.from_numpy(np.ascontiguousarray(storage, dtype=np.float32)).to(self.dev)
+        if self.dtype == B.FP8:
+            return torch.from_numpy(np.ascontiguousarray(storage, dtype=np.uint8)).to(self.dev).view(torch.float8_e4m3fn)
         t = torch.from_numpy(np.ascontiguousarray(storage).view(np.int16)).to(self.dev)
         return t.view(torch.bfloat16 if self.dtype == B.BF16 else torch.float16)
 
@@ -97,6 +101,8 @@ class ConvStack:
         op = self.ops[i]
         hi, wi = self.sizes[op.src]
         flags = (B.RELU if (self.relu and op.relu) else 0) | flags_extra
+        if out_dtype is None and self.dtype == B.FP8:
+            out_dtype = B.FP8       # an 8-bit stack hands on 8-bit activations
         return B.conv_desc(self.n, hi, wi, op.c_in, op.c_out, (op.k, op.k), (op.stride, op.stride),
                            (op.pad, op.pad), (1, 1), self.dtype, out_dtype, flags)
 
@@ -106,6 +112,8 @@ class ConvStack:
 
     def _matrix_core_shape(self, i: int) -> bool:
         op = self.ops[i]
+        if self.dtype == B.FP8:
+            return op.kind == "conv" and op.c_in % 16 == 0 and op.c_out % 16 == 0 and op.k * op.k <= 32
         return (op.kind == "conv" and self.dtype in (B.BF16, B.F16) and op.c_in % 8 == 0 and op.c_out % 8 == 0
                 and op.k * op.k <= 32)
 

@@ -168,9 +168,9 @@ def test_density_sweep_small(irr, mask_kind):
 
 # ------------------------------------------------------------------ stacks ----
 
-def _check_stack(ops, n, h, w, c_in, mask, seed):
+def _check_stack(ops, n, h, w, c_in, mask, seed, dtype=synth.BF16):
     torch = G.torch_mod()
-    dtype = synth.BF16
+    tol = 5e-4 if dtype == synth.FP8 else TOL_F32_OUT     # the 8-bit matrix instruction's summation
     stack = ConvStack(ops, n, h, w, dtype, seed=seed)
     x = synth.activations((n, h, w, c_in), dtype, seed, 1)
     outs, masks = stack.run(G.to_dev(x, dtype), G.mask_dev(mask))
@@ -204,8 +204,15 @@ def _check_stack(ops, n, h, w, c_in, mask, seed):
                                     dtype=dtype)
             o32 = B.focused_conv2d(stack.desc(i, out_dtype=B.F32), outs[op.src], stack.weights[i], stack.biases[i],
                                    mask_in=masks[op.src])
-        assert G.rel_err(G.to_f64(o32), want, keep) <= TOL_F32_OUT, op.name
-        assert torch.equal(outs[i], o32.to(outs[i].dtype)), op.name
+        assert G.rel_err(G.to_f64(o32), want, keep) <= tol, op.name
+        if dtype == synth.FP8:
+            # the stored codes are the oracle's narrowing of the fp32-output call's values
+            f32 = o32.cpu().numpy()
+            expect = O.narrow_fp8(f32.astype(np.float64))
+            expect[f32 == 0] = 0
+            np.testing.assert_array_equal(G.to_storage_np(outs[i], dtype), expect, err_msg=op.name)
+        else:
+            assert torch.equal(outs[i], o32.to(outs[i].dtype)), op.name
         assert not G.to_storage_np(outs[i], dtype)[~keep].any(), op.name
         macs = op.k * op.k * op.c_in * (op.c_out if op.kind == "conv" else 1)
         dense_macs += keep.size * macs
@@ -234,6 +241,14 @@ def test_resnet50_bottlenecks_small_batch():
     n, h, w = 2, 48, 64
     mask = synth.mask_objects(n, h, w, [0.35, 0.65], 364)
     _check_stack(workloads.resnet50_bottlenecks(), n, h, w, 64, mask, 365)
+
+
+def test_resnet50_bottlenecks_8bit_chain():
+    """The same 52 convs with 8-bit (E4M3) activations and weights all the way: every layer reads
+    the previous layer's bytes and is checked against the oracle fed those bytes."""
+    n, h, w = 2, 48, 64
+    mask = synth.mask_objects(n, h, w, [0.35, 0.65], 366)
+    _check_stack(workloads.resnet50_bottlenecks(), n, h, w, 64, mask, 367, dtype=synth.FP8)
 
 
 def test_mobilenetv2_stack_layer_by_layer():
