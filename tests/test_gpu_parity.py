@@ -412,8 +412,6 @@ HALO_LAYERS = [
 @pytest.mark.parametrize("layer", HALO_LAYERS)
 @pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", "mixed", None])
 def test_shared_halo_layers_match_oracle(layer, mask_kind):
-    if layer[0] >= 8 and mask_kind == "bernoulli":
-        pytest.skip("covered by the smaller shapes")
     out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=0.45, seed=207)
     assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
     assert not out.cpu().numpy()[~keep].view(np.uint32).any()
