@@ -35,7 +35,7 @@ FP8_MFMA_PEAK_TFLOPS = 5000.0
 # HBM bytes per launch of the conv kernel on the default workload (mean of the four layers),
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the counter read for a
 # 256 MiB streaming copy (x2.00 and x1.00): profiles/k_conv_dma_resnet50_3x3_b16_48pct.md
-TRAFFIC_BYTES_PER_LAUNCH = 41.0e6
+TRAFFIC_BYTES_PER_LAUNCH = 41.1e6
 
 
 def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch, in_dtype=None, out_dtype=None):
