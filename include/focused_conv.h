@@ -226,6 +226,29 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
                           const int32_t *idx, const int32_t *count, void *out,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same layer for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is
+ * fc_focused_conv2d(desc, x, mask_in, w, bias, NULL, NULL, NULL, out, <scratch>, ..., stream),
+ * i.e. the labels, the kept list and the split-K scratch of the call live in a device array
+ * of FC_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every GPU the library
+ * runs on holds one copy until the process ends).  The call allocates and frees nothing,
+ * enqueues kernel launches only, and gives bit for bit the result of that fc_focused_conv2d
+ * call.
+ *   - layers whose fc_workspace_bytes(desc) exceeds FC_NOALLOC_SCRATCH_BYTES (five bytes per
+ *     output position: more than about 8 million positions) are refused with FC_ERR_RANGE
+ *     before anything is launched.
+ *   - FC_WORKSPACE_READY is ignored (the call always clears the arrival counters itself);
+ *     FC_COMPACT_OUT / FC_COMPACT_IN need a caller's list and give FC_ERR_NULL here.
+ *   - all calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ *     (different streams, parallel graph branches) race and must be ordered by the caller.
+ *   - the address of the array is looked up on the first call on each device (or by
+ *     fc_noalloc_init, with that device current); do either once, eagerly, before capturing
+ *     a call into a graph. */
+#define FC_NOALLOC_SCRATCH_BYTES (40u << 20)
+int32_t fc_noalloc_init(void);
+int32_t fc_focused_conv2d_noalloc(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in,
+                                  const void *w, const float *bias, void *out, void *stream);
+
 /* The grouped layer: channels cut into `groups` equal slices, output slice g sees input slice
  * g only (the layer type between fc_focused_conv2d, groups = 1, and fc_focused_dwconv2d, one
  * channel per group; both are what this call runs in those two cases).  Sec. III-A unchanged

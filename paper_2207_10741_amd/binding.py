@@ -17,11 +17,13 @@ F32, BF16, F16, FP8 = 0, 1, 2, 3
 RELU, SKIP_ZERO_FILL, WORKSPACE_READY, COMPACT_OUT, COMPACT_IN = 1, 2, 4, 8, 16
 RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 WORKSPACE_COUNTER_BYTES = 2048
+NOALLOC_SCRATCH_BYTES = 40 << 20
 
 FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compact_workspace_bytes",
              "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact",
              "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_gconv2d",
+             "fc_noalloc_init", "fc_focused_conv2d_noalloc",
              "fc_expand_group_weights",
              "fc_focused_dwconv2d",
              "fc_maxpool2d", "fc_maxpool2d_masked")
@@ -64,6 +66,9 @@ def lib():
             raise ImportError(
                 "%s is missing: build it with `python -m paper_2207_10741_amd.build` "
                 "(hipcc --offload-arch=gfx950); there is no CPU fallback" % LIB_PATH)
+        # PyTorch ships its own HIP runtime; load it first so that this library binds to the same
+        # one (two runtimes in one process do not share the device)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
         L.fc_status_string.restype = ctypes.c_char_p
@@ -95,6 +100,10 @@ def lib():
                                       ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
         L.fc_focused_conv2d.restype = i32
         L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.fc_noalloc_init.restype = i32
+        L.fc_noalloc_init.argtypes = []
+        L.fc_focused_conv2d_noalloc.restype = i32
+        L.fc_focused_conv2d_noalloc.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 6
         L.fc_focused_gconv2d.restype = i32
         L.fc_focused_gconv2d.argtypes = [ctypes.POINTER(ConvDesc), i32] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_expand_group_weights.restype = i32
@@ -293,6 +302,14 @@ def focused_conv2d(desc: ConvDesc, x, w, bias=None, mask_in=None, mask_out=None,
     _check(lib().fc_focused_conv2d(ctypes.byref(desc), _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias),
                                    _ptr(mask_out), _ptr(idx), _ptr(count), _ptr(out), _ptr(workspace),
                                    ws_bytes, _stream(stream)), "fc_focused_conv2d")
+    return out
+
+
+def focused_conv2d_noalloc(desc: ConvDesc, x, w, bias, mask_in, out, stream=None):
+    """fc_focused_conv2d_noalloc: the caller passes inputs and the output tensor, nothing is allocated."""
+    _require_cuda(x, w, bias, mask_in, out)
+    _check(lib().fc_focused_conv2d_noalloc(ctypes.byref(desc), _ptr(x), _ptr(mask_in), _ptr(w), _ptr(bias),
+                                           _ptr(out), _stream(stream)), "fc_focused_conv2d_noalloc")
     return out
 
 

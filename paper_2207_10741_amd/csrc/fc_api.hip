@@ -1,5 +1,6 @@
 // C ABI of the library: argument checks on the host, then launches.
 #include "fc_internal.hpp"
+#include <atomic>
 
 using namespace fc;
 
@@ -462,6 +463,58 @@ int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
     if (!aligned16(workspace)) return FC_ERR_ALIGN;
     const hipError_t e = launch_mask_pyramid(a, mask_in, (int32_t *)workspace, (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
+// ---- the entry point that allocates nothing --------------------------------------------
+// Its workspace is this file-scope device array.  Every GPU the library is loaded on holds its
+// own copy at its own address; the name `noalloc_scratch` is only a handle for
+// hipGetSymbolAddress in host code, never a pointer to pass on.
+} // extern "C"
+static __device__ __align__(256) unsigned char noalloc_scratch[FC_NOALLOC_SCRATCH_BYTES];
+namespace {
+constexpr int kNoallocMaxDevices = 64;
+std::atomic<void *> noalloc_ptr[kNoallocMaxDevices];
+
+// Address of the current device's copy of the array (resolved once per device).
+int32_t noalloc_scratch_of_current_device(void **p)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FC_ERR_HIP;
+    if (dev < 0 || dev >= kNoallocMaxDevices) return FC_ERR_RANGE;
+    void *q = noalloc_ptr[dev].load(std::memory_order_acquire);
+    if (!q) {
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(noalloc_scratch)) != hipSuccess || !q) return FC_ERR_HIP;
+        noalloc_ptr[dev].store(q, std::memory_order_release); // (two threads store the same address)
+    }
+    *p = q;
+    return FC_OK;
+}
+} // namespace
+extern "C" {
+
+int32_t fc_noalloc_init(void)
+{
+    void *p;
+    return noalloc_scratch_of_current_device(&p);
+}
+
+int32_t fc_focused_conv2d_noalloc(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in, const void *w,
+                                  const float *bias, void *out, void *stream)
+{
+    Geom g;
+    const int32_t rc = make_geom(desc, &g);
+    if (rc != FC_OK) return rc;
+    // the whole workspace of the call (split-K scratch, labels, kept list) must fit the array
+    if (conv_ws_layout(g).total > (size_t)FC_NOALLOC_SCRATCH_BYTES) return FC_ERR_RANGE;
+    void *scratch;
+    const int32_t rs = noalloc_scratch_of_current_device(&scratch);
+    if (rs != FC_OK) return rs;
+    // the array keeps the last call's contents: the arrival counters are cleared by this call
+    // whatever the caller's flags say (everything else in it is written before it is read)
+    fc_conv_desc d = *desc;
+    d.flags &= ~(uint32_t)FC_WORKSPACE_READY;
+    return fc_focused_conv2d(&d, x, mask_in, w, bias, nullptr, nullptr, nullptr, out, scratch,
+                             (size_t)FC_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,
