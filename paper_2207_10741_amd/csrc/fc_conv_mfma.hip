@@ -39,70 +39,36 @@
 // and read the count on the device.  Layers with few tiles split every tile's reduction
 // over several workgroups, which meet through fp32 partial tiles in the workspace; the
 // one that arrives last adds them in a fixed order and writes the tile.
-#include "fc_mfma_util.hpp"
+#include "fc_dma_util.hpp"
 #include <cstdlib>
 #include <atomic>
 
 namespace fc {
 
-// LDS swizzle: slot of a row's 16-byte piece p is p ^ FC_SWZ(row)
-#ifndef FC_SWZ
-#define FC_SWZ(r) (((r) >> 1) & 7)
-#endif
-
-constexpr uint32_t kBufferLimit = 0xF0000000u; // tensors handled through one descriptor stay below this
-constexpr uint32_t kOutOfRange = kBufferLimit; // offset that is out of range for every descriptor
-constexpr int kStageBytes = 128;               // bytes of one pixel a stage gathers (64 16-bit or 128 8-bit channels)
 constexpr int kMaxSplits = 16;                 // most K-splits of one tile
 constexpr int kMinSplitStages = 8;            // fewest stages a K-split is left with
 constexpr int kBusySplitStages = 64;          // shortest reduction that is split on a busy chip
 constexpr int kSmallLayerTiles = 64;  // layers with at most this many 128 x 64 tiles use 64 x 64 tiles
-constexpr int kDeviceScope = 16;                // cache-policy bit sc1: the access is coherent across the XCDs' L2s
 [[maybe_unused]] constexpr int kMaxTaps = 32;                   // tap-valid bits per row live in one 32-bit word
-
-// Raw buffer descriptor (4 dwords) over `bytes` bytes at p: stride 0, so offsets are
-// plain byte offsets and anything at or beyond `bytes` reads as zero.
-__device__ __forceinline__ u32x4_t make_rsrc_words(const void *p, uint32_t bytes)
-{
-    const uint64_t a = reinterpret_cast<uint64_t>(p);
-    u32x4_t r;
-    r.x = (uint32_t)a;
-    r.y = (uint32_t)(a >> 32) & 0xffffu;
-    r.z = bytes;
-    r.w = 0x00020000u;
-    return r;
-}
-
-// One wave-wide 16-byte-per-lane load into LDS at lds_addr + 16 * lane (lds_addr is
-// wave-uniform and goes through M0).
-__device__ __forceinline__ void dma_load16(const u32x4_t &rsrc, uint32_t byte_offset, uint32_t lds_addr)
-{
-    __asm__ volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                     :
-                     : "s"(lds_addr), "v"(byte_offset), "s"(rsrc)
-                     : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    __asm__ volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
 
 // Bytes of the LDS stage region: NB buffers of (TM + TN) rows for the tap-by-tap loop; with the
 // shared-halo loop (SL > 0) also room for two buffers of SL pixel slots and NBW weight buffers.
-template <int TM, int TN, int NB, int SL, int NBW>
+// With KS > 1 wave groups per tile the region also has to hold the fp32 accumulators of the
+// groups after the first (they are added up through LDS at the end of a tile).
+template <int TM, int TN, int NB, int SL, int NBW, int KS>
 constexpr size_t dma_stage_region_bytes()
 {
     const size_t classic = (size_t)NB * (TM + TN) * 128;
     const size_t halo = SL > 0 ? (size_t)2 * SL * 128 + (size_t)NBW * TN * 128 : 0;
-    return classic > halo ? classic : halo;
+    const size_t reduce = (size_t)(KS - 1) * TM * TN * sizeof(float);
+    const size_t stage = classic > halo ? classic : halo;
+    return stage > reduce ? stage : reduce;
 }
 
-template <int TM, int TN, int NB, int SL, int NBW>
+template <int TM, int TN, int NB, int SL, int NBW, int KS>
 constexpr size_t dma_lds_bytes()
 {
-    return dma_stage_region_bytes<TM, TN, NB, SL, NBW>() + (size_t)TM * 5 * sizeof(int32_t) +
+    return dma_stage_region_bytes<TM, TN, NB, SL, NBW, KS>() + (size_t)TM * 5 * sizeof(int32_t) +
            (SL > 0 ? (size_t)(TM + 3 * SL + 8) * sizeof(int32_t) : 0);
 }
 
@@ -126,8 +92,17 @@ constexpr size_t dma_lds_bytes()
 // CMP: the instances that serve compacted activations (FC_COMPACT_IN / FC_COMPACT_OUT: rows
 // stored in list order).  Separate instances, so that the ordinary ones do not change by a
 // register: the 128 x 64 three-buffer instance loses 20 % with a handful more.
-template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW, bool CMP>
-__global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
+//
+// KS: wave groups per tile.  Each group is a full WM x WN grid of waves over the same tile and
+// the same LDS stages; group q multiplies the k-steps q * KK/KS ... of every stage, so a SIMD
+// holds KS waves of one tile that take turns at the matrix pipe (one reads fragments while the
+// other multiplies) without any more LDS traffic per multiply.  At the end of a tile the groups
+// after the first hand their fp32 accumulators to the first through LDS, which adds them in
+// group order and runs the epilogue.  For layers with so few tiles that a CU holds one
+// workgroup: there one wave per SIMD leaves the pipe idle more than half of the time.
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW, bool CMP,
+          int KS>
+__global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
                                                                  const uint8_t *__restrict__ mask_in,
                                                                  const uint8_t *__restrict__ mask_out,
                                                                  const uint16_t *__restrict__ w,
@@ -138,7 +113,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                                                                  float *__restrict__ partials,
                                                                  int32_t *__restrict__ tile_counters)
 {
-    constexpr int NT = WM * WN * 64;
+    constexpr int NT = WM * WN * 64 * KS;
+    constexpr int GT = WM * WN * 64;   // threads of one wave group
     constexpr int RPP = NT / 8;        // rows covered by one pass of wave loads
     constexpr int XR = TM / RPP;       // wave loads per thread for the activation tile
     constexpr int WR = TN / RPP;       // ... for the weight tile
@@ -150,6 +126,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     constexpr int EPP = 16 / ES;                           // elements per 16-byte piece
     constexpr uint32_t KSTEP = kStepBytes<DT>;             // bytes of a row per matrix instruction
     constexpr int KK = kStageBytes / (int)KSTEP;           // matrix instructions per stage and block pair
+    constexpr int KKG = KK / KS;                           // ... of which a wave group takes this many
+    static_assert(KS >= 1 && KK % KS == 0, "the k-steps of a stage are dealt out evenly to the wave groups");
     constexpr int ODT = DT == FC_FP8 ? FC_BF16 : DT;       // 16-bit output format
     // register sets of operand fragments: the 16-bit types fetch step kk + 1 while step kk is
     // multiplied; fp8 fragments are twice as large and its instructions twice as long, so one set,
@@ -162,7 +140,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     static_assert(TM <= NT && TN <= NT, "set-up assumes one thread per row / channel");
     static_assert(NB >= 2 && (NB - 1) * L <= 63, "vmcnt is a 6-bit counter");
     constexpr bool HALO = SL > 0;
-    constexpr size_t REGION = dma_stage_region_bytes<TM, TN, NB, SL, NBW>();
+    constexpr size_t REGION = dma_stage_region_bytes<TM, TN, NB, SL, NBW, KS>();
     static_assert(!HALO || (TAPC == 9 && SL % RPP == 0 && SL <= NT && SL > TM && (NBW == 2 || NBW == 3)),
                   "shared-halo loop: 3x3 kernels, whole load passes, one thread per slot");
 
@@ -183,7 +161,9 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw); // LDS byte address of the stage buffers
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_m = wave % WM, wave_n = wave / WM;
+    const int kgrp = KS > 1 ? wave / (WM * WN) : 0;       // wave group
+    const int gwave = wave - kgrp * (WM * WN), gtid = tid - kgrp * GT;
+    const int wave_m = gwave % WM, wave_n = gwave / WM;
     const int slot = tid & 7, prow = tid >> 3;
 
     // Kept rows.  With a list they are given.  Without one but with a mask (the launcher does
@@ -233,7 +213,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
     // rows, so the swizzle term depends on the lane only
     constexpr uint32_t HALF = KSTEP / 32u; // piece index of the upper half-wave within a step
     const uint32_t frag_row = (uint32_t)(lane & 31) * 128u;
-    const uint32_t frag_t16 = (uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(lane & 31)) * 16u;
+    const uint32_t frag_k0 = (uint32_t)(kgrp * KKG) * KSTEP; // byte offset of this group's first k-step in a row
+    const uint32_t frag_t16 = ((uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(lane & 31)) * 16u) ^ frag_k0;
 
     // Tile order: all row tiles of channel tile 0, then of channel tile 1, ...  Workgroups
     // are dispatched round-robin over the 8 XCDs, each with its own L2, so XCD j takes the
@@ -375,7 +356,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int co = co0 + wave_n * WTN + b * 32 + q * 8 + (lane >> 5) * 4;
-                bias_q[b][q] = (bias && split == 0 && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
+                bias_q[b][q] = (bias && split == 0 && kgrp == 0 && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
                                                                     : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         __syncthreads();
@@ -540,7 +521,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
                     const int sl = cs + t - 1;
-                    xfa[a][t] = (uint32_t)sl * 128u + (uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(sl)) * 16u;
+                    xfa[a][t] = (uint32_t)sl * 128u + (((uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(sl)) * 16u) ^ frag_k0);
                 }
             }
             const int groups = g.kh * cchunks;
@@ -617,15 +598,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                     const unsigned char *ws =
                         stage0 + 2u * XB + (uint32_t)cwb * WB + (wave_n * WTN) * 128 + frag_row;
                     const int nld = t == 0 ? WR + XL : WR;
-                    const int lpk = t == 0 ? (WR + XL + KK - 1) / KK : (WR + KK - 1) / KK;
+                    const int lpk = t == 0 ? (WR + XL + KKG - 1) / KKG : (WR + KKG - 1) / KKG;
                     Frag<DT> wf[FB][CB], xf[FB][PB];
 #pragma unroll
                     for (int b = 0; b < CB; ++b) wf[0][b].load(ws + b * 4096, frag_t16);
 #pragma unroll
                     for (int a = 0; a < PB; ++a) xf[0][a].load(xs, xfa[a][t]);
 #pragma unroll
-                    for (int kk = 0; kk < KK; ++kk) {
-                        if (FB == 2 && kk + 1 < KK) {
+                    for (int kk = 0; kk < KKG; ++kk) {
+                        if (FB == 2 && kk + 1 < KKG) {
                             const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
                             for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
@@ -640,7 +621,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                             for (int b = 0; b < CB; ++b)
                                 acc[a][b] = mfma32<DT>(wf[kk % FB][b], xf[kk % FB][a], acc[a][b]);
-                        if (FB == 1 && kk + 1 < KK) {
+                        if (FB == 1 && kk + 1 < KKG) {
                             __builtin_amdgcn_sched_barrier(0);
                             const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
@@ -713,7 +694,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             FC_ISSUE_LOADS(0, L)
         }
 
-        constexpr int LPK = (L + KK - 1) / KK; // wave loads issued per 16-wide k-step
+        constexpr int LPK = (L + KKG - 1) / KKG; // wave loads issued per k-step of this wave
         int cbuf = 0;                          // buffer of the stage being multiplied
         for (int s = 0; s < nst; ++s) {
             FC_PREPARE_STAGE()          // stage s + NB - 1: addresses only
@@ -727,8 +708,8 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
             for (int a = 0; a < PB; ++a) xf[0][a].load(xs + a * 4096, frag_t16);
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                if (FB == 2 && kk + 1 < KK) {
+            for (int kk = 0; kk < KKG; ++kk) {
+                if (FB == 2 && kk + 1 < KKG) {
                     const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
                     for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
@@ -745,7 +726,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                 for (int a = 0; a < PB; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[kk % FB][b], xf[kk % FB][a], acc[a][b]);
-                if (FB == 1 && kk + 1 < KK) {
+                if (FB == 1 && kk + 1 < KKG) {
                     __builtin_amdgcn_sched_barrier(0);
                     const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
@@ -764,6 +745,40 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         // lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
         wait_vmcnt<0>();
         __syncthreads();
+        if constexpr (KS > 1) {
+            // the wave groups after the first hand over their accumulators (accumulator order:
+            // every lane writes and reads whole 16-byte pieces at consecutive addresses); the
+            // first group adds them in group order
+            float4 *red = reinterpret_cast<float4 *>(smem_raw);
+            if (kgrp > 0) {
+#pragma unroll
+                for (int a = 0; a < PB; ++a)
+#pragma unroll
+                    for (int b = 0; b < CB; ++b)
+#pragma unroll
+                        for (int h = 0; h < 4; ++h)
+                            red[((kgrp - 1) * (PB * CB * 4) + (a * CB + b) * 4 + h) * GT + gtid] = make_float4(
+                                acc[a][b][4 * h], acc[a][b][4 * h + 1], acc[a][b][4 * h + 2], acc[a][b][4 * h + 3]);
+            }
+            __syncthreads();
+            if (kgrp == 0) {
+#pragma unroll
+                for (int q = 1; q < KS; ++q)
+#pragma unroll
+                    for (int a = 0; a < PB; ++a)
+#pragma unroll
+                        for (int b = 0; b < CB; ++b)
+#pragma unroll
+                            for (int h = 0; h < 4; ++h) {
+                                const float4 v = red[((q - 1) * (PB * CB * 4) + (a * CB + b) * 4 + h) * GT + gtid];
+                                acc[a][b][4 * h] += v.x;
+                                acc[a][b][4 * h + 1] += v.y;
+                                acc[a][b][4 * h + 2] += v.z;
+                                acc[a][b][4 * h + 3] += v.w;
+                            }
+            }
+            __syncthreads(); // the epilogue reuses this part of LDS
+        }
         if (S > 1) {
             // Park this unit's fp32 partial tile (accumulator order, coalesced), then count
             // in; the unit that arrives last adds the S partials in split order - a fixed
@@ -776,20 +791,22 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
                 partials, 0, (uint32_t)((size_t)kSplitGrid * kSplitTileFloats * sizeof(float)), 0x00020000);
             const uint32_t mine = (uint32_t)unit * (uint32_t)(TM * TN * 4);
+            if (kgrp == 0) {
 #pragma unroll
-            for (int a = 0; a < PB; ++a)
+                for (int a = 0; a < PB; ++a)
 #pragma unroll
-                for (int b = 0; b < CB; ++b)
+                    for (int b = 0; b < CB; ++b)
 #pragma unroll
-                    for (int h = 0; h < 4; ++h) {
-                        u32x4_t v;
-                        v.x = __float_as_uint(acc[a][b][4 * h]);
-                        v.y = __float_as_uint(acc[a][b][4 * h + 1]);
-                        v.z = __float_as_uint(acc[a][b][4 * h + 2]);
-                        v.w = __float_as_uint(acc[a][b][4 * h + 3]);
-                        __builtin_amdgcn_raw_buffer_store_b128(
-                            v, rp, mine + (uint32_t)(((a * CB + b) * 4 + h) * NT + tid) * 16u, 0, kDeviceScope);
-                    }
+                        for (int h = 0; h < 4; ++h) {
+                            u32x4_t v;
+                            v.x = __float_as_uint(acc[a][b][4 * h]);
+                            v.y = __float_as_uint(acc[a][b][4 * h + 1]);
+                            v.z = __float_as_uint(acc[a][b][4 * h + 2]);
+                            v.w = __float_as_uint(acc[a][b][4 * h + 3]);
+                            __builtin_amdgcn_raw_buffer_store_b128(
+                                v, rp, mine + (uint32_t)(((a * CB + b) * 4 + h) * GT + gtid) * 16u, 0, kDeviceScope);
+                        }
+            }
             wait_vmcnt<0>(); // this thread's partial stores have been acknowledged
             __syncthreads(); // ... and every other thread's
             if (tid == 0)
@@ -806,7 +823,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                 for (int b = 0; b < CB; ++b)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-            for (int sp = 0; sp < S; ++sp) {
+            for (int sp = 0; sp < S && kgrp == 0; ++sp) {
                 const uint32_t theirs = (uint32_t)(tile * S + sp) * (uint32_t)(TM * TN * 4);
 #pragma unroll
                 for (int a = 0; a < PB; ++a)
@@ -815,7 +832,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
                             const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(
-                                rp, theirs + (uint32_t)(((a * CB + b) * 4 + h) * NT + tid) * 16u, 0, kDeviceScope);
+                                rp, theirs + (uint32_t)(((a * CB + b) * 4 + h) * GT + gtid) * 16u, 0, kDeviceScope);
                             acc[a][b][4 * h] += __uint_as_float(v.x);
                             acc[a][b][4 * h + 1] += __uint_as_float(v.y);
                             acc[a][b][4 * h + 2] += __uint_as_float(v.z);
@@ -826,6 +843,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
         constexpr int OP = TN * (int)sizeof(TO) + 16;
         static_assert((size_t)TM * OP <= REGION, "output tile fits");
         unsigned char *Os = smem_raw;
+        if (kgrp == 0) {
 #pragma unroll
         for (int a = 0; a < PB; ++a) {
             const int r = wave_m * WTM + a * 32 + (lane & 31);
@@ -860,6 +878,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                         *reinterpret_cast<uint2 *>(Os + r * OP + cl * 2) = pk;
                     }
                 }
+        }
         }
         __syncthreads();
         constexpr int PPR = TN * (int)sizeof(TO) / 16;
@@ -919,13 +938,14 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 }
 #endif
 
-template <int DT, typename TO, bool CMP, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2>
+template <int DT, typename TO, bool CMP, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2,
+          int KS = 1>
 static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                              const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                              void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW, CMP>;
-    constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW>();
+    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW, CMP, KS>;
+    constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW, KS>();
     // more than 64 KB of dynamic LDS has to be allowed once per function and device; two
     // threads that both find the bit clear both set the attribute, which is harmless
     static std::atomic<uint64_t> attr_devices{0};
@@ -943,7 +963,7 @@ static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_i
     const int64_t cap = 256 * 8;
     int blocks = (int)((max_tiles < cap ? max_tiles : cap) + 7) & ~7; // a multiple of the XCD count
     if (partials) blocks = kSplitGrid; // few tiles: enough workgroups for the K-split to fill the chip
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64), lds, s, g, (const uint16_t *)x, mask_in, mask_out,
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64 * KS), lds, s, g, (const uint16_t *)x, mask_in, mask_out,
                        (const uint16_t *)w, bias, idx, count, (TO *)out, partials, tile_counters);
     return hipGetLastError();
 }
@@ -957,7 +977,7 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
 {
 #ifdef FC_TUNE
     // tuning builds only: pick a tile configuration by number (bf16 in/out, 3x3 only)
-    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 9 && !CMP) {
+    if constexpr (DT == FC_BF16 && TAPC == 9 && !CMP) {
         static const int cfg = getenv("FC_TILE_CONFIG") ? atoi(getenv("FC_TILE_CONFIG")) : 0;
         switch (cfg) {
         case 20: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 4, 1>(FC_ARGS);
@@ -976,6 +996,12 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
         case 44: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
         case 45: return launch_dma<DT, TO, CMP, 256, 128, 4, 2, TAPC, 2, 2, 320, 3>(FC_ARGS);
         case 46: return launch_dma<DT, TO, CMP, 256, 128, 4, 2, TAPC, 2, 2, 320, 2>(FC_ARGS);
+        case 60: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2, 192, 2, 2>(FC_ARGS);
+        case 61: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 3, 2, 0, 2, 2>(FC_ARGS);
+        case 62: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 192, 3, 2>(FC_ARGS);
+        case 63: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 0, 2, 2>(FC_ARGS);
+        case 64: return launch_dma<DT, TO, CMP, 256, 64, 4, 1, TAPC, 2, 2, 320, 3, 2>(FC_ARGS);
+        case 66: return launch_dma<DT, TO, CMP, 256, 128, 4, 1, TAPC, 2, 2, 320, 2, 2>(FC_ARGS);
         default: break;
         }
     }
