@@ -32,10 +32,74 @@ if ROOT not in sys.path:
 METRIC = "focused-conv effective TFLOP/s + speedup vs dense at 48% irrelevant pixels"
 BF16_MFMA_PEAK_TFLOPS = 2500.0
 FP8_MFMA_PEAK_TFLOPS = 5000.0
-# HBM bytes per launch of the conv kernel on the default workload (mean of the four layers),
-# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the counter read for a
-# 256 MiB streaming copy (x2.00 and x1.00): profiles/k_conv_dma_resnet50_3x3_b16_48pct.md
-TRAFFIC_BYTES_PER_LAUNCH = 41.1e6
+# HBM bytes per launch of the conv kernels on the default workload (mean of the four layers)
+# come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, each scaled by what the counter read
+# for a streaming copy of known size.  The summary of those runs is the one tracked place the
+# figure lives in; it also records the hash of the kernel sources it was measured on, and the
+# bench line carries the figure only while that hash is the one of the tree that runs.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "k_conv_resnet50_3x3_b16_48pct.md")
+HBM_PEAK_GBPS = 8000.0
+
+
+def kernel_source_hash():
+    """sha256 (first 16 hex digits) over the library's kernel sources, in name order."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    base = os.path.join(ROOT, "paper_2207_10741_amd", "csrc")
+    for f in sorted(glob.glob(os.path.join(base, "*.hip")) + glob.glob(os.path.join(base, "*.hpp"))):
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic():
+    """(bytes per launch, note): the figure of the tracked profile summary, or None when the summary is
+    missing or was measured on other kernel sources."""
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None, "no counter summary in profiles/"
+    m_t = re.search(r"traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", text)
+    m_h = re.search(r"kernel_source_hash\s*=\s*([0-9a-f]+)", text)
+    if not m_t or not m_h:
+        return None, "counter summary carries no figure"
+    if m_h.group(1) != kernel_source_hash():
+        return None, "counter summary was measured on other kernel sources (%s)" % m_h.group(1)
+    return float(m_t.group(1)), "rocprofv3 FETCH_SIZE + WRITE_SIZE, " + os.path.relpath(TRAFFIC_PROFILE, ROOT)
+
+
+def calibrate_peaks(torch, B, in_dtype):
+    """What this machine delivers: matrix-core rate of a register-only loop of independent matrix
+    instructions on every SIMD, and the rate of a streaming copy far larger than the memory-side
+    cache (bytes read + bytes written).  Best of three launches each, HIP events on the launch stream."""
+    dev = torch.device("cuda:0")
+    sink = torch.zeros((4096 * 256,), dtype=torch.float32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    best_f = 0.0
+    for _ in range(4):
+        a, b = ev(), ev()
+        a.record()
+        flop = B.calibrate_mfma(in_dtype, 2000, 4096, sink)
+        b.record()
+        torch.cuda.synchronize()
+        best_f = max(best_f, flop / (a.elapsed_time(b) * 1e-3))
+    src = torch.ones((128 << 20,), dtype=torch.int32, device=dev)     # 512 MiB
+    dst = torch.empty_like(src)
+    best_b = 0.0
+    for _ in range(4):
+        a, b = ev(), ev()
+        a.record()
+        nbytes = B.calibrate_copy(src, dst)
+        b.record()
+        torch.cuda.synchronize()
+        best_b = max(best_b, 2.0 * nbytes / (a.elapsed_time(b) * 1e-3))
+    del src, dst, sink
+    torch.cuda.empty_cache()
+    return {"mfma_tflops": round(best_f / 1e12, 1), "copy_gbps": round(best_b / 1e9, 1),
+            "how": "register-only loop of 8 independent matrix instructions per wave, 16 waves per CU; "
+                   "streaming copy of 512 MiB (read + written bytes); best of 4 launches each"}
 
 
 def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch, in_dtype=None, out_dtype=None):
@@ -400,6 +464,8 @@ def main():
                          "instead of the bench line")
     ap.add_argument("--grouped", action="store_true",
                     help="time the 3x3 grouped layers of a ResNeXt-50 (focused and dense) instead of the bench line")
+    ap.add_argument("--peaks", action="store_true",
+                    help="only measure this box's matrix-core and streaming-copy rates (the on-box rooflines)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
@@ -417,6 +483,12 @@ def main():
 
     irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
     batch = workloads.SWEEP_BATCH if args.batch is None else args.batch
+    if args.peaks:
+        out = {"peaks": True}
+        for name, code in (("bf16", B.BF16), ("fp8", B.FP8)):
+            out[name] = calibrate_peaks(torch, B, code)
+        print(json.dumps(out))
+        return
     if args.sweep:
         sweep(torch, B, synth, workloads, args, batch)
         return
@@ -491,17 +563,20 @@ def main():
                 c()
         return step
 
+    # A step takes about 0.1 ms, so a short --steps would time a couple of milliseconds: every timed
+    # "step" is `inner` replays of the step's graph (stated in the line), at least 100 replays in all.
+    inner = max(1, -(-100 // max(1, args.steps)))
     timings = {}
     for key in (() if args.roofline_only else ("whole", "call_focused", "call_dense", "call_conv_only")):
         step = step_of(key)
         timings[key + "_eager"] = time_loop(torch, step, args.steps, args.warmup)
         graph = capture(torch, step)
-        timings[key] = time_loop(torch, graph.replay, args.steps, args.warmup)
+        timings[key] = time_loop(torch, graph.replay, args.steps * inner, args.warmup)
     if not args.roofline_only:
         t_focused, t_dense, t_conv_only = (timings[k] for k in ("whole", "call_dense", "call_conv_only"))
-        # spread of the focused step: ten chunks of steps/10 replays each (a second pass)
+        # spread of the focused step: ten chunks of at least 20 replays each (a second pass)
         graph = capture(torch, step_of("whole"))
-        chunk = max(1, args.steps // 10)
+        chunk = max(20, args.steps * inner // 10)
         chunks = sorted(time_loop(torch, graph.replay, chunk, 0) for _ in range(10))
         t_min, t_median = chunks[0], 0.5 * (chunks[4] + chunks[5])
         # the same step with the activations coming from HBM: the four layers' tensors of one
@@ -525,18 +600,19 @@ def main():
         t_cold = time_loop(torch, graph.replay, max(1, args.steps // sets), max(1, args.warmup // sets)) / sets
         del graph, cold_calls
 
-    # ---- dominant kernel: the matrix-core conv kernel, one launch per call, timed
-    # with events on the stream it is launched on ----------------------------------
+    # ---- dominant kernel: the matrix-core conv kernel exactly as the step launches it (kept
+    # list given, zero-fill of the irrelevant rows in the same launch), one launch per call,
+    # timed with events on the stream it is launched on -----------------------------
     per_layer_ms = []
     for L in layers:
-        call = L["call_kernel"]
+        call = L["call_conv_only"]
         for _ in range(args.warmup):
             call()
         # events bracket runs of 10 back-to-back launches of this one kernel, so that the
         # cost of the event records themselves is spread thin
         burst = 10
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-               for _ in range(max(1, args.steps // burst))]
+               for _ in range(max(10, args.steps // burst))]
         for a, b in evs:
             a.record()
             for _ in range(burst):
@@ -544,25 +620,53 @@ def main():
             b.record()
         torch.cuda.synchronize()
         per_layer_ms.append(float(np.mean([a.elapsed_time(b) for a, b in evs])) / burst)
+    if args.roofline_only:
+        # the same launches without the zero-fill of the irrelevant rows (what a chained layer runs)
+        skip_ms = []
+        for L in layers:
+            call = L["call_kernel"]
+            for _ in range(args.warmup):
+                call()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+            for a, b in evs:
+                a.record()
+                for _ in range(10):
+                    call()
+                b.record()
+            torch.cuda.synchronize()
+            skip_ms.append(float(np.mean([a.elapsed_time(b) for a, b in evs])) / 10)
     flops_kept = sum(L["flops_kept"] for L in layers)
     kern_avg_s = sum(per_layer_ms) / 1e3 / len(layers)
     achieved = (flops_kept / len(layers)) / kern_avg_s / 1e12
     default_workload = (args.irrelevant is None and args.mask == "blobs" and args.batch is None and
-                        in_dtype == B.BF16)
+                        in_dtype == B.BF16 and out_dtype == B.BF16)
+    # algorithmic HBM bytes of a launch: input mask (gate and labels) + labels + the kept list once +
+    # every needed input pixel once (for these 3x3 unit-stride layers: the relevant pixels) + weights
+    # and bias once + every output row once (kept rows and zero-filled rows)
+    e_in, e_out = (1 if in_dtype == B.FP8 else 2), (1 if out_dtype == B.FP8 else 2)
+    algo_bytes = sum(2 * L["m"] + 4 * L["kept"] + L["kept"] * L["c"] * e_in + L["k"] * L["c"] * e_in + 4 * L["c"] +
+                     L["m"] * L["c"] * e_out for L in layers) / len(layers)
+    traffic, traffic_note = measured_traffic() if default_workload else (None, "not the workload of the counter summary")
+    peaks = calibrate_peaks(torch, B, in_dtype)
     roofline = {
-        "bound": "mfma", "kernel": "k_conv_dma", "achieved": round(achieved, 3), "peak": peak,
+        "bound": "mfma", "kernel": "k_conv_dma / k_conv_line (one launch per layer, zero-fill included)",
+        "achieved": round(achieved, 3), "peak": peak,
         "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-        "traffic": TRAFFIC_BYTES_PER_LAUNCH if default_workload else None,
+        "traffic": traffic, "traffic_source": traffic_note,
+        "algorithmic_bytes_per_launch": round(algo_bytes),
+        "traffic_over_algorithmic": None if traffic is None else round(traffic / algo_bytes, 3),
         "avg_launch_us": round(kern_avg_s * 1e6, 3),
         "flops_per_launch": round(flops_kept / len(layers)),
+        "measured_peak": peaks["mfma_tflops"], "frac_of_measured_peak": round(achieved / peaks["mfma_tflops"], 4),
+        "measured_copy_gbps": peaks["copy_gbps"], "peaks_how": peaks["how"],
     }
     if args.roofline_only:
         print(json.dumps({"roofline": roofline,
-                          "per_layer_conv_kernel_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, per_layer_ms)}}))
+                          "per_layer_conv_kernel_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, per_layer_ms)},
+                          "per_layer_without_zero_fill_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, skip_ms)}}))
         return
 
     value = flops_kept / t_focused / 1e12
-    images = batch * len(layers)
     result = {
         "metric": METRIC,
         "value": round(value, 3),
@@ -586,6 +690,7 @@ def main():
             "kept_fraction": round(sum(L["kept"] for L in layers) / sum(L["m"] for L in layers), 4),
         },
         "launch": "one HIP graph replay per step",
+        "replays_per_timed_step": inner, "timed_replays": args.steps * inner,
         "ms_per_step_min": round(t_min * 1e3, 4), "ms_per_step_median": round(t_median * 1e3, 4),
         "cold_ms_per_step": round(t_cold * 1e3, 4),
         "eager_ms_per_step": round(timings["whole_eager"] * 1e3, 4),
@@ -595,7 +700,7 @@ def main():
         "dense_tflops": round(sum(L["flops_dense"] for L in layers) / t_dense / 1e12, 3),
         "conv_only_ms_per_step": round(t_conv_only * 1e3, 4),
         "conv_only_tflops": round(flops_kept / t_conv_only / 1e12, 3),
-        "ms_per_image": round(t_focused * 1e3 / images, 6),
+        "ms_per_image": round(t_focused * 1e3 / batch, 6),
         "per_layer_conv_kernel_ms": {L["name"]: round(ms, 5) for L, ms in zip(layers, per_layer_ms)},
         "roofline": roofline,
     }

@@ -29,18 +29,25 @@
  *
  * Conventions for every entry point:
  *   - pointers marked "device" are HIP device memory owned by the caller; the
- *     library allocates nothing, frees nothing and keeps no state between calls.
+ *     library allocates nothing and frees nothing.  What it keeps between calls is
+ *     host-side only and per device: which kernel variants have had their dynamic
+ *     LDS limit raised, the CU count, and the address of the device array of
+ *     fc_focused_conv2d_noalloc.  No result depends on it.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     All device work is enqueued on it; no call waits for the device and no
  *     call reads results back to the host.
  *   - the return value is an fc_status.  Argument errors are found on the host
- *     before anything is launched and leave every output untouched.
+ *     before anything is launched and leave every output untouched.  FC_ERR_HIP
+ *     means the HIP runtime refused a launch: launches enqueued before it stay
+ *     enqueued, so the workspace (and, for calls that build their own kept list,
+ *     nothing else) may have been written; `out` is written by the last launch
+ *     of a call only.
  *   - device base pointers must be 16-byte aligned.
  *   - every call enqueues kernel launches only (no memsets, no copies, no
  *     allocation), so calls can be recorded into a HIP graph.  The first call
- *     that uses a given kernel variant also raises that kernel's dynamic LDS
- *     limit, once per process and on the host: run a call once eagerly before
- *     capturing it.
+ *     on a device that uses a given kernel variant also raises that kernel's
+ *     dynamic LDS limit (a host-side attribute call, once per variant and
+ *     device): run a call once eagerly before capturing it.
  */
 #ifndef FOCUSED_CONV_H
 #define FOCUSED_CONV_H
@@ -133,8 +140,8 @@ int32_t fc_mask_downsample(const uint8_t *mask_in, int32_t n, int32_t h, int32_t
                            int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w,
                            uint8_t *mask_out, void *stream);
 
-/* Patch labels by another rule.  Sec. III-A speaks of "a patch labelled irrelevant"
- * without saying how a per-pixel mask labels a patch; this library's reading is the
+/* Patch labels by another rule.  Sec. III-A drops the patches that carry an irrelevant
+ * label without saying how a per-pixel mask labels a whole patch; this library's reading is the
  * centre tap (fc_mask_downsample, and what fc_focused_conv2d derives by itself).  The
  * other two readings are offered here: FC_RULE_ANY keeps a patch if any pixel of its
  * window is relevant (conservative: a margin of context around the relevant region),
@@ -209,10 +216,13 @@ int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
  *   bias      device, c_out floats, or NULL
  *   mask_out  device [n][ho][wo] 0/1 bytes as fc_mask_downsample (or
  *             fc_mask_downsample_rule) writes them for this layer's geometry, or
- *             NULL (then derived from mask_in by the centre tap)
+ *             NULL (then derived from mask_in by the centre tap).  Given without
+ *             idx/count, the call compacts these labels itself (into the
+ *             workspace): the rows computed and the rows cleared follow them
  *   idx,count device, as fc_active_index_compact writes them from mask_out; both
  *             NULL = computed here into the workspace
- *   out       device, NHWC, out_dtype; must not overlap x
+ *   out       device, NHWC, out_dtype; its bytes must not overlap those of x
+ *             (FC_ERR_NULL)
  *   workspace device, >= fc_workspace_bytes(desc) when idx is NULL and mask_in is
  *             not; otherwise optional: when given (any call, also the dense
  *             layer), layers with few tiles split their reduction over more
@@ -293,6 +303,19 @@ int32_t fc_expand_group_weights(int32_t c_in, int32_t c_out, int32_t kh, int32_t
  * kept-position list and no workspace; one kernel launch on `stream`. */
 int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8_t *mask_in,
                             const void *w, const float *bias, void *out, void *stream);
+
+/* Calibration of the two rooflines the layers are priced against (measurement support, not
+ * part of the paper's method; Sec. III-A's operation count is what `flop` counts for a layer).
+ * fc_calibrate_mfma enqueues one launch in which `blocks` workgroups of four waves each run
+ * `iters` rounds of eight independent matrix instructions of the storage type `dtype`
+ * (FC_BF16, FC_F16 or FC_FP8) on register operands, and writes the FLOP of the launch to
+ * *flop (host); `sink` is a device buffer of at least blocks * 256 floats that is never
+ * written in practice.  fc_calibrate_copy enqueues one streaming copy of `bytes` bytes (a
+ * multiple of 16; both buffers device, 16-byte aligned, not overlapping).  The caller times the
+ * launches with events on `stream`. */
+int32_t fc_calibrate_mfma(int32_t dtype, int32_t iters, int32_t blocks, void *sink, double *flop,
+                          void *stream);
+int32_t fc_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /* Helper for conv stacks with pooling between layers (not part of the paper's
  * method): NHWC max-pool over the full tensor, window k, stride s, padding p

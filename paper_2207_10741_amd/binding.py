@@ -23,7 +23,7 @@ FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compac
              "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact",
              "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_gconv2d",
-             "fc_noalloc_init", "fc_focused_conv2d_noalloc",
+             "fc_noalloc_init", "fc_focused_conv2d_noalloc", "fc_calibrate_mfma", "fc_calibrate_copy",
              "fc_expand_group_weights",
              "fc_focused_dwconv2d",
              "fc_maxpool2d", "fc_maxpool2d_masked")
@@ -104,6 +104,10 @@ def lib():
         L.fc_noalloc_init.argtypes = []
         L.fc_focused_conv2d_noalloc.restype = i32
         L.fc_focused_conv2d_noalloc.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 6
+        L.fc_calibrate_mfma.restype = i32
+        L.fc_calibrate_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.fc_calibrate_copy.restype = i32
+        L.fc_calibrate_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.fc_focused_gconv2d.restype = i32
         L.fc_focused_gconv2d.argtypes = [ctypes.POINTER(ConvDesc), i32] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_expand_group_weights.restype = i32
@@ -411,6 +415,23 @@ class PreparedDwConv:
         if rc != 0:
             raise FcError(rc, "fc_focused_dwconv2d")
         return self.out
+
+
+def calibrate_mfma(dtype: int, iters: int, blocks: int, sink, stream=None) -> float:
+    """fc_calibrate_mfma: enqueues the register-only matrix-instruction loop; returns the FLOP of the launch."""
+    _require_cuda(sink)
+    flop = ctypes.c_double()
+    _check(lib().fc_calibrate_mfma(dtype, iters, blocks, _ptr(sink), ctypes.byref(flop), _stream(stream)),
+           "fc_calibrate_mfma")
+    return flop.value
+
+
+def calibrate_copy(src, dst, stream=None) -> int:
+    """fc_calibrate_copy: enqueues one streaming copy src -> dst; returns the bytes copied (each way)."""
+    _require_cuda(src, dst)
+    nbytes = src.numel() * src.element_size()
+    _check(lib().fc_calibrate_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "fc_calibrate_copy")
+    return nbytes
 
 
 def ready_workspace(workspace):

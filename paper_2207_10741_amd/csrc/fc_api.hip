@@ -9,6 +9,23 @@ namespace {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+size_t dtype_bytes(int32_t dt) { return dt == FC_F32 ? 4 : (dt == FC_FP8 ? 1 : 2); }
+
+// [x, x + x_bytes) and [out, out + out_bytes) share a byte?
+bool ranges_overlap(const void *x, size_t x_bytes, const void *out, size_t out_bytes)
+{
+    const uintptr_t a = reinterpret_cast<uintptr_t>(x), b = reinterpret_cast<uintptr_t>(out);
+    return a < b + out_bytes && b < a + x_bytes;
+}
+
+// input and output tensor of a layer (rows in list order count as full tensors: capacity)
+bool conv_tensors_overlap(const Geom &g, const fc_conv_desc *d, const void *x, const void *out)
+{
+    const size_t xb = (size_t)g.n * g.h * g.w * g.c_in * dtype_bytes(d->in_dtype);
+    const size_t ob = (size_t)g.m * g.c_out * dtype_bytes(d->out_dtype);
+    return ranges_overlap(x, xb, out, ob);
+}
+
 int32_t out_dim(int32_t in, int32_t k, int32_t s, int32_t p, int32_t d)
 {
     const int64_t span = (int64_t)in + 2 * (int64_t)p - (int64_t)d * (k - 1) - 1;
@@ -243,7 +260,7 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
     if (!mask_in && (idx || mask_out)) return FC_ERR_NULL; // a kept list without the mask that gates the taps
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(idx) || !aligned16(bias)) return FC_ERR_ALIGN;
-    if (x == out) return FC_ERR_NULL;
+    if (conv_tensors_overlap(g, desc, x, out)) return FC_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
 
     const bool mfma = conv_mfma_supported(g, desc->in_dtype, desc->out_dtype);
@@ -280,8 +297,10 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
         uint8_t *m_out = ws + l.mask_out;
         const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
         // a small layer on the matrix-core path ranks its kept positions inside the convolution
-        // kernel (16 positions per thread): no compaction launch
-        const bool rank_in_kernel = mfma && g.m <= kInlineRankPositions;
+        // kernel (16 positions per thread, labels from the centre tap): no compaction launch.
+        // Labels the caller brings (mask_out without a list) are compacted as they are, so that
+        // the rows computed and the rows cleared follow the same labels.
+        const bool rank_in_kernel = mfma && g.m <= kInlineRankPositions && !mask_out;
         if (!rank_in_kernel) {
             CompactExtras ex;
             if (tile_counters) {
@@ -289,10 +308,20 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
                 ex.zero_n = kSplitGrid;
                 counters_cleared = true;
             }
-            const hipError_t ec = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx),
-                                                 (int32_t *)(ws + l.count), (int32_t *)(ws + l.scan), ex, s);
+            hipError_t ec;
+            if (mask_out) {
+                // a flat mask is a 1 x 1 x m image seen through a 1x1 stride-1 window
+                MaskGeom fg = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
+                fg.w = fg.wo = g.m;
+                fg.m = g.m;
+                ec = launch_compact(fg, mask_out, nullptr, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                                    (int32_t *)(ws + l.scan), ex, s);
+            } else {
+                ec = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                                    (int32_t *)(ws + l.scan), ex, s);
+                mask_out = m_out;
+            }
             if (ec != hipSuccess) return FC_ERR_HIP;
-            mask_out = m_out;
             idx = (const int32_t *)(ws + l.idx);
             count = (const int32_t *)(ws + l.count);
         }
@@ -346,7 +375,7 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
     if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
     if (!mask_in && (idx || mask_out)) return FC_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(idx) || !aligned16(bias)) return FC_ERR_ALIGN;
-    if (x == out) return FC_ERR_NULL;
+    if (conv_tensors_overlap(g, desc, x, out)) return FC_ERR_NULL;
     hipStream_t s = (hipStream_t)stream;
     if (mask_in && !idx) {
         const ConvWorkspace l = conv_ws_layout(g);
@@ -354,10 +383,19 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
         if (!aligned16(workspace)) return FC_ERR_ALIGN;
         uint8_t *ws = (uint8_t *)workspace;
         const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
-        const hipError_t ec = launch_compact(mg, mask_in, ws + l.mask_out, (int32_t *)(ws + l.idx),
-                                             (int32_t *)(ws + l.count), (int32_t *)(ws + l.scan), CompactExtras(), s);
+        hipError_t ec;
+        if (mask_out) { // the caller's labels, compacted as they are
+            MaskGeom fg = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
+            fg.w = fg.wo = g.m;
+            fg.m = g.m;
+            ec = launch_compact(fg, mask_out, nullptr, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                                (int32_t *)(ws + l.scan), CompactExtras(), s);
+        } else {
+            ec = launch_compact(mg, mask_in, ws + l.mask_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                                (int32_t *)(ws + l.scan), CompactExtras(), s);
+            mask_out = ws + l.mask_out;
+        }
         if (ec != hipSuccess) return FC_ERR_HIP;
-        mask_out = ws + l.mask_out;
         idx = (const int32_t *)(ws + l.idx);
         count = (const int32_t *)(ws + l.count);
     }
@@ -398,7 +436,7 @@ int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8
     if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN)) return FC_ERR_DTYPE; // full layers only
     if (!x || !w || !out) return FC_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(bias)) return FC_ERR_ALIGN;
-    if (x == out) return FC_ERR_NULL;
+    if (conv_tensors_overlap(g, desc, x, out)) return FC_ERR_NULL;
     if (desc->in_dtype == FC_FP8 || desc->out_dtype == FC_FP8) return FC_ERR_DTYPE; // no 8-bit depthwise layer
     if (!conv_depthwise_supported(g, desc->in_dtype)) return FC_ERR_RANGE;
     const hipError_t e = launch_conv_depthwise(g, desc->in_dtype, desc->out_dtype, x, mask_in, w, bias, out,
@@ -543,6 +581,26 @@ int32_t fc_focused_conv2d_noalloc(const fc_conv_desc *desc, const void *x, const
     d.flags &= ~(uint32_t)FC_WORKSPACE_READY;
     return fc_focused_conv2d(&d, x, mask_in, w, bias, nullptr, nullptr, nullptr, out, scratch,
                              (size_t)FC_NOALLOC_SCRATCH_BYTES, stream);
+}
+
+int32_t fc_calibrate_mfma(int32_t dtype, int32_t iters, int32_t blocks, void *sink, double *flop, void *stream)
+{
+    if (!sink || !flop) return FC_ERR_NULL;
+    if (dtype != FC_BF16 && dtype != FC_F16 && dtype != FC_FP8) return FC_ERR_DTYPE;
+    if (iters <= 0 || blocks <= 0 || blocks > (1 << 20)) return FC_ERR_SHAPE;
+    // 8 instructions a round, 2 * 32 * 32 * K multiply-adds each (K = 16, or 64 for 8-bit operands), 4 waves
+    *flop = (double)blocks * 4.0 * (double)iters * 8.0 * 2.0 * 32.0 * 32.0 * (dtype == FC_FP8 ? 64.0 : 16.0);
+    return launch_calibrate_mfma(dtype, iters, blocks, (float *)sink, (hipStream_t)stream) == hipSuccess ? FC_OK
+                                                                                                            : FC_ERR_HIP;
+}
+
+int32_t fc_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    if (!src || !dst) return FC_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return FC_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return FC_ERR_ALIGN;
+    if (ranges_overlap(src, bytes, dst, bytes)) return FC_ERR_NULL;
+    return launch_calibrate_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 
 int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,

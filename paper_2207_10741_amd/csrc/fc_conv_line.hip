@@ -177,9 +177,10 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
     const int xgp = slot ^ FC_SWZ(prow); // 16-byte piece this lane fetches for its LDS slot (rows 64 apart share it)
 
     // ---- zero-fill of the irrelevant output rows: every wave takes 64 positions at a time.
-    // The labels of a wave's first 64 positions are asked for now and their rows are cleared
-    // once the first tile's list entries have been asked for, so that this round trip runs
-    // beside the set-up's; what is left (large layers) is cleared after the tiles. ----
+    // The labels of a wave's first 64 positions are asked for now, so that this round trip runs
+    // beside the set-up's; the rows are cleared after the tiles, when nothing waits on the
+    // memory counter any more (loads and stores share it: a store issued earlier would make the
+    // next wait for gathered data wait for its acknowledgement as well). ----
     const bool zero_fill = mask_in && !(g.flags & FC_SKIP_ZERO_FILL);
     const int zf_workers = (int)gridDim.x * kLineWaves;
     const int zf_first = ((int)blockIdx.x * kLineWaves + wave) * 64;
@@ -196,11 +197,11 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
         const int iw = min(max(ow * g.sw + cw0, 0), g.w - 1);
         return mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
     };
-    auto clear_rows = [&](int pp, bool kept, int32_t *dropped) {
+    auto clear_rows = [&](int pp, uint64_t drop, int32_t *dropped) {
         const int cpr = g.c_out * (int)sizeof(TO) / 16; // 16-byte pieces per row
         u32x4_t *o4 = reinterpret_cast<u32x4_t *>(out);
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-        const uint64_t drop = __ballot(!kept);
+        const bool kept = !((drop >> lane) & 1ull);
         const int nd = __popcll(drop);
         if (!kept) dropped[__popcll(drop & ((1ull << lane) - 1ull))] = pp; // in position order
         // (same wave wrote and reads the list: program order suffices)
@@ -211,8 +212,10 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
         }
     };
     bool zf_kept = true;
-    bool zf_pending = zero_fill && zf_first < g.m;
+    const bool zf_pending = zero_fill && zf_first < g.m;
     if (zf_pending) zf_kept = label_of(zf_first + lane);
+    uint64_t zf_drop = 0; // (taken from the labels once the first tile's list entries are on their way)
+    bool zf_have = false;
 
     int resident_nt = -1; // channel tile whose weights sit in LDS (WRES)
 
@@ -338,11 +341,9 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                 sa_prev[i] = (live && r > 0) ? (idx ? idx[m - 1] : m - 1) : -2;
                 sa_next[i] = (live && m + 1 < mm1) ? (idx ? idx[m + 1] : m + 1) : -2;
             }
-            if (zf_pending) {
-                // (the per-wave list sits in the front of LDS, which no gather has been sent to yet:
-                // the slabs asked for so far go to the weight ring behind the line buffers)
-                clear_rows(zf_first + lane, zf_kept, reinterpret_cast<int32_t *>(smem_raw) + wave * 64);
-                zf_pending = false;
+            if (zf_pending && !zf_have) {
+                zf_drop = __ballot(!zf_kept);
+                zf_have = true;
             }
             FC_STAMP(3);
             int sa_ow[RIT], sa_ih0[RIT], sa_iw0[RIT], sa_b[RIT], cnt[RIT], lead[RIT];
@@ -792,9 +793,9 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
     if (zero_fill) {
         __syncthreads(); // the last tile is done with the front of LDS
         int32_t *dropped = reinterpret_cast<int32_t *>(smem_raw) + wave * 64;
-        if (zf_pending) clear_rows(zf_first + lane, zf_kept, dropped); // (a workgroup that had no tile)
+        if (zf_pending) clear_rows(zf_first + lane, zf_have ? zf_drop : __ballot(!zf_kept), dropped);
         for (int p0 = zf_first + zf_workers * 64; p0 < g.m; p0 += zf_workers * 64)
-            clear_rows(p0 + lane, label_of(p0 + lane), dropped);
+            clear_rows(p0 + lane, __ballot(!label_of(p0 + lane)), dropped);
     }
 #ifdef FC_STAMPS
     wait_vmcnt<0>();

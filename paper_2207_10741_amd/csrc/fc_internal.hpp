@@ -252,6 +252,11 @@ hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const vo
                             const float *bias, const int32_t *idx, const int32_t *count, void *out,
                             float *partials, int32_t *tile_counters, hipStream_t s);
 
+// Calibration launches (see fc_calibrate.hip): `blocks` workgroups of four waves each run
+// `iters` rounds of eight matrix instructions; a streaming copy of `bytes` bytes.
+hipError_t launch_calibrate_mfma(int dtype, int iters, int blocks, float *sink, hipStream_t s);
+hipError_t launch_calibrate_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
+
 // One-workgroup-per-CU matrix-core path for 3x3 layers (see fc_conv_line.hip).  variant 1:
 // 128 output channels per tile, weights streamed; variant 2: up to 64 output channels, the
 // weight tensor resident in LDS.  Needs the kept list (or no mask at all).

@@ -72,6 +72,39 @@ def test_layer_with_window_rule_labels_matches_oracle(layer, rule):
     assert not out.cpu().numpy()[~keep].view(np.uint32).any()
 
 
+@pytest.mark.parametrize("rule", [B.RULE_ANY, B.RULE_ALL])
+@pytest.mark.parametrize("layer", [(1, 40, 56, 64, 128, 3, 1, 1, 1),      # 2240 positions: a layer that could rank its own rows
+                                   (4, 40, 56, 64, 128, 3, 1, 1, 1),      # 8960 positions
+                                   (2, 30, 41, 24, 40, 3, 1, 1, 1)])      # off the matrix-core tile sizes
+def test_layer_with_labels_but_no_list_follows_the_labels(layer, rule):
+    """Labels handed over without a kept list: the call compacts exactly these labels, so the rows it
+    computes and the rows it clears agree with them (not with the centre tap of the input mask)."""
+    torch = G.torch_mod()
+    n, h, w, ci, co, k, s, p, d = layer
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 114, 1)
+    wt = synth.he_weights(co, k, k, ci, dtype, 114, 2)
+    bias = synth.bias(co, 114, 3)
+    mask = synth.mask_objects(n, h, w, 0.48, 114, 4)
+    md = G.mask_dev(mask)
+    labels = B.mask_downsample_rule(md, (k, k), (s, s), (p, p), (d, d), rule)
+    desc = B.conv_desc(n, h, w, ci, co, (k, k), (s, s), (p, p), (d, d), dtype, B.F32, B.RELU)
+    ho, wo = B.out_dims(desc)
+    out = torch.full((n, ho, wo, co), 7.0, dtype=torch.float32, device=G.dev())
+    ws = torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=G.dev())
+    B.focused_conv2d(desc, G.to_dev(x, dtype), G.to_dev(wt, dtype), torch.from_numpy(bias).to(G.dev()), mask_in=md,
+                     mask_out=labels, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    want_labels = O.mask_downsample_rule(mask, k, k, (s, s), (p, p), (d, d), rule)
+    centre = O.mask_downsample(mask, k, k, (s, s), (p, p), (d, d))
+    assert (want_labels != centre).any()                       # the two labellings really differ here
+    want = O.focused_conv2d_labelled(O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=True), x, wt,
+                                     want_labels, bias=bias, mask_in=mask, dtype=dtype)
+    keep = want_labels != 0
+    assert G.rel_err(G.to_f64(out), want, keep) <= TOL_F32_OUT
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()
+
+
 @pytest.mark.parametrize("margin", [1, 2, 4])
 def test_context_margin_is_the_any_rule_with_a_wider_window(margin):
     """A mask grown by a margin of context pixels (every pixel within `margin` of a relevant

@@ -115,6 +115,13 @@ def test_null_pointers_rejected_before_any_launch():
     assert conv(a, a, a, None, None, None, None, o, None, 0, None) == -5      # needs a workspace
     assert conv(a, a, a, None, None, None, None, o, a, 16, None) == -5        # workspace too small
     assert conv(a, None, a, None, None, None, None, a, None, 0, None) == -1   # out aliases x
+    part = ctypes.c_void_p(0x1000 + 16 * 8)                                    # out starts inside x
+    assert conv(a, None, a, None, None, None, None, part, None, 0, None) == -1
+    before = ctypes.c_void_p(0x1000 - 16)                                      # out ends inside x
+    assert conv(a, None, a, None, None, None, None, before, None, 0, None) == -1
+    assert L.fc_focused_conv2d_noalloc(None, a, None, a, None, o, None) == -1
+    big = B.conv_desc(4, 2048, 1100, 8, 8, (1, 1), (1, 1), (0, 0), (1, 1), B.BF16, B.BF16)
+    assert L.fc_focused_conv2d_noalloc(ctypes.byref(big), a, a, a, None, o, None) == -6   # beyond the static scratch
     # 8-bit layers: only what the matrix-core path takes (16 | c_in, 8 | c_out, at most 32 taps)
     fp8 = lambda ci, co, k=(3, 3): L.fc_focused_conv2d(
         ctypes.byref(B.conv_desc(1, 8, 8, ci, co, k, pad=(k[0] // 2, k[1] // 2), in_dtype=B.FP8, out_dtype=B.F32)),
@@ -135,7 +142,8 @@ def test_null_pointers_rejected_before_any_launch():
     assert dw(d, a, None, a, odd, o, None) == -4
     assert dw(d, a, None, a, None, a, None) == -1                             # out aliases x
     assert dw(B.conv_desc(1, 8, 8, 8, 16), a, None, a, None, o, None) == -2   # not one filter per channel
-    assert dw(B.conv_desc(1, 40000, 40000, 8, 8, in_dtype=B.BF16), a, None, a, None, o, None) == -6
+    far = ctypes.c_void_p(1 << 45)                                            # (beyond the 25 GB such an x would span)
+    assert dw(B.conv_desc(1, 40000, 40000, 8, 8, in_dtype=B.BF16), a, None, a, None, far, None) == -6
     assert L.fc_maxpool2d(a, 1, 8, 8, 8, 0, 2, 2, 2, a, None) == -2
     assert L.fc_maxpool2d_masked(a, 1, 8, 8, 8, 0, 2, 2, 2, a, a, None) == -2
     assert L.fc_maxpool2d_masked(None, 1, 8, 8, 8, 0, 2, 2, 0, a, a, None) == -1
