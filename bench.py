@@ -436,6 +436,71 @@ def grouped_bench(torch, B, synth, workloads, args):
         "dense_TFLOPs": round(fl_d / t_d / 1e12, 2)}))
 
 
+def masks_bench(torch, B, synth, workloads, args):
+    """Mask propagation + ordered compaction at the mask sizes of the workloads, with byte masks and
+    with packed masks (one bit per pixel): the mask pyramid (every level's mask and kept list from the
+    one input mask, two launches) and the single-level compaction of the first level.  Each figure is
+    a HIP-graph replay of four calls; GB/s = algorithmic bytes / time, where the algorithmic bytes are
+    the input mask once, every level's mask written once and read once (the list pass), and four
+    bytes per kept position."""
+    dev = torch.device("cuda:0")
+    s1, s2, pool = ((3, 3), (1, 1), (1, 1), (1, 1)), ((3, 3), (2, 2), (1, 1), (1, 1)), ((2, 2), (2, 2), (0, 0), (1, 1))
+    cases = [
+        ("bench workload: 16 x 128 x 128, four resolutions", 16, 128, 128, [s1, s2, s2, s2], "objects", 0.48),
+        ("ResNet-50 bottlenecks: 32 x 120 x 160, four resolutions", 32, 120, 160, [s1, s2, s2, s2], "objects", 0.5),
+        ("VGG-16 on HD frames: 8 x 1080 x 1920, five resolutions", 8, 1080, 1920, [s1, pool, pool, pool, pool], "ramp", 0.5),
+    ]
+
+    def timed(call):
+        def fn():
+            for _ in range(4):
+                call()
+        return time_loop(torch, capture(torch, fn).replay, args.steps, args.warmup) / 4
+
+    rows = []
+    for what, n, h, w, steps, kind, irr in cases:
+        mask = synth.mask_depth_ramp(n, h, w, irr, 7, 0, 4) if kind == "ramp" else synth.mask_objects(n, h, w, irr, 7, 0, 4)
+        md = torch.from_numpy(mask).to(dev)
+        bits = B.mask_pack(md)
+        m0 = mask.size
+        pyr_b = B.PreparedPyramid(md, steps)
+        pyr_p = B.PreparedPyramid(md, steps, packed=True)
+        pyr_pp = B.PreparedPyramid(bits, steps, packed=True, packed_in=True, shape=(n, h, w))
+        levels = pyr_b()
+        torch.cuda.synchronize()
+        sizes = [lv[0].numel() for lv in levels]
+        kept = [int(lv[2].item()) for lv in levels]
+        for a_, b_ in zip(pyr_p(), levels):       # same lists either way
+            assert torch.equal(a_[1][:int(b_[2].item())], b_[1][:int(b_[2].item())])
+        lists = 4 * sum(kept)
+        bytes_b = m0 + 2 * sum(sizes) + lists
+        bytes_p = m0 + 2 * sum(sizes) / 8 + lists
+        bytes_pp = m0 / 8 + 2 * sum(sizes) / 8 + lists
+        t_b, t_p, t_pp = timed(pyr_b), timed(pyr_p), timed(pyr_pp)
+        # single-level compaction of the first level (labels given), bytes and bits
+        idx = torch.empty((sizes[0],), dtype=torch.int32, device=dev)
+        cnt = torch.empty((1,), dtype=torch.int32, device=dev)
+        ws = torch.empty((B.compact_workspace_bytes(sizes[0]),), dtype=torch.uint8, device=dev)
+        lab_b, lab_p = levels[0][0], pyr_p.levels[0][0]
+        t_cb = timed(lambda: B.active_index_compact(lab_b, idx, cnt, ws))
+        t_cp = timed(lambda: B.active_index_compact_packed(lab_p, sizes[0], idx, cnt, ws))
+        t_pack = timed(lambda: B.mask_pack(md, bits))
+        c_b, c_p = sizes[0] + 4 * kept[0], sizes[0] / 8 + 4 * kept[0]
+        gb = lambda nbytes, t: round(nbytes / t / 1e9, 1)
+        rows.append({
+            "masks": what, "positions_per_level": sizes, "kept_share": round(kept[0] / sizes[0], 3),
+            "pyramid_byte_masks": {"us": round(t_b * 1e6, 2), "algorithmic_MB": round(bytes_b / 1e6, 3), "GBps": gb(bytes_b, t_b)},
+            "pyramid_bytes_in_bits_out": {"us": round(t_p * 1e6, 2), "algorithmic_MB": round(bytes_p / 1e6, 3), "GBps": gb(bytes_p, t_p)},
+            "pyramid_bits_in_bits_out": {"us": round(t_pp * 1e6, 2), "algorithmic_MB": round(bytes_pp / 1e6, 3), "GBps": gb(bytes_pp, t_pp)},
+            "compaction_level0_bytes": {"us": round(t_cb * 1e6, 2), "algorithmic_MB": round(c_b / 1e6, 3), "GBps": gb(c_b, t_cb)},
+            "compaction_level0_bits": {"us": round(t_cp * 1e6, 2), "algorithmic_MB": round(c_p / 1e6, 3), "GBps": gb(c_p, t_cp)},
+            "pack": {"us": round(t_pack * 1e6, 2), "GBps": gb(m0 * 9 / 8, t_pack)},
+        })
+        del pyr_b, pyr_p, pyr_pp, levels
+    print(json.dumps({"masks_bench": True, "launch": "HIP graph replay of four calls", "steps": args.steps,
+                      "hbm_peak_GBps": HBM_PEAK_GBPS, "cases": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -464,6 +529,8 @@ def main():
                          "instead of the bench line")
     ap.add_argument("--grouped", action="store_true",
                     help="time the 3x3 grouped layers of a ResNeXt-50 (focused and dense) instead of the bench line")
+    ap.add_argument("--masks", action="store_true",
+                    help="time mask propagation + compaction (byte masks and packed masks) at the workloads' mask sizes")
     ap.add_argument("--peaks", action="store_true",
                     help="only measure this box's matrix-core and streaming-copy rates (the on-box rooflines)")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -488,6 +555,9 @@ def main():
         for name, code in (("bf16", B.BF16), ("fp8", B.FP8)):
             out[name] = calibrate_peaks(torch, B, code)
         print(json.dumps(out))
+        return
+    if args.masks:
+        masks_bench(torch, B, synth, workloads, args)
         return
     if args.sweep:
         sweep(torch, B, synth, workloads, args, batch)

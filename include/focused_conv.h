@@ -90,8 +90,12 @@ enum {
        else FC_ERR_DTYPE): rows stored in list order, row j = list entry j, nothing for the
        irrelevant positions.  Layers that see the same list can hand each other such tensors. */
     FC_COMPACT_OUT = 8u,     /* out is [count][c_out] (capacity n*ho*wo rows); no zero-fill */
-    FC_COMPACT_IN = 16u      /* x is [count][c_in]; 1x1 kernels with unit stride and no padding only
+    FC_COMPACT_IN = 16u,     /* x is [count][c_in]; 1x1 kernels with unit stride and no padding only
                                (else FC_ERR_SHAPE): row j of x is the pixel list entry j reads */
+    /* Packed masks: mask_in and mask_out of this call are one BIT per pixel instead of one byte
+       (see fc_mask_pack for the layout).  fc_focused_conv2d and fc_focused_gconv2d only; layers
+       with at most 4 input channels and depthwise layers take byte masks (FC_ERR_DTYPE). */
+    FC_PACKED_MASKS = 32u
 };
 
 /* The arrival counters of FC_WORKSPACE_READY live in this many leading bytes of the workspace. */
@@ -157,6 +161,26 @@ int32_t fc_mask_downsample_rule(const uint8_t *mask_in, int32_t n, int32_t h, in
                                 int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w,
                                 int32_t rule, uint8_t *mask_out, void *stream);
 
+/* Packed masks (Sec. III-B's per-layer mask at an eighth of the bytes): one bit per pixel,
+ * pixel p of the flat [n][h][w] order is bit p % 64 of the 64-bit word p / 64 (what a 64-lane
+ * ballot over 64 consecutive pixels gives; little-endian, so also bit p % 8 of byte p / 8); the
+ * bits of the last word past the last pixel are zero.  A packed mask of m pixels occupies
+ * fc_packed_mask_bytes(m) = 8 * ceil(m / 64) bytes and must be 16-byte aligned.
+ *   fc_mask_pack               bytes -> bits (a nonzero byte is a 1)
+ *   fc_mask_downsample_packed  fc_mask_downsample from bits to bits
+ *   fc_active_index_compact_packed  fc_active_index_compact from bits (same list, bit for bit)
+ *   fc_mask_pyramid_packed     fc_mask_pyramid with the levels' masks written as bits; the input
+ *                              mask is bytes (mask_in_packed = 0) or bits (1)
+ * and fc_focused_conv2d takes them with FC_PACKED_MASKS.  Arguments otherwise as the byte forms. */
+size_t fc_packed_mask_bytes(int64_t m);
+int32_t fc_mask_pack(const uint8_t *mask, int64_t m, uint64_t *bits, void *stream);
+int32_t fc_mask_downsample_packed(const uint64_t *bits_in, int32_t n, int32_t h, int32_t w,
+                                  int32_t kh, int32_t kw, int32_t stride_h, int32_t stride_w,
+                                  int32_t pad_h, int32_t pad_w, int32_t dil_h, int32_t dil_w,
+                                  uint64_t *bits_out, void *stream);
+int32_t fc_active_index_compact_packed(const uint64_t *bits, int64_t m, int32_t *idx, int32_t *count,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Which patches become columns (Sec. III-A: an irrelevant patch is not
  * converted).  Writes the ascending list of flat positions p in [0,m) with
  * mask[p] != 0 and their number.  One list serves every layer at that
@@ -205,6 +229,10 @@ int32_t fc_mask_pyramid_workspace_bytes(int32_t n, int32_t h, int32_t w, int32_t
 int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t levels,
                         const fc_mask_step *steps, uint8_t *const *mask_out, int32_t *const *idx,
                         int32_t *const *count, void *workspace, size_t workspace_bytes, void *stream);
+int32_t fc_mask_pyramid_packed(const void *mask_in, int32_t mask_in_packed, int32_t n, int32_t h, int32_t w,
+                               int32_t levels, const fc_mask_step *steps, uint64_t *const *bits_out,
+                               int32_t *const *idx, int32_t *const *count, void *workspace,
+                               size_t workspace_bytes, void *stream);
 
 /* The layer (Sec. III-A).  Gathers the receptive fields of the kept positions
  * (implicit im2col), multiplies by the unchanged weights on the matrix cores,

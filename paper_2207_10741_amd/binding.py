@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfocused_conv.so")
 
 F32, BF16, F16, FP8 = 0, 1, 2, 3
-RELU, SKIP_ZERO_FILL, WORKSPACE_READY, COMPACT_OUT, COMPACT_IN = 1, 2, 4, 8, 16
+RELU, SKIP_ZERO_FILL, WORKSPACE_READY, COMPACT_OUT, COMPACT_IN, PACKED_MASKS = 1, 2, 4, 8, 16, 32
 RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 WORKSPACE_COUNTER_BYTES = 2048
 NOALLOC_SCRATCH_BYTES = 40 << 20
@@ -24,6 +24,8 @@ FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compac
              "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_gconv2d",
              "fc_noalloc_init", "fc_focused_conv2d_noalloc", "fc_calibrate_mfma", "fc_calibrate_copy",
+             "fc_packed_mask_bytes", "fc_mask_pack", "fc_mask_downsample_packed", "fc_active_index_compact_packed",
+             "fc_mask_pyramid_packed",
              "fc_expand_group_weights",
              "fc_focused_dwconv2d",
              "fc_maxpool2d", "fc_maxpool2d_masked")
@@ -98,6 +100,17 @@ def lib():
         L.fc_mask_pyramid.restype = i32
         L.fc_mask_pyramid.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(MaskStep), ctypes.POINTER(vp),
                                       ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
+        L.fc_packed_mask_bytes.restype = ctypes.c_size_t
+        L.fc_packed_mask_bytes.argtypes = [i64]
+        L.fc_mask_pack.restype = i32
+        L.fc_mask_pack.argtypes = [vp, i64, vp, vp]
+        L.fc_mask_downsample_packed.restype = i32
+        L.fc_mask_downsample_packed.argtypes = [vp] + [i32] * 11 + [vp, vp]
+        L.fc_active_index_compact_packed.restype = i32
+        L.fc_active_index_compact_packed.argtypes = [vp, i64, vp, vp, vp, ctypes.c_size_t, vp]
+        L.fc_mask_pyramid_packed.restype = i32
+        L.fc_mask_pyramid_packed.argtypes = [vp, i32, i32, i32, i32, i32, ctypes.POINTER(MaskStep), ctypes.POINTER(vp),
+                                             ctypes.POINTER(vp), ctypes.POINTER(vp), vp, ctypes.c_size_t, vp]
         L.fc_focused_conv2d.restype = i32
         L.fc_focused_conv2d.argtypes = [ctypes.POINTER(ConvDesc)] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_noalloc_init.restype = i32
@@ -222,18 +235,70 @@ def mask_pyramid_dims(h: int, w: int, steps):
     return [(int(a), int(b)) for a, b in zip(hs, ws)]
 
 
-class PreparedPyramid:
-    """fc_mask_pyramid with its arguments marshalled once: all levels' masks and kept lists from
-    one input mask.  `levels` holds (mask_out, idx, count) per level."""
+def packed_mask_words(m: int) -> int:
+    """64-bit words of a packed mask of m pixels."""
+    return lib().fc_packed_mask_bytes(int(m)) // 8
 
-    def __init__(self, mask_in, steps):
+
+def _packed_tensor(m: int, device):
+    torch = _torch()
+    return torch.empty((max(packed_mask_words(m), 2),), dtype=torch.int64, device=device)   # (at least 16 bytes)
+
+
+def mask_pack(mask, out=None, stream=None):
+    """fc_mask_pack: uint8 [...] -> int64 words, one bit per pixel (bit p % 64 of word p // 64)."""
+    _require_cuda(mask, out)
+    m = mask.numel()
+    if out is None:
+        out = _packed_tensor(m, mask.device)
+    _check(lib().fc_mask_pack(_ptr(mask), m, _ptr(out), _stream(stream)), "fc_mask_pack")
+    return out
+
+
+def mask_downsample_packed(bits_in, shape, k=(3, 3), stride=(1, 1), pad=(1, 1), dil=(1, 1), out=None, stream=None):
+    """fc_mask_downsample_packed: packed [N,H,W] (shape = (N, H, W)) -> packed [N,Ho,Wo]; returns (bits, (N, Ho, Wo))."""
+    _require_cuda(bits_in, out)
+    n, h, w = shape
+    d = conv_desc(n, h, w, 1, 1, k, stride, pad, dil, F32)
+    ho, wo = out_dims(d)
+    if out is None:
+        out = _packed_tensor(n * ho * wo, bits_in.device)
+    _check(lib().fc_mask_downsample_packed(_ptr(bits_in), n, h, w, k[0], k[1], stride[0], stride[1], pad[0], pad[1],
+                                           dil[0], dil[1], _ptr(out), _stream(stream)), "fc_mask_downsample_packed")
+    return out, (n, ho, wo)
+
+
+def active_index_compact_packed(bits, m: int, idx=None, count=None, workspace=None, stream=None):
+    """fc_active_index_compact_packed: packed mask of m pixels -> (idx, count)."""
+    torch = _torch()
+    _require_cuda(bits, idx, count, workspace)
+    if idx is None:
+        idx = torch.empty((m,), dtype=torch.int32, device=bits.device)
+    if count is None:
+        count = torch.empty((1,), dtype=torch.int32, device=bits.device)
+    if workspace is None:
+        workspace = torch.empty((compact_workspace_bytes(m),), dtype=torch.uint8, device=bits.device)
+    _check(lib().fc_active_index_compact_packed(_ptr(bits), m, _ptr(idx), _ptr(count), _ptr(workspace),
+                                                workspace.numel(), _stream(stream)), "fc_active_index_compact_packed")
+    return idx, count
+
+
+class PreparedPyramid:
+    """fc_mask_pyramid (or, with packed=True, fc_mask_pyramid_packed) with its arguments marshalled
+    once: all levels' masks and kept lists from one input mask.  `levels` holds (mask_out, idx, count)
+    per level; with packed=True mask_out is the packed mask (int64 words) and `dims` its (N, H, W).
+    packed_in: the input mask is packed too (then `shape` = its (N, H, W))."""
+
+    def __init__(self, mask_in, steps, packed: bool = False, packed_in: bool = False, shape=None):
         torch = _torch()
         _require_cuda(mask_in)
-        n, h, w = mask_in.shape
+        n, h, w = shape if packed_in else mask_in.shape
         self._steps = _steps_array(steps)
         dims = mask_pyramid_dims(h, w, steps)
+        self.dims = [(n, hl, wl) for hl, wl in dims]
         dev = mask_in.device
-        self.levels = [(torch.empty((n, hl, wl), dtype=torch.uint8, device=dev),
+        self.levels = [((_packed_tensor(n * hl * wl, dev) if packed else
+                         torch.empty((n, hl, wl), dtype=torch.uint8, device=dev)),
                         torch.empty((n * hl * wl,), dtype=torch.int32, device=dev),
                         torch.empty((1,), dtype=torch.int32, device=dev)) for hl, wl in dims]
         b = ctypes.c_size_t()
@@ -243,9 +308,16 @@ class PreparedPyramid:
         vp = ctypes.c_void_p
         nl = len(steps)
         self._ptrs = tuple((vp * nl)(*[_ptr(lv[i]) for lv in self.levels]) for i in range(3))
-        self._args = (_ptr(mask_in), n, h, w, nl, self._steps, *self._ptrs, _ptr(self._ws), self._ws.numel())
+        if packed:
+            self._args = (_ptr(mask_in), 1 if packed_in else 0, n, h, w, nl, self._steps, *self._ptrs,
+                          _ptr(self._ws), self._ws.numel())
+            self._fn = lib().fc_mask_pyramid_packed
+        else:
+            if packed_in:
+                raise ValueError("a packed input mask gives packed levels: pass packed=True")
+            self._args = (_ptr(mask_in), n, h, w, nl, self._steps, *self._ptrs, _ptr(self._ws), self._ws.numel())
+            self._fn = lib().fc_mask_pyramid
         self.mask_in = mask_in   # (kept alive: the call reads it)
-        self._fn = lib().fc_mask_pyramid
         self._current_stream = torch.cuda.current_stream
 
     def __call__(self, stream=None):

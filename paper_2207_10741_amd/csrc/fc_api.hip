@@ -47,7 +47,8 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
     if (d->out_dtype != (d->in_dtype == FC_FP8 ? FC_BF16 : d->in_dtype) && d->out_dtype != FC_F32 &&
         !(d->in_dtype != FC_F32 && d->out_dtype == FC_FP8))
         return FC_ERR_DTYPE;
-    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY | FC_COMPACT_OUT | FC_COMPACT_IN))
+    if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY | FC_COMPACT_OUT | FC_COMPACT_IN |
+                               FC_PACKED_MASKS))
         return FC_ERR_DTYPE;
     const int32_t ho = out_dim(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
     const int32_t wo = out_dim(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
@@ -264,6 +265,9 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     hipStream_t s = (hipStream_t)stream;
 
     const bool mfma = conv_mfma_supported(g, desc->in_dtype, desc->out_dtype);
+    const bool packed = (g.flags & FC_PACKED_MASKS) != 0;
+    // the kernel for RGB stems reads byte masks image by image
+    if (packed && !mfma && conv_stem_supported(g, desc->in_dtype, desc->out_dtype)) return FC_ERR_DTYPE;
     // 8-bit layers exist on the matrix cores only (16 | c_in, 8 | c_out, at most 32 taps)
     if (desc->in_dtype == FC_FP8 && !mfma) return FC_ERR_DTYPE;
     // 8-bit outputs: the matrix-core kernels round to them, the direct kernel does not
@@ -314,10 +318,13 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
                 MaskGeom fg = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
                 fg.w = fg.wo = g.m;
                 fg.m = g.m;
+                fg.packed_in = packed;
                 ec = launch_compact(fg, mask_out, nullptr, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
                                     (int32_t *)(ws + l.scan), ex, s);
             } else {
-                ec = launch_compact(mg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+                MaskGeom pg = mg;
+                pg.packed_in = pg.packed_out = packed; // the derived labels take the form of the input mask
+                ec = launch_compact(pg, mask_in, m_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
                                     (int32_t *)(ws + l.scan), ex, s);
                 mask_out = m_out;
             }
@@ -370,6 +377,7 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
     // one channel per group with the labels of the input mask: the depthwise kernel
     if (groups == g.c_in && g.c_in == g.c_out && !idx && !mask_out)
         return fc_focused_dwconv2d(desc, x, mask_in, w, bias, out, stream);
+    if (groups == g.c_in && (g.flags & FC_PACKED_MASKS)) return FC_ERR_DTYPE; // (depthwise: byte masks)
     if (desc->in_dtype == FC_FP8 || desc->out_dtype == FC_FP8) return FC_ERR_DTYPE;
     if (!x || !w || !out) return FC_ERR_NULL;
     if ((idx == nullptr) != (count == nullptr)) return FC_ERR_NULL;
@@ -384,14 +392,18 @@ int32_t fc_focused_gconv2d(const fc_conv_desc *desc, int32_t groups, const void 
         uint8_t *ws = (uint8_t *)workspace;
         const MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
         hipError_t ec;
+        const bool packed = (g.flags & FC_PACKED_MASKS) != 0;
         if (mask_out) { // the caller's labels, compacted as they are
             MaskGeom fg = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
             fg.w = fg.wo = g.m;
             fg.m = g.m;
+            fg.packed_in = packed;
             ec = launch_compact(fg, mask_out, nullptr, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
                                 (int32_t *)(ws + l.scan), CompactExtras(), s);
         } else {
-            ec = launch_compact(mg, mask_in, ws + l.mask_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
+            MaskGeom pg = mg;
+            pg.packed_in = pg.packed_out = packed;
+            ec = launch_compact(pg, mask_in, ws + l.mask_out, (int32_t *)(ws + l.idx), (int32_t *)(ws + l.count),
                                 (int32_t *)(ws + l.scan), CompactExtras(), s);
             mask_out = ws + l.mask_out;
         }
@@ -433,7 +445,7 @@ int32_t fc_focused_dwconv2d(const fc_conv_desc *desc, const void *x, const uint8
     const int32_t rc = make_geom(desc, &g);
     if (rc != FC_OK) return rc;
     if (g.c_in != g.c_out) return FC_ERR_SHAPE;
-    if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN)) return FC_ERR_DTYPE; // full layers only
+    if (g.flags & (FC_COMPACT_OUT | FC_COMPACT_IN | FC_PACKED_MASKS)) return FC_ERR_DTYPE; // full layers, byte masks
     if (!x || !w || !out) return FC_ERR_NULL;
     if (!aligned16(x) || !aligned16(w) || !aligned16(out) || !aligned16(bias)) return FC_ERR_ALIGN;
     if (conv_tensors_overlap(g, desc, x, out)) return FC_ERR_NULL;
@@ -508,14 +520,18 @@ int32_t fc_mask_pyramid_workspace_bytes(int32_t n, int32_t h, int32_t w, int32_t
     return FC_OK;
 }
 
-int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t levels,
-                        const fc_mask_step *steps, uint8_t *const *mask_out, int32_t *const *idx,
-                        int32_t *const *count, void *workspace, size_t workspace_bytes, void *stream)
+static int32_t mask_pyramid_any(const uint8_t *mask_in, int32_t packed_in, int32_t packed_out, int32_t n, int32_t h,
+                                int32_t w, int32_t levels, const fc_mask_step *steps, uint8_t *const *mask_out,
+                                int32_t *const *idx, int32_t *const *count, void *workspace, size_t workspace_bytes,
+                                void *stream)
 {
     if (!mask_in || !mask_out || !idx || !count) return FC_ERR_NULL;
     PyramidArgs a;
     const int32_t rc = pyramid_geometry(n, h, w, levels, steps, &a);
     if (rc != FC_OK) return rc;
+    a.packed_in = packed_in ? 1 : 0;
+    a.packed_out = packed_out ? 1 : 0;
+    if (a.packed_in && !aligned16(mask_in)) return FC_ERR_ALIGN;
     for (int l = 0; l < levels; ++l) {
         if (!mask_out[l] || !idx[l] || !count[l]) return FC_ERR_NULL;
         if (!aligned16(mask_out[l]) || !aligned16(idx[l])) return FC_ERR_ALIGN;
@@ -528,6 +544,70 @@ int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w,
     if (!workspace || workspace_bytes < need) return FC_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FC_ERR_ALIGN;
     const hipError_t e = launch_mask_pyramid(a, mask_in, (int32_t *)workspace, (hipStream_t)stream);
+    return e == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
+int32_t fc_mask_pyramid(const uint8_t *mask_in, int32_t n, int32_t h, int32_t w, int32_t levels,
+                        const fc_mask_step *steps, uint8_t *const *mask_out, int32_t *const *idx,
+                        int32_t *const *count, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return mask_pyramid_any(mask_in, 0, 0, n, h, w, levels, steps, mask_out, idx, count, workspace, workspace_bytes,
+                            stream);
+}
+
+int32_t fc_mask_pyramid_packed(const void *mask_in, int32_t mask_in_packed, int32_t n, int32_t h, int32_t w,
+                               int32_t levels, const fc_mask_step *steps, uint64_t *const *bits_out,
+                               int32_t *const *idx, int32_t *const *count, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    return mask_pyramid_any((const uint8_t *)mask_in, mask_in_packed, 1, n, h, w, levels, steps,
+                            (uint8_t *const *)bits_out, idx, count, workspace, workspace_bytes, stream);
+}
+
+size_t fc_packed_mask_bytes(int64_t m) { return m <= 0 ? 0 : (size_t)((m + 63) / 64) * 8; }
+
+int32_t fc_mask_pack(const uint8_t *mask, int64_t m, uint64_t *bits, void *stream)
+{
+    if (!mask || !bits) return FC_ERR_NULL;
+    if (m <= 0) return FC_ERR_SHAPE;
+    if (m >= INT32_MAX) return FC_ERR_RANGE;
+    if (!aligned16(bits)) return FC_ERR_ALIGN;
+    return launch_mask_pack(mask, m, bits, (hipStream_t)stream) == hipSuccess ? FC_OK : FC_ERR_HIP;
+}
+
+int32_t fc_mask_downsample_packed(const uint64_t *bits_in, int32_t n, int32_t h, int32_t w, int32_t kh, int32_t kw,
+                                  int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w, int32_t dil_h,
+                                  int32_t dil_w, uint64_t *bits_out, void *stream)
+{
+    if (!bits_in || !bits_out) return FC_ERR_NULL;
+    if (n <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 ||
+        pad_w < 0 || dil_h <= 0 || dil_w <= 0)
+        return FC_ERR_SHAPE;
+    const int32_t ho = out_dim(h, kh, stride_h, pad_h, dil_h), wo = out_dim(w, kw, stride_w, pad_w, dil_w);
+    if (ho <= 0 || wo <= 0) return FC_ERR_SHAPE;
+    if ((int64_t)n * ho * wo >= INT32_MAX || (int64_t)n * h * w >= INT32_MAX) return FC_ERR_RANGE;
+    if (!aligned16(bits_in) || !aligned16(bits_out)) return FC_ERR_ALIGN;
+    MaskGeom g = mask_geom(n, h, w, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, ho, wo);
+    g.packed_in = g.packed_out = 1;
+    return launch_mask_rescale(g, (const uint8_t *)bits_in, (uint8_t *)bits_out, (hipStream_t)stream) == hipSuccess
+               ? FC_OK
+               : FC_ERR_HIP;
+}
+
+int32_t fc_active_index_compact_packed(const uint64_t *bits, int64_t m, int32_t *idx, int32_t *count, void *workspace,
+                                       size_t workspace_bytes, void *stream)
+{
+    if (!bits || !idx || !count) return FC_ERR_NULL;
+    if (m <= 0) return FC_ERR_SHAPE;
+    if (m >= INT32_MAX) return FC_ERR_RANGE;
+    if (!workspace || workspace_bytes < compact_ws(m)) return FC_ERR_WORKSPACE;
+    if (!aligned16(bits) || !aligned16(idx) || !aligned16(workspace)) return FC_ERR_ALIGN;
+    MaskGeom g = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
+    g.w = g.wo = (int32_t)m;
+    g.m = m;
+    g.packed_in = 1;
+    const hipError_t e = launch_compact(g, (const uint8_t *)bits, nullptr, idx, count, (int32_t *)workspace,
+                                        CompactExtras(), (hipStream_t)stream);
     return e == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kRowsThreads) void k_conv_rows(Geom g, const TI *__
                     tap_ok = live && ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
                     if (tap_ok) {
                         const int64_t pix = ((int64_t)b * g.h + ih) * g.w + iw;
-                        tap_ok = !mask_in || mask_in[pix] != 0;
+                        tap_ok = !mask_in || mask_at(mask_in, pix, (g.flags & FC_PACKED_MASKS) != 0);
                         xp = x + pix * x_pitch;
                     }
                     new_tap = false;

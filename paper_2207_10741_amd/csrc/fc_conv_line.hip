@@ -181,13 +181,14 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
     // beside the set-up's; the rows are cleared after the tiles, when nothing waits on the
     // memory counter any more (loads and stores share it: a store issued earlier would make the
     // next wait for gathered data wait for its acknowledgement as well). ----
+    const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0; // masks are one bit per pixel
     const bool zero_fill = mask_in && !(g.flags & FC_SKIP_ZERO_FILL);
     const int zf_workers = (int)gridDim.x * kLineWaves;
     const int zf_first = ((int)blockIdx.x * kLineWaves + wave) * 64;
     auto label_of = [&](int pp) -> bool {
         // kept?  (positions past the end count as kept: nothing to clear)
         if (pp >= g.m) return true;
-        if (mask_out) return mask_out[pp] != 0;
+        if (mask_out) return mask_at(mask_out, pp, packed_masks);
         const int ch0 = -g.ph + g.dh * ((g.kh - 1) / 2), cw0 = -g.pw + g.dw * ((g.kw - 1) / 2);
         const int q = (int)fast_div((uint32_t)pp, dv.wo);
         const int ow = pp - q * g.wo;
@@ -195,7 +196,7 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
         const int oh = q - b * g.ho;
         const int ih = min(max(oh * g.sh + ch0, 0), g.h - 1);
         const int iw = min(max(ow * g.sw + cw0, 0), g.w - 1);
-        return mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
+        return mask_at(mask_in, (int64_t)(b * g.h + ih) * g.w + iw, packed_masks);
     };
     auto clear_rows = [&](int pp, uint64_t drop, int32_t *dropped) {
         const int cpr = g.c_out * (int)sizeof(TO) / 16; // 16-byte pieces per row
@@ -477,8 +478,9 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                         const int kh_i = NQ == 3 ? q : q / KW, kw_i = NQ == 3 ? 0 : q - (q / KW) * KW;
                         const int ih = ih0 + kh_i * g.dh, iw = iw0 + kw_i * g.dw;
                         inb[q] = ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
-                        mv[q] = (mask_in && !self_tap) ? mask_in[inb[q] ? pix + kh_i * g.dh * g.w + kw_i * g.dw : 0]
-                                                       : (uint8_t)1;
+                        mv[q] = (mask_in && !self_tap)
+                                    ? (uint8_t)mask_at(mask_in, inb[q] ? pix + kh_i * g.dh * g.w + kw_i * g.dw : 0, packed_masks)
+                                    : (uint8_t)1;
                     }
                     uint32_t bits = 0;
 #pragma unroll

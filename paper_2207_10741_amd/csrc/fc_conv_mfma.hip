@@ -172,13 +172,15 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
     // prefix sum over the workgroup gives the rank of its first kept position; the set-up of a
     // tile then has every thread drop its positions of that tile's rank range into row_p.  A
     // small layer so needs no compaction launch before this one.
+    const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0; // masks are one bit per pixel
     const bool inline_rank = !idx && mask_in;
     uint32_t rank_flags = 0;
     int rank_base = 0;
     int rows = g.m;
     if (inline_rank) {
         MaskGeom mg = mask_geom(g.n, g.h, g.w, g.kh, g.kw, g.sh, g.sw, g.ph, g.pw, g.dh, g.dw, g.ho, g.wo);
-        if (reinterpret_cast<uintptr_t>(mask_in) & 15u) mg.identity = 0; // the 128-bit path needs alignment
+        mg.packed_in = (g.flags & FC_PACKED_MASKS) ? 1 : 0;
+        if (!mg.packed_in && (reinterpret_cast<uintptr_t>(mask_in) & 15u)) mg.identity = 0; // the 128-bit path needs alignment
         rank_flags = kept_flags16(mg, mask_in, (int64_t)tid * 16);
         const int cnt = __popc(rank_flags);
         const int incl = wave_inclusive_scan(cnt);
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                 bool kept = true;
                 if (pp < g.m) {
                     if (mask_out) {
-                        kept = mask_out[pp] != 0;
+                        kept = mask_at(mask_out, pp, packed_masks);
                     } else {
                         const int ow = pp % g.wo;
                         const int q = pp / g.wo;
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                         const int b = q / g.ho;
                         const int ih = min(max(oh * g.sh + ch0, 0), g.h - 1);
                         const int iw = min(max(ow * g.sw + cw0, 0), g.w - 1);
-                        kept = mask_in[(int64_t)(b * g.h + ih) * g.w + iw] != 0;
+                        kept = mask_at(mask_in, (int64_t)(b * g.h + ih) * g.w + iw, packed_masks);
                     }
                 }
                 const uint64_t drop = __ballot(!kept);
@@ -432,7 +434,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                 }
                 uint8_t smv[SIT];
 #pragma unroll
-                for (int i = 0; i < SIT; ++i) smv[i] = mask_in ? mask_in[spix_[i]] : (uint8_t)1;
+                for (int i = 0; i < SIT; ++i) smv[i] = mask_in ? (uint8_t)mask_at(mask_in, spix_[i], packed_masks) : (uint8_t)1;
 #pragma unroll
                 for (int i = 0; i < SIT; ++i)
                     if (sin_[i] && smv[i]) atomicOr(&slot_bits[ssl_[i]], 1u << skh_[i]);
@@ -462,7 +464,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
             }
             uint8_t mv[PAIR_CH];
 #pragma unroll
-            for (int i = 0; i < PAIR_CH; ++i) mv[i] = mask_in ? mask_in[ppix_[i]] : (uint8_t)1;
+            for (int i = 0; i < PAIR_CH; ++i) mv[i] = mask_in ? (uint8_t)mask_at(mask_in, ppix_[i], packed_masks) : (uint8_t)1;
 #pragma unroll
             for (int i = 0; i < PAIR_CH; ++i)
                 if (pin_[i] && mv[i]) atomicOr(&row_bits[prow_[i]], 1u << ptap_[i]);

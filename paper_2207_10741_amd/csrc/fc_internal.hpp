@@ -83,8 +83,18 @@ static inline int64_t compact_blocks(int64_t m) { return (m + kCompactBlockElems
 struct MaskGeom {
     int32_t n, h, w, ho, wo, sh, sw, ch0, cw0;
     int32_t identity; // output position p reads input pixel p (stride 1, same size, centred)
+    int32_t packed_in, packed_out; // the mask read / written is one bit per pixel (see mask_at)
     int64_t m;        // n*ho*wo
 };
+
+// A mask is one byte per pixel (nonzero = relevant) or, packed, one bit per pixel: bit p & 31
+// of the 32-bit word p >> 5 (little-endian, so the same bits as bit p & 63 of the 64-bit word
+// p >> 6, one wave ballot); bits past the last pixel are zero.
+__device__ __forceinline__ bool mask_at(const uint8_t *__restrict__ m, int64_t p, bool packed)
+{
+    if (packed) return (reinterpret_cast<const uint32_t *>(m)[p >> 5] >> (uint32_t)(p & 31)) & 1u;
+    return m[p] != 0;
+}
 
 __host__ __device__ static inline MaskGeom mask_geom(int n, int h, int w, int kh, int kw, int sh, int sw, int ph, int pw, int dh,
                                  int dw, int ho, int wo)
@@ -94,6 +104,7 @@ __host__ __device__ static inline MaskGeom mask_geom(int n, int h, int w, int kh
     g.ch0 = -ph + dh * ((kh - 1) / 2);
     g.cw0 = -pw + dw * ((kw - 1) / 2);
     g.identity = (sh == 1 && sw == 1 && ho == h && wo == w && g.ch0 == 0 && g.cw0 == 0) ? 1 : 0;
+    g.packed_in = g.packed_out = 0;
     g.m = (int64_t)n * ho * wo;
     return g;
 }
@@ -104,6 +115,12 @@ __device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_
 {
     uint32_t flags = 0;
     if (p0 >= g.m) return 0;
+    if (g.identity && g.packed_in) {
+        // p0 is a multiple of 16: the labels are one 16-bit piece of the packed mask
+        flags = reinterpret_cast<const uint16_t *>(mask_in)[p0 >> 4];
+        if (p0 + 16 > g.m) flags &= (1u << (uint32_t)(g.m - p0)) - 1u;
+        return flags;
+    }
     if (g.identity && p0 + 16 <= g.m) {
         const uint4 v = *reinterpret_cast<const uint4 *>(mask_in + p0);
         const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
@@ -133,6 +150,14 @@ __device__ __forceinline__ uint32_t kept_flags16(const MaskGeom &g, const uint8_
             }
             row_at = (b * g.h + min(max(oh * g.sh + g.ch0, 0), g.h - 1)) * g.w;
         }
+    }
+    if (g.packed_in) {
+        uint32_t got[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) got[j] = at[j] >= 0 ? reinterpret_cast<const uint32_t *>(mask_in)[at[j] >> 5] : 0u;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) flags |= ((got[j] >> (at[j] & 31)) & 1u) << j;
+        return flags;
     }
     uint8_t got[16];
 #pragma unroll
@@ -181,6 +206,7 @@ hipError_t launch_compact(const MaskGeom &g, const uint8_t *mask_in, uint8_t *ma
 constexpr int kMaxPyramidLevels = 8;
 struct PyramidArgs {
     int32_t levels, n;
+    int32_t packed_in, packed_out; // the input mask / the levels' masks are one bit per pixel
     int32_t identity0; // level 0 has the input's resolution, centred window, and the input is 16-byte aligned
     int32_t h[kMaxPyramidLevels + 1], w[kMaxPyramidLevels + 1]; // [0] = input mask, [l + 1] = level l
     int32_t sh[kMaxPyramidLevels], sw[kMaxPyramidLevels], ch0[kMaxPyramidLevels], cw0[kMaxPyramidLevels];
@@ -200,6 +226,10 @@ static inline int64_t tiled_rows(int n, int ho, int wo, int tile_h, int tile_w)
     return (int64_t)n * ((ho + tile_h - 1) / tile_h) * ((wo + tile_w - 1) / tile_w) * tile_h;
 }
 hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int32_t *block_counts, hipStream_t s);
+// bytes -> bits (nonzero byte = 1; the bits of the last word past m are zero), and the
+// centre-tap rescaling of a mask in either form into either form
+hipError_t launch_mask_pack(const uint8_t *mask, int64_t m, uint64_t *bits, hipStream_t s);
+hipError_t launch_mask_rescale(const MaskGeom &g, const uint8_t *mask_in, uint8_t *mask_out, hipStream_t s);
 hipError_t launch_zero_fill(const Geom &g, const uint8_t *mask_in, const uint8_t *mask_out, void *out,
                             int out_dtype, hipStream_t s);
 hipError_t launch_expand_group_weights(const void *wg, int c_in, int c_out, int taps, int groups, int esize,

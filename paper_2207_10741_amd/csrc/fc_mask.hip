@@ -171,7 +171,10 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_compact_scatter(MaskGe
 
     const int64_t p0 = (int64_t)blockIdx.x * kCompactBlockElems + (int64_t)tid * kCompactBytesPerThread;
     const uint32_t flags = kept_flags16(g, mask_in, p0);
-    if (mask_out) {
+    if (mask_out && g.packed_out) {
+        // sixteen labels = one 16-bit piece of the packed mask (zeros past the end, up to a whole word)
+        if (p0 < ((g.m + 63) & ~(int64_t)63)) reinterpret_cast<uint16_t *>(mask_out)[p0 >> 4] = (uint16_t)flags;
+    } else if (mask_out) {
         if (p0 + 16 <= g.m) {
             uint32_t wds[4];
 #pragma unroll
@@ -214,7 +217,7 @@ hipError_t launch_compact(const MaskGeom &g_in, const uint8_t *mask_in, uint8_t 
                           int32_t *count, int32_t *block_counts, const CompactExtras &extras, hipStream_t s)
 {
     MaskGeom g = g_in;
-    if (reinterpret_cast<uintptr_t>(mask_in) & 15u) g.identity = 0; // the 128-bit path needs alignment
+    if (!g.packed_in && (reinterpret_cast<uintptr_t>(mask_in) & 15u)) g.identity = 0; // the 128-bit path needs alignment
     const int nb = (int)compact_blocks(g.m);
     if (nb <= kCompactSingleLaunchBlocks) {
         hipLaunchKernelGGL(k_compact_scatter<true>, dim3(nb), dim3(kCompactBlockThreads), 0, s, g, mask_in,
@@ -365,7 +368,12 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_masks(PyramidA
     const int64_t p0 = (int64_t)(blockIdx.x - a.block0[l]) * kCompactBlockElems +
                        (int64_t)threadIdx.x * kCompactBytesPerThread;
     uint32_t flags = 0;
-    if (l == 0 && a.identity0 && p0 + 16 <= m) {
+    if (l == 0 && a.identity0 && a.packed_in) {
+        if (p0 < m) {
+            flags = reinterpret_cast<const uint16_t *>(mask_in)[p0 >> 4];
+            if (p0 + 16 > m) flags &= (1u << (uint32_t)(m - p0)) - 1u;
+        }
+    } else if (l == 0 && a.identity0 && p0 + 16 <= m) {
         // the first level keeps the resolution of an aligned input mask: one 128-bit load
         const uint4 v = *reinterpret_cast<const uint4 *>(mask_in + p0);
         const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
@@ -409,13 +417,24 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_masks(PyramidA
                 row_at = (b * a.h[0] + row_in(oh)) * a.w[0];
             }
         }
-        uint8_t got[16];
+        if (a.packed_in) {
+            uint32_t got[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) got[j] = at[j] >= 0 ? mask_in[at[j]] : (uint8_t)0;
+            for (int j = 0; j < 16; ++j)
+                got[j] = at[j] >= 0 ? reinterpret_cast<const uint32_t *>(mask_in)[at[j] >> 5] : 0u;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) flags |= got[j] ? (1u << j) : 0u;
+            for (int j = 0; j < 16; ++j) flags |= ((got[j] >> (at[j] & 31)) & 1u) << j;
+        } else {
+            uint8_t got[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) got[j] = at[j] >= 0 ? mask_in[at[j]] : (uint8_t)0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) flags |= got[j] ? (1u << j) : 0u;
+        }
     }
-    if (p0 < m) {
+    if (a.packed_out) {
+        if (p0 < ((m + 63) & ~(int64_t)63)) reinterpret_cast<uint16_t *>(a.mask_out[l])[p0 >> 4] = (uint16_t)flags;
+    } else if (p0 < m) {
         uint8_t *mo = a.mask_out[l];
         if (p0 + 16 <= m && (reinterpret_cast<uintptr_t>(mo) & 15u) == 0) {
             uint32_t wds[4];
@@ -451,7 +470,9 @@ __global__ __launch_bounds__(kCompactBlockThreads) void k_pyramid_lists(PyramidA
     const int64_t p0 = (int64_t)(blockIdx.x - first) * kCompactBlockElems + (int64_t)tid * kCompactBytesPerThread;
     const uint8_t *mo = a.mask_out[l];
     uint32_t flags = 0;
-    if (p0 + 16 <= m && (reinterpret_cast<uintptr_t>(mo) & 15u) == 0) {
+    if (a.packed_out) {
+        if (p0 < m) flags = reinterpret_cast<const uint16_t *>(mo)[p0 >> 4]; // (zeros past the end)
+    } else if (p0 + 16 <= m && (reinterpret_cast<uintptr_t>(mo) & 15u) == 0) {
         const uint4 v = *reinterpret_cast<const uint4 *>(mo + p0);
         const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -497,19 +518,59 @@ hipError_t launch_mask_pyramid(const PyramidArgs &a, const uint8_t *mask_in, int
 }
 
 // ---------------------------------------------------------------------------
+// Packed masks: one bit per pixel.  Packing: a thread turns sixteen bytes into sixteen bits.
+// Rescaling (centre tap) between the two forms: sixteen output labels per thread.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_mask_rescale(MaskGeom g, const uint8_t *__restrict__ mask_in,
+                                                      uint8_t *__restrict__ mask_out)
+{
+    const int64_t padded = g.packed_out ? ((g.m + 63) & ~(int64_t)63) : g.m;
+    for (int64_t p0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 16; p0 < padded; p0 += (int64_t)gridDim.x * 256 * 16) {
+        const uint32_t flags = kept_flags16(g, mask_in, p0);
+        if (g.packed_out) {
+            reinterpret_cast<uint16_t *>(mask_out)[p0 >> 4] = (uint16_t)flags;
+        } else {
+            for (int j = 0; j < 16 && p0 + j < g.m; ++j) mask_out[p0 + j] = (flags >> j) & 1u;
+        }
+    }
+}
+
+hipError_t launch_mask_rescale(const MaskGeom &g_in, const uint8_t *mask_in, uint8_t *mask_out, hipStream_t s)
+{
+    MaskGeom g = g_in;
+    if (!g.packed_in && (reinterpret_cast<uintptr_t>(mask_in) & 15u)) g.identity = 0; // the 128-bit path needs alignment
+    const int64_t threads = (g.m + 15) / 16 + 4;
+    int64_t blocks = (threads + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(k_mask_rescale, dim3((unsigned)blocks), dim3(256), 0, s, g, mask_in, mask_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_mask_pack(const uint8_t *mask, int64_t m, uint64_t *bits, hipStream_t s)
+{
+    // a flat mask is a 1 x 1 x m image seen through a 1x1 stride-1 window
+    MaskGeom g = mask_geom(1, 1, 1, 1, 1, 1, 1, 0, 0, 1, 1, 1, 1);
+    g.w = g.wo = (int32_t)m;
+    g.m = m;
+    g.packed_out = 1;
+    return launch_mask_rescale(g, mask, reinterpret_cast<uint8_t *>(bits), s);
+}
+
+// ---------------------------------------------------------------------------
 // Zero-fill of the irrelevant output rows: a lane owns 16 bytes of one row.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ bool position_kept(const Geom &g, const uint8_t *__restrict__ mask_in,
                                               const uint8_t *__restrict__ mask_out, int64_t p)
 {
-    if (mask_out) return mask_out[p] != 0;
+    const bool packed = (g.flags & FC_PACKED_MASKS) != 0;
+    if (mask_out) return mask_at(mask_out, p, packed);
     const uint32_t t = (uint32_t)p / (uint32_t)g.wo; // (position counts fit 31 bits)
     const int ow = (int)((uint32_t)p - t * (uint32_t)g.wo);
     const int b = (int)(t / (uint32_t)g.ho);
     const int oh = (int)(t - (uint32_t)b * (uint32_t)g.ho);
     int ih = min(max(oh * g.sh - g.ph + g.dh * ((g.kh - 1) / 2), 0), g.h - 1);
     int iw = min(max(ow * g.sw - g.pw + g.dw * ((g.kw - 1) / 2), 0), g.w - 1);
-    return mask_in[(b * g.h + ih) * g.w + iw] != 0;
+    return mask_at(mask_in, (int64_t)(b * g.h + ih) * g.w + iw, packed);
 }
 
 // Rows of whole 16-byte pieces: a wave looks at 64 positions at a time (one label each), lists
