@@ -1,7 +1,6 @@
 // C ABI of the library: argument checks on the host, then launches.
 #include "fc_internal.hpp"
 #include <atomic>
-#include <cstdlib>
 
 using namespace fc;
 
@@ -63,27 +62,18 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
     return FC_OK;
 }
 
-// Which variant of the one-workgroup-per-CU kernel serves this layer (0 = none): focused 3x3
-// layers of 65 .. 128 output channels whose kept rows come to at most one tile per CU (eight
-// 32-row blocks on each of 256 CUs).  There it deals the kept rows out evenly, so the time
-// follows the kept share instead of moving in steps of whole tile rounds.  Layers small enough
-// to rank their rows inside the tiled kernel stay there whether or not the caller brings a list
-// (one kernel, one summation order per layer).
-int line_variant(const Geom &g, int in_dtype, int out_dtype, bool focused)
+// Does the one-workgroup-per-CU kernel serve this layer?  Focused 3x3 layers of 65 .. 128 output
+// channels whose kept rows come to at most one tile per CU (eight 32-row blocks on each of 256
+// CUs).  There it deals the kept rows out evenly, so the time follows the kept share instead of
+// moving in steps of whole tile rounds.  Layers small enough to rank their rows inside the tiled
+// kernel stay there whether or not the caller brings a list (one kernel, one summation order per
+// layer).
+bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
 {
-    if (!conv_line_supported(g, in_dtype, out_dtype)) return 0;
-    if (g.m <= kInlineRankPositions) return 0;
-#ifdef FC_TUNE
-    if (const char *v = getenv("FC_LINE_VARIANT")) {
-        const int f = atoi(v);
-        if (f == 2 && (g.c_out > 64 || g.c_in > 64)) return 0;
-        return f;
-    }
-#endif
-    if (!focused) return 0;
-    if (g.c_out <= 64 || g.c_out > 128) return 0;
-    if ((int64_t)(g.m + 31) / 32 > 8 * 256) return 0;
-    return 1;
+    if (!focused || !conv_line_supported(g, in_dtype, out_dtype)) return false;
+    if (g.m <= kInlineRankPositions) return false;
+    if (g.c_out <= 64 || g.c_out > 128) return false;
+    return (int64_t)(g.m + 31) / 32 <= 8 * 256;
 }
 
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }
@@ -335,9 +325,8 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     }
 
     hipError_t e;
-    const int line = (mfma && (idx || !mask_in)) ? line_variant(g, desc->in_dtype, desc->out_dtype, mask_in != nullptr) : 0;
-    if (line) {
-        e = launch_conv_line(g, line, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
+    if (mfma && idx && conv_line_wanted(g, desc->in_dtype, desc->out_dtype, mask_in != nullptr)) {
+        e = launch_conv_line(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
         if (e != hipSuccess) return FC_ERR_HIP;
     } else if (mfma) {
         if (tile_counters && !counters_cleared && !(g.flags & FC_WORKSPACE_READY)) {

@@ -4,36 +4,31 @@
 // Same GEMM view and the same data path as the tiled kernel next door (rows = kept output
 // positions, reduction = (tap, input channel), gathers straight from global memory into
 // swizzled LDS rows, 32x32x16 matrix instructions with fp32 accumulators, bias-initialised
-// accumulators, one rounding in the epilogue), built for the layers that kernel serves
-// badly:
+// accumulators, one rounding in the epilogue), built for 3x3 layers with so few kept rows that
+// the chip holds about one tile per CU.  There the run time is one tile latency, and "a few
+// tiles more than CUs" costs a whole second round.  Here the launch is as many workgroups as
+// CUs, and the kept rows (known on the device only) are dealt out evenly in blocks of 32:
+// every workgroup gets the same share, one round whatever the kept count, so that the time
+// follows the kept share instead of moving in steps.
 //
-//  * layers with so few kept rows that the chip holds about one tile per CU.  There the run
-//    time is one tile latency, and "a few tiles more than CUs" costs a whole second round.
-//    Here the launch is as many workgroups as CUs, and the kept rows (known on the device
-//    only) are dealt out evenly in blocks of 32: every workgroup gets the same share, one
-//    round whatever the kept count.
-//  * 3x3 layers with few channels, which are bound by the bytes that have to pass from L2
-//    into LDS: a workgroup keeps the whole weight tensor of its output channels in LDS for
-//    the life of the launch (WRES), so that only pixels move.
-//
-// A workgroup is eight waves: WM x WN waves tile the rows and output channels of a tile
-// and KS such groups split the k-steps of every stage (a SIMD so holds KS waves that take
-// turns at the matrix pipe; their accumulators are added through LDS at the end of a tile).
-// The number of 32-row blocks a wave multiplies is a run-time value (up to PBW), which is what
-// lets the shares be even.
+// A workgroup is eight waves, WM x WN over the rows and output channels of a tile.  The number
+// of 32-row blocks a wave multiplies is a run-time value (up to PBW), which is what lets the
+// shares be even; the stage loop is instantiated once per block count, so that the loads and
+// multiplies of a stage stay straight-line code.
 //
 // Set-up is done once per "macro tile" of up to NSUB tiles: list entries -> positions ->
 // pixel line -> tap-valid bits are two dependent memory round trips, paid once for several
-// tiles; the tiles of a macro tile then only read tables in LDS.
+// tiles; the tiles of a macro tile then only read tables in LDS.  The first weight slabs are
+// requested before the set-up starts.
 //
-// Pixel line (3x3 kernels with unit horizontal stride and dilation): the kept positions of
-// a tile are sorted, so along a run of horizontally adjacent kept positions the left pixel of
-// one is the centre pixel of the one before.  A tile lays its pixels out on a line of slots:
-// one per kept position plus one before the first and one after the last position of every
-// run; position r's taps kw = 0, 1, 2 are slots cs(r) - 1, cs(r), cs(r) + 1.  For every
-// (kernel row, 64-channel chunk) the line is gathered once and multiplied three times.  A
-// macro tile whose lines would not fit (fragmented masks), and every other geometry, runs tap
-// by tap: one slot per position, one tap per gathered line.
+// Pixel line (unit horizontal stride and dilation): the kept positions of a tile are sorted,
+// so along a run of horizontally adjacent kept positions the left pixel of one is the centre
+// pixel of the one before.  A tile lays its pixels out on a line of slots: one per kept
+// position plus one before the first and one after the last position of every run; position
+// r's taps kw = 0, 1, 2 are slots cs(r) - 1, cs(r), cs(r) + 1.  For every (kernel row,
+// 64-channel chunk) the line is gathered once and multiplied three times.  A macro tile whose
+// lines would not fit (fragmented masks), and every other 3x3 geometry, runs tap by tap: one
+// slot per position, one tap per gathered line.
 #include "fc_dma_util.hpp"
 #include <atomic>
 #include <type_traits>
@@ -44,33 +39,21 @@ constexpr int kLineWaves = 8;
 constexpr int kLineThreads = kLineWaves * 64;
 constexpr int kLineRPP = kLineThreads / 8; // LDS rows one pass of wave loads covers (16 bytes per lane)
 
-#ifdef FC_STAMPS
-__device__ unsigned long long g_line_stamps[512 * 16];
-#define FC_STAMP(i)                                                                                       \
-    do {                                                                                                  \
-        if (tid == 0) g_line_stamps[blockIdx.x * 16 + (i)] = __builtin_readcyclecounter();                \
-    } while (0)
-#else
-#define FC_STAMP(i)
-#endif
-
 constexpr int line_round_up(int v, int to) { return (v + to - 1) / to * to; }
 // slots of one tile's pixel line: its rows, two run ends, one spare, in whole load passes
 constexpr int line_slots(int tm) { return line_round_up(tm + 32, kLineRPP); }
 
-// LDS bytes: two pixel-line buffers, the weights (a ring of slabs, or the whole tensor of the
-// channel tile when resident), then the tables of a macro tile.
+// LDS bytes: two pixel-line buffers, the ring of weight slabs, then the tables of a macro tile.
 template <int TM, int TN, int NSUB>
 constexpr size_t line_table_bytes()
 {
-    // row_p, row_cs [NSUB * TM]; slot_pix, slot_hw, slot_bits [NSUB * SL]; sub_row, sub_slot; scan parts
-    return (size_t)(2 * NSUB * TM + 3 * NSUB * line_slots(TM) + 2 * (NSUB + 1) + 64) * sizeof(int32_t);
+    // row_p, row_cs [NSUB * TM]; slot_pix, slot_hw, slot_bits [NSUB * SL]; sub_slot; scan parts
+    return (size_t)(2 * NSUB * TM + 3 * NSUB * line_slots(TM) + (NSUB + 1) + 64) * sizeof(int32_t);
 }
-template <int TM, int TN, int NSUB>
-static size_t line_lds_bytes(bool wres, int slabs)
+template <int TM, int TN, int NSUB, int NBW>
+constexpr size_t line_lds_bytes()
 {
-    (void)wres;
-    return (size_t)2 * line_slots(TM) * 128 + (size_t)slabs * TN * 128 + line_table_bytes<TM, TN, NSUB>();
+    return (size_t)2 * line_slots(TM) * 128 + (size_t)NBW * TN * 128 + line_table_bytes<TM, TN, NSUB>();
 }
 
 // divisors of the position decode, prepared on the host
@@ -81,15 +64,14 @@ struct LineDivs {
 };
 
 // DT: storage type (bf16 / f16); TO: float or the 16-bit / 8-bit carrier of the output; TN: output
-// channels per tile; WM x WN x KS: waves; PBW: most 32-row blocks per wave (tile height up to
-// WM * PBW * 32); NSUB: tiles per macro tile; TAPC: 9 (3x3) or 1 (1x1); WRES: weights resident;
-// NBW: ring of weight slabs when they are streamed (NBW - 1 stages ahead).
+// channels per tile; WM x WN: waves; PBW: most 32-row blocks per wave (tile height up to
+// WM * PBW * 32); NSUB: tiles per macro tile; NBW: ring of weight slabs (NBW - 1 stages ahead).
 //
 // Stage order (both loops): kernel row, 64-channel chunk, horizontal tap.  On a shared line the
 // three horizontal taps of one (kernel row, chunk) read one gathered line; tap by tap every
 // stage gathers its own.  The weight stream is the same either way, so its first slabs are
 // requested before the set-up knows which loop a macro tile takes.
-template <int DT, typename TO, int TN, int WM, int WN, int KS, int PBW, int NSUB, int TAPC, bool WRES, int NBW, int MINW>
+template <int DT, typename TO, int TN, int WM, int WN, int PBW, int NSUB, int NBW, int MINW>
 __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDivs dv, const uint16_t *__restrict__ x,
                                                                   const uint8_t *__restrict__ mask_in,
                                                                   const uint8_t *__restrict__ mask_out,
@@ -99,10 +81,10 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                                                                   const int32_t *__restrict__ count,
                                                                   TO *__restrict__ out)
 {
-    static_assert(WM * WN * KS == kLineWaves, "eight waves");
+    static_assert(WM * WN == kLineWaves, "eight waves");
     static_assert(DT == FC_BF16 || DT == FC_F16, "16-bit storage");
     static_assert(NBW == 3 || NBW == 4, "weight ring");
-    constexpr int NT = kLineThreads, GT = WM * WN * 64;
+    constexpr int NT = kLineThreads;
     constexpr int RPP = kLineRPP;
     constexpr int TM = WM * PBW * 32;          // most rows of a tile
     constexpr int RMAX = NSUB * TM;            // most rows of a macro tile
@@ -112,23 +94,21 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
     constexpr int CB = TN / (WN * 32);
     constexpr int ES = 2, TK = kStageBytes / ES, EPP = 16 / ES;
     constexpr uint32_t KSTEP = kStepBytes<DT>;
-    constexpr int KK = kStageBytes / (int)KSTEP, KKG = KK / KS;
+    constexpr int KK = kStageBytes / (int)KSTEP; // matrix instructions per stage and block pair
     constexpr int RIT = (RMAX + NT - 1) / NT;  // rows per thread in the set-up
     constexpr uint32_t XB = (uint32_t)SL * 128u, WB = (uint32_t)TN * 128u;
-    constexpr int KW = TAPC == 9 ? 3 : 1;      // horizontal taps = stages per (kernel row, chunk)
-    static_assert(TN % RPP == 0 && TN % (WN * 32) == 0 && KK % KS == 0, "tile shape");
-    static_assert(TAPC == 9 || TAPC == 1, "3x3 or 1x1 kernels");
-    // the accumulators of the wave groups after the first, and a 128-row piece of the output
-    // tile, pass through the front of LDS when the loop is over
-    constexpr size_t FRONT = (size_t)2 * XB + (WRES ? 0 : (size_t)NBW * WB);
+    constexpr int KW = 3, TAPC = 9;            // 3x3 kernels: horizontal taps = stages per (kernel row, chunk)
+    static_assert(TN % RPP == 0 && TN % (WN * 32) == 0, "tile shape");
+    // a 128-row piece of the output tile passes through the front of LDS when the loop is over
+    constexpr size_t FRONT = (size_t)2 * XB + (size_t)NBW * WB;
     constexpr int OP = TN * (int)sizeof(TO) + 16;
-    static_assert((size_t)(KS - 1) * TM * TN * sizeof(float) <= FRONT && (size_t)128 * OP <= FRONT, "front of LDS");
+    static_assert((size_t)128 * OP <= FRONT, "front of LDS");
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);
     const int cchunks = (g.c_in + TK - 1) / TK;
     const int nstage = TAPC * cchunks;
-    const uint32_t wbuf_bytes = (uint32_t)(WRES ? nstage : NBW) * WB;
+    const uint32_t wbuf_bytes = (uint32_t)NBW * WB;
     unsigned char *const wbuf = smem_raw + 2 * XB;
     int32_t *row_p = reinterpret_cast<int32_t *>(smem_raw + 2 * XB + wbuf_bytes);
     int32_t *row_cs = row_p + RMAX;
@@ -140,14 +120,11 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // (wave-uniform: kept in a scalar register)
-    const int kgrp = wave / (WM * WN);
-    const int gwave = wave - kgrp * (WM * WN), gtid = tid - kgrp * GT;
     // (waves w and w + 4 share a SIMD: with the channel index fastest they take different rows
     // of the tile, so a SIMD's two waves together hold an even number of row blocks)
-    const int wave_n = gwave % WN, wave_m = gwave / WN;
+    const int wave_n = wave % WN, wave_m = wave / WN;
     const int slot = tid & 7, prow = tid >> 3;
 
-    FC_STAMP(0);
     const int rows = idx ? *count : g.m;
     const int n_nt = dv.n_nt;
     const int nb = (rows + 31) >> 5;          // 32-row blocks of the kept rows
@@ -170,10 +147,9 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
 
     // fragment addressing (see the tiled kernel): lane reads row (lane & 31) of a 32-row
     // block; in k-step q that is the 16-byte piece 2q + (lane >> 5), stored at slot
-    // piece ^ swizzle(row); the first k-step of this wave's group is folded in
-    const uint32_t frag_k0 = (uint32_t)(kgrp * KKG) * KSTEP;
+    // piece ^ swizzle(row)
     const uint32_t frag_row = (uint32_t)(lane & 31) * 128u;
-    const uint32_t frag_t16 = ((uint32_t)((lane >> 5) ^ FC_SWZ(lane & 31)) * 16u) ^ frag_k0;
+    const uint32_t frag_t16 = (uint32_t)((lane >> 5) ^ FC_SWZ(lane & 31)) * 16u;
     const int xgp = slot ^ FC_SWZ(prow); // 16-byte piece this lane fetches for its LDS slot (rows 64 apart share it)
 
     // ---- zero-fill of the irrelevant output rows: every wave takes 64 positions at a time.
@@ -218,7 +194,6 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
     uint64_t zf_drop = 0; // (taken from the labels once the first tile's list entries are on their way)
     bool zf_have = false;
 
-    int resident_nt = -1; // channel tile whose weights sit in LDS (WRES)
 
     for (int slot_t = blockIdx.x >> 3; slot_t < per_xcd; slot_t += gridDim.x >> 3) {
         const int unit = xcd * per_xcd + slot_t;
@@ -238,24 +213,6 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
             woff[j] = co < g.c_out ? ((uint32_t)co * (uint32_t)(TAPC * g.c_in) + (uint32_t)xgp * EPP) * ES : kOutOfRange;
         }
         __syncthreads(); // the previous unit is done with LDS
-        FC_STAMP(1);
-        if constexpr (WRES) {
-            if (resident_nt != nt) {
-                // all slabs of this channel tile, once: slab (tap, chunk) at wbuf + (tap * cchunks + chunk) * WB
-                for (int sidx = 0; sidx < nstage; ++sidx) {
-                    const int tp = sidx / cchunks, cc = sidx - tp * cchunks;
-#pragma unroll
-                    for (int j = 0; j < WR; ++j) {
-                        const bool ok = cc * TK + xgp * EPP < g.c_in;
-                        const uint32_t off = ok ? woff[j] + (uint32_t)(tp * g.c_in + cc * TK) * ES : kOutOfRange;
-                        dma_load16(rsrc_w, off,
-                                   __builtin_amdgcn_readfirstlane(lds0 + 2u * XB + (uint32_t)sidx * WB +
-                                                                  (uint32_t)wave * 1024u + (uint32_t)j * (RPP * 128)));
-                    }
-                }
-                resident_nt = nt;
-            }
-        }
 
         float4 bias_q[CB][4];
 #pragma unroll
@@ -263,8 +220,8 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int co = co0 + wave_n * (CB * 32) + b * 32 + q * 8 + (lane >> 5) * 4;
-                bias_q[b][q] = (bias && kgrp == 0 && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
-                                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+                bias_q[b][q] = (bias && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
+                                                      : make_float4(0.f, 0.f, 0.f, 0.f);
             }
 
         // weight-slab cursor of the tile being prepared (kernel row, chunk, horizontal tap)
@@ -292,15 +249,13 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
         };
         // the first NBW - 1 slabs of a tile: asked for as early as LDS is free
         auto weight_prologue = [&]() {
-            if constexpr (!WRES) {
-                wkh = 0; wcc = 0; wkw = 0; wleft = nstage; wbuf_i = 0;
+            wkh = 0; wcc = 0; wkw = 0; wleft = nstage; wbuf_i = 0;
 #pragma unroll
-                for (int d = 0; d < NBW - 1; ++d) {
-                    prep_w();
+            for (int d = 0; d < NBW - 1; ++d) {
+                prep_w();
 #pragma unroll
-                    for (int j = 0; j < WR; ++j) issue_w(j);
-                    advance_w();
-                }
+                for (int j = 0; j < WR; ++j) issue_w(j);
+                advance_w();
             }
         };
 
@@ -325,7 +280,6 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
             }
 
             if (mb0 != ub0) __syncthreads(); // the previous macro tile is done with LDS and the tables
-            FC_STAMP(2);
             weight_prologue();
 
             // A: the rows' positions and those of their list neighbours in one round trip (thread t
@@ -346,7 +300,6 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                 zf_drop = __ballot(!zf_kept);
                 zf_have = true;
             }
-            FC_STAMP(3);
             int sa_ow[RIT], sa_ih0[RIT], sa_iw0[RIT], sa_b[RIT], cnt[RIT], lead[RIT];
             bool ladj[RIT], radj[RIT];
 #pragma unroll
@@ -381,10 +334,9 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                 if (lane == 63) scan_part[i * kLineWaves + wave] = incl;
                 cnt[i] = incl - cnt[i]; // exclusive, inside the wave
             }
-            FC_STAMP(4);
             __syncthreads();
             // B: slot tables in the shared-line form (kept if every tile's line fits)
-            const bool shared_geom = TAPC == 9 && g.sw == 1 && g.dw == 1;
+            const bool shared_geom = g.sw == 1 && g.dw == 1;
             {
                 int carry = 0;
 #pragma unroll
@@ -460,13 +412,11 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                 for (int s = 0; s <= NSUB; ++s) tile_s[s] = tile_b[s] * 32;
                 __syncthreads();
             }
-            FC_STAMP(5);
 
             // C: one thread per (slot, q): inside the image and relevant?  q = kernel row on a
             // shared line (the slot's own column), tap otherwise
             auto tap_bits = [&](auto nq_c, const int nsl) {
                 constexpr int NQ = decltype(nq_c)::value;
-                const bool self_tap = TAPC == 1 && g.ph == 0 && g.pw == 0;
                 for (int sl = tid; sl < nsl; sl += NT) {
                     const int hw = slot_hw[sl];
                     const int pix = slot_pix[sl];
@@ -478,7 +428,7 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                         const int kh_i = NQ == 3 ? q : q / KW, kw_i = NQ == 3 ? 0 : q - (q / KW) * KW;
                         const int ih = ih0 + kh_i * g.dh, iw = iw0 + kw_i * g.dw;
                         inb[q] = ih >= 0 && ih < g.h && iw >= 0 && iw < g.w;
-                        mv[q] = (mask_in && !self_tap)
+                        mv[q] = mask_in
                                     ? (uint8_t)mask_at(mask_in, inb[q] ? pix + kh_i * g.dh * g.w + kw_i * g.dw : 0, packed_masks)
                                     : (uint8_t)1;
                     }
@@ -491,7 +441,6 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
             if (use_shared) tap_bits(std::integral_constant<int, 3>{}, tile_s[NSUB]);
             else tap_bits(std::integral_constant<int, TAPC>{}, rpad);
             __syncthreads();
-            FC_STAMP(6);
 
             // ---- the tiles of this macro tile ----
 #pragma unroll 1
@@ -578,9 +527,8 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
 #pragma unroll
                     for (int j = 0; j < XL; ++j) issue_x(j);
                     advance_x();
-                    int cxb = 0, cwb = 0, ckh = 0, ccc = 0; // line buffer, slab, (kernel row, chunk) being multiplied
-                    FC_STAMP(7);
-                    const int ngroups = KW == 3 ? 3 * cchunks : cchunks; // (kernel row, chunk) pairs
+                    int cxb = 0, cwb = 0; // line buffer and slab being multiplied
+                    const int ngroups = 3 * cchunks; // (kernel row, chunk) pairs
                     for (int gi = 0; gi < ngroups; ++gi) {
 #pragma unroll
                         for (int t = 0; t < KW; ++t) {
@@ -589,35 +537,29 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                             // line, the next line) are spread over its k-steps.  Issue order: three-tap
                             // lines slab then line, one-tap lines line then slab.  Before that, wait
                             // for this stage's own slab and line: the counts are what may stay in flight.
-                            if constexpr (!WRES) prep_w();
+                            prep_w();
                             if (new_line) prep_x();
                             if (gi == 0 && t == 0) {
                                 wait_vmcnt<0>(); // (the first slabs went out before the set-up's own loads)
-                            } else if constexpr (!WRES) {
+                            } else {
                                 if (TG == 1) wait_vmcnt<WR>();
                                 else if (t == 0) wait_vmcnt<(NBW - 2) * WR>();
                                 else wait_vmcnt<(NBW - 2) * WR + XL>();
-                            } else {
-                                if (new_line) wait_vmcnt<0>();
                             }
-                            if (!WRES || new_line) __syncthreads();
-                            if (gi == 0 && t == 0) FC_STAMP(8);
-                            if (gi == 1 && t == 0) FC_STAMP(9);
+                            __syncthreads();
                             const unsigned char *xs = smem_raw + (uint32_t)cxb * XB;
-                            const unsigned char *ws =
-                                (WRES ? wbuf + (uint32_t)((ckh * KW + t) * cchunks + ccc) * WB : wbuf + (uint32_t)cwb * WB) +
-                                (wave_n * (CB * 32)) * 128 + frag_row;
+                            const unsigned char *ws = wbuf + (uint32_t)cwb * WB + (wave_n * (CB * 32)) * 128 + frag_row;
                             // LDS addresses of this lane's fragments in the line
                             uint32_t xfa[NBM > 0 ? NBM : 1];
 #pragma unroll
                             for (int a = 0; a < NBM; ++a) {
                                 const int sl = cs_l[a] + (TG == 3 ? t - 1 : 0);
-                                xfa[a] = (uint32_t)sl * 128u + (((uint32_t)((lane >> 5) ^ FC_SWZ(sl)) * 16u) ^ frag_k0);
+                                xfa[a] = (uint32_t)sl * 128u + (uint32_t)((lane >> 5) ^ FC_SWZ(sl)) * 16u;
                             }
-                            constexpr int NLW = WRES ? 0 : WR;
+                            constexpr int NLW = WR;
                             const int nlx = new_line ? XL : 0;
                             const int nld = NLW + nlx;
-                            const int lpk = (nld + KKG - 1) / KKG;
+                            const int lpk = (nld + KK - 1) / KK;
                             Frag<DT> wf[2][CB], xf[2][NBM > 0 ? NBM : 1];
                             if (NBM > 0) {
 #pragma unroll
@@ -626,8 +568,8 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                                 for (int a = 0; a < NBM; ++a) xf[0][a].load(xs, xfa[a]);
                             }
 #pragma unroll
-                            for (int kk = 0; kk < KKG; ++kk) {
-                                if (NBM > 0 && kk + 1 < KKG) {
+                            for (int kk = 0; kk < KK; ++kk) {
+                                if (NBM > 0 && kk + 1 < KK) {
                                     const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
                                     for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
@@ -650,15 +592,12 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
 #pragma unroll
                                     for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[kk & 1][b], xf[kk & 1][a], acc[a][b]);
                             }
-                            if constexpr (!WRES) advance_w();
+                            advance_w();
                             if (new_line) advance_x();
                             cwb = (cwb + 1 == NBW) ? 0 : cwb + 1;
                             if (TG == 1) cxb ^= 1;
                         }
                         if (TG == 3) cxb ^= 1;
-                        const int wrap = (ccc + 1 == cchunks);
-                        ccc = wrap ? 0 : ccc + 1;
-                        ckh += wrap;
                     }
                 };
                 auto run_blocks = [&](auto tg_c) {
@@ -679,48 +618,8 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                 else run_blocks(std::integral_constant<int, 1>{});
 
                 // ---- epilogue ----
-                FC_STAMP(10);
                 wait_vmcnt<0>();
                 __syncthreads();
-                FC_STAMP(11);
-                if constexpr (KS > 1) {
-                    float4 *red = reinterpret_cast<float4 *>(smem_raw);
-                    if (kgrp > 0) {
-#pragma unroll
-                        for (int a = 0; a < PBW; ++a)
-                            if (a < nb_mine) {
-#pragma unroll
-                                for (int b = 0; b < CB; ++b)
-#pragma unroll
-                                    for (int h = 0; h < 4; ++h)
-                                        red[((kgrp - 1) * (PBW * CB * 4) + (a * CB + b) * 4 + h) * GT + gtid] =
-                                            make_float4(acc[a][b][4 * h], acc[a][b][4 * h + 1], acc[a][b][4 * h + 2],
-                                                        acc[a][b][4 * h + 3]);
-                            }
-                    }
-                    __syncthreads();
-                    if (kgrp == 0) {
-#pragma unroll
-                        for (int q = 1; q < KS; ++q)
-#pragma unroll
-                            for (int a = 0; a < PBW; ++a)
-                                if (a < nb_mine) {
-#pragma unroll
-                                    for (int b = 0; b < CB; ++b)
-#pragma unroll
-                                        for (int h = 0; h < 4; ++h) {
-                                            const float4 v =
-                                                red[((q - 1) * (PBW * CB * 4) + (a * CB + b) * 4 + h) * GT + gtid];
-                                            acc[a][b][4 * h] += v.x;
-                                            acc[a][b][4 * h + 1] += v.y;
-                                            acc[a][b][4 * h + 2] += v.z;
-                                            acc[a][b][4 * h + 3] += v.w;
-                                        }
-                                }
-                    }
-                    __syncthreads();
-                }
-                FC_STAMP(12);
                 // the tile leaves through LDS in pieces of 128 rows: one rounding, ReLU, then every
                 // thread stores 16 contiguous bytes of a kept row
                 unsigned char *Os = smem_raw;
@@ -730,7 +629,7 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                 constexpr int NPASS = 128 / RPI;
                 static_assert(NT % PPR == 0 && 128 % RPI == 0, "store walk");
                 for (int c0 = 0; c0 < nblk * 32; c0 += 128) {
-                    if (kgrp == 0) {
+                    {
 #pragma unroll
                         for (int a = 0; a < PBW; ++a) {
                             const int blk = wave_m * nblk_w + a;
@@ -788,7 +687,6 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                     }
                     __syncthreads();
                 }
-                FC_STAMP(13);
             } // tiles
         }     // macro tiles
     }         // units
@@ -799,19 +697,7 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
         for (int p0 = zf_first + zf_workers * 64; p0 < g.m; p0 += zf_workers * 64)
             clear_rows(p0 + lane, __ballot(!label_of(p0 + lane)), dropped);
     }
-#ifdef FC_STAMPS
-    wait_vmcnt<0>();
-    FC_STAMP(14);
-    if (tid == 0) g_line_stamps[blockIdx.x * 16 + 15] = __builtin_amdgcn_s_memrealtime();
-#endif
 }
-
-#ifdef FC_STAMPS
-extern "C" int fc_debug_line_stamps(unsigned long long *host, int n)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_line_stamps), (size_t)n * sizeof(unsigned long long));
-}
-#endif
 
 // ---------------------------------------------------------------------------
 
@@ -848,22 +734,21 @@ static int line_grid()
     return v;
 }
 
-template <int DT, typename TO, int TN, int WM, int WN, int KS, int PBW, int NSUB, int TAPC, bool WRES, int NBW, int MINW>
+template <int DT, typename TO, int TN, int WM, int WN, int PBW, int NSUB, int NBW, int MINW>
 static hipError_t launch_line(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                               const void *w, const float *bias, const int32_t *idx, const int32_t *count, void *out,
                               hipStream_t s)
 {
-    auto kern = k_conv_line<DT, TO, TN, WM, WN, KS, PBW, NSUB, TAPC, WRES, NBW, MINW>;
+    auto kern = k_conv_line<DT, TO, TN, WM, WN, PBW, NSUB, NBW, MINW>;
     constexpr int TM = WM * PBW * 32;
-    const int slabs = g.kh * g.kw * ((g.c_in + 63) / 64);
-    const size_t lds = line_lds_bytes<TM, TN, NSUB>(WRES, WRES ? slabs : NBW);
+    constexpr size_t lds = line_lds_bytes<TM, TN, NSUB, NBW>();
+    static_assert(lds <= 160 * 1024, "LDS of a CU");
     LineDivs dv;
     dv.wo = make_fastdiv((uint32_t)g.wo);
     dv.ho = make_fastdiv((uint32_t)g.ho);
     dv.n_nt = (g.c_out + TN - 1) / TN;
     dv.n_rs_max = line_grid() / dv.n_nt < 1 ? 1 : line_grid() / dv.n_nt;
     dv.rs = make_fastdiv((uint32_t)dv.n_rs_max);
-    if (lds > 160 * 1024) return hipErrorInvalidValue;
     // the dynamic LDS limit is raised once per function and device to the most any layer can ask for
     static std::atomic<uint64_t> attr_devices{0};
     int dev = 0;
@@ -872,7 +757,7 @@ static hipError_t launch_line(const Geom &g, const void *x, const uint8_t *mask_
     const uint64_t dev_bit = 1ull << (dev & 63);
     if (!(attr_devices.load(std::memory_order_acquire) & dev_bit)) {
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                160 * 1024);
+                                (int)lds);
         if (e != hipSuccess) return e;
         attr_devices.fetch_or(dev_bit, std::memory_order_release);
     }
@@ -883,28 +768,20 @@ static hipError_t launch_line(const Geom &g, const void *x, const uint8_t *mask_
 
 #define FC_LINE_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
 
+// 128 output channels per tile, 2 x 4 waves, tiles of up to 8 blocks, three weight slabs in the ring
 template <int DT, typename TO>
-static hipError_t launch_line_shape(const Geom &g, int variant, const void *x, const uint8_t *mask_in,
-                                    const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
-                                    const int32_t *count, void *out, hipStream_t s)
+static hipError_t launch_line_shape(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
+                                    const void *w, const float *bias, const int32_t *idx, const int32_t *count,
+                                    void *out, hipStream_t s)
 {
-    switch (variant) {
-    // 128 output channels per tile, 2 x 4 waves, tiles of up to 8 blocks, weights streamed
-    case 1: return launch_line<DT, TO, 128, 2, 4, 1, 4, 1, 9, false, 3, 2>(FC_LINE_ARGS);
-#ifdef FC_TUNE
-    case 2: return launch_line<DT, TO, 64, 2, 2, 2, 3, 4, 9, true, 3, 2>(FC_LINE_ARGS);
-    case 3: return launch_line<DT, TO, 128, 2, 4, 1, 3, 2, 9, false, 4, 2>(FC_LINE_ARGS);
-    case 4: return launch_line<DT, TO, 128, 2, 4, 1, 4, 1, 9, false, 4, 2>(FC_LINE_ARGS);
-#endif
-    default: return hipErrorInvalidValue;
-    }
+    return launch_line<DT, TO, 128, 2, 4, 4, 1, 3, 2>(FC_LINE_ARGS);
 }
 
-hipError_t launch_conv_line(const Geom &g, int variant, int in_dtype, int out_dtype, const void *x,
+hipError_t launch_conv_line(const Geom &g, int in_dtype, int out_dtype, const void *x,
                             const uint8_t *mask_in, const uint8_t *mask_out, const void *w, const float *bias,
                             const int32_t *idx, const int32_t *count, void *out, hipStream_t s)
 {
-#define FC_LINE_CALL(DT, TO) launch_line_shape<DT, TO>(g, variant, x, mask_in, mask_out, w, bias, idx, count, out, s)
+#define FC_LINE_CALL(DT, TO) launch_line_shape<DT, TO>(g, x, mask_in, mask_out, w, bias, idx, count, out, s)
     if (in_dtype == FC_BF16) {
         if (out_dtype == FC_F32) return FC_LINE_CALL(FC_BF16, float);
         if (out_dtype == FC_FP8) return FC_LINE_CALL(FC_BF16, uint8_t);

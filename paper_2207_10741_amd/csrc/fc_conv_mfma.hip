@@ -40,7 +40,6 @@
 // over several workgroups, which meet through fp32 partial tiles in the workspace; the
 // one that arrives last adds them in a fixed order and writes the tile.
 #include "fc_dma_util.hpp"
-#include <cstdlib>
 #include <atomic>
 
 namespace fc {
@@ -53,22 +52,18 @@ constexpr int kSmallLayerTiles = 64;  // layers with at most this many 128 x 64 
 
 // Bytes of the LDS stage region: NB buffers of (TM + TN) rows for the tap-by-tap loop; with the
 // shared-halo loop (SL > 0) also room for two buffers of SL pixel slots and NBW weight buffers.
-// With KS > 1 wave groups per tile the region also has to hold the fp32 accumulators of the
-// groups after the first (they are added up through LDS at the end of a tile).
-template <int TM, int TN, int NB, int SL, int NBW, int KS>
+template <int TM, int TN, int NB, int SL, int NBW>
 constexpr size_t dma_stage_region_bytes()
 {
     const size_t classic = (size_t)NB * (TM + TN) * 128;
     const size_t halo = SL > 0 ? (size_t)2 * SL * 128 + (size_t)NBW * TN * 128 : 0;
-    const size_t reduce = (size_t)(KS - 1) * TM * TN * sizeof(float);
-    const size_t stage = classic > halo ? classic : halo;
-    return stage > reduce ? stage : reduce;
+    return classic > halo ? classic : halo;
 }
 
-template <int TM, int TN, int NB, int SL, int NBW, int KS>
+template <int TM, int TN, int NB, int SL, int NBW>
 constexpr size_t dma_lds_bytes()
 {
-    return dma_stage_region_bytes<TM, TN, NB, SL, NBW, KS>() + (size_t)TM * 5 * sizeof(int32_t) +
+    return dma_stage_region_bytes<TM, TN, NB, SL, NBW>() + (size_t)TM * 5 * sizeof(int32_t) +
            (SL > 0 ? (size_t)(TM + 3 * SL + 8) * sizeof(int32_t) : 0);
 }
 
@@ -92,17 +87,8 @@ constexpr size_t dma_lds_bytes()
 // CMP: the instances that serve compacted activations (FC_COMPACT_IN / FC_COMPACT_OUT: rows
 // stored in list order).  Separate instances, so that the ordinary ones do not change by a
 // register: the 128 x 64 three-buffer instance loses 20 % with a handful more.
-//
-// KS: wave groups per tile.  Each group is a full WM x WN grid of waves over the same tile and
-// the same LDS stages; group q multiplies the k-steps q * KK/KS ... of every stage, so a SIMD
-// holds KS waves of one tile that take turns at the matrix pipe (one reads fragments while the
-// other multiplies) without any more LDS traffic per multiply.  At the end of a tile the groups
-// after the first hand their fp32 accumulators to the first through LDS, which adds them in
-// group order and runs the epilogue.  For layers with so few tiles that a CU holds one
-// workgroup: there one wave per SIMD leaves the pipe idle more than half of the time.
-template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW, bool CMP,
-          int KS>
-__global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
+template <int DT, typename TO, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL, int NBW, bool CMP>
+__global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const uint16_t *__restrict__ x,
                                                                  const uint8_t *__restrict__ mask_in,
                                                                  const uint8_t *__restrict__ mask_out,
                                                                  const uint16_t *__restrict__ w,
@@ -113,8 +99,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                                                                  float *__restrict__ partials,
                                                                  int32_t *__restrict__ tile_counters)
 {
-    constexpr int NT = WM * WN * 64 * KS;
-    constexpr int GT = WM * WN * 64;   // threads of one wave group
+    constexpr int NT = WM * WN * 64;
     constexpr int RPP = NT / 8;        // rows covered by one pass of wave loads
     constexpr int XR = TM / RPP;       // wave loads per thread for the activation tile
     constexpr int WR = TN / RPP;       // ... for the weight tile
@@ -126,8 +111,6 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
     constexpr int EPP = 16 / ES;                           // elements per 16-byte piece
     constexpr uint32_t KSTEP = kStepBytes<DT>;             // bytes of a row per matrix instruction
     constexpr int KK = kStageBytes / (int)KSTEP;           // matrix instructions per stage and block pair
-    constexpr int KKG = KK / KS;                           // ... of which a wave group takes this many
-    static_assert(KS >= 1 && KK % KS == 0, "the k-steps of a stage are dealt out evenly to the wave groups");
     constexpr int ODT = DT == FC_FP8 ? FC_BF16 : DT;       // 16-bit output format
     // register sets of operand fragments: the 16-bit types fetch step kk + 1 while step kk is
     // multiplied; fp8 fragments are twice as large and its instructions twice as long, so one set,
@@ -140,7 +123,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
     static_assert(TM <= NT && TN <= NT, "set-up assumes one thread per row / channel");
     static_assert(NB >= 2 && (NB - 1) * L <= 63, "vmcnt is a 6-bit counter");
     constexpr bool HALO = SL > 0;
-    constexpr size_t REGION = dma_stage_region_bytes<TM, TN, NB, SL, NBW, KS>();
+    constexpr size_t REGION = dma_stage_region_bytes<TM, TN, NB, SL, NBW>();
     static_assert(!HALO || (TAPC == 9 && SL % RPP == 0 && SL <= NT && SL > TM && (NBW == 2 || NBW == 3)),
                   "shared-halo loop: 3x3 kernels, whole load passes, one thread per slot");
 
@@ -161,9 +144,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw); // LDS byte address of the stage buffers
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int kgrp = KS > 1 ? wave / (WM * WN) : 0;       // wave group
-    const int gwave = wave - kgrp * (WM * WN), gtid = tid - kgrp * GT;
-    const int wave_m = gwave % WM, wave_n = gwave / WM;
+    const int wave_m = wave % WM, wave_n = wave / WM;
     const int slot = tid & 7, prow = tid >> 3;
 
     // Kept rows.  With a list they are given.  Without one but with a mask (the launcher does
@@ -215,8 +196,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
     // rows, so the swizzle term depends on the lane only
     constexpr uint32_t HALF = KSTEP / 32u; // piece index of the upper half-wave within a step
     const uint32_t frag_row = (uint32_t)(lane & 31) * 128u;
-    const uint32_t frag_k0 = (uint32_t)(kgrp * KKG) * KSTEP; // byte offset of this group's first k-step in a row
-    const uint32_t frag_t16 = ((uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(lane & 31)) * 16u) ^ frag_k0;
+    const uint32_t frag_t16 = (uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(lane & 31)) * 16u;
 
     // Tile order: all row tiles of channel tile 0, then of channel tile 1, ...  Workgroups
     // are dispatched round-robin over the 8 XCDs, each with its own L2, so XCD j takes the
@@ -358,7 +338,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int co = co0 + wave_n * WTN + b * 32 + q * 8 + (lane >> 5) * 4;
-                bias_q[b][q] = (bias && split == 0 && kgrp == 0 && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
+                bias_q[b][q] = (bias && split == 0 && co < g.c_out) ? *reinterpret_cast<const float4 *>(bias + co)
                                                                     : make_float4(0.f, 0.f, 0.f, 0.f);
             }
         __syncthreads();
@@ -523,7 +503,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
                     const int sl = cs + t - 1;
-                    xfa[a][t] = (uint32_t)sl * 128u + (((uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(sl)) * 16u) ^ frag_k0);
+                    xfa[a][t] = (uint32_t)sl * 128u + (uint32_t)(((lane >> 5) * HALF) ^ FC_SWZ(sl)) * 16u;
                 }
             }
             const int groups = g.kh * cchunks;
@@ -600,15 +580,15 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                     const unsigned char *ws =
                         stage0 + 2u * XB + (uint32_t)cwb * WB + (wave_n * WTN) * 128 + frag_row;
                     const int nld = t == 0 ? WR + XL : WR;
-                    const int lpk = t == 0 ? (WR + XL + KKG - 1) / KKG : (WR + KKG - 1) / KKG;
+                    const int lpk = t == 0 ? (WR + XL + KK - 1) / KK : (WR + KK - 1) / KK;
                     Frag<DT> wf[FB][CB], xf[FB][PB];
 #pragma unroll
                     for (int b = 0; b < CB; ++b) wf[0][b].load(ws + b * 4096, frag_t16);
 #pragma unroll
                     for (int a = 0; a < PB; ++a) xf[0][a].load(xs, xfa[a][t]);
 #pragma unroll
-                    for (int kk = 0; kk < KKG; ++kk) {
-                        if (FB == 2 && kk + 1 < KKG) {
+                    for (int kk = 0; kk < KK; ++kk) {
+                        if (FB == 2 && kk + 1 < KK) {
                             const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
                             for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
@@ -623,7 +603,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
 #pragma unroll
                             for (int b = 0; b < CB; ++b)
                                 acc[a][b] = mfma32<DT>(wf[kk % FB][b], xf[kk % FB][a], acc[a][b]);
-                        if (FB == 1 && kk + 1 < KKG) {
+                        if (FB == 1 && kk + 1 < KK) {
                             __builtin_amdgcn_sched_barrier(0);
                             const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
@@ -696,7 +676,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
             FC_ISSUE_LOADS(0, L)
         }
 
-        constexpr int LPK = (L + KKG - 1) / KKG; // wave loads issued per k-step of this wave
+        constexpr int LPK = (L + KK - 1) / KK; // wave loads issued per 16-wide k-step
         int cbuf = 0;                          // buffer of the stage being multiplied
         for (int s = 0; s < nst; ++s) {
             FC_PREPARE_STAGE()          // stage s + NB - 1: addresses only
@@ -710,8 +690,8 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
 #pragma unroll
             for (int a = 0; a < PB; ++a) xf[0][a].load(xs + a * 4096, frag_t16);
 #pragma unroll
-            for (int kk = 0; kk < KKG; ++kk) {
-                if (FB == 2 && kk + 1 < KKG) {
+            for (int kk = 0; kk < KK; ++kk) {
+                if (FB == 2 && kk + 1 < KK) {
                     const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
                     for (int b = 0; b < CB; ++b) wf[(kk + 1) & 1][b].load(ws + b * 4096, o);
@@ -728,7 +708,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                 for (int a = 0; a < PB; ++a)
 #pragma unroll
                     for (int b = 0; b < CB; ++b) acc[a][b] = mfma32<DT>(wf[kk % FB][b], xf[kk % FB][a], acc[a][b]);
-                if (FB == 1 && kk + 1 < KKG) {
+                if (FB == 1 && kk + 1 < KK) {
                     __builtin_amdgcn_sched_barrier(0);
                     const uint32_t o = ((uint32_t)(kk + 1) * KSTEP) ^ frag_t16;
 #pragma unroll
@@ -747,40 +727,6 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
         // lane stores 16 contiguous bytes.  First let every LDS write in flight land. ----
         wait_vmcnt<0>();
         __syncthreads();
-        if constexpr (KS > 1) {
-            // the wave groups after the first hand over their accumulators (accumulator order:
-            // every lane writes and reads whole 16-byte pieces at consecutive addresses); the
-            // first group adds them in group order
-            float4 *red = reinterpret_cast<float4 *>(smem_raw);
-            if (kgrp > 0) {
-#pragma unroll
-                for (int a = 0; a < PB; ++a)
-#pragma unroll
-                    for (int b = 0; b < CB; ++b)
-#pragma unroll
-                        for (int h = 0; h < 4; ++h)
-                            red[((kgrp - 1) * (PB * CB * 4) + (a * CB + b) * 4 + h) * GT + gtid] = make_float4(
-                                acc[a][b][4 * h], acc[a][b][4 * h + 1], acc[a][b][4 * h + 2], acc[a][b][4 * h + 3]);
-            }
-            __syncthreads();
-            if (kgrp == 0) {
-#pragma unroll
-                for (int q = 1; q < KS; ++q)
-#pragma unroll
-                    for (int a = 0; a < PB; ++a)
-#pragma unroll
-                        for (int b = 0; b < CB; ++b)
-#pragma unroll
-                            for (int h = 0; h < 4; ++h) {
-                                const float4 v = red[((q - 1) * (PB * CB * 4) + (a * CB + b) * 4 + h) * GT + gtid];
-                                acc[a][b][4 * h] += v.x;
-                                acc[a][b][4 * h + 1] += v.y;
-                                acc[a][b][4 * h + 2] += v.z;
-                                acc[a][b][4 * h + 3] += v.w;
-                            }
-            }
-            __syncthreads(); // the epilogue reuses this part of LDS
-        }
         if (S > 1) {
             // Park this unit's fp32 partial tile (accumulator order, coalesced), then count
             // in; the unit that arrives last adds the S partials in split order - a fixed
@@ -793,22 +739,20 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
             const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
                 partials, 0, (uint32_t)((size_t)kSplitGrid * kSplitTileFloats * sizeof(float)), 0x00020000);
             const uint32_t mine = (uint32_t)unit * (uint32_t)(TM * TN * 4);
-            if (kgrp == 0) {
 #pragma unroll
-                for (int a = 0; a < PB; ++a)
+            for (int a = 0; a < PB; ++a)
 #pragma unroll
-                    for (int b = 0; b < CB; ++b)
+                for (int b = 0; b < CB; ++b)
 #pragma unroll
-                        for (int h = 0; h < 4; ++h) {
-                            u32x4_t v;
-                            v.x = __float_as_uint(acc[a][b][4 * h]);
-                            v.y = __float_as_uint(acc[a][b][4 * h + 1]);
-                            v.z = __float_as_uint(acc[a][b][4 * h + 2]);
-                            v.w = __float_as_uint(acc[a][b][4 * h + 3]);
-                            __builtin_amdgcn_raw_buffer_store_b128(
-                                v, rp, mine + (uint32_t)(((a * CB + b) * 4 + h) * GT + gtid) * 16u, 0, kDeviceScope);
-                        }
-            }
+                    for (int h = 0; h < 4; ++h) {
+                        u32x4_t v;
+                        v.x = __float_as_uint(acc[a][b][4 * h]);
+                        v.y = __float_as_uint(acc[a][b][4 * h + 1]);
+                        v.z = __float_as_uint(acc[a][b][4 * h + 2]);
+                        v.w = __float_as_uint(acc[a][b][4 * h + 3]);
+                        __builtin_amdgcn_raw_buffer_store_b128(
+                            v, rp, mine + (uint32_t)(((a * CB + b) * 4 + h) * NT + tid) * 16u, 0, kDeviceScope);
+                    }
             wait_vmcnt<0>(); // this thread's partial stores have been acknowledged
             __syncthreads(); // ... and every other thread's
             if (tid == 0)
@@ -825,7 +769,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                 for (int b = 0; b < CB; ++b)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-            for (int sp = 0; sp < S && kgrp == 0; ++sp) {
+            for (int sp = 0; sp < S; ++sp) {
                 const uint32_t theirs = (uint32_t)(tile * S + sp) * (uint32_t)(TM * TN * 4);
 #pragma unroll
                 for (int a = 0; a < PB; ++a)
@@ -834,7 +778,7 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
 #pragma unroll
                         for (int h = 0; h < 4; ++h) {
                             const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(
-                                rp, theirs + (uint32_t)(((a * CB + b) * 4 + h) * GT + gtid) * 16u, 0, kDeviceScope);
+                                rp, theirs + (uint32_t)(((a * CB + b) * 4 + h) * NT + tid) * 16u, 0, kDeviceScope);
                             acc[a][b][4 * h] += __uint_as_float(v.x);
                             acc[a][b][4 * h + 1] += __uint_as_float(v.y);
                             acc[a][b][4 * h + 2] += __uint_as_float(v.z);
@@ -845,7 +789,6 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
         constexpr int OP = TN * (int)sizeof(TO) + 16;
         static_assert((size_t)TM * OP <= REGION, "output tile fits");
         unsigned char *Os = smem_raw;
-        if (kgrp == 0) {
 #pragma unroll
         for (int a = 0; a < PB; ++a) {
             const int r = wave_m * WTM + a * 32 + (lane & 31);
@@ -880,7 +823,6 @@ __global__ __launch_bounds__(WM *WN * 64 * KS, MINW) void k_conv_dma(Geom g, con
                         *reinterpret_cast<uint2 *>(Os + r * OP + cl * 2) = pk;
                     }
                 }
-        }
         }
         __syncthreads();
         constexpr int PPR = TN * (int)sizeof(TO) / 16;
@@ -940,14 +882,13 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
 }
 #endif
 
-template <int DT, typename TO, bool CMP, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2,
-          int KS = 1>
+template <int DT, typename TO, bool CMP, int TM, int TN, int WM, int WN, int TAPC, int NB, int MINW, int SL = 0, int NBW = 2>
 static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                              const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                              void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW, CMP, KS>;
-    constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW, KS>();
+    auto kern = k_conv_dma<DT, TO, TM, TN, WM, WN, TAPC, NB, MINW, SL, NBW, CMP>;
+    constexpr size_t lds = dma_lds_bytes<TM, TN, NB, SL, NBW>();
     // more than 64 KB of dynamic LDS has to be allowed once per function and device; two
     // threads that both find the bit clear both set the attribute, which is harmless
     static std::atomic<uint64_t> attr_devices{0};
@@ -965,7 +906,7 @@ static hipError_t launch_dma(const Geom &g, const void *x, const uint8_t *mask_i
     const int64_t cap = 256 * 8;
     int blocks = (int)((max_tiles < cap ? max_tiles : cap) + 7) & ~7; // a multiple of the XCD count
     if (partials) blocks = kSplitGrid; // few tiles: enough workgroups for the K-split to fill the chip
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64 * KS), lds, s, g, (const uint16_t *)x, mask_in, mask_out,
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(WM * WN * 64), lds, s, g, (const uint16_t *)x, mask_in, mask_out,
                        (const uint16_t *)w, bias, idx, count, (TO *)out, partials, tile_counters);
     return hipGetLastError();
 }
@@ -977,51 +918,6 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
                               const void *w, const float *bias, const int32_t *idx, const int32_t *count,
                               void *out, float *partials, int32_t *tile_counters, hipStream_t s)
 {
-#ifdef FC_TUNE
-    // tuning builds only: pick a tile configuration by number (bf16 in/out, 3x3 only)
-    if constexpr (DT == FC_BF16 && TAPC == 9 && !CMP) {
-        static const int cfg = getenv("FC_TILE_CONFIG") ? atoi(getenv("FC_TILE_CONFIG")) : 0;
-        switch (cfg) {
-        case 20: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 4, 1>(FC_ARGS);
-        case 21: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
-        case 22: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
-        case 23: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
-        case 24: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 4, 1>(FC_ARGS);
-        case 25: return launch_dma<DT, TO, CMP, 256, 128, 2, 2, TAPC, 3, 1>(FC_ARGS);
-        case 26: return launch_dma<DT, TO, CMP, 256, 128, 4, 1, TAPC, 3, 1>(FC_ARGS);
-        case 27: return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
-        case 28: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
-        case 29: return launch_dma<DT, TO, CMP, 256, 64, 4, 1, TAPC, 2, 1>(FC_ARGS);
-        case 30: return launch_dma<DT, TO, CMP, 128, 64, 4, 1, TAPC, 2, 3>(FC_ARGS);
-        case 31: return launch_dma<DT, TO, CMP, 64, 64, 2, 1, TAPC, 3, 4>(FC_ARGS);
-        case 41: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
-        case 44: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
-        case 45: return launch_dma<DT, TO, CMP, 256, 128, 4, 2, TAPC, 2, 2, 320, 3>(FC_ARGS);
-        case 46: return launch_dma<DT, TO, CMP, 256, 128, 4, 2, TAPC, 2, 2, 320, 2>(FC_ARGS);
-        case 60: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2, 192, 2, 2>(FC_ARGS);
-        case 61: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 3, 2, 0, 2, 2>(FC_ARGS);
-        case 62: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 192, 3, 2>(FC_ARGS);
-        case 63: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 0, 2, 2>(FC_ARGS);
-        case 64: return launch_dma<DT, TO, CMP, 256, 64, 4, 1, TAPC, 2, 2, 320, 3, 2>(FC_ARGS);
-        case 66: return launch_dma<DT, TO, CMP, 256, 128, 4, 1, TAPC, 2, 2, 320, 2, 2>(FC_ARGS);
-        default: break;
-        }
-    }
-    if constexpr (DT == FC_BF16 && sizeof(TO) == 2 && TAPC == 1 && !CMP) {
-        static const int cfg1 = getenv("FC_TILE_CONFIG_1X1") ? atoi(getenv("FC_TILE_CONFIG_1X1")) : 0;
-        switch (cfg1) {
-        case 22: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2>(FC_ARGS);
-        case 23: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2>(FC_ARGS);
-        case 28: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 3>(FC_ARGS);
-        case 27: return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 4, 2>(FC_ARGS);
-        case 50: return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 2, 4>(FC_ARGS);
-        case 51: return launch_dma<DT, TO, CMP, 64, 64, 2, 2, TAPC, 2, 5>(FC_ARGS);
-        case 52: return launch_dma<DT, TO, CMP, 256, 64, 4, 1, TAPC, 2, 2>(FC_ARGS);
-        case 53: return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 3>(FC_ARGS);
-        default: break;
-        }
-    }
-#endif
     // 128 x 128 tiles when there are enough of them to give every CU two workgroups;
     // otherwise 128 x 64, which doubles the tile count (the kept count is not known here,
     // so the dense row count decides)

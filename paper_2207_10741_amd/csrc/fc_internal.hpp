@@ -287,11 +287,10 @@ hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const vo
 hipError_t launch_calibrate_mfma(int dtype, int iters, int blocks, float *sink, hipStream_t s);
 hipError_t launch_calibrate_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 
-// One-workgroup-per-CU matrix-core path for 3x3 layers (see fc_conv_line.hip).  variant 1:
-// 128 output channels per tile, weights streamed; variant 2: up to 64 output channels, the
-// weight tensor resident in LDS.  Needs the kept list (or no mask at all).
+// One-workgroup-per-CU matrix-core path for 3x3 layers (see fc_conv_line.hip): 128 output
+// channels per tile.  Needs the kept list (or no mask at all).
 bool conv_line_supported(const Geom &g, int in_dtype, int out_dtype);
-hipError_t launch_conv_line(const Geom &g, int variant, int in_dtype, int out_dtype, const void *x,
+hipError_t launch_conv_line(const Geom &g, int in_dtype, int out_dtype, const void *x,
                             const uint8_t *mask_in, const uint8_t *mask_out, const void *w, const float *bias,
                             const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
