@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
 {
     static_assert(WM * WN == kLineWaves, "eight waves");
     static_assert(DT == FC_BF16 || DT == FC_F16, "16-bit storage");
-    static_assert(NBW == 3 || NBW == 4, "weight ring");
+    static_assert(NBW >= 3, "weight ring");
     constexpr int NT = kLineThreads;
     constexpr int RPP = kLineRPP;
     constexpr int TM = WM * PBW * 32;          // most rows of a tile
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(kLineThreads, MINW) void k_conv_line(Geom g, LineDi
                                 wait_vmcnt<0>(); // (the first slabs went out before the set-up's own loads)
                             } else {
                                 if (TG == 1) wait_vmcnt<WR>();
-                                else if (t == 0) wait_vmcnt<(NBW - 2) * WR>();
+                                else if (t == 0) wait_vmcnt<(NBW - 2 < 2 ? NBW - 2 : 2) * WR>(); // (behind this group's line: at most two slabs)
                                 else wait_vmcnt<(NBW - 2) * WR + XL>();
                             }
                             __syncthreads();
