@@ -64,13 +64,16 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
 
 // Does the one-workgroup-per-CU kernel serve this layer?  Focused 3x3 layers of 65 .. 128 output
 // channels whose kept rows come to at most one tile per CU (eight 32-row blocks on each of 256
-// CUs).  There it deals the kept rows out evenly, so the time follows the kept share instead of
-// moving in steps of whole tile rounds.  Layers small enough to rank their rows inside the tiled
-// kernel stay there whether or not the caller brings a list (one kernel, one summation order per
-// layer).
+// CUs) and whose irrelevant rows are left unwritten (FC_SKIP_ZERO_FILL: a layer inside a chain).
+// There it deals the kept rows out evenly, one round whatever the kept count (12 % faster than the
+// tiled kernel at a kept share of one half).  With the zero-fill in the launch the tiled kernel
+// stays: its idle workgroups clear rows beside the tiles, while a launch that keeps every CU
+// busy can only clear them after its tiles (measured: no gain at one half, slower elsewhere).
+// Layers small enough to rank their rows inside the tiled kernel stay there as well, whether
+// or not the caller brings a list (one kernel, one summation order per layer).
 bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
 {
-    if (!focused || !conv_line_supported(g, in_dtype, out_dtype)) return false;
+    if (!focused || !(g.flags & FC_SKIP_ZERO_FILL) || !conv_line_supported(g, in_dtype, out_dtype)) return false;
     if (g.m <= kInlineRankPositions) return false;
     if (g.c_out <= 64 || g.c_out > 128) return false;
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;

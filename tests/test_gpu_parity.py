@@ -461,6 +461,40 @@ def test_shared_halo_precomputed_list_and_16bit_output(layer):
     assert G.rel_err(G.to_f64(a), want, keep) <= TOL_F32_OUT
 
 
+# Chained 3x3 layers (irrelevant rows left unwritten) of 65 .. 128 output channels and up to 65536
+# positions run on the one-workgroup-per-CU kernel: kept rows dealt out in 32-row blocks, one
+# pixel line per tile, tap by tap where a tile's line would not fit or the geometry has none
+CHAINED_LINE_LAYERS = [
+    # n, h, w, ci, co, k, s, p, d
+    (2, 40, 56, 64, 128, 3, 1, 1, 1),               # 4480 positions: a block or two per workgroup
+    (8, 96, 64, 64, 128, 3, 1, 1, 1),               # 49152 positions: several blocks per workgroup
+    (16, 64, 64, 128, 128, 3, 1, 1, 1),             # the bench shape: two channel chunks, eight blocks when dense
+    (3, 47, 61, 72, 96, 3, 1, 1, 1),                # channel tails on both sides, ragged rows
+    (2, 61, 47, 64, 128, 3, (2, 1), (0, 2), (2, 1)),  # vertical stride and dilation, wide padding
+    (2, 63, 65, 64, 128, 3, 2, 1, 1),               # stride 2: no shared line, tap by tap
+    (1, 70, 70, 64, 104, 3, 1, 1, 2),               # dilation 2: tap by tap
+]
+
+
+@pytest.mark.parametrize("layer", CHAINED_LINE_LAYERS)
+@pytest.mark.parametrize("mask_kind,irr", [("objects", 0.48), ("bernoulli", 0.5), ("mixed", 0.5), ("objects", 0.95),
+                                           ("objects", 0.0), ("objects", 1.0)])
+def test_chained_layers_on_the_one_workgroup_per_cu_kernel(layer, mask_kind, irr):
+    torch = G.torch_mod()
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=irr, seed=209,
+                                 flags_extra=B.SKIP_ZERO_FILL, precomputed=True)
+    got = G.to_f64(out)
+    if keep.any():
+        rms = float(np.sqrt(np.mean(np.square(want[keep]))))
+        assert float(np.abs(got[keep] - want[keep]).max()) / rms <= TOL_F32_OUT
+    assert (got[~keep] == 7.0).all()                    # irrelevant rows untouched
+    # 16-bit outputs: the same sums, rounded once
+    o16, _, _ = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=irr, seed=209, flags_extra=B.SKIP_ZERO_FILL,
+                           precomputed=True, out_dtype=synth.BF16)
+    k = torch.from_numpy(keep).to(G.dev())
+    assert torch.equal(o16[k], out[k].to(o16.dtype))
+
+
 # layers with at most 4 input channels run on the matrix cores through an element-wise gather
 STEM_LAYERS = [
     # n, h, w, ci, co, k, s, p, d
