@@ -534,7 +534,7 @@ def main():
     ap.add_argument("--peaks", action="store_true",
                     help="only measure this box's matrix-core and streaming-copy rates (the on-box rooflines)")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (calibrates the "
+                    help="for rocprofv3 --pmc runs: one 256 MiB streaming copy (fc_calibrate_copy: calibrates the "
                          "FETCH_SIZE / WRITE_SIZE counters), then --steps eager steps; no timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -612,13 +612,14 @@ def main():
     if args.traffic_probe:
         src = torch.ones((64 << 20,), dtype=torch.int32, device="cuda:0")   # 256 MiB
         dst = torch.empty_like(src)
-        torch.add(src, 0, out=dst)               # reads 256 MiB, writes 256 MiB
+        B.calibrate_copy(src, dst)               # k_calibrate_copy: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         for _ in range(args.steps):
             for L in layers:
-                L["call_focused"]()
+                L["call_conv_only"]()        # the launch the step makes: kept list given, zero-fill included
             torch.cuda.synchronize()
         print(json.dumps({"traffic_probe": True, "copy_bytes_each_way": src.numel() * 4, "steps": args.steps,
+                          "kernel_source_hash": kernel_source_hash(),
                           "kept_rows": {L["name"]: L["kept"] for L in layers}}))
         return
 
