@@ -102,6 +102,43 @@ def calibrate_peaks(torch, B, in_dtype):
                    "streaming copy of 512 MiB (read + written bytes); best of 4 launches each"}
 
 
+ISSUE_ITEMS = ("two matrix instructions only", "+ one 1 KB load into LDS", "+ twelve dependent integer instructions",
+               "+ one 16-byte-per-lane LDS read (the next operand)", "+ the LDS load and the LDS read")
+
+
+def issue_probe(torch, B):
+    """What a SIMD can do beside its matrix instructions (fc_calibrate_issue): every wave runs steps
+    of two 32x32x16 bf16 matrix instructions plus one item, with 1, 2 and 4 waves per SIMD on
+    every CU.  Reported: wall time of the launch per step (HIP events, best of three; a step of
+    the launch is one step of every wave) and the shader cycles per step that the first wave of
+    a workgroup counted for itself (the oldest wave is served first, so with several waves per
+    SIMD it finishes before the others)."""
+    dev = torch.device("cuda:0")
+    src = torch.ones((1 << 18,), dtype=torch.int32, device=dev)     # 1 MiB
+    steps, blocks = 4000, torch.cuda.get_device_properties(0).multi_processor_count
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    table = {}
+    for waves in (1, 2, 4):
+        row = {}
+        for mode, name in enumerate(ISSUE_ITEMS):
+            best, cyc = None, None
+            for _ in range(3):
+                a, b = ev(), ev()
+                a.record()
+                cyc = B.calibrate_issue(mode, waves, steps, blocks, src)
+                b.record()
+                torch.cuda.synchronize()
+                t = a.elapsed_time(b) * 1e6 / steps
+                best = t if best is None else min(best, t)
+            row[name] = {"ns_per_step": round(best, 1),
+                         "ns_per_matrix_instruction": round(best / (2 * waves), 2),
+                         "first_wave_cycles_per_step": round(float(cyc.double().mean().item()) / steps, 1)}
+        table["%d waves per SIMD" % waves] = row
+    return {"per_step": table, "steps": steps, "workgroups": blocks,
+            "how": "every wave: steps of two independent 32x32x16 bf16 matrix instructions plus the item; one launch, "
+                   "HIP events around it (launch overhead of about 10 us included), best of three"}
+
+
 def build_sweep_layers(torch, B, synth, workloads, irrelevant, mask_kind, batch, in_dtype=None, out_dtype=None):
     """Device tensors for the four ResNet-50 3x3 shapes (bf16 storage, or E4M3 bytes with
     bf16 or E4M3 outputs)."""
@@ -554,6 +591,7 @@ def main():
         out = {"peaks": True}
         for name, code in (("bf16", B.BF16), ("fp8", B.FP8)):
             out[name] = calibrate_peaks(torch, B, code)
+        out["issue"] = issue_probe(torch, B)
         print(json.dumps(out))
         return
     if args.masks:

@@ -345,6 +345,21 @@ int32_t fc_calibrate_mfma(int32_t dtype, int32_t iters, int32_t blocks, void *si
                           void *stream);
 int32_t fc_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream);
 
+/* What a wave can issue beside its matrix instructions (measurement support as above; it is
+ * what decides how many waves per SIMD the layer kernels need).  One launch of `blocks`
+ * workgroups with `waves_per_simd` (1, 2 or 4) waves on every SIMD; every wave runs `steps`
+ * steps of two independent 32x32x16 bf16 matrix instructions plus the item `mode` names:
+ *   0 nothing, 1 one 1 KB load from `src` into LDS, 2 twelve dependent integer instructions,
+ *   3 one 16-byte-per-lane LDS read of the next operand, 4 items 1 and 3.
+ *   src       device, at least 1 MiB (src_bytes; else FC_ERR_WORKSPACE), 16-byte aligned, read only
+ *   cycles    device, `blocks` 64-bit integers: shader cycles the loop took in the first wave
+ *             of every workgroup (divide by `steps`)
+ *   sink      device, `blocks` floats, never written in practice
+ * Errors: FC_ERR_NULL, FC_ERR_SHAPE (mode, waves_per_simd, steps or blocks out of range),
+ * FC_ERR_WORKSPACE, FC_ERR_ALIGN, FC_ERR_HIP. */
+int32_t fc_calibrate_issue(int32_t mode, int32_t waves_per_simd, int32_t steps, int32_t blocks,
+                           const void *src, size_t src_bytes, int64_t *cycles, void *sink, void *stream);
+
 /* Helper for conv stacks with pooling between layers (not part of the paper's
  * method): NHWC max-pool over the full tensor, window k, stride s, padding p
  * (padding never wins the max).  x/out device, dtype as given. */

@@ -23,7 +23,7 @@ FUNCTIONS = ("fc_status_string", "fc_out_dims", "fc_workspace_bytes", "fc_compac
              "fc_mask_downsample", "fc_mask_downsample_rule", "fc_active_index_compact",
              "fc_compact_tiled_workspace_bytes", "fc_active_index_compact_tiled", "fc_mask_pyramid_dims",
              "fc_mask_pyramid_workspace_bytes", "fc_mask_pyramid", "fc_focused_conv2d", "fc_focused_gconv2d",
-             "fc_noalloc_init", "fc_focused_conv2d_noalloc", "fc_calibrate_mfma", "fc_calibrate_copy",
+             "fc_noalloc_init", "fc_focused_conv2d_noalloc", "fc_calibrate_mfma", "fc_calibrate_copy", "fc_calibrate_issue",
              "fc_packed_mask_bytes", "fc_mask_pack", "fc_mask_downsample_packed", "fc_active_index_compact_packed",
              "fc_mask_pyramid_packed",
              "fc_expand_group_weights",
@@ -121,6 +121,8 @@ def lib():
         L.fc_calibrate_mfma.argtypes = [i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.fc_calibrate_copy.restype = i32
         L.fc_calibrate_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.fc_calibrate_issue.restype = i32
+        L.fc_calibrate_issue.argtypes = [i32, i32, i32, i32, vp, ctypes.c_size_t, vp, vp, vp]
         L.fc_focused_gconv2d.restype = i32
         L.fc_focused_gconv2d.argtypes = [ctypes.POINTER(ConvDesc), i32] + [vp] * 9 + [ctypes.c_size_t, vp]
         L.fc_expand_group_weights.restype = i32
@@ -504,6 +506,18 @@ def calibrate_copy(src, dst, stream=None) -> int:
     nbytes = src.numel() * src.element_size()
     _check(lib().fc_calibrate_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "fc_calibrate_copy")
     return nbytes
+
+
+def calibrate_issue(mode: int, waves_per_simd: int, steps: int, blocks: int, src, stream=None):
+    """fc_calibrate_issue: enqueues the issue probe; returns the device tensor of per-workgroup
+    shader cycles (int64, `blocks` entries) of the whole loop."""
+    torch = _torch()
+    _require_cuda(src)
+    cycles = torch.zeros((blocks,), dtype=torch.int64, device=src.device)
+    sink = torch.zeros((blocks,), dtype=torch.float32, device=src.device)
+    _check(lib().fc_calibrate_issue(mode, waves_per_simd, steps, blocks, _ptr(src), src.numel() * src.element_size(),
+                                    _ptr(cycles), _ptr(sink), _stream(stream)), "fc_calibrate_issue")
+    return cycles
 
 
 def ready_workspace(workspace):

@@ -675,6 +675,20 @@ int32_t fc_calibrate_copy(const void *src, void *dst, size_t bytes, void *stream
     return launch_calibrate_copy(src, dst, bytes, (hipStream_t)stream) == hipSuccess ? FC_OK : FC_ERR_HIP;
 }
 
+int32_t fc_calibrate_issue(int32_t mode, int32_t waves_per_simd, int32_t steps, int32_t blocks, const void *src,
+                           size_t src_bytes, int64_t *cycles, void *sink, void *stream)
+{
+    if (!src || !cycles || !sink) return FC_ERR_NULL;
+    if (mode < 0 || mode > 4 || (waves_per_simd != 1 && waves_per_simd != 2 && waves_per_simd != 4)) return FC_ERR_SHAPE;
+    if (steps <= 0 || blocks <= 0 || blocks > 65536) return FC_ERR_SHAPE;
+    if (src_bytes < ((size_t)1 << 20)) return FC_ERR_WORKSPACE;
+    if (!aligned16(src)) return FC_ERR_ALIGN;
+    return launch_calibrate_issue(mode, waves_per_simd, steps, blocks, src, (long long *)cycles, (float *)sink,
+                                  (hipStream_t)stream) == hipSuccess
+               ? FC_OK
+               : FC_ERR_HIP;
+}
+
 int32_t fc_maxpool2d(const void *x, int32_t n, int32_t h, int32_t w, int32_t c, int32_t dtype, int32_t k,
                      int32_t stride, int32_t pad, void *out, void *stream)
 {

@@ -286,6 +286,10 @@ hipError_t launch_conv_mfma(const Geom &g, int in_dtype, int out_dtype, const vo
 // `iters` rounds of eight matrix instructions; a streaming copy of `bytes` bytes.
 hipError_t launch_calibrate_mfma(int dtype, int iters, int blocks, float *sink, hipStream_t s);
 hipError_t launch_calibrate_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
+// `steps` steps of two matrix instructions plus item `mode` per wave, 1, 2 or 4 waves per SIMD;
+// cycles[block] = shader cycles of the loop.
+hipError_t launch_calibrate_issue(int mode, int waves_per_simd, int steps, int blocks, const void *src,
+                                  long long *cycles, float *sink, hipStream_t s);
 
 // One-workgroup-per-CU matrix-core path for 3x3 layers (see fc_conv_line.hip): 128 output
 // channels per tile.  Needs the kept list (or no mask at all).

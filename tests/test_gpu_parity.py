@@ -627,3 +627,21 @@ def test_maxpool_helper():
             kd = torch.from_numpy(keep != 0).to(G.dev())
             assert torch.equal(canary[kd], got[kd])
             assert not canary[~kd].view(torch.int16).any()
+
+
+def test_issue_probe_runs_and_counts_cycles():
+    """fc_calibrate_issue: every mode and wave count runs, reports positive cycle counts, and two
+    matrix instructions cannot take less than their 2 x 8 passes of four cycles."""
+    torch = G.torch_mod()
+    src = torch.ones((1 << 18,), dtype=torch.int32, device=G.dev())
+    for waves in (1, 2, 4):
+        for mode in range(5):
+            cyc = B.calibrate_issue(mode, waves, 200, 8, src)
+            torch.cuda.synchronize()
+            per_step = cyc.double().cpu().numpy() / 200
+            assert (per_step >= 40).all() and (per_step < 5000).all()
+    with pytest.raises(B.FcError):
+        B.calibrate_issue(7, 1, 10, 1, src)
+    with pytest.raises(B.FcError):
+        B.calibrate_issue(0, 3, 10, 1, src)
+
