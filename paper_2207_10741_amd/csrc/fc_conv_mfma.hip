@@ -40,6 +40,7 @@
 // over several workgroups, which meet through fp32 partial tiles in the workspace; the
 // one that arrives last adds them in a fixed order and writes the tile.
 #include "fc_dma_util.hpp"
+#include <type_traits>
 #include <atomic>
 
 namespace fc {
@@ -486,13 +487,21 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             constexpr int XL = HALO ? SL / RPP : 1;
             constexpr uint32_t XB = (uint32_t)SL * 128u;
             constexpr uint32_t WB = (uint32_t)TN * 128u;
+            // A slot's offset is that of its first kernel row, which may lie above or left of the
+            // image; the load instruction adds the kernel row's offset itself and range-checks
+            // the per-lane part alone, so that part must not be negative: the line is gathered
+            // through a descriptor that starts (pad_h rows + pad_w pixels) before the tensor.
+            // (Nothing in front of the tensor is ever read: those taps are switched off.)
+            const uint32_t xbias = (uint32_t)(g.ph * g.w + g.pw) * (uint32_t)g.c_in * (uint32_t)ES;
+            const u32x4_t rsrc_xb = make_rsrc_words(reinterpret_cast<const unsigned char *>(x) - xbias,
+                                                    (uint32_t)g.n * g.h * g.w * g.c_in * (uint32_t)ES + xbias);
             uint32_t hxoff[XL], hxbits[XL];
             int hxgp[XL];
 #pragma unroll
             for (int j = 0; j < XL; ++j) {
                 const int sl = prow + j * RPP;
                 hxgp[j] = slot ^ FC_SWZ(sl);
-                hxoff[j] = ((uint32_t)slot_pix[sl] * (uint32_t)g.c_in + (uint32_t)hxgp[j] * EPP) * ES;
+                hxoff[j] = ((uint32_t)slot_pix[sl] * (uint32_t)g.c_in + (uint32_t)hxgp[j] * EPP) * ES + xbias;
                 hxbits[j] = slot_bits[sl];
             }
             // fragment addressing: the three slots of this lane's rows
@@ -510,61 +519,88 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
             const int g_begin = (int)((int64_t)split * groups / S), g_end = (int)((int64_t)(split + 1) * groups / S);
             const int ng = g_end - g_begin;
             // cursors: next pixel line to gather, next weight slab to fetch
-            int xkh = g_begin / cchunks, xcc = g_begin - xkh * cchunks, xleft = ng, xbuf_i = 0;
-            int wkh = xkh, wcc = xcc, wkw = 0, wleft = 3 * ng, wbuf_i = 0;
-            uint32_t ld_off[WR + XL], ld_lds[WR + XL];
+            int xkh = g_begin / cchunks, xcc = g_begin - xkh * cchunks, xleft = ng;
+            int wkh = xkh, wcc = xcc, wkw = 0, wleft = 3 * ng;
+            uint32_t ld_off[WR + XL];
+            // (buffer numbers are compile-time values throughout: the group loop is unrolled over
+            // the two line buffers, so fragment and gather addresses inside LDS need no arithmetic)
+            // Offsets of a stage's loads: a per-lane part (ld_off) and a wave-uniform part that the
+            // load instruction adds itself (ld_sx for the line, ld_sw for the slab).  When the
+            // input channels are whole 64-channel chunks the per-lane part of a weight row never
+            // changes and that of a slot only depends on its tap-valid bit; with a channel tail
+            // the lanes past the last channel are switched off one by one.
+            const bool k_tail = (g.c_in % TK) != 0;
+            uint32_t ld_sx = 0, ld_sw = 0;
 #define FC_HALO_PREP_X(at)                                                                                \
     {                                                                                                     \
         const uint32_t sx = (uint32_t)((xkh * g.dh) * g.w * g.c_in + xcc * TK) * ES;                      \
-        const uint32_t l0 = lds0 + (uint32_t)xbuf_i * XB + (uint32_t)wave * 1024u;                        \
         const bool in_k = xleft > 0;                                                                      \
         --xleft;                                                                                          \
-        _Pragma("unroll") for (int j = 0; j < XL; ++j)                                                    \
-        {                                                                                                 \
-            const bool ok = in_k && xcc * TK + hxgp[j] * EPP < g.c_in && ((hxbits[j] >> (xkh & 31)) & 1u); \
-            ld_off[(at) + j] = ok ? hxoff[j] + sx : kOutOfRange;                                          \
-            ld_lds[(at) + j] = l0 + (uint32_t)j * (RPP * 128);                                            \
+        if (k_tail) {                                                                                     \
+            ld_sx = 0;                                                                                    \
+            _Pragma("unroll") for (int j = 0; j < XL; ++j)                                                \
+            {                                                                                             \
+                const bool ok = in_k && xcc * TK + hxgp[j] * EPP < g.c_in && ((hxbits[j] >> (xkh & 31)) & 1u); \
+                ld_off[(at) + j] = ok ? hxoff[j] + sx : kOutOfRange;                                      \
+            }                                                                                             \
+        } else {                                                                                          \
+            ld_sx = in_k ? sx : 0u;                                                                       \
+            const uint32_t sel = in_k ? 1u << (xkh & 31) : 0u;                                            \
+            _Pragma("unroll") for (int j = 0; j < XL; ++j)                                                \
+                ld_off[(at) + j] = (hxbits[j] & sel) ? hxoff[j] : kOutOfRange;                            \
         }                                                                                                 \
         const int wrap = (xcc + 1 == cchunks);                                                            \
         xcc = wrap ? 0 : xcc + 1;                                                                         \
         xkh += wrap;                                                                                      \
-        xbuf_i ^= 1;                                                                                      \
     }
 #define FC_HALO_PREP_W()                                                                                  \
     {                                                                                                     \
         const uint32_t sw = (uint32_t)((wkh * 3 + wkw) * g.c_in + wcc * TK) * ES;                         \
-        const uint32_t l0 = lds0 + 2u * XB + (uint32_t)wbuf_i * WB + (uint32_t)wave * 1024u;              \
         const bool in_k = wleft > 0;                                                                      \
         --wleft;                                                                                          \
-        _Pragma("unroll") for (int j = 0; j < WR; ++j)                                                    \
-        {                                                                                                 \
-            const bool ok = in_k && wcc * TK + wgp[j] * EPP < g.c_in;                                     \
-            ld_off[j] = ok ? woff[j] + sw : kOutOfRange;                                                  \
-            ld_lds[j] = l0 + (uint32_t)j * (RPP * 128);                                                   \
+        if (k_tail) {                                                                                     \
+            ld_sw = 0;                                                                                    \
+            _Pragma("unroll") for (int j = 0; j < WR; ++j)                                                \
+            {                                                                                             \
+                const bool ok = in_k && wcc * TK + wgp[j] * EPP < g.c_in;                                 \
+                ld_off[j] = ok ? woff[j] + sw : kOutOfRange;                                              \
+            }                                                                                             \
+        } else {                                                                                          \
+            ld_sw = in_k ? sw : 0u;                                                                       \
+            _Pragma("unroll") for (int j = 0; j < WR; ++j) ld_off[j] = in_k ? woff[j] : kOutOfRange;      \
         }                                                                                                 \
         const int w3 = (wkw == 2);                                                                        \
         wkw = w3 ? 0 : wkw + 1;                                                                           \
         const int wc = w3 & (wcc + 1 == cchunks);                                                         \
         wcc = w3 ? (wc ? 0 : wcc + 1) : wcc;                                                              \
         wkh += wc;                                                                                        \
-        wbuf_i = (wbuf_i + 1 == NBW) ? 0 : wbuf_i + 1;                                                    \
     }
-#define FC_HALO_ISSUE(first, last, total)                                                                 \
+            // wave loads j in [first, last) of a stage's issue list: the weight slab (to ring
+            // position wb) first, then, where the stage has one, the pixel line (to line buffer xb)
+            const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds0 + (uint32_t)wave * 1024u);
+#define FC_HALO_ISSUE(first, last, total, xb, wb)                                                         \
     _Pragma("unroll") for (int j = (first); j < (last); ++j)                                              \
-        if (j < (total)) dma_load16(j < WR ? rsrc_w : rsrc_x, ld_off[j], __builtin_amdgcn_readfirstlane(ld_lds[j]));
+        if (j < (total))                                                                                  \
+            dma_load16_s(j < WR ? rsrc_w : rsrc_xb, ld_off[j], j < WR ? ld_sw : ld_sx,                    \
+                         lds_wave + (j < WR ? 2u * XB + (uint32_t)(wb) * WB + (uint32_t)j * (RPP * 128)   \
+                                            : (uint32_t)(xb) * XB + (uint32_t)(j - WR) * (RPP * 128)));
 
-            // prologue, in this order: first pixel line, then NBW - 1 weight slabs
+            // prologue, in this order: first pixel line (to buffer 0), then NBW - 1 weight slabs
             FC_HALO_PREP_X(WR)
-            FC_HALO_ISSUE(WR, WR + XL, WR + XL)
+            FC_HALO_ISSUE(WR, WR + XL, WR + XL, 0, 0)
 #pragma unroll
             for (int d = 0; d < NBW - 1; ++d) {
                 FC_HALO_PREP_W()
-                FC_HALO_ISSUE(0, WR, WR)
+                FC_HALO_ISSUE(0, WR, WR, 0, d)
             }
-            int cxb = 0, cwb = 0; // buffers being multiplied
-            for (int gi = 0; gi < ng; ++gi) {
+            // one group: line buffer CXB is multiplied three times; the slab of tap t sits at ring
+            // position (CW0 + t) % NBW
+            auto group = [&](auto cxb_c, auto cw0_c) __attribute__((always_inline)) {
+                constexpr int CXB = decltype(cxb_c)::value, CW0 = decltype(cw0_c)::value;
 #pragma unroll
                 for (int t = 0; t < 3; ++t) {
+                    const int cwb = (CW0 + t) % NBW;            // (compile-time after unrolling)
+                    const int iwb = (cwb + NBW - 1) % NBW;      // ring position the slab issued now goes to
                     // this stage issues the weight slab NBW - 1 stages ahead and, on the first
                     // tap, after it, the next group's pixel line
                     FC_HALO_PREP_W()
@@ -576,7 +612,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                     if (t == 1) wait_vmcnt<kBehindW + XL>();
                     if (t == 2) wait_vmcnt<(NBW == 3 ? WR + XL : 0)>();
                     __syncthreads();
-                    const unsigned char *xs = stage0 + (uint32_t)cxb * XB;
+                    const unsigned char *xs = stage0 + (uint32_t)CXB * XB;
                     const unsigned char *ws =
                         stage0 + 2u * XB + (uint32_t)cwb * WB + (wave_n * WTN) * 128 + frag_row;
                     const int nld = t == 0 ? WR + XL : WR;
@@ -597,7 +633,7 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                                 xf[(kk + 1) & 1][a].load(xs, xfa[a][t] ^ ((uint32_t)(kk + 1) * KSTEP));
                         }
                         __builtin_amdgcn_sched_barrier(0);
-                        FC_HALO_ISSUE(kk * lpk, (kk + 1) * lpk, nld)
+                        FC_HALO_ISSUE(kk * lpk, (kk + 1) * lpk, nld, CXB ^ 1, iwb)
 #pragma unroll
                         for (int a = 0; a < PB; ++a)
 #pragma unroll
@@ -612,9 +648,15 @@ __global__ __launch_bounds__(WM *WN * 64, MINW) void k_conv_dma(Geom g, const ui
                             for (int a = 0; a < PB; ++a) xf[0][a].load(xs, xfa[a][t] ^ ((uint32_t)(kk + 1) * KSTEP));
                         }
                     }
-                    cwb = (cwb + 1 == NBW) ? 0 : cwb + 1;
                 }
-                cxb ^= 1;
+            };
+            // groups alternate between the two line buffers; with a ring of two slabs the ring
+            // position of a group's first slab alternates as well (three stages per group), with
+            // a ring of three it is always position 0
+            static_assert(NBW == 2 || NBW == 3, "weight ring of the shared-halo loop");
+            for (int gi = 0; gi < ng; gi += 2) {
+                group(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                if (gi + 1 < ng) group(std::integral_constant<int, 1>{}, std::integral_constant<int, (NBW == 2 ? 1 : 0)>{});
             }
 #undef FC_HALO_ISSUE
 #undef FC_HALO_PREP_W
@@ -876,7 +918,8 @@ bool conv_mfma_supported(const Geom &g, int in_dtype, int out_dtype)
     // row origins are packed into signed 16-bit halves
     if (g.h > 16384 || g.w > 16384 || g.ph > 8192 || g.pw > 8192) return false;
     // x and w are each addressed through one buffer descriptor with 32-bit byte offsets
-    if ((uint64_t)g.n * g.h * g.w * g.c_in * es >= kBufferLimit) return false;
+    // (the shared pixel line reads x through a descriptor that starts pad_h rows + pad_w pixels early)
+    if (((uint64_t)g.n * g.h * g.w + (uint64_t)g.ph * g.w + g.pw) * g.c_in * es >= kBufferLimit) return false;
     if ((uint64_t)g.c_out * g.kh * g.kw * g.c_in * es >= kBufferLimit) return false;
     return true;
 }

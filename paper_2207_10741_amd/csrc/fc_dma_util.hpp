@@ -39,6 +39,19 @@ __device__ __forceinline__ void dma_load16(const u32x4_t &rsrc, uint32_t byte_of
                      : "memory");
 }
 
+// The same with a wave-uniform byte offset added by the instruction (the scalar offset operand):
+// the part of an address that is the same for every lane costs no vector arithmetic.  An
+// out-of-range `byte_offset` stays out of range whatever the scalar offset is (it is checked
+// against the descriptor's size less the scalar offset).
+__device__ __forceinline__ void dma_load16_s(const u32x4_t &rsrc, uint32_t byte_offset, uint32_t scalar_offset,
+                                             uint32_t lds_addr)
+{
+    __asm__ volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_addr), "v"(byte_offset), "s"(rsrc), "s"(scalar_offset)
+                     : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
