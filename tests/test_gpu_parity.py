@@ -439,6 +439,7 @@ HALO_LAYERS = [
     (1, 33, 47, 72, 136, 3, (2, 1), (0, 2), (2, 1)),  # vertical stride and dilation, wide padding, channel tails
     (3, 17, 32, 128, 72, 3, (1, 1), (1, 0), (1, 1)),  # no horizontal padding: the output is narrower
     (128, 16, 16, 64, 256, 3, 1, 1, 1),             # 16-pixel rows, 512 tiles of 128 x 128: short runs on the pixel line
+    (2, 30, 70, 64, 128, 3, 1, (3, 2), (3, 1)),     # three padded rows and two padded pixels: first taps far outside
 ]
 
 
