@@ -1,4 +1,7 @@
 // C ABI of the library: argument checks on the host, then launches.
+#ifdef FC_TUNE
+#include <cstdlib>
+#endif
 #include "fc_internal.hpp"
 #include <atomic>
 
@@ -77,6 +80,18 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
     if (g.m <= kInlineRankPositions) return false;
     if (g.c_out <= 64 || g.c_out > 128) return false;
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;
+}
+
+// Does the pointwise kernel serve this layer?  1x1 layers without padding whose weights stay in
+// LDS (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
+// labelling rule reduces to the one pixel under the tap, so a kept row never has a gated tap
+// and the kernel reads no input mask while it gathers.
+bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
+{
+#ifdef FC_TUNE
+    if (getenv("FC_NO_PW")) return false;
+#endif
+    return g.m > kInlineRankPositions && conv_pw_supported(g, in_dtype, out_dtype);
 }
 
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }
@@ -330,6 +345,9 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     hipError_t e;
     if (mfma && idx && conv_line_wanted(g, desc->in_dtype, desc->out_dtype, mask_in != nullptr)) {
         e = launch_conv_line(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
+        if (e != hipSuccess) return FC_ERR_HIP;
+    } else if (mfma && (idx || !mask_in) && conv_pw_wanted(g, desc->in_dtype, desc->out_dtype)) {
+        e = launch_conv_pw(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
         if (e != hipSuccess) return FC_ERR_HIP;
     } else if (mfma) {
         if (tile_counters && !counters_cleared && !(g.flags & FC_WORKSPACE_READY)) {

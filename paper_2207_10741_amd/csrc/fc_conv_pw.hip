@@ -1,0 +1,462 @@
+// Focused 1x1 convolution on the gfx950 matrix cores for layers whose whole weight matrix fits
+// LDS (Sec. III-A: a GEMM over the kept patches only, with the dense layer's weights).
+//
+// A 1x1 layer without padding is a plain GEMM of the kept pixels with a [C_in x C_out] matrix:
+// one gathered stage per row tile, then a store-heavy epilogue (the 64 -> 256 expansions of a
+// bottleneck write four times what they read).  The tiled kernel spends such a layer waiting:
+// set-up, the single gather and the epilogue of a tile follow one another and only a second
+// workgroup on the CU fills the gaps.  Here the weights (at most 32 KB) stay in LDS for the
+// whole launch, the launch is one workgroup of twelve waves per CU, and every wave is a
+// pipeline of its own over units of 32 kept rows: the rows of the next unit are on their way
+// (a wave-wide load into LDS, counted and waited for by the wave itself) while the current unit
+// is multiplied against all output channels and stored.  Waves do not cooperate after the
+// prologue: no barrier in the loop, and three waves per SIMD cover each other's waits.
+// 16-bit outputs leave through LDS as whole 128-byte lines (the accumulator layout by itself
+// gives 32-byte pieces, which cost a 64 -> 256 layer a third of its time).
+//
+// Layers of 64 or 128 input channels only.  With 256 input channels (four chunks per unit) the
+// same loop measured 5 .. 15 % slower than the tiled kernel, with two, three or four chunk
+// buffers per wave alike, so those layers stay on the tiled kernel.
+//
+// Rows = kept output positions (from the list, or all positions of a dense layer); a row's pixel
+// is the position's centre tap (stride allowed, no padding), or row j of a compacted input.  The
+// pixel that decided to keep a position is the only one the position reads, so no mask byte is
+// looked at in the loop.  fp32 accumulators, bias added after the reduction, one rounding.
+#include "fc_dma_util.hpp"
+#include <atomic>
+
+namespace fc {
+
+constexpr uint32_t kPwChunkBytes = 32u * 128u;  // a chunk buffer: 32 rows x 64 channels
+// LDS of a wave: RING chunk buffers + the list entries of a unit
+constexpr uint32_t pw_wave_bytes(int ring) { return (uint32_t)ring * kPwChunkBytes + 256u; }
+constexpr uint32_t kPwMaxWeightBytes = 32u * 1024u;
+
+struct PwDivs {
+    FastDiv wo, ho;
+};
+
+__device__ __forceinline__ void pw_dma_load4(const u32x4_t &rsrc, uint32_t byte_offset, uint32_t lds_addr)
+{
+    __asm__ volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                     :
+                     : "s"(lds_addr), "v"(byte_offset), "s"(rsrc)
+                     : "memory");
+}
+
+// s_waitcnt takes its count as an immediate, and n (wave-uniform) is known at run time only: a
+// jump into a table of 16 waits for the even counts 0 .. 30 (each followed by a branch to the
+// end), taking the largest even count that is not above n.
+#define FC_WJ(k) "s_waitcnt vmcnt(" #k ")\n\ts_branch 1f\n\t"
+__device__ __forceinline__ void pw_wait_vmcnt(int n)
+{
+    // the table starts 12 bytes after the address s_getpc_b64 returns; an entry is 8 bytes
+    const uint32_t off = (uint32_t)(min(n, 30) >> 1) * 8u + 12u;
+    __asm__ volatile("s_getpc_b64 vcc\n\t"
+                     "s_add_u32 vcc_lo, vcc_lo, %0\n\t"
+                     "s_addc_u32 vcc_hi, vcc_hi, 0\n\t"
+                     "s_setpc_b64 vcc\n\t"
+                     FC_WJ(0) FC_WJ(2) FC_WJ(4) FC_WJ(6) FC_WJ(8) FC_WJ(10) FC_WJ(12) FC_WJ(14)
+                     FC_WJ(16) FC_WJ(18) FC_WJ(20) FC_WJ(22) FC_WJ(24) FC_WJ(26) FC_WJ(28) FC_WJ(30)
+                     "1:"
+                     :
+                     : "s"(off)
+                     : "vcc", "scc", "memory");
+}
+#undef FC_WJ
+
+// DT: storage type (bf16 / f16); TO: float or the 16-bit / 8-bit carrier of the output; KCH:
+// 64-channel chunks of the input; NCB: 32-channel blocks of the output; NW: waves per workgroup.
+template <int DT, typename TO, int KCH, int NCB, int NW, int RING>
+__global__ __launch_bounds__(NW * 64, 1)
+void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t *__restrict__ mask_in,
+               const uint8_t *__restrict__ mask_out, const uint16_t *__restrict__ w,
+               const float *__restrict__ bias, const int32_t *__restrict__ idx,
+               const int32_t *__restrict__ count, TO *__restrict__ out)
+{
+    static_assert(DT == FC_BF16 || DT == FC_F16, "16-bit storage");
+    static_assert(KCH == 1 || NCB <= 4, "with several input chunks all accumulators are live at once");
+    constexpr int CIN = KCH * 64, COUT = NCB * 32;
+    constexpr int GB = NCB < 4 ? NCB : 4;     // channel blocks multiplied at a time
+    constexpr uint32_t WBYTES = (uint32_t)KCH * COUT * 128u;
+    static_assert(WBYTES <= kPwMaxWeightBytes, "the weights stay in LDS");
+
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const float *bias_s = reinterpret_cast<const float *>(smem_raw + WBYTES);
+    unsigned char *const my = smem_raw + WBYTES + 1024u + (size_t)wave * pw_wave_bytes(RING);
+    const uint32_t my0 = lds0 + WBYTES + 1024u + (uint32_t)wave * pw_wave_bytes(RING);
+    const int32_t *const idx_w = reinterpret_cast<const int32_t *>(my + RING * kPwChunkBytes);
+
+    const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0;
+    const bool compact_in = (g.flags & FC_COMPACT_IN) != 0, compact_out = (g.flags & FC_COMPACT_OUT) != 0;
+    const int rows = idx ? *count : g.m;
+
+    // ---- the weights: LDS row (chunk, output channel) holds that channel's 64 input channels
+    // of the chunk, its 16-byte pieces swizzled by the channel ----
+    {
+        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)COUT * CIN * 2u);
+        constexpr int LOADS = KCH * COUT / 8; // wave loads of 8 rows each
+        for (int ii = wave; ii < LOADS; ii += NW) {
+            const int ch = ii / (COUT / 8), co = (ii - ch * (COUT / 8)) * 8 + (lane >> 3);
+            const uint32_t off = ((uint32_t)co * CIN + (uint32_t)ch * 64u) * 2u + (uint32_t)((lane & 7) ^ FC_SWZ(co)) * 16u;
+            dma_load16(rsrc_w, off, lds0 + (uint32_t)ii * 1024u);
+        }
+        for (int c = tid; c < COUT; c += NW * 64)
+            reinterpret_cast<float *>(smem_raw + WBYTES)[c] = bias ? bias[c] : 0.f;
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    // ---- my share of the kept rows: units of 32 rows, the same number (+-1) for every wave of
+    // the launch; workgroup b runs on XCD b mod 8, and XCD j takes the j-th contiguous eighth ----
+    const int nwv = (int)gridDim.x * NW;
+    const int wv = (((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3)) * NW + wave;
+    const int nb = (rows + 31) >> 5;
+    const int share_q = nb / nwv, share_r = nb - share_q * nwv;
+    const int b0 = wv * share_q + (wv * share_r) / nwv;
+    const int b1 = (wv + 1) * share_q + ((wv + 1) * share_r) / nwv;
+    const int nu = b1 - b0;
+
+    const uint32_t x_rows = compact_in ? (uint32_t)g.m : (uint32_t)g.n * g.h * g.w;
+    const u32x4_t rsrc_x = make_rsrc_words(x, x_rows * (uint32_t)(CIN * 2));
+    const u32x4_t rsrc_i = make_rsrc_words(idx, (uint32_t)rows * 4u);
+    const bool unit_step = g.sh == 1 && g.sw == 1; // (no padding: the pixel of a position is the position)
+
+    // loads issued so far by this wave, and that count right after the last load of what is awaited
+    int issued = 0, mark_idx = 0, mark_x[RING] = {};
+
+    auto issue_idx = [&](int v) {
+        if (!idx) return;
+        const uint32_t r = (uint32_t)(b0 + v) * 32u + (uint32_t)lane;
+        pw_dma_load4(rsrc_i, lane < 32 ? r * 4u : kOutOfRange, my0 + RING * kPwChunkBytes);
+        issued += 1;
+        mark_idx = issued;
+    };
+    // a unit's rows: where this lane's row is stored (-1: no row), and the byte offsets of the
+    // four rows whose pieces this lane gathers (row 8j + lane / 8 in wave load j)
+    int st_p[2] = {-1, -1};
+    int st_pr[2][4]; // where row 8j + lane / 8 is stored (16-bit outputs leave through LDS, in the gather's row order)
+    uint32_t st_off[2][4];
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st_off[k][j] = kOutOfRange, st_pr[k][j] = -1;
+    auto setup = [&](int v, int k) {
+        const int r = (b0 + v) * 32 + l32;
+        const bool valid = r < rows;
+        int p = r;
+        if (idx) {
+            pw_wait_vmcnt(issued - mark_idx);
+            p = idx_w[l32];
+        }
+        int pix = p;
+        if (compact_in) {
+            pix = r;
+        } else if (!unit_step) {
+            const int q1 = (int)fast_div((uint32_t)(valid ? p : 0), dv.wo);
+            const int ow = (valid ? p : 0) - q1 * g.wo;
+            const int n = (int)fast_div((uint32_t)q1, dv.ho);
+            const int oh = q1 - n * g.ho;
+            pix = (n * g.h + oh * g.sh) * g.w + ow * g.sw;
+        }
+        const uint32_t off = valid ? (uint32_t)pix * (uint32_t)(CIN * 2) : kOutOfRange;
+        st_p[k] = valid ? (compact_out ? r : p) : -1;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = j * 8 + (lane >> 3);
+            const uint32_t o = (uint32_t)__shfl((int)off, row, 64);
+            st_off[k][j] = o == kOutOfRange ? o : o + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
+            if constexpr (sizeof(TO) == 2) st_pr[k][j] = __shfl(st_p[k], row, 64);
+        }
+    };
+    // one stage: chunk c of the unit with state k, into ring buffer `buf`
+    auto issue_x = [&](int k, int c, int buf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            dma_load16_s(rsrc_x, st_off[k][j], (uint32_t)c * 128u, my0 + (uint32_t)buf * kPwChunkBytes + (uint32_t)j * 1024u);
+        issued += 4;
+#pragma unroll
+        for (int r = 0; r < RING; ++r) mark_x[r] = buf == r ? issued : mark_x[r];
+    };
+
+    // fragment addressing: lane reads row (lane & 31); in k-step kk that is the 16-byte piece
+    // 2 kk + (lane >> 5), stored at slot piece ^ swizzle(row)
+    const uint32_t frag = (uint32_t)l32 * 128u + (uint32_t)(half ^ FC_SWZ(l32)) * 16u;
+
+    // fp32 and 8-bit outputs: one rounding, ReLU, and every lane stores its four channels
+    auto store_block = [&](const f32x16_t &a, int cb, int p_mine) {
+        float v[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 bq = *reinterpret_cast<const float4 *>(bias_s + cb * 32 + q * 8 + half * 4);
+            v[q * 4 + 0] = a[q * 4 + 0] + bq.x;
+            v[q * 4 + 1] = a[q * 4 + 1] + bq.y;
+            v[q * 4 + 2] = a[q * 4 + 2] + bq.z;
+            v[q * 4 + 3] = a[q * 4 + 3] + bq.w;
+        }
+        TO *row = out + (int64_t)(p_mine < 0 ? 0 : p_mine) * COUT + cb * 32;
+        if constexpr (sizeof(TO) == 4) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float v0 = v[q * 4], v1 = v[q * 4 + 1], v2 = v[q * 4 + 2], v3 = v[q * 4 + 3];
+                if (g.flags & FC_RELU) {
+                    v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
+                    v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
+                }
+                if (p_mine >= 0) store4<DT, TO>(row + q * 8 + half * 4, v0, v1, v2, v3);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t pk;
+                store4<DT, TO>(reinterpret_cast<TO *>(&pk), v[q * 4], v[q * 4 + 1], v[q * 4 + 2], v[q * 4 + 3]);
+                if (g.flags & FC_RELU) pk = relu_packed8(pk);
+                if (p_mine >= 0) *reinterpret_cast<uint32_t *>(row + q * 8 + half * 4) = pk;
+            }
+        }
+    };
+
+    // 16-bit outputs: two blocks of 32 channels (128 bytes of every row) go through LDS, laid out
+    // like a gathered chunk, and leave as whole 128-byte lines: eight lanes per row, 16 bytes each.
+    // The staging area is the ring buffer of the chunk just consumed (its fragments are in
+    // registers); a wave's LDS accesses execute in order, so no barrier is needed.
+    auto store_pair = [&](const f32x16_t &a0, const f32x16_t &a1, int cb, unsigned char *stg) {
+        if constexpr (sizeof(TO) == 2) {
+#pragma unroll
+            for (int bl = 0; bl < 2; ++bl) {
+                const f32x16_t &a = bl ? a1 : a0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 bq = *reinterpret_cast<const float4 *>(bias_s + (cb + bl) * 32 + q * 8 + half * 4);
+                    uint2 pk;
+                    store4<DT, TO>(reinterpret_cast<TO *>(&pk), a[q * 4] + bq.x, a[q * 4 + 1] + bq.y,
+                                   a[q * 4 + 2] + bq.z, a[q * 4 + 3] + bq.w);
+                    if (g.flags & FC_RELU) {
+                        pk.x = relu_packed16(pk.x);
+                        pk.y = relu_packed16(pk.y);
+                    }
+                    const uint32_t at = (uint32_t)l32 * 128u + (uint32_t)((bl * 4 + q) ^ FC_SWZ(l32)) * 16u + (uint32_t)half * 8u;
+                    *reinterpret_cast<uint2 *>(stg + at) = pk;
+                }
+            }
+            __asm__ volatile("" ::: "memory");
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = j * 8 + (lane >> 3);
+                const uint32_t at = (uint32_t)row * 128u + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
+                const u32x4_t piece = *reinterpret_cast<const u32x4_t *>(stg + at);
+                const int pr = st_pr[0][j];
+                if (pr >= 0)
+                    *reinterpret_cast<u32x4_t *>(out + (int64_t)pr * COUT + cb * 32 + (lane & 7) * 8) = piece;
+            }
+            __asm__ volatile("" ::: "memory");
+        }
+    };
+
+    // ---- the pipeline: stage t = (unit t / KCH, chunk t % KCH) lives in ring buffer t % RING,
+    // and stage t + RING - 1 is issued when stage t is about to be consumed ----
+    constexpr int AHEAD = RING - 1;
+    static_assert(AHEAD >= 1 && AHEAD <= KCH, "the stages in flight belong to this unit or the next");
+    if (nu > 0) {
+        issue_idx(0);
+        setup(0, 0);
+        if (nu > 1) issue_idx(1);
+#pragma unroll
+        for (int c = 0; c < AHEAD; ++c) issue_x(0, c, c);
+    }
+    f32x16_t acc[GB];
+    int buf = 0;
+    for (int u = 0; u < nu; ++u) {
+        const int p_mine = st_p[0];
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) {
+            // a stage goes out first, into the buffer freed last: a later chunk of this unit, or
+            // a chunk of the next unit (whose rows are looked up before its first chunk)
+            const int bufn = buf == 0 ? RING - 1 : buf - 1;
+            if (c + AHEAD < KCH) {
+                issue_x(0, c + AHEAD, bufn);
+            } else if (u + 1 < nu) {
+                if (c + AHEAD == KCH) {
+                    setup(u + 1, 1);
+                    if (u + 2 < nu) issue_idx(u + 2);
+                }
+                issue_x(1, c + AHEAD - KCH, bufn);
+            }
+            int awaited = 0;
+#pragma unroll
+            for (int r = 0; r < RING; ++r) awaited = buf == r ? mark_x[r] : awaited;
+            pw_wait_vmcnt(issued - awaited);
+            const unsigned char *xs = my + (size_t)buf * kPwChunkBytes;
+            Frag<DT> xf[4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) xf[kk].load(xs, frag ^ (uint32_t)(kk * 32));
+#pragma unroll
+            for (int gb = 0; gb < NCB; gb += GB) {
+                if (c == 0 || NCB > GB) {
+#pragma unroll
+                    for (int b = 0; b < GB; ++b)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+                }
+                const unsigned char *ws = smem_raw + (size_t)(c * COUT + gb * 32) * 128u;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    Frag<DT> wf[GB];
+#pragma unroll
+                    for (int b = 0; b < GB; ++b) wf[b].load(ws + b * 4096, frag ^ (uint32_t)(kk * 32));
+#pragma unroll
+                    for (int b = 0; b < GB; ++b) acc[b] = mfma32<DT>(wf[b], xf[kk], acc[b]);
+                }
+                if (c == KCH - 1) {
+                    if constexpr (sizeof(TO) == 2) {
+#pragma unroll
+                        for (int b = 0; b < GB; b += 2)
+                            store_pair(acc[b], acc[b + 1], gb + b, my + (size_t)buf * kPwChunkBytes);
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < GB; ++b) store_block(acc[b], gb + b, p_mine);
+                    }
+                }
+            }
+            buf = buf + 1 == RING ? 0 : buf + 1;
+        }
+        st_p[0] = st_p[1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st_off[0][j] = st_off[1][j], st_pr[0][j] = st_pr[1][j];
+    }
+
+    // ---- zero-fill of the irrelevant output rows: every wave takes 64 positions at a time ----
+    if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL) && !compact_out) {
+        __syncthreads(); // everybody is done with LDS
+        int32_t *dropped = reinterpret_cast<int32_t *>(smem_raw) + wave * 64;
+        u32x4_t *o4 = reinterpret_cast<u32x4_t *>(out);
+        const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+        const int cpr = COUT * (int)sizeof(TO) / 16; // 16-byte pieces per row
+        const int workers = (int)gridDim.x * NW;
+        for (int p0 = ((int)blockIdx.x * NW + wave) * 64; p0 < g.m; p0 += workers * 64) {
+            const int pp = p0 + lane;
+            bool kept = true; // (positions past the end count as kept: nothing to clear)
+            if (pp < g.m) {
+                if (mask_out) {
+                    kept = mask_at(mask_out, pp, packed_masks);
+                } else {
+                    const int q = (int)fast_div((uint32_t)pp, dv.wo);
+                    const int ow = pp - q * g.wo;
+                    const int b = (int)fast_div((uint32_t)q, dv.ho);
+                    const int oh = q - b * g.ho;
+                    kept = mask_at(mask_in, (int64_t)(b * g.h + oh * g.sh) * g.w + ow * g.sw, packed_masks);
+                }
+            }
+            const uint64_t drop = __ballot(!kept);
+            if (!kept) dropped[__popcll(drop & ((1ull << lane) - 1ull))] = pp; // in position order
+            const int total = __popcll(drop) * cpr;
+            for (int c = lane; c < total; c += 64) {
+                const int rk = c / cpr, pc = c - rk * cpr;
+                __builtin_nontemporal_store(zero4, o4 + (int64_t)dropped[rk] * cpr + pc);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+
+bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
+{
+    if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
+    if (out_dtype != in_dtype && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
+    if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0)) return false;
+    if (g.c_in != 64 && g.c_in != 128) return false;
+    if (g.c_out != 64 && g.c_out != 128 && g.c_out != 256) return false;
+    if ((uint32_t)g.c_in * g.c_out * 2u > kPwMaxWeightBytes) return false;
+    if (g.c_in > 64 && g.c_out > 128) return false; // (all accumulators of a row are live at once)
+    if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
+    if ((uint64_t)g.m * 4u >= kBufferLimit) return false; // the list goes through a descriptor as well
+    return true;
+}
+
+static int pw_grid()
+{
+    // one workgroup per CU (the count is read once per process; all devices of a node are alike)
+    static std::atomic<int> cus{0};
+    int v = cus.load(std::memory_order_relaxed);
+    if (v == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            v = prop.multiProcessorCount;
+        if (v <= 0) v = 256;
+        v &= ~7; // a multiple of the XCD count
+        if (v < 8) v = 8;
+        cus.store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
+
+template <int DT, typename TO, int KCH, int NCB, int RING>
+static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
+                            const void *w, const float *bias, const int32_t *idx, const int32_t *count, void *out,
+                            hipStream_t s)
+{
+    // twelve waves per CU where the weights leave room for their buffers, else eight, else what fits
+    constexpr uint32_t WBYTES = (uint32_t)KCH * NCB * 32u * 128u;
+    constexpr int FIT = (int)((160u * 1024u - WBYTES - 1024u) / pw_wave_bytes(RING));
+    constexpr int NW = FIT >= 12 ? 12 : FIT >= 8 ? 8 : FIT;
+    static_assert(NW >= 4, "a wave per SIMD at least");
+    constexpr size_t lds = WBYTES + 1024u + (size_t)NW * pw_wave_bytes(RING);
+    auto kern = k_conv_pw<DT, TO, KCH, NCB, NW, RING>;
+    PwDivs dv;
+    dv.wo = make_fastdiv((uint32_t)g.wo);
+    dv.ho = make_fastdiv((uint32_t)g.ho);
+    // the dynamic LDS limit is raised once per function and device
+    static std::atomic<uint64_t> attr_devices{0};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t dev_bit = 1ull << (dev & 63);
+    if (!(attr_devices.load(std::memory_order_acquire) & dev_bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_devices.fetch_or(dev_bit, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kern, dim3(pw_grid()), dim3(NW * 64), lds, s, g, dv, (const uint16_t *)x, mask_in, mask_out,
+                       (const uint16_t *)w, bias, idx, count, (TO *)out);
+    return hipGetLastError();
+}
+
+template <int DT, typename TO>
+static hipError_t launch_pw_shape(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
+                                  const void *w, const float *bias, const int32_t *idx, const int32_t *count,
+                                  void *out, hipStream_t s)
+{
+#define FC_PW_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
+    const int kch = g.c_in / 64, ncb = g.c_out / 32;
+    if (kch == 1 && ncb == 2) return launch_pw<DT, TO, 1, 2, 2>(FC_PW_ARGS);
+    if (kch == 1 && ncb == 4) return launch_pw<DT, TO, 1, 4, 2>(FC_PW_ARGS);
+    if (kch == 1 && ncb == 8) return launch_pw<DT, TO, 1, 8, 2>(FC_PW_ARGS);
+    if (kch == 2 && ncb == 2) return launch_pw<DT, TO, 2, 2, 2>(FC_PW_ARGS);
+    if (kch == 2 && ncb == 4) return launch_pw<DT, TO, 2, 4, 2>(FC_PW_ARGS);
+    return hipErrorInvalidValue;
+#undef FC_PW_ARGS
+}
+
+hipError_t launch_conv_pw(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
+                          const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
+                          const int32_t *count, void *out, hipStream_t s)
+{
+#define FC_PW_CALL(DT, TO) launch_pw_shape<DT, TO>(g, x, mask_in, mask_out, w, bias, idx, count, out, s)
+    if (in_dtype == FC_BF16) {
+        if (out_dtype == FC_F32) return FC_PW_CALL(FC_BF16, float);
+        if (out_dtype == FC_FP8) return FC_PW_CALL(FC_BF16, uint8_t);
+        return FC_PW_CALL(FC_BF16, uint16_t);
+    }
+    if (out_dtype == FC_F32) return FC_PW_CALL(FC_F16, float);
+    if (out_dtype == FC_FP8) return FC_PW_CALL(FC_F16, uint8_t);
+    return FC_PW_CALL(FC_F16, uint16_t);
+#undef FC_PW_CALL
+}
+
+} // namespace fc

@@ -298,4 +298,11 @@ hipError_t launch_conv_line(const Geom &g, int in_dtype, int out_dtype, const vo
                             const uint8_t *mask_in, const uint8_t *mask_out, const void *w, const float *bias,
                             const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
+// Pointwise matrix-core path (see fc_conv_pw.hip): 1x1 layers without padding, 64 .. 256 channels
+// on either side, whose weights fit 64 KB of LDS.  Needs the kept list (or no mask at all).
+bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype);
+hipError_t launch_conv_pw(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
+                          const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
+                          const int32_t *count, void *out, hipStream_t s);
+
 } // namespace fc

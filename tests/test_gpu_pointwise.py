@@ -1,0 +1,189 @@
+"""GPU parity of the pointwise (1x1, no padding) matrix-core kernel that keeps the layer's weights in
+LDS: layers of more than 4096 positions with 64 or 128 input channels and 64, 128 or 256 output
+channels, against the CPU oracle (the layers of 256 input channels in the list run on the tiled
+kernel and are held to the same bars).  fp32 outputs within 1e-4 of the RMS of the kept outputs (fp32 accumulation of at
+most 256 products of 16-bit values); 16-bit and 8-bit outputs are the one rounding of the kernel's
+own fp32 output, bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import fc_oracle as O
+from paper_2207_10741_amd import binding as B, synth
+from tests import gpu_util as G
+from tests.test_gpu_packed_masks import bits_dev
+from tests.test_gpu_parity import _run_layer, TOL_F32_OUT
+
+pytestmark = pytest.mark.gpu
+
+PW_LAYERS = [
+    # n, h, w, ci, co, k, s, p, d
+    (2, 60, 70, 64, 64, 1, 1, 0, 1),          # 8400 positions, ragged last unit of 32 rows
+    (2, 50, 47, 64, 256, 1, 1, 0, 1),         # eight blocks of output channels, two groups of four
+    (1, 80, 81, 256, 64, 1, 1, 0, 1),         # 256 input channels: the tiled kernel
+    (2, 48, 50, 256, 128, 1, 1, 0, 1),
+    (1, 70, 66, 128, 128, 1, 1, 0, 1),        # two chunks of input channels per unit
+    (3, 41, 37, 128, 64, 1, 1, 0, 1),
+    (2, 95, 97, 128, 128, 1, 2, 0, 1),        # strided projection: 4704 positions
+    (1, 121, 83, 64, 256, 1, (2, 1), 0, 1),   # vertical stride only
+    (1, 300, 310, 64, 64, 1, 1, 0, 1),        # 93000 positions: several units per wave
+]
+
+
+def _check_f32(out, want, keep, zero_filled=True):
+    got = G.to_f64(out)
+    if keep.any():
+        rms = float(np.sqrt(np.mean(np.square(want[keep]))))
+        assert float(np.abs(got[keep] - want[keep]).max()) / rms <= TOL_F32_OUT
+    if zero_filled:
+        assert not out.cpu().numpy()[~keep].view(np.uint32).any()      # +0, bit for bit
+    else:
+        assert (got[~keep] == 7.0).all()
+
+
+@pytest.mark.parametrize("layer", PW_LAYERS)
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", "mixed", None])
+def test_pointwise_layers_match_oracle(layer, mask_kind):
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=231)
+    _check_f32(out, want, keep)
+
+
+@pytest.mark.parametrize("layer", [PW_LAYERS[0], PW_LAYERS[1], PW_LAYERS[3], PW_LAYERS[6]])
+@pytest.mark.parametrize("irr", [0.0, 1.0, 0.97])
+def test_pointwise_extreme_densities(layer, irr):
+    out, want, keep = _run_layer(*layer, synth.BF16, irr=irr, seed=232)
+    _check_f32(out, want, keep)
+
+
+@pytest.mark.parametrize("layer", [PW_LAYERS[0], PW_LAYERS[2], PW_LAYERS[4], PW_LAYERS[7]])
+def test_pointwise_f16_no_bias_no_relu_precomputed_list(layer):
+    out, want, keep = _run_layer(*layer, synth.F16, relu=False, use_bias=False, precomputed=True, seed=233)
+    _check_f32(out, want, keep)
+    again, _, _ = _run_layer(*layer, synth.F16, relu=False, use_bias=False, seed=233)
+    torch = G.torch_mod()
+    assert torch.equal(out, again)                      # the list built inside the call gives the same rows
+
+
+@pytest.mark.parametrize("layer", [PW_LAYERS[0], PW_LAYERS[1], PW_LAYERS[3], PW_LAYERS[6]])
+@pytest.mark.parametrize("mask_kind,irr", [("objects", 0.48), ("bernoulli", 0.5), ("objects", 1.0)])
+def test_pointwise_chained_leaves_irrelevant_rows_untouched(layer, mask_kind, irr):
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, irr=irr, seed=234,
+                                 flags_extra=B.SKIP_ZERO_FILL, precomputed=True)
+    _check_f32(out, want, keep, zero_filled=False)
+
+
+@pytest.mark.parametrize("layer", PW_LAYERS[:7])
+@pytest.mark.parametrize("dtype", [synth.BF16, synth.F16])
+def test_pointwise_16bit_output_is_rne_of_fp32_output(layer, dtype):
+    torch = G.torch_mod()
+    o32, _, keep = _run_layer(*layer, dtype, seed=235)
+    o16, _, _ = _run_layer(*layer, dtype, seed=235, out_dtype=dtype)
+    assert torch.equal(o16, o32.to(o16.dtype))          # kept rows rounded once, the others +0
+    assert not o16.cpu().view(torch.int16).numpy()[~keep].any()
+
+
+@pytest.mark.parametrize("layer", [PW_LAYERS[0], PW_LAYERS[1], PW_LAYERS[3]])
+def test_pointwise_fp8_output_is_the_narrowing_of_fp32_output(layer):
+    torch = G.torch_mod()
+    o32, want, keep = _run_layer(*layer, synth.BF16, seed=236)
+    o8, _, _ = _run_layer(*layer, synth.BF16, seed=236, out_dtype=B.FP8)
+    got = o8.view(torch.uint8).cpu().numpy()
+    f32 = o32.cpu().numpy()
+    expect = O.narrow_fp8(f32.astype(np.float64))
+    expect[f32 == 0] = 0
+    np.testing.assert_array_equal(got[keep], expect[keep])
+    assert not got[~keep].any()
+
+
+@pytest.mark.parametrize("with_list", [False, True])
+@pytest.mark.parametrize("layer", [PW_LAYERS[0], PW_LAYERS[3], PW_LAYERS[6]])
+def test_pointwise_with_packed_masks_equals_byte_masks(layer, with_list):
+    torch = G.torch_mod()
+    n, h, w, ci, co, k, s, p, d = layer
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 237, 1)
+    wt = synth.he_weights(co, k, k, ci, dtype, 237, 2)
+    bias = synth.bias(co, 237, 3)
+    mask = synth.mask_objects(n, h, w, 0.48, 237, 4)
+    xd, wd, bd = G.to_dev(x, dtype), G.to_dev(wt, dtype), torch.from_numpy(bias).to(G.dev())
+    md = G.mask_dev(mask)
+    mbits = bits_dev(mask)
+    geom = ((k, k), (s, s), (p, p), (d, d))
+    outs = []
+    for packed in (False, True):
+        desc = B.conv_desc(n, h, w, ci, co, *geom, dtype, B.F32, B.RELU | (B.PACKED_MASKS if packed else 0))
+        ho, wo = B.out_dims(desc)
+        out = torch.full((n, ho, wo, co), 7.0, dtype=torch.float32, device=G.dev())
+        kw = {}
+        if with_list:
+            if packed:
+                labels, shape = B.mask_downsample_packed(mbits, (n, h, w), *geom)
+                idx, count = B.active_index_compact_packed(labels, shape[0] * shape[1] * shape[2])
+            else:
+                labels = B.mask_downsample(md, *geom)
+                idx, count = B.active_index_compact(labels)
+            kw = dict(mask_out=labels, idx=idx, count=count)
+        ws = torch.empty((B.workspace_bytes(desc),), dtype=torch.uint8, device=G.dev())
+        B.focused_conv2d(desc, xd, wd, bd, mask_in=mbits if packed else md, out=out, workspace=ws, **kw)
+        torch.cuda.synchronize()
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])
+    want = O.focused_conv2d(O.ConvShape(n, h, w, ci, co, k, k, (s, s), (p, p), (d, d), relu=True), x, wt, bias=bias,
+                            mask_in=mask, dtype=dtype)
+    keep = O.mask_downsample(mask, k, k, (s, s), (p, p), (d, d)) != 0
+    _check_f32(outs[1], want, keep)
+
+
+@pytest.mark.parametrize("irr", [0.48, 0.0, 0.97, 1.0])
+@pytest.mark.parametrize("c_mid,c_out", [(64, 256), (128, 64), (128, 128)])
+def test_pointwise_on_compacted_activations(c_mid, c_out, irr):
+    """A 1x1 layer that reads and writes compacted rows (rows in list order) gives, bit for bit, the
+    rows the spatial layout holds at the list's entries; rows past the count stay untouched."""
+    torch = G.torch_mod()
+    n, h, w = 2, 61, 70
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, c_mid), dtype, 238, 1)
+    w1 = synth.he_weights(c_out, 1, 1, c_mid, dtype, 238, 2)
+    b1 = synth.bias(c_out, 238, 3)
+    mask = synth.mask_objects(n, h, w, irr, 238, 4)
+    md = G.mask_dev(mask)
+    idx, count = B.active_index_compact(md)
+    cnt = int(count.item())
+    lists = dict(mask_in=md, mask_out=md, idx=idx, count=count)
+    xd, w1d, b1d = G.to_dev(x, dtype), G.to_dev(w1, dtype), torch.from_numpy(b1).to(G.dev())
+    li = idx[:cnt].long()
+    x_compact = torch.zeros((n * h * w, c_mid), dtype=xd.dtype, device=G.dev())
+    x_compact[:cnt] = xd.reshape(-1, c_mid)[li]
+    geom = ((1, 1), (1, 1), (0, 0), (1, 1))
+    for out_dtype in (B.F32, dtype):
+        d1 = B.conv_desc(n, h, w, c_mid, c_out, *geom, dtype, out_dtype, B.RELU)
+        z_spatial = B.focused_conv2d(d1, xd, w1d, b1d, **lists)
+        for flags in (B.COMPACT_OUT, B.COMPACT_IN | B.COMPACT_OUT):
+            dc = B.conv_desc(n, h, w, c_mid, c_out, *geom, dtype, out_dtype, B.RELU | flags)
+            z = torch.full((n * h * w, c_out), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
+            B.focused_conv2d(dc, x_compact if flags & B.COMPACT_IN else xd, w1d, b1d, out=z, **lists)
+            assert torch.equal(z[:cnt], z_spatial.reshape(-1, c_out)[li])
+            assert bool((z[cnt:] == 7.0).all())
+    want = O.focused_conv2d(O.ConvShape(n, h, w, c_mid, c_out, 1, 1, pad=(0, 0), relu=True), x, w1, bias=b1,
+                            mask_in=mask, dtype=dtype)
+    d32 = B.conv_desc(n, h, w, c_mid, c_out, *geom, dtype, B.F32, B.RELU)
+    _check_f32(B.focused_conv2d(d32, xd, w1d, b1d, **lists), want, mask != 0)
+
+
+def test_pointwise_two_runs_are_bit_identical_and_nan_does_not_leak():
+    torch = G.torch_mod()
+    n, h, w, ci, co = 2, 60, 70, 64, 256
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 239, 1)
+    wt = synth.he_weights(co, 1, 1, ci, dtype, 239, 2)
+    mask = synth.mask_objects(n, h, w, 0.48, 239, 4)
+    md = G.mask_dev(mask)
+    xd, wd = G.to_dev(x, dtype), G.to_dev(wt, dtype)
+    desc = B.conv_desc(n, h, w, ci, co, (1, 1), (1, 1), (0, 0), (1, 1), dtype, B.F32, 0)
+    a = B.focused_conv2d(desc, xd, wd, None, mask_in=md)
+    b = B.focused_conv2d(desc, xd, wd, None, mask_in=md)
+    assert torch.equal(a, b)
+    # NaN under every irrelevant pixel: no kept row reads it, every irrelevant row is +0
+    xn = xd.clone()
+    xn[~md.bool().reshape(n, h, w)] = float("nan")
+    c = B.focused_conv2d(desc, xn, wd, None, mask_in=md)
+    assert torch.equal(a, c)
