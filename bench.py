@@ -404,6 +404,63 @@ def depthwise_bench(torch, B, synth, workloads, args):
         "dense_GBps": round(bytes_d / t_d / 1e9, 1)}))
 
 
+def pointwise_bench(torch, B, synth, workloads, args):
+    """The 1x1 layers of a ResNet-50's first stage on the post-stem activation of 480x640 images,
+    batch 32, bf16, blob masks with the list given: per layer the dense call, the focused call
+    (irrelevant rows cleared) and the chained call (irrelevant rows left alone), each as a
+    HIP-graph replay of four calls.  These layers are bound by memory traffic: algorithmic bytes =
+    kept input rows + kept output rows (+ the cleared rows) + the list + weights and bias."""
+    irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
+    n = workloads.POINTWISE_BATCH if args.batch is None else args.batch
+    h, w_ = workloads.POINTWISE_H, workloads.POINTWISE_W
+    dev = torch.device("cuda:0")
+    gen = synth.mask_bernoulli if args.mask == "bernoulli" else synth.mask_objects
+    mask = gen(n, h, w_, irr, 9, 0, 4)
+    md = torch.from_numpy(mask).to(dev)
+    idx, count = B.active_index_compact(md)
+    kept, m = int(count.item()), n * h * w_
+    to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    rows, tot = [], {"dense": [0.0, 0.0], "focused": [0.0, 0.0], "chained": [0.0, 0.0]}
+    for li, (ci, co) in enumerate(workloads.resnet50_stage1_pointwise()):
+        xd = to_dev(synth.activations_large((n, h, w_, ci), synth.BF16, 9, li, 1))
+        wd = to_dev(synth.he_weights(co, 1, 1, ci, synth.BF16, 9, li, 2))
+        bd = torch.from_numpy(synth.bias(co, 9, li, 3)).to(dev)
+        out = torch.empty((n, h, w_, co), dtype=torch.bfloat16, device=dev)
+        fixed = ci * co * 2 + co * 4
+        row = {"layer": "%d->%d" % (ci, co), "kernel": "k_conv_pw" if ci <= 128 else "k_conv_dma"}
+        for kind in ("dense", "focused", "chained"):
+            flags = B.RELU | (B.SKIP_ZERO_FILL if kind == "chained" else 0)
+            desc = B.conv_desc(n, h, w_, ci, co, (1, 1), (1, 1), (0, 0), (1, 1), B.BF16, B.BF16, flags)
+            kw = {} if kind == "dense" else dict(mask_in=md, mask_out=md, idx=idx, count=count)
+            call = B.PreparedConv(desc, xd, wd, bd, out=out, **kw)
+
+            def fn():
+                for _ in range(4):
+                    call()
+            t = time_loop(torch, capture(torch, fn).replay, args.steps, args.warmup) / 4
+            r = m if kind == "dense" else kept
+            by = r * (ci + co) * 2 + fixed + (0 if kind == "dense" else kept * 4) \
+                + ((m - kept) * co * 2 if kind == "focused" else 0)
+            row[kind + "_us"] = round(t * 1e6, 2)
+            row[kind + "_GBps"] = round(by / t / 1e9, 1)
+            tot[kind][0] += t
+            tot[kind][1] += by
+        rows.append(row)
+        del xd, out
+    copy_gbps = calibrate_peaks(torch, B, B.BF16)["copy_gbps"]
+    t_f, by_f = tot["focused"]
+    print(json.dumps({
+        "pointwise": True, "workload": "ResNet-50 first-stage 1x1 layers, batch %d, %dx%d positions, bf16, %s masks, "
+        "%d %% irrelevant, kept list given" % (n, h, w_, args.mask, round(irr * 100)),
+        "launch": "HIP graph replay of four calls", "steps": args.steps, "kept_fraction": round(kept / m, 4),
+        "layers": rows, "dense_ms": round(tot["dense"][0] * 1e3, 4), "focused_ms": round(t_f * 1e3, 4),
+        "chained_ms": round(tot["chained"][0] * 1e3, 4), "speedup_vs_dense": round(tot["dense"][0] / t_f, 3),
+        "roofline": {"bound": "hbm", "achieved": round(by_f / t_f / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
+                     "frac": round(by_f / t_f / 8e12, 4), "traffic": None, "measured_copy_gbps": copy_gbps},
+        "dense_GBps": round(tot["dense"][1] / tot["dense"][0] / 1e9, 1),
+        "chained_GBps": round(tot["chained"][1] / tot["chained"][0] / 1e9, 1)}))
+
+
 def grouped_bench(torch, B, synth, workloads, args):
     """The 3x3 grouped layers of a ResNeXt-50 (32 groups of 4 to 32 channels), bf16, blob masks:
     per layer the focused call (list given) and the dense call, each as a HIP-graph replay of four
@@ -561,6 +618,8 @@ def main():
     ap.add_argument("--stack", choices=sorted(STACKS), default=None,
                     help="time a whole conv stack (dense / focused / focused without zero-fill between "
                          "convs) instead of the bench line")
+    ap.add_argument("--pointwise", action="store_true",
+                    help="time the 1x1 layers of a ResNet-50's first stage (dense, focused, chained) and exit")
     ap.add_argument("--depthwise", action="store_true",
                     help="time the depthwise layers of a MobileNetV2 backbone (focused and dense) "
                          "instead of the bench line")
@@ -602,6 +661,9 @@ def main():
         return
     if args.stack:
         stack_bench(torch, B, synth, workloads, args)
+        return
+    if args.pointwise:
+        pointwise_bench(torch, B, synth, workloads, args)
         return
     if args.depthwise:
         depthwise_bench(torch, B, synth, workloads, args)

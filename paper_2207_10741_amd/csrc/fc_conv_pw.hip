@@ -94,6 +94,9 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0;
     const bool compact_in = (g.flags & FC_COMPACT_IN) != 0, compact_out = (g.flags & FC_COMPACT_OUT) != 0;
     const int rows = idx ? *count : g.m;
+    // an output larger than the memory-side cache (256 MB) is streamed past it: measured on a
+    // 64 -> 256 layer, 314 MB of rows leave 22 % faster that way, 164 MB of rows 10 % slower
+    const bool stream_out = (int64_t)rows * COUT * (int)sizeof(TO) > (256ll << 20);
 
     // ---- the weights: LDS row (chunk, output channel) holds that channel's 64 input channels
     // of the chunk, its 16-byte pieces swizzled by the channel ----
@@ -244,14 +247,27 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
                 }
             }
             __asm__ volatile("" ::: "memory");
+            u32x4_t piece[4];
+            u32x4_t *at16[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int row = j * 8 + (lane >> 3);
                 const uint32_t at = (uint32_t)row * 128u + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
-                const u32x4_t piece = *reinterpret_cast<const u32x4_t *>(stg + at);
+                piece[j] = *reinterpret_cast<const u32x4_t *>(stg + at);
                 const int pr = st_pr[0][j];
-                if (pr >= 0)
-                    *reinterpret_cast<u32x4_t *>(out + (int64_t)pr * COUT + cb * 32 + (lane & 7) * 8) = piece;
+                at16[j] = reinterpret_cast<u32x4_t *>(out + (int64_t)(pr < 0 ? 0 : pr) * COUT + cb * 32 + (lane & 7) * 8);
+            }
+            // (the non-temporal stores are written out: the compiler folds a store and its
+            // non-temporal twin into one plain store when they sit in the two arms of a branch)
+            if (stream_out) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (st_pr[0][j] >= 0)
+                        __asm__ volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(at16[j]), "v"(piece[j]) : "memory");
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (st_pr[0][j] >= 0) *at16[j] = piece[j];
             }
             __asm__ volatile("" ::: "memory");
         }

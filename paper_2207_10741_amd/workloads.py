@@ -116,6 +116,15 @@ def mobilenetv2_depthwise():
             (384, 14, 1), (576, 14, 1), (576, 14, 2), (960, 7, 1)]
 
 
+def resnet50_stage1_pointwise():
+    """(input channels, output channels) of the 1x1 layers in the first stage of a ResNet-50, whose
+    activations are the largest of the network: the reduction into the first block, the three
+    expansions (and the projection shortcut, same shape), the two reductions of the later blocks,
+    and the reduction that opens the second stage."""
+    return [(64, 64), (64, 256), (256, 64), (256, 128)]
+
+
+POINTWISE_BATCH, POINTWISE_H, POINTWISE_W = 32, 120, 160   # the post-stem activation of 480 x 640 images
 DEPTHWISE_BATCH = 32
 SWEEP_BATCH = 16
 HEADLINE_IRRELEVANT = 0.48   # Sec. II-B: the paper's overall irrelevant-pixel share

@@ -187,3 +187,38 @@ def test_pointwise_two_runs_are_bit_identical_and_nan_does_not_leak():
     xn[~md.bool().reshape(n, h, w)] = float("nan")
     c = B.focused_conv2d(desc, xn, wd, None, mask_in=md)
     assert torch.equal(a, c)
+
+
+@pytest.mark.parametrize("irr", [None, 0.1])
+def test_pointwise_at_the_bench_size_with_a_streamed_output(irr):
+    """64 -> 256 channels on 32 x 120 x 160 positions: more than 256 MB of 16-bit rows, which the
+    kernel streams past the memory-side cache.  The fp32 output is checked against the oracle on a
+    sample of positions; the 16-bit output must be its rounding everywhere."""
+    torch = G.torch_mod()
+    n, h, w, ci, co = 32, 120, 160, 64, 256
+    dtype = synth.BF16
+    x = synth.activations_large((n, h, w, ci), dtype, 240, 1)
+    wt = synth.he_weights(co, 1, 1, ci, dtype, 240, 2)
+    bias = synth.bias(co, 240, 3)
+    mask = None if irr is None else synth.mask_objects(n, h, w, irr, 240, 4)
+    g = synth.rng(240, 5)
+    pos = np.unique(np.concatenate([g.integers(0, n * h * w, size=3000), [0, n * h * w - 1]])).astype(np.int64)
+    shape = O.ConvShape(n, h, w, ci, co, 1, 1, (1, 1), (0, 0), (1, 1), relu=True)
+    want = O.focused_conv2d_at(shape, x, wt, pos, bias=bias, mask_in=mask, dtype=dtype)
+    keep_rows = np.ones(pos.size, bool) if mask is None else mask.reshape(-1)[pos] != 0
+    xd, wd, bd = G.to_dev(x, dtype), G.to_dev(wt, dtype), torch.from_numpy(bias).to(G.dev())
+    md = None if mask is None else G.mask_dev(mask)
+    if md is not None:
+        assert int(md.sum().item()) * co * 2 > (256 << 20)
+    outs = {}
+    for out_dtype in (B.F32, dtype):
+        desc = B.conv_desc(n, h, w, ci, co, (1, 1), (1, 1), (0, 0), (1, 1), dtype, out_dtype, B.RELU)
+        out = torch.full((n, h, w, co), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
+        B.focused_conv2d(desc, xd, wd, bd, mask_in=md, out=out)
+        outs[out_dtype] = out
+    torch.cuda.synchronize()
+    got = outs[B.F32].reshape(-1, co)[torch.from_numpy(pos).to(G.dev())].to(torch.float64).cpu().numpy()
+    rms = float(np.sqrt(np.mean(want[keep_rows] ** 2)))
+    assert float(np.abs(got - want).max()) / rms <= TOL_F32_OUT
+    assert not got[~keep_rows].any()
+    assert torch.equal(outs[dtype], outs[B.F32].to(outs[dtype].dtype))
