@@ -82,16 +82,22 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;
 }
 
-// Does the pointwise kernel serve this layer?  1x1 layers without padding whose weights stay in
-// LDS (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
+// Does the pointwise kernel serve this layer?  1x1 layers without padding of 64 .. 512 input
+// channels whose weights, cut into slices of 64 .. 256 output channels, stay in LDS (see
+// fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
 // labelling rule reduces to the one pixel under the tap, so a kept row never has a gated tap
-// and the kernel reads no input mask while it gathers.
+// and the kernel reads no input mask while it gathers.  Measured against the tiled kernel on
+// the 1x1 layers of a ResNet-50 at batch 32: 10 .. 45 % faster wherever the output channels
+// make two slices or more or the input has at most 128 channels; 256 input channels into one
+// slice (256 -> 64, 256 -> 128 on the largest activations, bound by reading them) are 5 .. 15 %
+// slower and stay on the tiled kernel.
 bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
 {
 #ifdef FC_TUNE
     if (getenv("FC_NO_PW")) return false;
 #endif
-    return g.m > kInlineRankPositions && conv_pw_supported(g, in_dtype, out_dtype);
+    if (g.m <= kInlineRankPositions || !conv_pw_supported(g, in_dtype, out_dtype)) return false;
+    return g.c_in <= 128 || g.c_out >= 256;
 }
 
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }

@@ -30,10 +30,10 @@ namespace fc {
 constexpr uint32_t kPwChunkBytes = 32u * 128u;  // a chunk buffer: 32 rows x 64 channels
 // LDS of a wave: RING chunk buffers + the list entries of a unit
 constexpr uint32_t pw_wave_bytes(int ring) { return (uint32_t)ring * kPwChunkBytes + 256u; }
-constexpr uint32_t kPwMaxWeightBytes = 32u * 1024u;
+constexpr uint32_t kPwMaxWeightBytes = 64u * 1024u;
 
 struct PwDivs {
-    FastDiv wo, ho;
+    FastDiv wo, ho, cpr; // output width, output height, 16-byte pieces per output row
 };
 
 __device__ __forceinline__ void pw_dma_load4(const u32x4_t &rsrc, uint32_t byte_offset, uint32_t lds_addr)
@@ -65,6 +65,18 @@ __device__ __forceinline__ void pw_wait_vmcnt(int n)
 }
 #undef FC_WJ
 
+// Between the wait for a load into LDS and the first read of what it brought: one LDS read of
+// the same buffer, waited for.  Measured on this kernel: a read issued in the cycles right after
+// s_waitcnt vmcnt lets go can still return the buffer's previous contents (one wrong 32-row
+// block in about one launch of ten, with 37 000 waits per launch; four idle cycles in between
+// change nothing, the round trip of an LDS instruction ends it).  The tiled kernels have a
+// workgroup barrier in that place.
+__device__ __forceinline__ void pw_lds_settle(uint32_t lds_addr)
+{
+    uint32_t probe;
+    __asm__ volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(probe) : "v"(lds_addr) : "memory");
+}
+
 // DT: storage type (bf16 / f16); TO: float or the 16-bit / 8-bit carrier of the output; KCH:
 // 64-channel chunks of the input; NCB: 32-channel blocks of the output; NW: waves per workgroup.
 template <int DT, typename TO, int KCH, int NCB, int NW, int RING>
@@ -94,14 +106,22 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0;
     const bool compact_in = (g.flags & FC_COMPACT_IN) != 0, compact_out = (g.flags & FC_COMPACT_OUT) != 0;
     const int rows = idx ? *count : g.m;
+    // A workgroup multiplies by one slice of COUT output channels.  Workgroup b runs on XCD
+    // b mod 8; the workgroups of an XCD form groups of n_slices neighbours that share their rows
+    // (each takes another slice, so the rows come out of that XCD's L2 for all but the first),
+    // and XCD j takes the j-th contiguous eighth of the rows.
+    const int n_slices = g.c_out / COUT;
+    const int in_xcd = (int)blockIdx.x >> 3, groups_per_xcd = ((int)gridDim.x >> 3) / n_slices;
+    const int co0 = (in_xcd % n_slices) * COUT;
+    const int group = ((int)blockIdx.x & 7) * groups_per_xcd + in_xcd / n_slices;
     // an output larger than the memory-side cache (256 MB) is streamed past it: measured on a
     // 64 -> 256 layer, 314 MB of rows leave 22 % faster that way, 164 MB of rows 10 % slower
-    const bool stream_out = (int64_t)rows * COUT * (int)sizeof(TO) > (256ll << 20);
+    const bool stream_out = (int64_t)rows * g.c_out * (int)sizeof(TO) > (256ll << 20);
 
     // ---- the weights: LDS row (chunk, output channel) holds that channel's 64 input channels
     // of the chunk, its 16-byte pieces swizzled by the channel ----
     {
-        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)COUT * CIN * 2u);
+        const u32x4_t rsrc_w = make_rsrc_words(w + (size_t)co0 * CIN, (uint32_t)COUT * CIN * 2u);
         constexpr int LOADS = KCH * COUT / 8; // wave loads of 8 rows each
         for (int ii = wave; ii < LOADS; ii += NW) {
             const int ch = ii / (COUT / 8), co = (ii - ch * (COUT / 8)) * 8 + (lane >> 3);
@@ -109,15 +129,15 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
             dma_load16(rsrc_w, off, lds0 + (uint32_t)ii * 1024u);
         }
         for (int c = tid; c < COUT; c += NW * 64)
-            reinterpret_cast<float *>(smem_raw + WBYTES)[c] = bias ? bias[c] : 0.f;
+            reinterpret_cast<float *>(smem_raw + WBYTES)[c] = bias ? bias[co0 + c] : 0.f;
     }
     wait_vmcnt<0>();
     __syncthreads();
 
     // ---- my share of the kept rows: units of 32 rows, the same number (+-1) for every wave of
-    // the launch; workgroup b runs on XCD b mod 8, and XCD j takes the j-th contiguous eighth ----
-    const int nwv = (int)gridDim.x * NW;
-    const int wv = (((int)blockIdx.x & 7) * ((int)gridDim.x >> 3) + ((int)blockIdx.x >> 3)) * NW + wave;
+    // the groups ----
+    const int nwv = 8 * groups_per_xcd * NW;
+    const int wv = group * NW + wave;
     const int nb = (rows + 31) >> 5;
     const int share_q = nb / nwv, share_r = nb - share_q * nwv;
     const int b0 = wv * share_q + (wv * share_r) / nwv;
@@ -154,6 +174,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
         int p = r;
         if (idx) {
             pw_wait_vmcnt(issued - mark_idx);
+            pw_lds_settle(my0 + RING * kPwChunkBytes);
             p = idx_w[l32];
         }
         int pix = p;
@@ -201,7 +222,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
             v[q * 4 + 2] = a[q * 4 + 2] + bq.z;
             v[q * 4 + 3] = a[q * 4 + 3] + bq.w;
         }
-        TO *row = out + (int64_t)(p_mine < 0 ? 0 : p_mine) * COUT + cb * 32;
+        TO *row = out + (int64_t)(p_mine < 0 ? 0 : p_mine) * g.c_out + co0 + cb * 32;
         if constexpr (sizeof(TO) == 4) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -255,7 +276,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
                 const uint32_t at = (uint32_t)row * 128u + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
                 piece[j] = *reinterpret_cast<const u32x4_t *>(stg + at);
                 const int pr = st_pr[0][j];
-                at16[j] = reinterpret_cast<u32x4_t *>(out + (int64_t)(pr < 0 ? 0 : pr) * COUT + cb * 32 + (lane & 7) * 8);
+                at16[j] = reinterpret_cast<u32x4_t *>(out + (int64_t)(pr < 0 ? 0 : pr) * g.c_out + co0 + cb * 32 + (lane & 7) * 8);
             }
             // (the non-temporal stores are written out: the compiler folds a store and its
             // non-temporal twin into one plain store when they sit in the two arms of a branch)
@@ -306,6 +327,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
 #pragma unroll
             for (int r = 0; r < RING; ++r) awaited = buf == r ? mark_x[r] : awaited;
             pw_wait_vmcnt(issued - awaited);
+            pw_lds_settle(my0 + (uint32_t)buf * kPwChunkBytes);
             const unsigned char *xs = my + (size_t)buf * kPwChunkBytes;
             Frag<DT> xf[4];
 #pragma unroll
@@ -345,16 +367,21 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
         for (int j = 0; j < 4; ++j) st_off[0][j] = st_off[1][j], st_pr[0][j] = st_pr[1][j];
     }
 
-    // ---- zero-fill of the irrelevant output rows: every wave takes 64 positions at a time ----
+    // ---- zero-fill of the irrelevant output rows.  An item is 64 consecutive positions, or one
+    // of `parts` interleaved shares of their 16-byte pieces when there are fewer such blocks than
+    // waves (wide rows, few positions); a wave goes on to its items as soon as its own units are
+    // done and lists the dropped positions of a block in its own (now idle) chunk buffer ----
     if (mask_in && !(g.flags & FC_SKIP_ZERO_FILL) && !compact_out) {
-        __syncthreads(); // everybody is done with LDS
-        int32_t *dropped = reinterpret_cast<int32_t *>(smem_raw) + wave * 64;
+        int32_t *dropped = reinterpret_cast<int32_t *>(my);
         u32x4_t *o4 = reinterpret_cast<u32x4_t *>(out);
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-        const int cpr = COUT * (int)sizeof(TO) / 16; // 16-byte pieces per row
+        const int cpr = g.c_out * (int)sizeof(TO) / 16; // 16-byte pieces per row
         const int workers = (int)gridDim.x * NW;
-        for (int p0 = ((int)blockIdx.x * NW + wave) * 64; p0 < g.m; p0 += workers * 64) {
-            const int pp = p0 + lane;
+        const int nblocks = (g.m + 63) >> 6;
+        const int parts = min(max(workers / nblocks, 1), 16);
+        for (int item = (int)blockIdx.x * NW + wave; item < nblocks * parts; item += workers) {
+            const int blk = item / parts, part = item - blk * parts;
+            const int pp = blk * 64 + lane;
             bool kept = true; // (positions past the end count as kept: nothing to clear)
             if (pp < g.m) {
                 if (mask_out) {
@@ -370,8 +397,8 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
             const uint64_t drop = __ballot(!kept);
             if (!kept) dropped[__popcll(drop & ((1ull << lane) - 1ull))] = pp; // in position order
             const int total = __popcll(drop) * cpr;
-            for (int c = lane; c < total; c += 64) {
-                const int rk = c / cpr, pc = c - rk * cpr;
+            for (int c = part * 64 + lane; c < total; c += parts * 64) {
+                const int rk = (int)fast_div((uint32_t)c, dv.cpr), pc = c - rk * cpr;
                 __builtin_nontemporal_store(zero4, o4 + (int64_t)dropped[rk] * cpr + pc);
             }
         }
@@ -380,18 +407,15 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
 
 // ---------------------------------------------------------------------------
 
-bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
+// 32-channel blocks in a workgroup's slice of the output channels: the widest slice whose weights
+// fit (256 channels from 64 input channels, where a row's accumulators are computed in two
+// halves; 128 channels else), 0 if the layer has no whole number of slices
+static int pw_slice_blocks(const Geom &g)
 {
-    if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
-    if (out_dtype != in_dtype && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
-    if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0)) return false;
-    if (g.c_in != 64 && g.c_in != 128) return false;
-    if (g.c_out != 64 && g.c_out != 128 && g.c_out != 256) return false;
-    if ((uint32_t)g.c_in * g.c_out * 2u > kPwMaxWeightBytes) return false;
-    if (g.c_in > 64 && g.c_out > 128) return false; // (all accumulators of a row are live at once)
-    if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
-    if ((uint64_t)g.m * 4u >= kBufferLimit) return false; // the list goes through a descriptor as well
-    return true;
+    if (g.c_in == 64 && g.c_out % 256 == 0) return 8;
+    if (g.c_in <= 256 && g.c_out % 128 == 0) return 4;
+    if (g.c_out % 64 == 0) return 2;
+    return 0;
 }
 
 static int pw_grid()
@@ -412,6 +436,22 @@ static int pw_grid()
     return v;
 }
 
+bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
+{
+    if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
+    if (out_dtype != in_dtype && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
+    if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0)) return false;
+    if (g.c_in != 64 && g.c_in != 128 && g.c_in != 256 && g.c_in != 512) return false;
+    const int ncb = pw_slice_blocks(g);
+    if (ncb == 0) return false;
+    // the slices of a group of workgroups sit on one XCD
+    const int n_slices = g.c_out / (ncb * 32), per_xcd = pw_grid() >> 3;
+    if (n_slices > per_xcd || per_xcd % n_slices != 0) return false;
+    if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
+    if ((uint64_t)g.m * 4u >= kBufferLimit) return false; // the list goes through a descriptor as well
+    return true;
+}
+
 template <int DT, typename TO, int KCH, int NCB, int RING>
 static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                             const void *w, const float *bias, const int32_t *idx, const int32_t *count, void *out,
@@ -427,6 +467,7 @@ static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in
     PwDivs dv;
     dv.wo = make_fastdiv((uint32_t)g.wo);
     dv.ho = make_fastdiv((uint32_t)g.ho);
+    dv.cpr = make_fastdiv((uint32_t)g.c_out * (uint32_t)sizeof(TO) / 16u);
     // the dynamic LDS limit is raised once per function and device
     static std::atomic<uint64_t> attr_devices{0};
     int dev = 0;
@@ -449,12 +490,15 @@ static hipError_t launch_pw_shape(const Geom &g, const void *x, const uint8_t *m
                                   void *out, hipStream_t s)
 {
 #define FC_PW_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
-    const int kch = g.c_in / 64, ncb = g.c_out / 32;
+    const int kch = g.c_in / 64, ncb = pw_slice_blocks(g);
     if (kch == 1 && ncb == 2) return launch_pw<DT, TO, 1, 2, 2>(FC_PW_ARGS);
     if (kch == 1 && ncb == 4) return launch_pw<DT, TO, 1, 4, 2>(FC_PW_ARGS);
     if (kch == 1 && ncb == 8) return launch_pw<DT, TO, 1, 8, 2>(FC_PW_ARGS);
     if (kch == 2 && ncb == 2) return launch_pw<DT, TO, 2, 2, 2>(FC_PW_ARGS);
     if (kch == 2 && ncb == 4) return launch_pw<DT, TO, 2, 4, 2>(FC_PW_ARGS);
+    if (kch == 4 && ncb == 2) return launch_pw<DT, TO, 4, 2, 2>(FC_PW_ARGS);
+    if (kch == 4 && ncb == 4) return launch_pw<DT, TO, 4, 4, 2>(FC_PW_ARGS);
+    if (kch == 8 && ncb == 2) return launch_pw<DT, TO, 8, 2, 2>(FC_PW_ARGS);
     return hipErrorInvalidValue;
 #undef FC_PW_ARGS
 }

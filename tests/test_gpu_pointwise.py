@@ -26,6 +26,13 @@ PW_LAYERS = [
     (2, 95, 97, 128, 128, 1, 2, 0, 1),        # strided projection: 4704 positions
     (1, 121, 83, 64, 256, 1, (2, 1), 0, 1),   # vertical stride only
     (1, 300, 310, 64, 64, 1, 1, 0, 1),        # 93000 positions: several units per wave
+    (2, 50, 47, 128, 512, 1, 1, 0, 1),        # four slices of 128 output channels
+    (1, 80, 81, 256, 1024, 1, 1, 0, 1),       # eight slices, four chunks of input channels
+    (1, 70, 66, 64, 512, 1, 1, 0, 1),         # two slices of 256 output channels
+    (2, 95, 97, 256, 192, 1, 2, 0, 1),        # three slices of 64: not a divisor of the workgroups per XCD
+    (1, 71, 67, 256, 2048, 1, 1, 0, 1),       # sixteen slices
+    (2, 50, 47, 512, 128, 1, 1, 0, 1),        # eight chunks of input channels, two slices of 64
+    (1, 80, 81, 512, 2048, 1, 1, 0, 1),       # thirty-two slices: a whole XCD per group of rows
 ]
 
 
