@@ -405,29 +405,33 @@ def depthwise_bench(torch, B, synth, workloads, args):
 
 
 def pointwise_bench(torch, B, synth, workloads, args):
-    """The 1x1 layers of a ResNet-50's first stage on the post-stem activation of 480x640 images,
-    batch 32, bf16, blob masks with the list given: per layer the dense call, the focused call
-    (irrelevant rows cleared) and the chained call (irrelevant rows left alone), each as a
-    HIP-graph replay of four calls.  These layers are bound by memory traffic: algorithmic bytes =
-    kept input rows + kept output rows (+ the cleared rows) + the list + weights and bias."""
+    """1x1 layers of a ResNet-50 (up to 512 input channels) at the resolutions its stages see them
+    on 480x640 images, batch 32, bf16, blob masks with the list given: per layer the dense call,
+    the focused call (irrelevant rows cleared) and the chained call (irrelevant rows left alone),
+    each as a HIP-graph replay of four calls.  These layers are bound by memory traffic:
+    algorithmic bytes = kept input rows + kept output rows (+ the cleared rows) + the list +
+    weights and bias."""
     irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
     n = workloads.POINTWISE_BATCH if args.batch is None else args.batch
-    h, w_ = workloads.POINTWISE_H, workloads.POINTWISE_W
     dev = torch.device("cuda:0")
     gen = synth.mask_bernoulli if args.mask == "bernoulli" else synth.mask_objects
-    mask = gen(n, h, w_, irr, 9, 0, 4)
-    md = torch.from_numpy(mask).to(dev)
-    idx, count = B.active_index_compact(md)
-    kept, m = int(count.item()), n * h * w_
+    mask0 = gen(n, workloads.POINTWISE_H, workloads.POINTWISE_W, irr, 9, 0, 4)
     to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
     rows, tot = [], {"dense": [0.0, 0.0], "focused": [0.0, 0.0], "chained": [0.0, 0.0]}
-    for li, (ci, co) in enumerate(workloads.resnet50_stage1_pointwise()):
+    kept0 = float(np.count_nonzero(mask0)) / mask0.size
+    for li, (ci, co, div) in enumerate(workloads.resnet50_pointwise()):
+        mask = np.ascontiguousarray(mask0[:, ::div, ::div])      # the centre-tap labels at that stage
+        h, w_ = mask.shape[1], mask.shape[2]
+        md = torch.from_numpy(mask).to(dev)
+        idx, count = B.active_index_compact(md)
+        kept, m = int(count.item()), n * h * w_
         xd = to_dev(synth.activations_large((n, h, w_, ci), synth.BF16, 9, li, 1))
         wd = to_dev(synth.he_weights(co, 1, 1, ci, synth.BF16, 9, li, 2))
         bd = torch.from_numpy(synth.bias(co, 9, li, 3)).to(dev)
         out = torch.empty((n, h, w_, co), dtype=torch.bfloat16, device=dev)
         fixed = ci * co * 2 + co * 4
-        row = {"layer": "%d->%d" % (ci, co), "kernel": "k_conv_pw" if ci <= 128 else "k_conv_dma"}
+        row = {"layer": "%d->%d@%dx%d" % (ci, co, h, w_),
+               "kernel": "k_conv_dma" if ci == 256 and co < 256 else "k_conv_pw"}
         for kind in ("dense", "focused", "chained"):
             flags = B.RELU | (B.SKIP_ZERO_FILL if kind == "chained" else 0)
             desc = B.conv_desc(n, h, w_, ci, co, (1, 1), (1, 1), (0, 0), (1, 1), B.BF16, B.BF16, flags)
@@ -450,9 +454,10 @@ def pointwise_bench(torch, B, synth, workloads, args):
     copy_gbps = calibrate_peaks(torch, B, B.BF16)["copy_gbps"]
     t_f, by_f = tot["focused"]
     print(json.dumps({
-        "pointwise": True, "workload": "ResNet-50 first-stage 1x1 layers, batch %d, %dx%d positions, bf16, %s masks, "
-        "%d %% irrelevant, kept list given" % (n, h, w_, args.mask, round(irr * 100)),
-        "launch": "HIP graph replay of four calls", "steps": args.steps, "kept_fraction": round(kept / m, 4),
+        "pointwise": True, "workload": "ResNet-50 1x1 layers of up to 512 input channels, batch %d, 480x640 images "
+        "(120x160 positions after the stem, halved per stage), bf16, %s masks, %d %% irrelevant, kept list given"
+        % (n, args.mask, round(irr * 100)),
+        "launch": "HIP graph replay of four calls", "steps": args.steps, "kept_fraction": round(kept0, 4),
         "layers": rows, "dense_ms": round(tot["dense"][0] * 1e3, 4), "focused_ms": round(t_f * 1e3, 4),
         "chained_ms": round(tot["chained"][0] * 1e3, 4), "speedup_vs_dense": round(tot["dense"][0] / t_f, 3),
         "roofline": {"bound": "hbm", "achieved": round(by_f / t_f / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
@@ -619,7 +624,7 @@ def main():
                     help="time a whole conv stack (dense / focused / focused without zero-fill between "
                          "convs) instead of the bench line")
     ap.add_argument("--pointwise", action="store_true",
-                    help="time the 1x1 layers of a ResNet-50's first stage (dense, focused, chained) and exit")
+                    help="time 1x1 layers of a ResNet-50 at their stages' resolutions (dense, focused, chained) and exit")
     ap.add_argument("--depthwise", action="store_true",
                     help="time the depthwise layers of a MobileNetV2 backbone (focused and dense) "
                          "instead of the bench line")

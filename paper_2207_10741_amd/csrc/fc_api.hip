@@ -1,7 +1,4 @@
 // C ABI of the library: argument checks on the host, then launches.
-#ifdef FC_TUNE
-#include <cstdlib>
-#endif
 #include "fc_internal.hpp"
 #include <atomic>
 
@@ -87,17 +84,13 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
 // fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
 // labelling rule reduces to the one pixel under the tap, so a kept row never has a gated tap
 // and the kernel reads no input mask while it gathers.  Measured against the tiled kernel on
-// the 1x1 layers of a ResNet-50 at batch 32: 10 .. 45 % faster wherever the output channels
-// make two slices or more or the input has at most 128 channels; 256 input channels into one
-// slice (256 -> 64, 256 -> 128 on the largest activations, bound by reading them) are 5 .. 15 %
-// slower and stay on the tiled kernel.
+// the 1x1 layers of a ResNet-50 at batch 32: 10 .. 45 % faster except with 256 input channels
+// into a single slice (256 -> 64, 256 -> 128 on the largest activations, bound by reading
+// them), which are 5 .. 15 % slower and stay on the tiled kernel.
 bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
 {
-#ifdef FC_TUNE
-    if (getenv("FC_NO_PW")) return false;
-#endif
     if (g.m <= kInlineRankPositions || !conv_pw_supported(g, in_dtype, out_dtype)) return false;
-    return g.c_in <= 128 || g.c_out >= 256;
+    return g.c_in != 256 || g.c_out >= 256;
 }
 
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }

@@ -116,12 +116,13 @@ def mobilenetv2_depthwise():
             (384, 14, 1), (576, 14, 1), (576, 14, 2), (960, 7, 1)]
 
 
-def resnet50_stage1_pointwise():
-    """(input channels, output channels) of the 1x1 layers in the first stage of a ResNet-50, whose
-    activations are the largest of the network: the reduction into the first block, the three
-    expansions (and the projection shortcut, same shape), the two reductions of the later blocks,
-    and the reduction that opens the second stage."""
-    return [(64, 64), (64, 256), (256, 64), (256, 128)]
+def resnet50_pointwise():
+    """(input channels, output channels, divisor of the post-stem side) of 1x1 layers of a ResNet-50
+    with up to 512 input channels: the reductions and expansions of the four stages' bottlenecks
+    (repeats of a shape listed once, projections with a stride left out)."""
+    return [(64, 64, 1), (64, 256, 1), (256, 64, 1), (256, 128, 1),
+            (128, 512, 2), (512, 128, 2), (512, 256, 2),
+            (256, 1024, 4), (512, 2048, 8)]
 
 
 POINTWISE_BATCH, POINTWISE_H, POINTWISE_W = 32, 120, 160   # the post-stem activation of 480 x 640 images
