@@ -106,6 +106,8 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0;
     const bool compact_in = (g.flags & FC_COMPACT_IN) != 0, compact_out = (g.flags & FC_COMPACT_OUT) != 0;
     const int rows = idx ? *count : g.m;
+    // rows compacted on both sides are row j in, row j out: a plain GEMM, the list is not read
+    const bool use_list = idx && !(compact_in && compact_out);
     // A workgroup multiplies by one slice of COUT output channels.  Workgroup b runs on XCD
     // b mod 8; the workgroups of an XCD form groups of n_slices neighbours that share their rows
     // (each takes another slice, so the rows come out of that XCD's L2 for all but the first),
@@ -153,7 +155,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     int issued = 0, mark_idx = 0, mark_x[RING] = {};
 
     auto issue_idx = [&](int v) {
-        if (!idx) return;
+        if (!use_list) return;
         const uint32_t r = (uint32_t)(b0 + v) * 32u + (uint32_t)lane;
         pw_dma_load4(rsrc_i, lane < 32 ? r * 4u : kOutOfRange, my0 + RING * kPwChunkBytes);
         issued += 1;
@@ -172,7 +174,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
         const int r = (b0 + v) * 32 + l32;
         const bool valid = r < rows;
         int p = r;
-        if (idx) {
+        if (use_list) {
             pw_wait_vmcnt(issued - mark_idx);
             pw_lds_settle(my0 + RING * kPwChunkBytes);
             p = idx_w[l32];
