@@ -79,18 +79,23 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;
 }
 
-// Does the pointwise kernel serve this layer?  1x1 layers without padding of 64 .. 512 input
-// channels whose weights, cut into slices of 64 .. 256 output channels, stay in LDS (see
-// fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
+// Does the pointwise kernel serve this layer?  1x1 layers without padding whose channel counts
+// are multiples of 8 and whose weights, cut into slices of 64 .. 256 output channels, stay in LDS
+// (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
 // labelling rule reduces to the one pixel under the tap, so a kept row never has a gated tap
 // and the kernel reads no input mask while it gathers.  Measured against the tiled kernel on
-// the 1x1 layers of a ResNet-50 at batch 32: 10 .. 45 % faster except with 256 input channels
-// into a single slice (256 -> 64, 256 -> 128 on the largest activations, bound by reading
-// them), which are 5 .. 15 % slower and stay on the tiled kernel.
+// the 1x1 layers of a ResNet-50 (batch 32) and of a MobileNetV2 (batch 256): 10 .. 45 % faster,
+// except (a) 256 input channels into at most 128 output channels on the largest activations
+// (bound by reading them: 5 .. 15 % slower) and (b) three or more input chunks into a single
+// slice on fewer than 100 000 positions (48 .. 72 KB of weights per workgroup for a few rows
+// each: up to 20 % slower).  Those stay on the tiled kernel.
 bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
 {
     if (g.m <= kInlineRankPositions || !conv_pw_supported(g, in_dtype, out_dtype)) return false;
-    return g.c_in != 256 || g.c_out >= 256;
+    if (g.c_in == 256 && g.c_out <= 128) return false;
+    const int kch = (g.c_in + 63) / 64;
+    if (kch >= 3 && g.c_out <= (kch > 4 ? 64 : 128) && g.m < 100000) return false;
+    return true;
 }
 
 size_t compact_ws(int64_t m) { return align_up((size_t)compact_blocks(m) * sizeof(int32_t), 256); }

@@ -1,22 +1,20 @@
-// Focused 1x1 convolution on the gfx950 matrix cores for layers whose whole weight matrix fits
-// LDS (Sec. III-A: a GEMM over the kept patches only, with the dense layer's weights).
+// Focused 1x1 convolution on the gfx950 matrix cores with the layer's weights resident in LDS
+// (Sec. III-A: a GEMM over the kept patches only, with the dense layer's weights).
 //
 // A 1x1 layer without padding is a plain GEMM of the kept pixels with a [C_in x C_out] matrix:
-// one gathered stage per row tile, then a store-heavy epilogue (the 64 -> 256 expansions of a
-// bottleneck write four times what they read).  The tiled kernel spends such a layer waiting:
-// set-up, the single gather and the epilogue of a tile follow one another and only a second
-// workgroup on the CU fills the gaps.  Here the weights (at most 32 KB) stay in LDS for the
-// whole launch, the launch is one workgroup of twelve waves per CU, and every wave is a
-// pipeline of its own over units of 32 kept rows: the rows of the next unit are on their way
-// (a wave-wide load into LDS, counted and waited for by the wave itself) while the current unit
-// is multiplied against all output channels and stored.  Waves do not cooperate after the
-// prologue: no barrier in the loop, and three waves per SIMD cover each other's waits.
-// 16-bit outputs leave through LDS as whole 128-byte lines (the accumulator layout by itself
-// gives 32-byte pieces, which cost a 64 -> 256 layer a third of its time).
-//
-// Layers of 64 or 128 input channels only.  With 256 input channels (four chunks per unit) the
-// same loop measured 5 .. 15 % slower than the tiled kernel, with two, three or four chunk
-// buffers per wave alike, so those layers stay on the tiled kernel.
+// one gathered row per kept position, a short reduction, and as many bytes written as read or
+// more (a bottleneck's 64 -> 256 expansion writes four times what it reads).  The tiled kernel
+// spends such a layer on fixed costs: set-up, the one or few stages and the epilogue of a tile
+// follow one another, and every tile fetches its own weights.  Here a workgroup (one per CU)
+// keeps one slice of the output channels' weights (at most 72 KB) in LDS for the whole launch,
+// and every one of its eight or twelve waves is a pipeline of its own over units of 32 kept
+// rows: the next 64-channel chunk of its rows is on its way (a wave-wide load into LDS, counted
+// and waited for by the wave itself) while the current one is multiplied against the slice.
+// Waves do not cooperate after the prologue: no barrier in the loop, two or three waves per SIMD
+// cover each other's waits.  16-bit outputs leave through LDS as whole 128-byte lines (the
+// accumulator layout by itself gives 32-byte pieces, which cost a 64 -> 256 layer a third of its
+// time).  Channel counts are any multiples of 8; which layers the library sends here is decided
+// in fc_api.hip (conv_pw_wanted), from measurements against the tiled kernel.
 //
 // Rows = kept output positions (from the list, or all positions of a dense layer); a row's pixel
 // is the position's centre tap (stride allowed, no padding), or row j of a compacted input.  The
@@ -30,7 +28,6 @@ namespace fc {
 constexpr uint32_t kPwChunkBytes = 32u * 128u;  // a chunk buffer: 32 rows x 64 channels
 // LDS of a wave: RING chunk buffers + the list entries of a unit
 constexpr uint32_t pw_wave_bytes(int ring) { return (uint32_t)ring * kPwChunkBytes + 256u; }
-constexpr uint32_t kPwMaxWeightBytes = 64u * 1024u;
 
 struct PwDivs {
     FastDiv wo, ho, cpr; // output width, output height, 16-byte pieces per output row
@@ -77,30 +74,38 @@ __device__ __forceinline__ void pw_lds_settle(uint32_t lds_addr)
     __asm__ volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(probe) : "v"(lds_addr) : "memory");
 }
 
-// DT: storage type (bf16 / f16); TO: float or the 16-bit / 8-bit carrier of the output; KCH:
-// 64-channel chunks of the input; NCB: 32-channel blocks of the output; NW: waves per workgroup.
-template <int DT, typename TO, int KCH, int NCB, int NW, int RING>
-__global__ __launch_bounds__(NW * 64, 1)
-void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t *__restrict__ mask_in,
+// DT: storage type (bf16 / f16); TO: float or the 16-bit / 8-bit carrier of the output; NCB:
+// 32-channel blocks of a workgroup's slice of the output channels; KCT: the number of 64-channel
+// chunks of the input where the chunk loop is unrolled (1, 2, 4, 8: 10 % faster on layers of
+// several chunks), 0 = a launch parameter.  The waves of the workgroup (blockDim.x / 64) are a
+// launch parameter.  Channel counts are multiples of 8 (16-byte pieces): the pieces of the last chunk
+// past c_in and the channels of the last slice past c_out are read as zeros and never stored.
+template <int DT, typename TO, int NCB, int KCT>
+__global__ __launch_bounds__(768, 1)
+void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, const uint8_t *__restrict__ mask_in,
                const uint8_t *__restrict__ mask_out, const uint16_t *__restrict__ w,
                const float *__restrict__ bias, const int32_t *__restrict__ idx,
                const int32_t *__restrict__ count, TO *__restrict__ out)
 {
     static_assert(DT == FC_BF16 || DT == FC_F16, "16-bit storage");
-    static_assert(KCH == 1 || NCB <= 4, "with several input chunks all accumulators are live at once");
-    constexpr int CIN = KCH * 64, COUT = NCB * 32;
+    constexpr int RING = 2;                   // chunk buffers per wave
+    constexpr int COUT = NCB * 32;
     constexpr int GB = NCB < 4 ? NCB : 4;     // channel blocks multiplied at a time
-    constexpr uint32_t WBYTES = (uint32_t)KCH * COUT * 128u;
-    static_assert(WBYTES <= kPwMaxWeightBytes, "the weights stay in LDS");
+    // (with several input chunks all accumulators of a row are live at once: the host gives
+    // slices of eight blocks to layers of one chunk only)
+    static_assert(NCB <= 4 || KCT == 1, "slices of eight blocks: one chunk");
+    const int kch = KCT ? KCT : kch_arg;
+    const uint32_t wbytes = (uint32_t)kch * COUT * 128u;
+    const int nw = (int)blockDim.x >> 6;
 
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>(smem_raw);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const float *bias_s = reinterpret_cast<const float *>(smem_raw + WBYTES);
-    unsigned char *const my = smem_raw + WBYTES + 1024u + (size_t)wave * pw_wave_bytes(RING);
-    const uint32_t my0 = lds0 + WBYTES + 1024u + (uint32_t)wave * pw_wave_bytes(RING);
+    const float *bias_s = reinterpret_cast<const float *>(smem_raw + wbytes);
+    unsigned char *const my = smem_raw + wbytes + 1024u + (size_t)wave * pw_wave_bytes(RING);
+    const uint32_t my0 = lds0 + wbytes + 1024u + (uint32_t)wave * pw_wave_bytes(RING);
     const int32_t *const idx_w = reinterpret_cast<const int32_t *>(my + RING * kPwChunkBytes);
 
     const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0;
@@ -111,45 +116,59 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     // A workgroup multiplies by one slice of COUT output channels.  Workgroup b runs on XCD
     // b mod 8; the workgroups of an XCD form groups of n_slices neighbours that share their rows
     // (each takes another slice, so the rows come out of that XCD's L2 for all but the first),
-    // and XCD j takes the j-th contiguous eighth of the rows.
-    const int n_slices = g.c_out / COUT;
+    // and XCD j takes the j-th contiguous eighth of the rows.  Workgroups left over when the
+    // slices do not divide an XCD's workgroups take no rows (they still clear rows below).
+    const int n_slices = (g.c_out + COUT - 1) / COUT;
     const int in_xcd = (int)blockIdx.x >> 3, groups_per_xcd = ((int)gridDim.x >> 3) / n_slices;
-    const int co0 = (in_xcd % n_slices) * COUT;
+    const bool spare = in_xcd >= groups_per_xcd * n_slices;
+    const int co0 = spare ? 0 : (in_xcd % n_slices) * COUT;
     const int group = ((int)blockIdx.x & 7) * groups_per_xcd + in_xcd / n_slices;
+    const int co_left = g.c_out - co0; // channels of this slice and after it
     // an output larger than the memory-side cache (256 MB) is streamed past it: measured on a
     // 64 -> 256 layer, 314 MB of rows leave 22 % faster that way, 164 MB of rows 10 % slower
     const bool stream_out = (int64_t)rows * g.c_out * (int)sizeof(TO) > (256ll << 20);
+    const int cin8 = g.c_in >> 3; // 16-byte pieces of an input row
 
     // ---- the weights: LDS row (chunk, output channel) holds that channel's 64 input channels
     // of the chunk, its 16-byte pieces swizzled by the channel ----
-    {
-        const u32x4_t rsrc_w = make_rsrc_words(w + (size_t)co0 * CIN, (uint32_t)COUT * CIN * 2u);
-        constexpr int LOADS = KCH * COUT / 8; // wave loads of 8 rows each
-        for (int ii = wave; ii < LOADS; ii += NW) {
+    if (!spare) {
+        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * (uint32_t)g.c_in * 2u);
+        const int loads = kch * (COUT / 8); // wave loads of 8 rows each
+        for (int ii = wave; ii < loads; ii += nw) {
             const int ch = ii / (COUT / 8), co = (ii - ch * (COUT / 8)) * 8 + (lane >> 3);
-            const uint32_t off = ((uint32_t)co * CIN + (uint32_t)ch * 64u) * 2u + (uint32_t)((lane & 7) ^ FC_SWZ(co)) * 16u;
-            dma_load16(rsrc_w, off, lds0 + (uint32_t)ii * 1024u);
+            const int piece = ch * 8 + ((lane & 7) ^ (int)FC_SWZ(co));
+            const bool ok = co < co_left && piece < cin8;
+            const uint32_t off = ((uint32_t)(co0 + co) * (uint32_t)g.c_in) * 2u + (uint32_t)piece * 16u;
+            dma_load16(rsrc_w, ok ? off : kOutOfRange, lds0 + (uint32_t)ii * 1024u);
         }
-        for (int c = tid; c < COUT; c += NW * 64)
-            reinterpret_cast<float *>(smem_raw + WBYTES)[c] = bias ? bias[co0 + c] : 0.f;
+        for (int c = tid; c < COUT; c += nw * 64)
+            reinterpret_cast<float *>(smem_raw + wbytes)[c] = (bias && c < co_left) ? bias[co0 + c] : 0.f;
     }
     wait_vmcnt<0>();
     __syncthreads();
 
     // ---- my share of the kept rows: units of 32 rows, the same number (+-1) for every wave of
     // the groups ----
-    const int nwv = 8 * groups_per_xcd * NW;
-    const int wv = group * NW + wave;
+    const int nwv = 8 * groups_per_xcd * nw;
+    const int wv = group * nw + wave;
     const int nb = (rows + 31) >> 5;
     const int share_q = nb / nwv, share_r = nb - share_q * nwv;
     const int b0 = wv * share_q + (wv * share_r) / nwv;
     const int b1 = (wv + 1) * share_q + ((wv + 1) * share_r) / nwv;
-    const int nu = b1 - b0;
+    const int nu = spare ? 0 : b1 - b0;
 
     const uint32_t x_rows = compact_in ? (uint32_t)g.m : (uint32_t)g.n * g.h * g.w;
-    const u32x4_t rsrc_x = make_rsrc_words(x, x_rows * (uint32_t)(CIN * 2));
+    const uint32_t row_bytes = (uint32_t)g.c_in * 2u;
+    const u32x4_t rsrc_x = make_rsrc_words(x, x_rows * row_bytes);
     const u32x4_t rsrc_i = make_rsrc_words(idx, (uint32_t)rows * 4u);
     const bool unit_step = g.sh == 1 && g.sw == 1; // (no padding: the pixel of a position is the position)
+    // the last chunk of a row may be short: bit j says whether the piece this lane gathers in
+    // wave load j lies inside the row there
+    const int tail8 = cin8 - (kch - 1) * 8;
+    uint32_t tail_ok = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        tail_ok |= (uint32_t)(((lane & 7) ^ (int)FC_SWZ(j * 8 + (lane >> 3))) < tail8) << j;
 
     // loads issued so far by this wave, and that count right after the last load of what is awaited
     int issued = 0, mark_idx = 0, mark_x[RING] = {};
@@ -189,7 +208,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
             const int oh = q1 - n * g.ho;
             pix = (n * g.h + oh * g.sh) * g.w + ow * g.sw;
         }
-        const uint32_t off = valid ? (uint32_t)pix * (uint32_t)(CIN * 2) : kOutOfRange;
+        const uint32_t off = valid ? (uint32_t)pix * row_bytes : kOutOfRange;
         st_p[k] = valid ? (compact_out ? r : p) : -1;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -201,9 +220,12 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     };
     // one stage: chunk c of the unit with state k, into ring buffer `buf`
     auto issue_x = [&](int k, int c, int buf) {
+        const bool last = c == kch - 1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            dma_load16_s(rsrc_x, st_off[k][j], (uint32_t)c * 128u, my0 + (uint32_t)buf * kPwChunkBytes + (uint32_t)j * 1024u);
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t o = (last && !((tail_ok >> j) & 1u)) ? kOutOfRange : st_off[k][j];
+            dma_load16_s(rsrc_x, o, (uint32_t)c * 128u, my0 + (uint32_t)buf * kPwChunkBytes + (uint32_t)j * 1024u);
+        }
         issued += 4;
 #pragma unroll
         for (int r = 0; r < RING; ++r) mark_x[r] = buf == r ? issued : mark_x[r];
@@ -233,7 +255,8 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
                     v0 = relu_keep_nan(v0); v1 = relu_keep_nan(v1);
                     v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
                 }
-                if (p_mine >= 0) store4<DT, TO>(row + q * 8 + half * 4, v0, v1, v2, v3);
+                if (p_mine >= 0 && cb * 32 + q * 8 + half * 4 < co_left)
+                    store4<DT, TO>(row + q * 8 + half * 4, v0, v1, v2, v3);
             }
         } else {
 #pragma unroll
@@ -241,7 +264,8 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
                 uint32_t pk;
                 store4<DT, TO>(reinterpret_cast<TO *>(&pk), v[q * 4], v[q * 4 + 1], v[q * 4 + 2], v[q * 4 + 3]);
                 if (g.flags & FC_RELU) pk = relu_packed8(pk);
-                if (p_mine >= 0) *reinterpret_cast<uint32_t *>(row + q * 8 + half * 4) = pk;
+                if (p_mine >= 0 && cb * 32 + q * 8 + half * 4 < co_left)
+                    *reinterpret_cast<uint32_t *>(row + q * 8 + half * 4) = pk;
             }
         }
     };
@@ -252,6 +276,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
     // registers); a wave's LDS accesses execute in order, so no barrier is needed.
     auto store_pair = [&](const f32x16_t &a0, const f32x16_t &a1, int cb, unsigned char *stg) {
         if constexpr (sizeof(TO) == 2) {
+            if (cb * 32 >= co_left) return; // (a pair wholly past the last channel)
 #pragma unroll
             for (int bl = 0; bl < 2; ++bl) {
                 const f32x16_t &a = bl ? a1 : a0;
@@ -272,6 +297,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
             __asm__ volatile("" ::: "memory");
             u32x4_t piece[4];
             u32x4_t *at16[4];
+            const bool inside = cb * 32 + (lane & 7) * 8 < co_left; // this lane's 8 channels exist
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int row = j * 8 + (lane >> 3);
@@ -285,50 +311,42 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
             if (stream_out) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (st_pr[0][j] >= 0)
+                    if (st_pr[0][j] >= 0 && inside)
                         __asm__ volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(at16[j]), "v"(piece[j]) : "memory");
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (st_pr[0][j] >= 0) *at16[j] = piece[j];
+                    if (st_pr[0][j] >= 0 && inside) *at16[j] = piece[j];
             }
             __asm__ volatile("" ::: "memory");
         }
     };
 
-    // ---- the pipeline: stage t = (unit t / KCH, chunk t % KCH) lives in ring buffer t % RING,
-    // and stage t + RING - 1 is issued when stage t is about to be consumed ----
-    constexpr int AHEAD = RING - 1;
-    static_assert(AHEAD >= 1 && AHEAD <= KCH, "the stages in flight belong to this unit or the next");
+    // ---- the pipeline: stage t = (unit t / kch, chunk t % kch) lives in ring buffer t % 2, and
+    // stage t + 1 is issued when stage t is about to be consumed ----
     if (nu > 0) {
         issue_idx(0);
         setup(0, 0);
         if (nu > 1) issue_idx(1);
-#pragma unroll
-        for (int c = 0; c < AHEAD; ++c) issue_x(0, c, c);
+        issue_x(0, 0, 0);
     }
     f32x16_t acc[GB];
     int buf = 0;
     for (int u = 0; u < nu; ++u) {
         const int p_mine = st_p[0];
-#pragma unroll
-        for (int c = 0; c < KCH; ++c) {
-            // a stage goes out first, into the buffer freed last: a later chunk of this unit, or
-            // a chunk of the next unit (whose rows are looked up before its first chunk)
-            const int bufn = buf == 0 ? RING - 1 : buf - 1;
-            if (c + AHEAD < KCH) {
-                issue_x(0, c + AHEAD, bufn);
+#pragma unroll(KCT ? KCT : 1)
+        for (int c = 0; c < kch; ++c) {
+            // a stage goes out first, into the buffer freed last: the next chunk of this unit, or
+            // the first chunk of the next unit (whose rows are looked up before it)
+            const int bufn = buf ^ 1;
+            if (c + 1 < kch) {
+                issue_x(0, c + 1, bufn);
             } else if (u + 1 < nu) {
-                if (c + AHEAD == KCH) {
-                    setup(u + 1, 1);
-                    if (u + 2 < nu) issue_idx(u + 2);
-                }
-                issue_x(1, c + AHEAD - KCH, bufn);
+                setup(u + 1, 1);
+                if (u + 2 < nu) issue_idx(u + 2);
+                issue_x(1, 0, bufn);
             }
-            int awaited = 0;
-#pragma unroll
-            for (int r = 0; r < RING; ++r) awaited = buf == r ? mark_x[r] : awaited;
-            pw_wait_vmcnt(issued - awaited);
+            pw_wait_vmcnt(issued - (buf == 0 ? mark_x[0] : mark_x[1]));
             pw_lds_settle(my0 + (uint32_t)buf * kPwChunkBytes);
             const unsigned char *xs = my + (size_t)buf * kPwChunkBytes;
             Frag<DT> xf[4];
@@ -351,7 +369,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
 #pragma unroll
                     for (int b = 0; b < GB; ++b) acc[b] = mfma32<DT>(wf[b], xf[kk], acc[b]);
                 }
-                if (c == KCH - 1) {
+                if (c == kch - 1) {
                     if constexpr (sizeof(TO) == 2) {
 #pragma unroll
                         for (int b = 0; b < GB; b += 2)
@@ -362,7 +380,7 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
                     }
                 }
             }
-            buf = buf + 1 == RING ? 0 : buf + 1;
+            buf ^= 1;
         }
         st_p[0] = st_p[1];
 #pragma unroll
@@ -378,10 +396,10 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
         u32x4_t *o4 = reinterpret_cast<u32x4_t *>(out);
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
         const int cpr = g.c_out * (int)sizeof(TO) / 16; // 16-byte pieces per row
-        const int workers = (int)gridDim.x * NW;
+        const int workers = (int)gridDim.x * nw;
         const int nblocks = (g.m + 63) >> 6;
         const int parts = min(max(workers / nblocks, 1), 16);
-        for (int item = (int)blockIdx.x * NW + wave; item < nblocks * parts; item += workers) {
+        for (int item = (int)blockIdx.x * nw + wave; item < nblocks * parts; item += workers) {
             const int blk = item / parts, part = item - blk * parts;
             const int pp = blk * 64 + lane;
             bool kept = true; // (positions past the end count as kept: nothing to clear)
@@ -409,14 +427,19 @@ void k_conv_pw(Geom g, PwDivs dv, const uint16_t *__restrict__ x, const uint8_t 
 
 // ---------------------------------------------------------------------------
 
-// 32-channel blocks in a workgroup's slice of the output channels: the widest slice whose weights
-// fit (256 channels from 64 input channels, where a row's accumulators are computed in two
-// halves; 128 channels else), 0 if the layer has no whole number of slices
+constexpr uint32_t kPwLdsBytes = 160u * 1024u;
+
+// 32-channel blocks in a workgroup's slice of the output channels, 0 if the layer does not fit.
+// A layer of one input chunk takes slices of up to 256 channels (a row's accumulators are then
+// computed in two halves) and so reads every row once for up to 256 output channels; with more
+// chunks all accumulators of a row are live at once and a slice is 128 channels, or 64 where
+// 128 would not leave room for eight waves beside the weights.
 static int pw_slice_blocks(const Geom &g)
 {
-    if (g.c_in == 64 && g.c_out % 256 == 0) return 8;
-    if (g.c_in <= 256 && g.c_out % 128 == 0) return 4;
-    if (g.c_out % 64 == 0) return 2;
+    const int kch = (g.c_in + 63) / 64;
+    if (kch == 1) return g.c_out <= 64 ? 2 : g.c_out <= 128 ? 4 : 8;
+    for (int ncb = g.c_out <= 64 ? 2 : 4; ncb >= 2; ncb -= 2)
+        if ((uint32_t)kch * ncb * 32u * 128u + 1024u + 8u * pw_wave_bytes(2) <= kPwLdsBytes) return ncb;
     return 0;
 }
 
@@ -443,29 +466,33 @@ bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
     if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
     if (out_dtype != in_dtype && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
     if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0)) return false;
-    if (g.c_in != 64 && g.c_in != 128 && g.c_in != 256 && g.c_in != 512) return false;
+    // rows of whole 16-byte pieces on both sides
+    if (g.c_in < 8 || g.c_in % 8 != 0 || g.c_out < 8 || g.c_out % 8 != 0) return false;
+    if (out_dtype == FC_FP8 && g.c_out % 16 != 0) return false;
     const int ncb = pw_slice_blocks(g);
     if (ncb == 0) return false;
     // the slices of a group of workgroups sit on one XCD
-    const int n_slices = g.c_out / (ncb * 32), per_xcd = pw_grid() >> 3;
-    if (n_slices > per_xcd || per_xcd % n_slices != 0) return false;
+    const int n_slices = (g.c_out + ncb * 32 - 1) / (ncb * 32), per_xcd = pw_grid() >> 3;
+    if (n_slices > per_xcd) return false;
     if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
+    if ((uint64_t)g.c_out * g.c_in * 2u >= kBufferLimit) return false;
     if ((uint64_t)g.m * 4u >= kBufferLimit) return false; // the list goes through a descriptor as well
     return true;
 }
 
-template <int DT, typename TO, int KCH, int NCB, int RING>
+template <int DT, typename TO, int NCB, int KCT>
 static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                             const void *w, const float *bias, const int32_t *idx, const int32_t *count, void *out,
                             hipStream_t s)
 {
-    // twelve waves per CU where the weights leave room for their buffers, else eight, else what fits
-    constexpr uint32_t WBYTES = (uint32_t)KCH * NCB * 32u * 128u;
-    constexpr int FIT = (int)((160u * 1024u - WBYTES - 1024u) / pw_wave_bytes(RING));
-    constexpr int NW = FIT >= 12 ? 12 : FIT >= 8 ? 8 : FIT;
-    static_assert(NW >= 4, "a wave per SIMD at least");
-    constexpr size_t lds = WBYTES + 1024u + (size_t)NW * pw_wave_bytes(RING);
-    auto kern = k_conv_pw<DT, TO, KCH, NCB, NW, RING>;
+    // twelve waves per CU where the weights leave room for their buffers, else eight
+    const int kch = (g.c_in + 63) / 64;
+    const uint32_t wbytes = (uint32_t)kch * NCB * 32u * 128u;
+    const int fit = (int)((kPwLdsBytes - wbytes - 1024u) / pw_wave_bytes(2));
+    if (fit < 8) return hipErrorInvalidValue;
+    const int nw = fit >= 12 ? 12 : 8;
+    const size_t lds = wbytes + 1024u + (size_t)nw * pw_wave_bytes(2);
+    auto kern = k_conv_pw<DT, TO, NCB, KCT>;
     PwDivs dv;
     dv.wo = make_fastdiv((uint32_t)g.wo);
     dv.ho = make_fastdiv((uint32_t)g.ho);
@@ -477,11 +504,12 @@ static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in
     if (e != hipSuccess) return e;
     const uint64_t dev_bit = 1ull << (dev & 63);
     if (!(attr_devices.load(std::memory_order_acquire) & dev_bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kPwLdsBytes);
         if (e != hipSuccess) return e;
         attr_devices.fetch_or(dev_bit, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(pw_grid()), dim3(NW * 64), lds, s, g, dv, (const uint16_t *)x, mask_in, mask_out,
+    hipLaunchKernelGGL(kern, dim3(pw_grid()), dim3(nw * 64), lds, s, g, dv, kch, (const uint16_t *)x, mask_in, mask_out,
                        (const uint16_t *)w, bias, idx, count, (TO *)out);
     return hipGetLastError();
 }
@@ -492,15 +520,21 @@ static hipError_t launch_pw_shape(const Geom &g, const void *x, const uint8_t *m
                                   void *out, hipStream_t s)
 {
 #define FC_PW_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
-    const int kch = g.c_in / 64, ncb = pw_slice_blocks(g);
-    if (kch == 1 && ncb == 2) return launch_pw<DT, TO, 1, 2, 2>(FC_PW_ARGS);
-    if (kch == 1 && ncb == 4) return launch_pw<DT, TO, 1, 4, 2>(FC_PW_ARGS);
-    if (kch == 1 && ncb == 8) return launch_pw<DT, TO, 1, 8, 2>(FC_PW_ARGS);
-    if (kch == 2 && ncb == 2) return launch_pw<DT, TO, 2, 2, 2>(FC_PW_ARGS);
-    if (kch == 2 && ncb == 4) return launch_pw<DT, TO, 2, 4, 2>(FC_PW_ARGS);
-    if (kch == 4 && ncb == 2) return launch_pw<DT, TO, 4, 2, 2>(FC_PW_ARGS);
-    if (kch == 4 && ncb == 4) return launch_pw<DT, TO, 4, 4, 2>(FC_PW_ARGS);
-    if (kch == 8 && ncb == 2) return launch_pw<DT, TO, 8, 2, 2>(FC_PW_ARGS);
+    const int ncb = pw_slice_blocks(g), kch = (g.c_in + 63) / 64;
+    if (ncb == 8) return launch_pw<DT, TO, 8, 1>(FC_PW_ARGS);
+    if (ncb == 4) {
+        if (kch == 1) return launch_pw<DT, TO, 4, 1>(FC_PW_ARGS);
+        if (kch == 2) return launch_pw<DT, TO, 4, 2>(FC_PW_ARGS);
+        if (kch == 4) return launch_pw<DT, TO, 4, 4>(FC_PW_ARGS);
+        return launch_pw<DT, TO, 4, 0>(FC_PW_ARGS);
+    }
+    if (ncb == 2) {
+        if (kch == 1) return launch_pw<DT, TO, 2, 1>(FC_PW_ARGS);
+        if (kch == 2) return launch_pw<DT, TO, 2, 2>(FC_PW_ARGS);
+        if (kch == 4) return launch_pw<DT, TO, 2, 4>(FC_PW_ARGS);
+        if (kch == 8) return launch_pw<DT, TO, 2, 8>(FC_PW_ARGS);
+        return launch_pw<DT, TO, 2, 0>(FC_PW_ARGS);
+    }
     return hipErrorInvalidValue;
 #undef FC_PW_ARGS
 }

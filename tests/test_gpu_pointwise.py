@@ -1,7 +1,7 @@
 """GPU parity of the pointwise (1x1, no padding) matrix-core kernel that keeps the layer's weights in
-LDS: layers of more than 4096 positions with 64 or 128 input channels and 64, 128 or 256 output
-channels, against the CPU oracle (the layers of 256 input channels in the list run on the tiled
-kernel and are held to the same bars).  fp32 outputs within 1e-4 of the RMS of the kept outputs (fp32 accumulation of at
+LDS: layers of more than 4096 positions whose channel counts are multiples of 8, against the CPU
+oracle (the two layers of 256 input channels and at most 128 output channels in the list run on
+the tiled kernel and are held to the same bars).  fp32 outputs within 1e-4 of the RMS of the kept outputs (fp32 accumulation of at
 most 256 products of 16-bit values); 16-bit and 8-bit outputs are the one rounding of the kernel's
 own fp32 output, bit for bit."""
 import numpy as np
@@ -35,6 +35,22 @@ PW_LAYERS = [
     (1, 80, 81, 512, 2048, 1, 1, 0, 1),       # thirty-two slices: a whole XCD per group of rows
 ]
 
+# channel counts off the chunk and slice sizes (MobileNetV2's expansions and projections among them)
+PW_TAIL_LAYERS = [
+    (2, 60, 70, 16, 96, 1, 1, 0, 1),          # a quarter of a chunk in, three blocks out
+    (2, 60, 70, 24, 144, 1, 1, 0, 1),         # 48-byte rows in; a slice of eight blocks, 144 channels of it real
+    (2, 60, 70, 144, 24, 1, 1, 0, 1),         # three chunks, the last a quarter full; 48-byte rows out
+    (2, 50, 47, 32, 16, 1, 1, 0, 1),
+    (1, 80, 81, 192, 64, 1, 1, 0, 1),
+    (1, 80, 81, 384, 96, 1, 1, 0, 1),         # six chunks, two slices of 64, the second half full
+    (1, 80, 81, 576, 160, 1, 1, 0, 1),        # nine chunks (72 KB of weights), three slices: two workgroups per XCD spare
+    (1, 70, 66, 160, 960, 1, 1, 0, 1),        # eight slices of 128, the last half full
+    (1, 70, 66, 320, 1280, 1, 1, 0, 1),       # ten slices: three groups per XCD
+    (1, 71, 67, 8, 8, 1, 1, 0, 1),            # one piece in, one piece out
+    (1, 71, 67, 72, 40, 1, 2, 0, 1),          # one piece in the second chunk; strided
+    (1, 71, 67, 64, 384, 1, 1, 0, 1),         # two slices of 256, the second half full
+]
+
 
 def _check_f32(out, want, keep, zero_filled=True):
     got = G.to_f64(out)
@@ -52,6 +68,36 @@ def _check_f32(out, want, keep, zero_filled=True):
 def test_pointwise_layers_match_oracle(layer, mask_kind):
     out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=231)
     _check_f32(out, want, keep)
+
+
+@pytest.mark.parametrize("layer", PW_TAIL_LAYERS)
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", None])
+def test_pointwise_channel_tails_match_oracle(layer, mask_kind):
+    torch = G.torch_mod()
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=242)
+    _check_f32(out, want, keep)
+    # 16-bit output: the same sums rounded once, through the staged stores
+    o16, _, _ = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=242, out_dtype=synth.BF16)
+    assert torch.equal(o16, out.to(o16.dtype))
+    # chained: irrelevant rows untouched, also past a short last slice
+    oc, _, _ = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=242, out_dtype=synth.BF16,
+                          flags_extra=B.SKIP_ZERO_FILL, precomputed=True)
+    k = torch.from_numpy(keep).to(G.dev())
+    assert torch.equal(oc[k], o16[k]) and bool((oc[~k] == 7.0).all())
+
+
+@pytest.mark.parametrize("layer", [PW_TAIL_LAYERS[0], PW_TAIL_LAYERS[4], PW_TAIL_LAYERS[6], PW_TAIL_LAYERS[7]])
+def test_pointwise_channel_tails_f16_and_fp8_output(layer):
+    torch = G.torch_mod()
+    o32, want, keep = _run_layer(*layer, synth.F16, seed=243)
+    _check_f32(o32, want, keep)
+    o8, _, _ = _run_layer(*layer, synth.F16, seed=243, out_dtype=B.FP8)
+    got = o8.view(torch.uint8).cpu().numpy()
+    f32 = o32.cpu().numpy()
+    expect = O.narrow_fp8(f32.astype(np.float64))
+    expect[f32 == 0] = 0
+    np.testing.assert_array_equal(got[keep], expect[keep])
+    assert not got[~keep].any()
 
 
 @pytest.mark.parametrize("layer", [PW_LAYERS[0], PW_LAYERS[1], PW_LAYERS[3], PW_LAYERS[6]])
