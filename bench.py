@@ -404,6 +404,18 @@ def depthwise_bench(torch, B, synth, workloads, args):
         "dense_GBps": round(bytes_d / t_d / 1e9, 1)}))
 
 
+def pointwise_kernel_of(ci, co, m):
+    """Which matrix-core kernel the library gives a 1x1 layer (the rule of its dispatch, restated
+    for the bench's table: the profiler's kernel names are the evidence)."""
+    kch = (ci + 63) // 64
+    fits = kch == 1 or kch * 64 * 128 + 1024 + 8 * 8448 <= 160 * 1024
+    if m <= 4096 or ci % 8 or co % 8 or not fits or (ci == 256 and co <= 128):
+        return "k_conv_dma"
+    if kch >= 3 and co <= (64 if kch > 4 else 128) and m < 100000:
+        return "k_conv_dma"
+    return "k_conv_pw"
+
+
 def pointwise_bench(torch, B, synth, workloads, args):
     """1x1 layers of a ResNet-50 (up to 512 input channels) at the resolutions its stages see them
     on 480x640 images, batch 32, bf16, blob masks with the list given: per layer the dense call,
@@ -412,14 +424,15 @@ def pointwise_bench(torch, B, synth, workloads, args):
     algorithmic bytes = kept input rows + kept output rows (+ the cleared rows) + the list +
     weights and bias."""
     irr = workloads.HEADLINE_IRRELEVANT if args.irrelevant is None else args.irrelevant
-    n = workloads.POINTWISE_BATCH if args.batch is None else args.batch
+    mbv2 = args.pointwise == "mobilenetv2"    # the 1x1 layers of a MobileNetV2 on 224x224 images, batch 256
+    n = (256 if mbv2 else workloads.POINTWISE_BATCH) if args.batch is None else args.batch
     dev = torch.device("cuda:0")
     gen = synth.mask_bernoulli if args.mask == "bernoulli" else synth.mask_objects
-    mask0 = gen(n, workloads.POINTWISE_H, workloads.POINTWISE_W, irr, 9, 0, 4)
+    mask0 = gen(n, 224, 224, irr, 9, 0, 4) if mbv2 else gen(n, workloads.POINTWISE_H, workloads.POINTWISE_W, irr, 9, 0, 4)
     to_dev = lambda bits: torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
     rows, tot = [], {"dense": [0.0, 0.0], "focused": [0.0, 0.0], "chained": [0.0, 0.0]}
     kept0 = float(np.count_nonzero(mask0)) / mask0.size
-    for li, (ci, co, div) in enumerate(workloads.resnet50_pointwise()):
+    for li, (ci, co, div) in enumerate(workloads.mobilenetv2_pointwise() if mbv2 else workloads.resnet50_pointwise()):
         mask = np.ascontiguousarray(mask0[:, ::div, ::div])      # the centre-tap labels at that stage
         h, w_ = mask.shape[1], mask.shape[2]
         md = torch.from_numpy(mask).to(dev)
@@ -431,7 +444,7 @@ def pointwise_bench(torch, B, synth, workloads, args):
         out = torch.empty((n, h, w_, co), dtype=torch.bfloat16, device=dev)
         fixed = ci * co * 2 + co * 4
         row = {"layer": "%d->%d@%dx%d" % (ci, co, h, w_),
-               "kernel": "k_conv_dma" if ci == 256 and co < 256 else "k_conv_pw"}
+               "kernel": pointwise_kernel_of(ci, co, m)}
         for kind in ("dense", "focused", "chained"):
             flags = B.RELU | (B.SKIP_ZERO_FILL if kind == "chained" else 0)
             desc = B.conv_desc(n, h, w_, ci, co, (1, 1), (1, 1), (0, 0), (1, 1), B.BF16, B.BF16, flags)
@@ -454,9 +467,11 @@ def pointwise_bench(torch, B, synth, workloads, args):
     copy_gbps = calibrate_peaks(torch, B, B.BF16)["copy_gbps"]
     t_f, by_f = tot["focused"]
     print(json.dumps({
-        "pointwise": True, "workload": "ResNet-50 1x1 layers of up to 512 input channels, batch %d, 480x640 images "
-        "(120x160 positions after the stem, halved per stage), bf16, %s masks, %d %% irrelevant, kept list given"
-        % (n, args.mask, round(irr * 100)),
+        "pointwise": True, "workload": ("MobileNetV2 1x1 layers, batch %d, 224x224 images, bf16, %s masks, %d %% "
+                                        "irrelevant, kept list given" if mbv2 else
+                                        "ResNet-50 1x1 layers of up to 512 input channels, batch %d, 480x640 images "
+                                        "(120x160 positions after the stem, halved per stage), bf16, %s masks, %d %% "
+                                        "irrelevant, kept list given") % (n, args.mask, round(irr * 100)),
         "launch": "HIP graph replay of four calls", "steps": args.steps, "kept_fraction": round(kept0, 4),
         "layers": rows, "dense_ms": round(tot["dense"][0] * 1e3, 4), "focused_ms": round(t_f * 1e3, 4),
         "chained_ms": round(tot["chained"][0] * 1e3, 4), "speedup_vs_dense": round(tot["dense"][0] / t_f, 3),
@@ -623,8 +638,9 @@ def main():
     ap.add_argument("--stack", choices=sorted(STACKS), default=None,
                     help="time a whole conv stack (dense / focused / focused without zero-fill between "
                          "convs) instead of the bench line")
-    ap.add_argument("--pointwise", action="store_true",
-                    help="time 1x1 layers of a ResNet-50 at their stages' resolutions (dense, focused, chained) and exit")
+    ap.add_argument("--pointwise", nargs="?", const="resnet50", default=None, choices=["resnet50", "mobilenetv2"],
+                    help="time the 1x1 layers of a ResNet-50 (default) or of a MobileNetV2 at their stages' "
+                         "resolutions (dense, focused, chained) and exit")
     ap.add_argument("--depthwise", action="store_true",
                     help="time the depthwise layers of a MobileNetV2 backbone (focused and dense) "
                          "instead of the bench line")

@@ -125,6 +125,15 @@ def resnet50_pointwise():
             (256, 1024, 4), (512, 2048, 8)]
 
 
+def mobilenetv2_pointwise():
+    """(input channels, output channels, divisor of the image side) of the 1x1 layers of a MobileNetV2
+    backbone (the expansions and projections of its inverted-residual blocks and the final layer);
+    repeats of a shape listed once."""
+    return [(32, 16, 2), (16, 96, 2), (96, 24, 4), (24, 144, 4), (144, 24, 4), (144, 32, 8), (32, 192, 8),
+            (192, 32, 8), (192, 64, 16), (64, 384, 16), (384, 64, 16), (384, 96, 16), (96, 576, 16),
+            (576, 96, 16), (576, 160, 32), (160, 960, 32), (960, 160, 32), (960, 320, 32), (320, 1280, 32)]
+
+
 POINTWISE_BATCH, POINTWISE_H, POINTWISE_W = 32, 120, 160   # the post-stem activation of 480 x 640 images
 DEPTHWISE_BATCH = 32
 SWEEP_BATCH = 16
