@@ -187,7 +187,7 @@ def test_pointwise_with_packed_masks_equals_byte_masks(layer, with_list):
 
 
 @pytest.mark.parametrize("irr", [0.48, 0.0, 0.97, 1.0])
-@pytest.mark.parametrize("c_mid,c_out", [(64, 256), (128, 64), (128, 128)])
+@pytest.mark.parametrize("c_mid,c_out", [(64, 256), (128, 64), (128, 128), (24, 144), (144, 24), (320, 1280)])
 def test_pointwise_on_compacted_activations(c_mid, c_out, irr):
     """A 1x1 layer that reads and writes compacted rows (rows in list order) gives, bit for bit, the
     rows the spatial layout holds at the list's entries; rows past the count stay untouched."""
