@@ -79,21 +79,22 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;
 }
 
-// Does the pointwise kernel serve this layer?  1x1 layers without padding whose channel counts
-// are multiples of 8 and whose weights, cut into slices of 64 .. 256 output channels, stay in LDS
-// (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a layer every
-// labelling rule reduces to the one pixel under the tap, so a kept row never has a gated tap
-// and the kernel reads no input mask while it gathers.  Measured against the tiled kernel on
-// the 1x1 layers of a ResNet-50 (batch 32) and of a MobileNetV2 (batch 256): 10 .. 45 % faster,
-// except (a) 256 input channels into at most 128 output channels on the largest activations
-// (bound by reading them: 5 .. 15 % slower) and (b) three or more input chunks into a single
-// slice on fewer than 100 000 positions (48 .. 72 KB of weights per workgroup for a few rows
-// each: up to 20 % slower).  Those stay on the tiled kernel.
+// Does the pointwise kernel serve this layer?  1x1 layers without padding whose rows are whole
+// 16-byte pieces on both sides and whose weights, cut into slices of 64 .. 256 output channels,
+// stay in LDS (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a
+// layer every labelling rule reduces to the one pixel under the tap, so a kept row never has a
+// gated tap and the kernel reads no input mask while it gathers.  Measured against the tiled
+// kernel on the 1x1 layers of a ResNet-50 (batch 32, 16-bit and 8-bit storage) and of a
+// MobileNetV2 (batch 256): 10 .. 45 % faster, except (a) 16-bit rows of four 128-byte chunks
+// into at most 128 output channels on the largest activations (256 -> 64, 256 -> 128: bound by
+// reading them, 5 .. 15 % slower) and (b) three or more chunks into a single slice on fewer than
+// 100 000 positions (48 .. 72 KB of weights per workgroup for a few rows each: up to 20 %
+// slower).  Those stay on the tiled kernel.
 bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
 {
     if (g.m <= kInlineRankPositions || !conv_pw_supported(g, in_dtype, out_dtype)) return false;
-    if (g.c_in == 256 && g.c_out <= 128) return false;
-    const int kch = (g.c_in + 63) / 64;
+    const int kch = (g.c_in * (in_dtype == FC_FP8 ? 1 : 2) + 127) / 128; // 128-byte chunks of an input row
+    if (in_dtype != FC_FP8 && kch == 4 && g.c_out <= 128) return false;
     if (kch >= 3 && g.c_out <= (kch > 4 ? 64 : 128) && g.m < 100000) return false;
     return true;
 }

@@ -8,12 +8,13 @@
 // follow one another, and every tile fetches its own weights.  Here a workgroup (one per CU)
 // keeps one slice of the output channels' weights (at most 72 KB) in LDS for the whole launch,
 // and every one of its eight or twelve waves is a pipeline of its own over units of 32 kept
-// rows: the next 64-channel chunk of its rows is on its way (a wave-wide load into LDS, counted
+// rows: the next 128-byte chunk of its rows is on its way (a wave-wide load into LDS, counted
 // and waited for by the wave itself) while the current one is multiplied against the slice.
 // Waves do not cooperate after the prologue: no barrier in the loop, two or three waves per SIMD
 // cover each other's waits.  16-bit outputs leave through LDS as whole 128-byte lines (the
 // accumulator layout by itself gives 32-byte pieces, which cost a 64 -> 256 layer a third of its
-// time).  Channel counts are any multiples of 8; which layers the library sends here is decided
+// time), 8-bit ones the same way.  Storage is bf16, f16 or E4M3 (the 8-bit matrix instruction);
+// rows are whole 16-byte pieces; which layers the library sends here is decided
 // in fc_api.hip (conv_pw_wanted), from measurements against the tiled kernel.
 //
 // Rows = kept output positions (from the list, or all positions of a dense layer); a row's pixel
@@ -74,20 +75,24 @@ __device__ __forceinline__ void pw_lds_settle(uint32_t lds_addr)
     __asm__ volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(probe) : "v"(lds_addr) : "memory");
 }
 
-// DT: storage type (bf16 / f16); TO: float or the 16-bit / 8-bit carrier of the output; NCB:
-// 32-channel blocks of a workgroup's slice of the output channels; KCT: the number of 64-channel
-// chunks of the input where the chunk loop is unrolled (1, 2, 4, 8: 10 % faster on layers of
-// several chunks), 0 = a launch parameter.  The waves of the workgroup (blockDim.x / 64) are a
-// launch parameter.  Channel counts are multiples of 8 (16-byte pieces): the pieces of the last chunk
-// past c_in and the channels of the last slice past c_out are read as zeros and never stored.
+// DT: storage type (bf16 / f16 / E4M3); TO: float or the 16-bit / 8-bit carrier of the output;
+// NCB: 32-channel blocks of a workgroup's slice of the output channels; KCT: the number of
+// 128-byte chunks of an input row (64 channels of a 16-bit type, 128 of the 8-bit one) where the
+// chunk loop is unrolled (1, 2, 4, 8: 10 % faster on layers of several chunks), 0 = a launch
+// parameter.  The waves of the workgroup (blockDim.x / 64) are a launch parameter.  Rows are whole
+// 16-byte pieces on both sides: the pieces of the last chunk past c_in and the channels of the
+// last slice past c_out are read as zeros and never stored.
 template <int DT, typename TO, int NCB, int KCT>
 __global__ __launch_bounds__(768, 1)
-void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, const uint8_t *__restrict__ mask_in,
-               const uint8_t *__restrict__ mask_out, const uint16_t *__restrict__ w,
+void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__ x, const uint8_t *__restrict__ mask_in,
+               const uint8_t *__restrict__ mask_out, const unsigned char *__restrict__ w,
                const float *__restrict__ bias, const int32_t *__restrict__ idx,
                const int32_t *__restrict__ count, TO *__restrict__ out)
 {
-    static_assert(DT == FC_BF16 || DT == FC_F16, "16-bit storage");
+    constexpr int ES = DT == FC_FP8 ? 1 : 2;            // bytes per stored element
+    constexpr int ODT = DT == FC_FP8 ? FC_BF16 : DT;    // 16-bit output format
+    constexpr uint32_t KSTEP = kStepBytes<DT>;          // bytes of a chunk row per matrix instruction
+    constexpr int KK = 128 / (int)KSTEP;                // matrix instructions per chunk and block
     constexpr int RING = 2;                   // chunk buffers per wave
     constexpr int COUT = NCB * 32;
     constexpr int GB = NCB < 4 ? NCB : 4;     // channel blocks multiplied at a time
@@ -127,18 +132,18 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
     // an output larger than the memory-side cache (256 MB) is streamed past it: measured on a
     // 64 -> 256 layer, 314 MB of rows leave 22 % faster that way, 164 MB of rows 10 % slower
     const bool stream_out = (int64_t)rows * g.c_out * (int)sizeof(TO) > (256ll << 20);
-    const int cin8 = g.c_in >> 3; // 16-byte pieces of an input row
+    const int cin8 = (g.c_in * ES) >> 4; // 16-byte pieces of an input row
 
-    // ---- the weights: LDS row (chunk, output channel) holds that channel's 64 input channels
-    // of the chunk, its 16-byte pieces swizzled by the channel ----
+    // ---- the weights: LDS row (chunk, output channel) holds that channel's 128 bytes of input
+    // channels of the chunk, its 16-byte pieces swizzled by the channel ----
     if (!spare) {
-        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * (uint32_t)g.c_in * 2u);
+        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * (uint32_t)g.c_in * (uint32_t)ES);
         const int loads = kch * (COUT / 8); // wave loads of 8 rows each
         for (int ii = wave; ii < loads; ii += nw) {
             const int ch = ii / (COUT / 8), co = (ii - ch * (COUT / 8)) * 8 + (lane >> 3);
             const int piece = ch * 8 + ((lane & 7) ^ (int)FC_SWZ(co));
             const bool ok = co < co_left && piece < cin8;
-            const uint32_t off = ((uint32_t)(co0 + co) * (uint32_t)g.c_in) * 2u + (uint32_t)piece * 16u;
+            const uint32_t off = ((uint32_t)(co0 + co) * (uint32_t)g.c_in) * (uint32_t)ES + (uint32_t)piece * 16u;
             dma_load16(rsrc_w, ok ? off : kOutOfRange, lds0 + (uint32_t)ii * 1024u);
         }
         for (int c = tid; c < COUT; c += nw * 64)
@@ -158,7 +163,7 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
     const int nu = spare ? 0 : b1 - b0;
 
     const uint32_t x_rows = compact_in ? (uint32_t)g.m : (uint32_t)g.n * g.h * g.w;
-    const uint32_t row_bytes = (uint32_t)g.c_in * 2u;
+    const uint32_t row_bytes = (uint32_t)g.c_in * (uint32_t)ES;
     const u32x4_t rsrc_x = make_rsrc_words(x, x_rows * row_bytes);
     const u32x4_t rsrc_i = make_rsrc_words(idx, (uint32_t)rows * 4u);
     const bool unit_step = g.sh == 1 && g.sw == 1; // (no padding: the pixel of a position is the position)
@@ -215,7 +220,7 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
             const int row = j * 8 + (lane >> 3);
             const uint32_t o = (uint32_t)__shfl((int)off, row, 64);
             st_off[k][j] = o == kOutOfRange ? o : o + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
-            if constexpr (sizeof(TO) == 2) st_pr[k][j] = __shfl(st_p[k], row, 64);
+            if constexpr (sizeof(TO) <= 2) st_pr[k][j] = __shfl(st_p[k], row, 64);
         }
     };
     // one stage: chunk c of the unit with state k, into ring buffer `buf`
@@ -232,10 +237,11 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
     };
 
     // fragment addressing: lane reads row (lane & 31); in k-step kk that is the 16-byte piece
-    // 2 kk + (lane >> 5), stored at slot piece ^ swizzle(row)
-    const uint32_t frag = (uint32_t)l32 * 128u + (uint32_t)(half ^ FC_SWZ(l32)) * 16u;
+    // 2 kk + (lane >> 5) (8-bit storage: the pieces 4 kk + 2 (lane >> 5) and the one after it),
+    // stored at slot piece ^ swizzle(row)
+    const uint32_t frag = (uint32_t)l32 * 128u + (uint32_t)((half * (int)(KSTEP / 32u)) ^ FC_SWZ(l32)) * 16u;
 
-    // fp32 and 8-bit outputs: one rounding, ReLU, and every lane stores its four channels
+    // fp32 outputs: one rounding, ReLU, and every lane stores its four channels
     auto store_block = [&](const f32x16_t &a, int cb, int p_mine) {
         float v[16];
 #pragma unroll
@@ -256,16 +262,7 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
                     v2 = relu_keep_nan(v2); v3 = relu_keep_nan(v3);
                 }
                 if (p_mine >= 0 && cb * 32 + q * 8 + half * 4 < co_left)
-                    store4<DT, TO>(row + q * 8 + half * 4, v0, v1, v2, v3);
-            }
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                uint32_t pk;
-                store4<DT, TO>(reinterpret_cast<TO *>(&pk), v[q * 4], v[q * 4 + 1], v[q * 4 + 2], v[q * 4 + 3]);
-                if (g.flags & FC_RELU) pk = relu_packed8(pk);
-                if (p_mine >= 0 && cb * 32 + q * 8 + half * 4 < co_left)
-                    *reinterpret_cast<uint32_t *>(row + q * 8 + half * 4) = pk;
+                    store4<ODT, TO>(row + q * 8 + half * 4, v0, v1, v2, v3);
             }
         }
     };
@@ -284,7 +281,7 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
                 for (int q = 0; q < 4; ++q) {
                     const float4 bq = *reinterpret_cast<const float4 *>(bias_s + (cb + bl) * 32 + q * 8 + half * 4);
                     uint2 pk;
-                    store4<DT, TO>(reinterpret_cast<TO *>(&pk), a[q * 4] + bq.x, a[q * 4 + 1] + bq.y,
+                    store4<ODT, TO>(reinterpret_cast<TO *>(&pk), a[q * 4] + bq.x, a[q * 4 + 1] + bq.y,
                                    a[q * 4 + 2] + bq.z, a[q * 4 + 3] + bq.w);
                     if (g.flags & FC_RELU) {
                         pk.x = relu_packed16(pk.x);
@@ -322,6 +319,40 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
         }
     };
 
+    // 8-bit outputs: the (two or four) blocks of a group, 32 bytes of a row each, go through LDS the
+    // same way and leave as 16-byte pieces, up to 128 bytes of a row per store instruction.
+    auto store_bytes = [&](const f32x16_t *a, int cb, unsigned char *stg) {
+        if constexpr (sizeof(TO) == 1) {
+            if (cb * 32 >= co_left) return; // (a group wholly past the last channel)
+#pragma unroll
+            for (int bl = 0; bl < GB; ++bl) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 bq = *reinterpret_cast<const float4 *>(bias_s + (cb + bl) * 32 + q * 8 + half * 4);
+                    uint32_t pk;
+                    store4<ODT, TO>(reinterpret_cast<TO *>(&pk), a[bl][q * 4] + bq.x, a[bl][q * 4 + 1] + bq.y,
+                                    a[bl][q * 4 + 2] + bq.z, a[bl][q * 4 + 3] + bq.w);
+                    if (g.flags & FC_RELU) pk = relu_packed8(pk);
+                    const uint32_t at = (uint32_t)l32 * 128u + (uint32_t)((bl * 2 + (q >> 1)) ^ FC_SWZ(l32)) * 16u +
+                                        (uint32_t)((q & 1) * 8 + half * 4);
+                    *reinterpret_cast<uint32_t *>(stg + at) = pk;
+                }
+            }
+            __asm__ volatile("" ::: "memory");
+            const bool inside = (lane & 7) < GB * 2 && cb * 32 + (lane & 7) * 16 < co_left; // this lane's 16 channels exist
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = j * 8 + (lane >> 3);
+                const uint32_t at = (uint32_t)row * 128u + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
+                const u32x4_t piece = *reinterpret_cast<const u32x4_t *>(stg + at);
+                const int pr = st_pr[0][j];
+                if (pr >= 0 && inside)
+                    *reinterpret_cast<u32x4_t *>(out + (int64_t)pr * g.c_out + co0 + cb * 32 + (lane & 7) * 16) = piece;
+            }
+            __asm__ volatile("" ::: "memory");
+        }
+    };
+
     // ---- the pipeline: stage t = (unit t / kch, chunk t % kch) lives in ring buffer t % 2, and
     // stage t + 1 is issued when stage t is about to be consumed ----
     if (nu > 0) {
@@ -349,9 +380,9 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
             pw_wait_vmcnt(issued - (buf == 0 ? mark_x[0] : mark_x[1]));
             pw_lds_settle(my0 + (uint32_t)buf * kPwChunkBytes);
             const unsigned char *xs = my + (size_t)buf * kPwChunkBytes;
-            Frag<DT> xf[4];
+            Frag<DT> xf[KK];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) xf[kk].load(xs, frag ^ (uint32_t)(kk * 32));
+            for (int kk = 0; kk < KK; ++kk) xf[kk].load(xs, frag ^ ((uint32_t)kk * KSTEP));
 #pragma unroll
             for (int gb = 0; gb < NCB; gb += GB) {
                 if (c == 0 || NCB > GB) {
@@ -362,10 +393,10 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
                 }
                 const unsigned char *ws = smem_raw + (size_t)(c * COUT + gb * 32) * 128u;
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
+                for (int kk = 0; kk < KK; ++kk) {
                     Frag<DT> wf[GB];
 #pragma unroll
-                    for (int b = 0; b < GB; ++b) wf[b].load(ws + b * 4096, frag ^ (uint32_t)(kk * 32));
+                    for (int b = 0; b < GB; ++b) wf[b].load(ws + b * 4096, frag ^ ((uint32_t)kk * KSTEP));
 #pragma unroll
                     for (int b = 0; b < GB; ++b) acc[b] = mfma32<DT>(wf[b], xf[kk], acc[b]);
                 }
@@ -374,6 +405,8 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const uint16_t *__restrict__ x, c
 #pragma unroll
                         for (int b = 0; b < GB; b += 2)
                             store_pair(acc[b], acc[b + 1], gb + b, my + (size_t)buf * kPwChunkBytes);
+                    } else if constexpr (sizeof(TO) == 1) {
+                        store_bytes(acc, gb, my + (size_t)buf * kPwChunkBytes);
                     } else {
 #pragma unroll
                         for (int b = 0; b < GB; ++b) store_block(acc[b], gb + b, p_mine);
@@ -434,9 +467,9 @@ constexpr uint32_t kPwLdsBytes = 160u * 1024u;
 // computed in two halves) and so reads every row once for up to 256 output channels; with more
 // chunks all accumulators of a row are live at once and a slice is 128 channels, or 64 where
 // 128 would not leave room for eight waves beside the weights.
-static int pw_slice_blocks(const Geom &g)
+static int pw_slice_blocks(const Geom &g, int es)
 {
-    const int kch = (g.c_in + 63) / 64;
+    const int kch = (g.c_in * es + 127) / 128; // chunks of 128 bytes
     if (kch == 1) return g.c_out <= 64 ? 2 : g.c_out <= 128 ? 4 : 8;
     for (int ncb = g.c_out <= 64 ? 2 : 4; ncb >= 2; ncb -= 2)
         if ((uint32_t)kch * ncb * 32u * 128u + 1024u + 8u * pw_wave_bytes(2) <= kPwLdsBytes) return ncb;
@@ -463,19 +496,20 @@ static int pw_grid()
 
 bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
 {
-    if (in_dtype != FC_BF16 && in_dtype != FC_F16) return false;
-    if (out_dtype != in_dtype && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
+    if (in_dtype != FC_BF16 && in_dtype != FC_F16 && in_dtype != FC_FP8) return false;
+    if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
+    const int es = in_dtype == FC_FP8 ? 1 : 2;
     if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0)) return false;
     // rows of whole 16-byte pieces on both sides
-    if (g.c_in < 8 || g.c_in % 8 != 0 || g.c_out < 8 || g.c_out % 8 != 0) return false;
+    if (g.c_in * es < 16 || (g.c_in * es) % 16 != 0 || g.c_out < 8 || g.c_out % 8 != 0) return false;
     if (out_dtype == FC_FP8 && g.c_out % 16 != 0) return false;
-    const int ncb = pw_slice_blocks(g);
+    const int ncb = pw_slice_blocks(g, es);
     if (ncb == 0) return false;
     // the slices of a group of workgroups sit on one XCD
     const int n_slices = (g.c_out + ncb * 32 - 1) / (ncb * 32), per_xcd = pw_grid() >> 3;
     if (n_slices > per_xcd) return false;
-    if ((uint64_t)g.n * g.h * g.w * g.c_in * 2u >= kBufferLimit) return false;
-    if ((uint64_t)g.c_out * g.c_in * 2u >= kBufferLimit) return false;
+    if ((uint64_t)g.n * g.h * g.w * g.c_in * (uint64_t)es >= kBufferLimit) return false;
+    if ((uint64_t)g.c_out * g.c_in * (uint64_t)es >= kBufferLimit) return false;
     if ((uint64_t)g.m * 4u >= kBufferLimit) return false; // the list goes through a descriptor as well
     return true;
 }
@@ -486,7 +520,8 @@ static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in
                             hipStream_t s)
 {
     // twelve waves per CU where the weights leave room for their buffers, else eight
-    const int kch = (g.c_in + 63) / 64;
+    constexpr int es = DT == FC_FP8 ? 1 : 2;
+    const int kch = (g.c_in * es + 127) / 128;
     const uint32_t wbytes = (uint32_t)kch * NCB * 32u * 128u;
     const int fit = (int)((kPwLdsBytes - wbytes - 1024u) / pw_wave_bytes(2));
     if (fit < 8) return hipErrorInvalidValue;
@@ -509,8 +544,8 @@ static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in
         if (e != hipSuccess) return e;
         attr_devices.fetch_or(dev_bit, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(pw_grid()), dim3(nw * 64), lds, s, g, dv, kch, (const uint16_t *)x, mask_in, mask_out,
-                       (const uint16_t *)w, bias, idx, count, (TO *)out);
+    hipLaunchKernelGGL(kern, dim3(pw_grid()), dim3(nw * 64), lds, s, g, dv, kch, (const unsigned char *)x, mask_in, mask_out,
+                       (const unsigned char *)w, bias, idx, count, (TO *)out);
     return hipGetLastError();
 }
 
@@ -520,7 +555,8 @@ static hipError_t launch_pw_shape(const Geom &g, const void *x, const uint8_t *m
                                   void *out, hipStream_t s)
 {
 #define FC_PW_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
-    const int ncb = pw_slice_blocks(g), kch = (g.c_in + 63) / 64;
+    constexpr int es = DT == FC_FP8 ? 1 : 2;
+    const int ncb = pw_slice_blocks(g, es), kch = (g.c_in * es + 127) / 128;
     if (ncb == 8) return launch_pw<DT, TO, 8, 1>(FC_PW_ARGS);
     if (ncb == 4) {
         if (kch == 1) return launch_pw<DT, TO, 4, 1>(FC_PW_ARGS);
@@ -548,6 +584,11 @@ hipError_t launch_conv_pw(const Geom &g, int in_dtype, int out_dtype, const void
         if (out_dtype == FC_F32) return FC_PW_CALL(FC_BF16, float);
         if (out_dtype == FC_FP8) return FC_PW_CALL(FC_BF16, uint8_t);
         return FC_PW_CALL(FC_BF16, uint16_t);
+    }
+    if (in_dtype == FC_FP8) {
+        if (out_dtype == FC_F32) return FC_PW_CALL(FC_FP8, float);
+        if (out_dtype == FC_FP8) return FC_PW_CALL(FC_FP8, uint8_t);
+        return FC_PW_CALL(FC_FP8, uint16_t);
     }
     if (out_dtype == FC_F32) return FC_PW_CALL(FC_F16, float);
     if (out_dtype == FC_FP8) return FC_PW_CALL(FC_F16, uint8_t);

@@ -307,3 +307,44 @@ def test_pointwise_many_launches_of_a_many_stage_layer_are_bit_identical():
                             dtype=dtype)
     _check_f32(outs[B.F32], want, mask != 0)
     assert torch.equal(outs[dtype], outs[B.F32].to(outs[dtype].dtype))
+
+
+# ---- 8-bit (E4M3) storage: chunks of 128 channels, the 8-bit matrix instruction ----
+PW_FP8_LAYERS = [
+    (2, 60, 70, 128, 128, 1, 1, 0, 1),        # one chunk
+    (2, 50, 47, 64, 256, 1, 1, 0, 1),         # half a chunk, a slice of eight blocks
+    (1, 80, 81, 256, 1024, 1, 1, 0, 1),       # two chunks, eight slices
+    (1, 80, 81, 512, 128, 1, 1, 0, 1),        # four chunks into one slice: the tiled kernel
+    (1, 80, 81, 1024, 256, 1, 1, 0, 1),       # eight chunks, slices of 64
+    (1, 70, 66, 144, 48, 1, 2, 0, 1),         # tails on both sides, strided
+    (1, 300, 310, 64, 64, 1, 1, 0, 1),        # several units per wave
+]
+
+
+@pytest.mark.parametrize("layer", PW_FP8_LAYERS)
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", None])
+def test_pointwise_fp8_storage_matches_oracle(layer, mask_kind):
+    from tests.test_gpu_fp8 import TOL_FP8
+    torch = G.torch_mod()
+    out, want, keep = _run_layer(*layer, synth.FP8, mask_kind=mask_kind, seed=244)
+    got = G.to_f64(out)
+    rms = float(np.sqrt(np.mean(np.square(want[keep]))))
+    assert float(np.abs(got[keep] - want[keep]).max()) / rms <= TOL_FP8
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()
+    # bf16 output: the fp32 output rounded once; 8-bit output: its narrowing (+0 for -0 under ReLU)
+    o16, _, _ = _run_layer(*layer, synth.FP8, mask_kind=mask_kind, seed=244, out_dtype=B.BF16)
+    assert torch.equal(o16, out.to(torch.bfloat16))
+    if layer[4] % 16 == 0:
+        o8, _, _ = _run_layer(*layer, synth.FP8, mask_kind=mask_kind, seed=244, out_dtype=B.FP8)
+        codes = o8.view(torch.uint8).cpu().numpy()
+        f32 = out.cpu().numpy()
+        expect = O.narrow_fp8(f32.astype(np.float64))
+        expect[f32 == 0] = 0
+        np.testing.assert_array_equal(codes[keep], expect[keep])
+        assert not codes[~keep].any()
+        # chained, list given: the same codes on kept rows, the canary elsewhere
+        oc, _, _ = _run_layer(*layer, synth.FP8, mask_kind=mask_kind, seed=244, out_dtype=B.FP8,
+                              flags_extra=B.SKIP_ZERO_FILL, precomputed=True)
+        cc = oc.view(torch.uint8).cpu().numpy()
+        np.testing.assert_array_equal(cc[keep], codes[keep])
+        assert (cc[~keep] == 0x4E).all()
