@@ -88,7 +88,7 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
 // MobileNetV2 (batch 256): 10 .. 45 % faster, except (a) 16-bit rows of four 128-byte chunks
 // into at most 128 output channels on the largest activations (256 -> 64, 256 -> 128: bound by
 // reading them, 5 .. 15 % slower) and (b) three or more chunks into a single slice on fewer than
-// 100 000 positions (48 .. 72 KB of weights per workgroup for a few rows each: up to 20 %
+// 100 000 positions (24 .. 88 KB of weights per workgroup for a few rows each: up to 20 %
 // slower).  Those stay on the tiled kernel.
 bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
 {

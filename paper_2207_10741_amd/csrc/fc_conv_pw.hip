@@ -6,7 +6,7 @@
 // more (a bottleneck's 64 -> 256 expansion writes four times what it reads).  The tiled kernel
 // spends such a layer on fixed costs: set-up, the one or few stages and the epilogue of a tile
 // follow one another, and every tile fetches its own weights.  Here a workgroup (one per CU)
-// keeps one slice of the output channels' weights (at most 72 KB) in LDS for the whole launch,
+// keeps one slice of the output channels' weights (at most 88 KB) in LDS for the whole launch,
 // and every one of its eight or twelve waves is a pipeline of its own over units of 32 kept
 // rows: the next 128-byte chunk of its rows is on its way (a wave-wide load into LDS, counted
 // and waited for by the wave itself) while the current one is multiplied against the slice.
