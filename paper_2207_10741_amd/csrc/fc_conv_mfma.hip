@@ -982,10 +982,16 @@ static hipError_t launch_tile(const Geom &g, const void *x, const uint8_t *mask_
             // 13 % faster dense and 17 % faster focused than tap by tap)
             if (g.c_out > 64 && tiles128 >= 512)
                 return launch_dma<DT, TO, CMP, 128, 128, 2, 2, TAPC, 2, 2, 160, 2>(FC_ARGS);
-            // narrow layers: only with many tiles (C64@128: -7 % focused, -4..8 % dense from batch 128
-            // on; at batch 16 three workgroups per CU, below, are as fast)
-            const bool many_narrow_tiles = (int64_t)((g.m + 127) / 128) >= 4096;
+            // narrow layers: only with very many tiles (C64@128: -7 % focused, -4..8 % dense from batch
+            // 128 on, 16 384 row tiles; at 4 800 row tiles, 64 -> 64 on 32 x 120 x 160 positions, three
+            // workgroups per CU, below, are 7 % faster, and at batch 16 as fast)
+            const bool many_narrow_tiles = (int64_t)((g.m + 127) / 128) >= 8192;
             if (g.wo >= 32 && (g.c_out > 64 || partials || many_narrow_tiles))
+                return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
+            // shorter image rows, wide layers, a few hundred tiles (C512 on 32 x 15 x 20 positions:
+            // 66 us dense / 45 us chained against 102 / 49 us tap by tap; with 128 tiles, C512@16 at
+            // batch 16, tap by tap stays ahead)
+            if (g.c_out > 64 && tiles128 >= 256)
                 return launch_dma<DT, TO, CMP, 128, 64, 2, 2, TAPC, 3, 2, 160, 3>(FC_ARGS);
         }
     }
