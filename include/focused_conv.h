@@ -95,7 +95,15 @@ enum {
     /* Packed masks: mask_in and mask_out of this call are one BIT per pixel instead of one byte
        (see fc_mask_pack for the layout).  fc_focused_conv2d and fc_focused_gconv2d only; layers
        with at most 4 input channels and depthwise layers take byte masks (FC_ERR_DTYPE). */
-    FC_PACKED_MASKS = 32u
+    FC_PACKED_MASKS = 32u,
+    /* Kernel choice.  The library picks the kernel of a matrix-core layer from its shape by rules
+       measured on the layers of ResNet, VGG and MobileNet backbones.  With this flag a layer that
+       the resident-weights kernel supports (1x1 without padding, and 3x3 whose pixels are 128
+       bytes: 64 channels of a 16-bit type or 128 of the 8-bit one; more than 4 096 output
+       positions; a kept list or no mask) runs on that kernel whatever the rule says; on any other
+       layer the flag changes nothing.  Results are the same to the documented tolerance either
+       way (fp32 accumulation in a different order). */
+    FC_RESIDENT_WEIGHTS = 64u
 };
 
 /* The arrival counters of FC_WORKSPACE_READY live in this many leading bytes of the workspace. */

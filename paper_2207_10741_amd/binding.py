@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfocused_conv.so")
 
 F32, BF16, F16, FP8 = 0, 1, 2, 3
-RELU, SKIP_ZERO_FILL, WORKSPACE_READY, COMPACT_OUT, COMPACT_IN, PACKED_MASKS = 1, 2, 4, 8, 16, 32
+RELU, SKIP_ZERO_FILL, WORKSPACE_READY, COMPACT_OUT, COMPACT_IN, PACKED_MASKS, RESIDENT_WEIGHTS = 1, 2, 4, 8, 16, 32, 64
 RULE_CENTRE, RULE_ANY, RULE_ALL = 0, 1, 2
 WORKSPACE_COUNTER_BYTES = 2048
 NOALLOC_SCRATCH_BYTES = 40 << 20

@@ -47,7 +47,7 @@ int32_t make_geom(const fc_conv_desc *d, Geom *g)
         !(d->in_dtype != FC_F32 && d->out_dtype == FC_FP8))
         return FC_ERR_DTYPE;
     if (d->flags & ~(uint32_t)(FC_RELU | FC_SKIP_ZERO_FILL | FC_WORKSPACE_READY | FC_COMPACT_OUT | FC_COMPACT_IN |
-                               FC_PACKED_MASKS))
+                               FC_PACKED_MASKS | FC_RESIDENT_WEIGHTS))
         return FC_ERR_DTYPE;
     const int32_t ho = out_dim(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
     const int32_t wo = out_dim(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
@@ -79,6 +79,22 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;
 }
 
+// 3x3 layers of 64 16-bit channels into at most 64 (the first stage of ResNet-18/34 and the 3x3
+// of a ResNet-50's first stage, VGG's conv1_2): the nine taps' weights (72 KB) stay in LDS and
+// every wave runs its own pipeline, against 128-row tiles that stage the weights again for every
+// tile.  Measured against the tiled kernel at 48 % irrelevant pixels on 50 000 .. 2.5 M
+// positions: without a mask 12 .. 25 % faster up to 0.6 M positions (6 % slower at 2.5 M);
+// chained (no zero-fill) equal at 50 000, 1 .. 17 % faster from 100 000 on; with zero-fill 4 .. 7 %
+// slower up to 0.4 M (the zero-fill comes after a wave's units instead of between tiles), 16 %
+// faster at 0.6 M, equal at 2.5 M.  Into 128 channels the tiled kernels win.
+static bool conv_pw_wanted_3x3(const Geom &g, int in_dtype, bool masked)
+{
+    if (in_dtype == FC_FP8 || g.c_out > 64) return false;
+    if (!masked) return g.m >= 40000 && g.m < 1500000;
+    if (g.flags & (FC_SKIP_ZERO_FILL | FC_COMPACT_OUT)) return g.m >= 80000;
+    return g.m >= 500000 && g.m < 2000000;
+}
+
 // Does the pointwise kernel serve this layer?  1x1 layers without padding whose rows are whole
 // 16-byte pieces on both sides and whose weights, cut into slices of 64 .. 256 output channels,
 // stay in LDS (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a
@@ -90,9 +106,11 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
 // reading them, 5 .. 15 % slower) and (b) three or more chunks into a single slice on fewer than
 // 100 000 positions (24 .. 88 KB of weights per workgroup for a few rows each: up to 20 %
 // slower).  Those stay on the tiled kernel.
-bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype)
+bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype, bool masked)
 {
     if (g.m <= kInlineRankPositions || !conv_pw_supported(g, in_dtype, out_dtype)) return false;
+    if (g.flags & FC_RESIDENT_WEIGHTS) return true; // the caller's choice
+    if (g.kh == 3) return conv_pw_wanted_3x3(g, in_dtype, masked);
     const int kch = (g.c_in * (in_dtype == FC_FP8 ? 1 : 2) + 127) / 128; // 128-byte chunks of an input row
     if (in_dtype != FC_FP8 && kch == 4 && g.c_out <= 128) return false;
     if (kch >= 3 && g.c_out <= (kch > 4 ? 64 : 128) && g.m < 100000) return false;
@@ -348,10 +366,12 @@ int32_t fc_focused_conv2d(const fc_conv_desc *desc, const void *x, const uint8_t
     }
 
     hipError_t e;
-    if (mfma && idx && conv_line_wanted(g, desc->in_dtype, desc->out_dtype, mask_in != nullptr)) {
+    const bool pw = mfma && (idx || !mask_in) && conv_pw_wanted(g, desc->in_dtype, desc->out_dtype, mask_in != nullptr);
+    if (mfma && idx && !(pw && (g.flags & FC_RESIDENT_WEIGHTS)) &&
+        conv_line_wanted(g, desc->in_dtype, desc->out_dtype, mask_in != nullptr)) {
         e = launch_conv_line(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
         if (e != hipSuccess) return FC_ERR_HIP;
-    } else if (mfma && (idx || !mask_in) && conv_pw_wanted(g, desc->in_dtype, desc->out_dtype)) {
+    } else if (pw) {
         e = launch_conv_pw(g, desc->in_dtype, desc->out_dtype, x, mask_in, mask_out, w, bias, idx, count, out, s);
         if (e != hipSuccess) return FC_ERR_HIP;
     } else if (mfma) {

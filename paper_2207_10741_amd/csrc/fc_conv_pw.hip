@@ -29,6 +29,9 @@ namespace fc {
 constexpr uint32_t kPwChunkBytes = 32u * 128u;  // a chunk buffer: 32 rows x 64 channels
 // LDS of a wave: RING chunk buffers + the list entries of a unit
 constexpr uint32_t pw_wave_bytes(int ring) { return (uint32_t)ring * kPwChunkBytes + 256u; }
+// 3x3 layers: + the mask bytes under the nine taps of a unit's rows (five wave loads of a dword per lane)
+constexpr uint32_t kPwTapMaskBytes = 5u * 256u;
+constexpr uint32_t pw_wave_bytes_of(int ring, int taps) { return pw_wave_bytes(ring) + (taps > 1 ? kPwTapMaskBytes : 0u); }
 
 struct PwDivs {
     FastDiv wo, ho, cpr; // output width, output height, 16-byte pieces per output row
@@ -42,6 +45,15 @@ __device__ __forceinline__ void pw_dma_load4(const u32x4_t &rsrc, uint32_t byte_
                      : "memory");
 }
 
+// one byte per lane, zero-extended into the lane's dword of LDS (out of range: zero)
+__device__ __forceinline__ void pw_dma_load1(const u32x4_t &rsrc, uint32_t byte_offset, uint32_t lds_addr)
+{
+    __asm__ volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_ubyte %1, %2, 0 offen lds"
+                     :
+                     : "s"(lds_addr), "v"(byte_offset), "s"(rsrc)
+                     : "memory");
+}
+
 // s_waitcnt takes its count as an immediate, and n (wave-uniform) is known at run time only: a
 // jump into a table of 16 waits for the even counts 0 .. 30 (each followed by a branch to the
 // end), taking the largest even count that is not above n.
@@ -49,7 +61,8 @@ __device__ __forceinline__ void pw_dma_load4(const u32x4_t &rsrc, uint32_t byte_
 __device__ __forceinline__ void pw_wait_vmcnt(int n)
 {
     // the table starts 12 bytes after the address s_getpc_b64 returns; an entry is 8 bytes
-    const uint32_t off = (uint32_t)(min(n, 30) >> 1) * 8u + 12u;
+    // (n is wave-uniform; the scalar operand below must not be handed a vector register)
+    const uint32_t off = (uint32_t)(min(__builtin_amdgcn_readfirstlane(n), 30) >> 1) * 8u + 12u;
     __asm__ volatile("s_getpc_b64 vcc\n\t"
                      "s_add_u32 vcc_lo, vcc_lo, %0\n\t"
                      "s_addc_u32 vcc_hi, vcc_hi, 0\n\t"
@@ -63,16 +76,16 @@ __device__ __forceinline__ void pw_wait_vmcnt(int n)
 }
 #undef FC_WJ
 
-// Between the wait for a load into LDS and the first read of what it brought: one LDS read of
-// the same buffer, waited for.  Measured on this kernel: a read issued in the cycles right after
-// s_waitcnt vmcnt lets go can still return the buffer's previous contents (one wrong 32-row
-// block in about one launch of ten, with 37 000 waits per launch; four idle cycles in between
-// change nothing, the round trip of an LDS instruction ends it).  The tiled kernels have a
-// workgroup barrier in that place.
-__device__ __forceinline__ void pw_lds_settle(uint32_t lds_addr)
+// Before a load into LDS is issued: every LDS read this wave has issued has returned.  The reads
+// of the area the load overwrites come earlier in program order, but issued is not done: the
+// compiler places the matrix instructions that wait for them after the (asynchronous, to it
+// opaque) load, and the LDS queue of a workgroup whose waves all read weights can hold a read
+// back for longer than a load that hits in the cache takes to come back.  Measured before this
+// wait was there: in about one launch of ten of a 512 -> 2048 layer one unit's last k-step of a
+// chunk was multiplied with the data of the chunk two stages later, on a prefix of its rows.
+__device__ __forceinline__ void pw_lds_reads_done()
 {
-    uint32_t probe;
-    __asm__ volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(probe) : "v"(lds_addr) : "memory");
+    __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
 
 // DT: storage type (bf16 / f16 / E4M3); TO: float or the 16-bit / 8-bit carrier of the output;
@@ -82,7 +95,7 @@ __device__ __forceinline__ void pw_lds_settle(uint32_t lds_addr)
 // parameter.  The waves of the workgroup (blockDim.x / 64) are a launch parameter.  Rows are whole
 // 16-byte pieces on both sides: the pieces of the last chunk past c_in and the channels of the
 // last slice past c_out are read as zeros and never stored.
-template <int DT, typename TO, int NCB, int KCT>
+template <int DT, typename TO, int NCB, int KCT, int TAPS>
 __global__ __launch_bounds__(768, 1)
 void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__ x, const uint8_t *__restrict__ mask_in,
                const uint8_t *__restrict__ mask_out, const unsigned char *__restrict__ w,
@@ -93,7 +106,9 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
     constexpr int ODT = DT == FC_FP8 ? FC_BF16 : DT;    // 16-bit output format
     constexpr uint32_t KSTEP = kStepBytes<DT>;          // bytes of a chunk row per matrix instruction
     constexpr int KK = 128 / (int)KSTEP;                // matrix instructions per chunk and block
+    static_assert(TAPS == 1 || (TAPS == 9 && NCB == 2), "1x1, or 3x3 with a pixel of one 128-byte chunk");
     constexpr int RING = 2;                   // chunk buffers per wave
+    constexpr uint32_t WAVEB = pw_wave_bytes_of(RING, TAPS);
     constexpr int COUT = NCB * 32;
     constexpr int GB = NCB < 4 ? NCB : 4;     // channel blocks multiplied at a time
     // (with several input chunks all accumulators of a row are live at once: the host gives
@@ -109,8 +124,8 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const float *bias_s = reinterpret_cast<const float *>(smem_raw + wbytes);
-    unsigned char *const my = smem_raw + wbytes + 1024u + (size_t)wave * pw_wave_bytes(RING);
-    const uint32_t my0 = lds0 + wbytes + 1024u + (uint32_t)wave * pw_wave_bytes(RING);
+    unsigned char *const my = smem_raw + wbytes + 1024u + (size_t)wave * WAVEB;
+    const uint32_t my0 = lds0 + wbytes + 1024u + (uint32_t)wave * WAVEB;
     const int32_t *const idx_w = reinterpret_cast<const int32_t *>(my + RING * kPwChunkBytes);
 
     const bool packed_masks = (g.flags & FC_PACKED_MASKS) != 0;
@@ -132,18 +147,20 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
     // an output larger than the memory-side cache (256 MB) is streamed past it: measured on a
     // 64 -> 256 layer, 314 MB of rows leave 22 % faster that way, 164 MB of rows 10 % slower
     const bool stream_out = (int64_t)rows * g.c_out * (int)sizeof(TO) > (256ll << 20);
-    const int cin8 = (g.c_in * ES) >> 4; // 16-byte pieces of an input row
+    // 16-byte pieces of a weight row (a 3x3 layer's row is its nine taps' pixels, one chunk each:
+    // the layer is the 1x1 layer of the 9 C_in-channel patch)
+    const int cin8 = (TAPS * g.c_in * ES) >> 4;
 
     // ---- the weights: LDS row (chunk, output channel) holds that channel's 128 bytes of input
     // channels of the chunk, its 16-byte pieces swizzled by the channel ----
     if (!spare) {
-        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * (uint32_t)g.c_in * (uint32_t)ES);
+        const u32x4_t rsrc_w = make_rsrc_words(w, (uint32_t)g.c_out * (uint32_t)(TAPS * g.c_in) * (uint32_t)ES);
         const int loads = kch * (COUT / 8); // wave loads of 8 rows each
         for (int ii = wave; ii < loads; ii += nw) {
             const int ch = ii / (COUT / 8), co = (ii - ch * (COUT / 8)) * 8 + (lane >> 3);
             const int piece = ch * 8 + ((lane & 7) ^ (int)FC_SWZ(co));
             const bool ok = co < co_left && piece < cin8;
-            const uint32_t off = ((uint32_t)(co0 + co) * (uint32_t)g.c_in) * (uint32_t)ES + (uint32_t)piece * 16u;
+            const uint32_t off = ((uint32_t)(co0 + co) * (uint32_t)(TAPS * g.c_in)) * (uint32_t)ES + (uint32_t)piece * 16u;
             dma_load16(rsrc_w, ok ? off : kOutOfRange, lds0 + (uint32_t)ii * 1024u);
         }
         for (int c = tid; c < COUT; c += nw * 64)
@@ -177,10 +194,12 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
 
     // loads issued so far by this wave, and that count right after the last load of what is awaited
     int issued = 0, mark_idx = 0, mark_x[RING] = {};
+    [[maybe_unused]] int mark_m = 0;
 
     auto issue_idx = [&](int v) {
         if (!use_list) return;
         const uint32_t r = (uint32_t)(b0 + v) * 32u + (uint32_t)lane;
+        pw_lds_reads_done();
         pw_dma_load4(rsrc_i, lane < 32 ? r * 4u : kOutOfRange, my0 + RING * kPwChunkBytes);
         issued += 1;
         mark_idx = issued;
@@ -190,17 +209,97 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
     int st_p[2] = {-1, -1};
     int st_pr[2][4]; // where row 8j + lane / 8 is stored (16-bit outputs leave through LDS, in the gather's row order)
     uint32_t st_off[2][4];
+    // 3x3 only: per gathered row the taps that are read (inside the image and relevant: bit kh * 3 + kw;
+    // st_off is then the row's origin, tap (0, 0), which may lie before the tensor), and the
+    // position of this lane's row in the unit after the next set-up
+    [[maybe_unused]] uint32_t st_val[2][4] = {};
+    [[maybe_unused]] int st_pn = -1;
 #pragma unroll
     for (int k = 0; k < 2; ++k)
 #pragma unroll
         for (int j = 0; j < 4; ++j) st_off[k][j] = kOutOfRange, st_pr[k][j] = -1;
-    auto setup = [&](int v, int k) {
+
+    // ---- 3x3: a unit is set up in two steps.  presetup (a unit ahead of setup) takes the list
+    // entries and sends for the mask bytes under the nine taps of every row: wave load q brings
+    // tap 2q of row (lane & 31) for lanes 0 .. 31 and tap 2q + 1 for lanes 32 .. 63 ----
+    const uint32_t mask0 = my0 + RING * kPwChunkBytes + 256u;
+    const uint32_t *const mask_w = reinterpret_cast<const uint32_t *>(my + RING * kPwChunkBytes + 256u);
+    const u32x4_t rsrc_m = make_rsrc_words(mask_in, packed_masks ? (uint32_t)(((int64_t)g.n * g.h * g.w + 7) >> 3)
+                                                                 : (uint32_t)g.n * g.h * g.w);
+    // pixel index under tap t of the position (n, oh, ow), or -1 outside the image
+    auto tap_pixel = [&](int n, int oh, int ow, int t) -> int {
+        const int kh = (t * 11) >> 5, kw = t - kh * 3; // t / 3 for t < 10
+        const int ih = oh * g.sh - g.ph + kh * g.dh, iw = ow * g.sw - g.pw + kw * g.dw;
+        const bool in = t < 9 && (uint32_t)ih < (uint32_t)g.h && (uint32_t)iw < (uint32_t)g.w;
+        return in ? (n * g.h + ih) * g.w + iw : -1;
+    };
+    [[maybe_unused]] auto presetup = [&](int v) {
         const int r = (b0 + v) * 32 + l32;
         const bool valid = r < rows;
         int p = r;
         if (use_list) {
             pw_wait_vmcnt(issued - mark_idx);
-            pw_lds_settle(my0 + RING * kPwChunkBytes);
+            p = idx_w[l32];
+        }
+        st_pn = valid ? p : -1;
+        if (mask_in) {
+            const int q1 = (int)fast_div((uint32_t)(valid ? p : 0), dv.wo);
+            const int ow = (valid ? p : 0) - q1 * g.wo;
+            const int n = (int)fast_div((uint32_t)q1, dv.ho);
+            const int oh = q1 - n * g.ho;
+            pw_lds_reads_done();
+#pragma unroll
+            for (int q = 0; q < 5; ++q) {
+                const int px = valid ? tap_pixel(n, oh, ow, 2 * q + half) : -1;
+                pw_dma_load1(rsrc_m, px < 0 ? kOutOfRange : (uint32_t)(packed_masks ? px >> 3 : px), mask0 + (uint32_t)q * 256u);
+            }
+            issued += 5;
+            mark_m = issued;
+        }
+    };
+    auto setup = [&](int v, int k) {
+        const int r = (b0 + v) * 32 + l32;
+        if constexpr (TAPS == 9) {
+            const int p = st_pn;
+            const bool valid = p >= 0;
+            const int q1 = (int)fast_div((uint32_t)(valid ? p : 0), dv.wo);
+            const int ow = (valid ? p : 0) - q1 * g.wo;
+            const int n = (int)fast_div((uint32_t)q1, dv.ho);
+            const int oh = q1 - n * g.ho;
+            // this lane's taps (2q + half): inside the image, and relevant
+            uint32_t bits = 0;
+            if (mask_in) {
+                pw_wait_vmcnt(issued - mark_m);
+            }
+#pragma unroll
+            for (int q = 0; q < 5; ++q) {
+                const int t = 2 * q + half;
+                const int px = valid ? tap_pixel(n, oh, ow, t) : -1;
+                uint32_t on = px >= 0;
+                if (mask_in) {
+                    const uint32_t b = mask_w[q * 64 + lane];
+                    on &= packed_masks ? (b >> (px & 7)) & 1u : (uint32_t)(b != 0);
+                }
+                bits |= on << t;
+            }
+            bits |= (uint32_t)__shfl((int)bits, lane ^ 32, 64);
+            // the row's origin (tap (0, 0)); it may be outside the image, the taps read are not
+            const int pix0 = (n * g.h + oh * g.sh - g.ph) * g.w + ow * g.sw - g.pw;
+            const uint32_t off = (uint32_t)pix0 * row_bytes;
+            st_p[k] = valid ? (compact_out ? r : p) : -1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = j * 8 + (lane >> 3);
+                st_off[k][j] = (uint32_t)__shfl((int)off, row, 64) + (uint32_t)((lane & 7) ^ FC_SWZ(row)) * 16u;
+                st_val[k][j] = (uint32_t)__shfl((int)bits, row, 64);
+                if constexpr (sizeof(TO) <= 2) st_pr[k][j] = __shfl(st_p[k], row, 64);
+            }
+            return;
+        }
+        const bool valid = r < rows;
+        int p = r;
+        if (use_list) {
+            pw_wait_vmcnt(issued - mark_idx);
             p = idx_w[l32];
         }
         int pix = p;
@@ -225,11 +324,23 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
     };
     // one stage: chunk c of the unit with state k, into ring buffer `buf`
     auto issue_x = [&](int k, int c, int buf) {
-        const bool last = c == kch - 1;
+        pw_lds_reads_done();
+        if constexpr (TAPS == 9) {
+            // chunk c is the pixel under tap c: the row's origin + (kh dil_h W + kw dil_w) pixels
+            const int kh = (c * 11) >> 5, kw = c - kh * 3;
+            const uint32_t delta = (uint32_t)((kh * g.dh * g.w + kw * g.dw) * (int)row_bytes);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t o = (last && !((tail_ok >> j) & 1u)) ? kOutOfRange : st_off[k][j];
-            dma_load16_s(rsrc_x, o, (uint32_t)c * 128u, my0 + (uint32_t)buf * kPwChunkBytes + (uint32_t)j * 1024u);
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t o = ((st_val[k][j] >> c) & 1u) ? st_off[k][j] + delta : kOutOfRange;
+                dma_load16_s(rsrc_x, o, 0u, my0 + (uint32_t)buf * kPwChunkBytes + (uint32_t)j * 1024u);
+            }
+        } else {
+            const bool last = c == kch - 1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t o = (last && !((tail_ok >> j) & 1u)) ? kOutOfRange : st_off[k][j];
+                dma_load16_s(rsrc_x, o, (uint32_t)c * 128u, my0 + (uint32_t)buf * kPwChunkBytes + (uint32_t)j * 1024u);
+            }
         }
         issued += 4;
 #pragma unroll
@@ -357,6 +468,7 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
     // stage t + 1 is issued when stage t is about to be consumed ----
     if (nu > 0) {
         issue_idx(0);
+        if constexpr (TAPS == 9) presetup(0);
         setup(0, 0);
         if (nu > 1) issue_idx(1);
         issue_x(0, 0, 0);
@@ -372,13 +484,22 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
             const int bufn = buf ^ 1;
             if (c + 1 < kch) {
                 issue_x(0, c + 1, bufn);
+                if constexpr (TAPS == 9) {
+                    // the next unit's list entries have long arrived: its mask bytes go out now,
+                    // and the entries of the unit after it
+                    if (c == 0 && u + 1 < nu) {
+                        presetup(u + 1);
+                        if (u + 2 < nu) issue_idx(u + 2);
+                    }
+                }
             } else if (u + 1 < nu) {
                 setup(u + 1, 1);
-                if (u + 2 < nu) issue_idx(u + 2);
+                if constexpr (TAPS == 1) {
+                    if (u + 2 < nu) issue_idx(u + 2);
+                }
                 issue_x(1, 0, bufn);
             }
             pw_wait_vmcnt(issued - (buf == 0 ? mark_x[0] : mark_x[1]));
-            pw_lds_settle(my0 + (uint32_t)buf * kPwChunkBytes);
             const unsigned char *xs = my + (size_t)buf * kPwChunkBytes;
             Frag<DT> xf[KK];
 #pragma unroll
@@ -417,7 +538,7 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
         }
         st_p[0] = st_p[1];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) st_off[0][j] = st_off[1][j], st_pr[0][j] = st_pr[1][j];
+        for (int j = 0; j < 4; ++j) st_off[0][j] = st_off[1][j], st_pr[0][j] = st_pr[1][j], st_val[0][j] = st_val[1][j];
     }
 
     // ---- zero-fill of the irrelevant output rows.  An item is 64 consecutive positions, or one
@@ -444,7 +565,10 @@ void k_conv_pw(Geom g, PwDivs dv, int kch_arg, const unsigned char *__restrict__
                     const int ow = pp - q * g.wo;
                     const int b = (int)fast_div((uint32_t)q, dv.ho);
                     const int oh = q - b * g.ho;
-                    kept = mask_at(mask_in, (int64_t)(b * g.h + oh * g.sh) * g.w + ow * g.sw, packed_masks);
+                    // (the centre tap, clamped into the image)
+                    const int ihc = min(max(oh * g.sh - g.ph + g.dh * ((g.kh - 1) / 2), 0), g.h - 1);
+                    const int iwc = min(max(ow * g.sw - g.pw + g.dw * ((g.kw - 1) / 2), 0), g.w - 1);
+                    kept = mask_at(mask_in, (int64_t)(b * g.h + ihc) * g.w + iwc, packed_masks);
                 }
             }
             const uint64_t drop = __ballot(!kept);
@@ -467,8 +591,13 @@ constexpr uint32_t kPwLdsBytes = 160u * 1024u;
 // computed in two halves) and so reads every row once for up to 256 output channels; with more
 // chunks all accumulators of a row are live at once and a slice is 128 channels, or 64 where
 // 128 would not leave room for eight waves beside the weights.
+// 3x3 layers whose pixels are one chunk (128 bytes) run as the 1x1 layer of their nine-pixel
+// patches: nine chunks, slices of 64 output channels (72 KB of weights)
+static bool pw_is_3x3(const Geom &g, int es) { return g.kh == 3 && g.kw == 3 && g.c_in * es == 128; }
+
 static int pw_slice_blocks(const Geom &g, int es)
 {
+    if (pw_is_3x3(g, es)) return 2;
     const int kch = (g.c_in * es + 127) / 128; // chunks of 128 bytes
     if (kch == 1) return g.c_out <= 64 ? 2 : g.c_out <= 128 ? 4 : 8;
     for (int ncb = g.c_out <= 64 ? 2 : 4; ncb >= 2; ncb -= 2)
@@ -499,7 +628,8 @@ bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
     if (in_dtype != FC_BF16 && in_dtype != FC_F16 && in_dtype != FC_FP8) return false;
     if (out_dtype != (in_dtype == FC_FP8 ? FC_BF16 : in_dtype) && out_dtype != FC_F32 && out_dtype != FC_FP8) return false;
     const int es = in_dtype == FC_FP8 ? 1 : 2;
-    if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0)) return false;
+    if (!(g.kh == 1 && g.kw == 1 && g.ph == 0 && g.pw == 0) && !pw_is_3x3(g, es)) return false;
+    if (pw_is_3x3(g, es) && (g.flags & FC_COMPACT_IN)) return false;
     // rows of whole 16-byte pieces on both sides
     if (g.c_in * es < 16 || (g.c_in * es) % 16 != 0 || g.c_out < 8 || g.c_out % 8 != 0) return false;
     if (out_dtype == FC_FP8 && g.c_out % 16 != 0) return false;
@@ -514,20 +644,20 @@ bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype)
     return true;
 }
 
-template <int DT, typename TO, int NCB, int KCT>
+template <int DT, typename TO, int NCB, int KCT, int TAPS = 1>
 static hipError_t launch_pw(const Geom &g, const void *x, const uint8_t *mask_in, const uint8_t *mask_out,
                             const void *w, const float *bias, const int32_t *idx, const int32_t *count, void *out,
                             hipStream_t s)
 {
     // twelve waves per CU where the weights leave room for their buffers, else eight
     constexpr int es = DT == FC_FP8 ? 1 : 2;
-    const int kch = (g.c_in * es + 127) / 128;
+    const int kch = TAPS * ((g.c_in * es + 127) / 128);
     const uint32_t wbytes = (uint32_t)kch * NCB * 32u * 128u;
-    const int fit = (int)((kPwLdsBytes - wbytes - 1024u) / pw_wave_bytes(2));
+    const int fit = (int)((kPwLdsBytes - wbytes - 1024u) / pw_wave_bytes_of(2, TAPS));
     if (fit < 8) return hipErrorInvalidValue;
     const int nw = fit >= 12 ? 12 : 8;
-    const size_t lds = wbytes + 1024u + (size_t)nw * pw_wave_bytes(2);
-    auto kern = k_conv_pw<DT, TO, NCB, KCT>;
+    const size_t lds = wbytes + 1024u + (size_t)nw * pw_wave_bytes_of(2, TAPS);
+    auto kern = k_conv_pw<DT, TO, NCB, KCT, TAPS>;
     PwDivs dv;
     dv.wo = make_fastdiv((uint32_t)g.wo);
     dv.ho = make_fastdiv((uint32_t)g.ho);
@@ -556,6 +686,7 @@ static hipError_t launch_pw_shape(const Geom &g, const void *x, const uint8_t *m
 {
 #define FC_PW_ARGS g, x, mask_in, mask_out, w, bias, idx, count, out, s
     constexpr int es = DT == FC_FP8 ? 1 : 2;
+    if (pw_is_3x3(g, es)) return launch_pw<DT, TO, 2, 9, 9>(FC_PW_ARGS);
     const int ncb = pw_slice_blocks(g, es), kch = (g.c_in * es + 127) / 128;
     if (ncb == 8) return launch_pw<DT, TO, 8, 1>(FC_PW_ARGS);
     if (ncb == 4) {

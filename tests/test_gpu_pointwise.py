@@ -279,9 +279,9 @@ def test_pointwise_at_the_bench_size_with_a_streamed_output(irr):
 
 def test_pointwise_many_launches_of_a_many_stage_layer_are_bit_identical():
     """512 -> 2048 channels on 6480 positions: 32 slices, eight chunk loads per unit, 37 000 waits for
-    a load into LDS per launch.  Every launch must give the same bits (a read that overtakes the
-    load it waited for shows up as one differing block in about one launch of ten), and the
-    first one must match the oracle."""
+    a load into LDS per launch.  Every launch must give the same bits (a load into a ring buffer that
+    overtakes the last read of the chunk before shows up as one differing block in about one launch
+    of ten), and the first one must match the oracle."""
     torch = G.torch_mod()
     n, h, w, ci, co = 1, 80, 81, 512, 2048
     dtype = synth.BF16
@@ -348,3 +348,120 @@ def test_pointwise_fp8_storage_matches_oracle(layer, mask_kind):
         cc = oc.view(torch.uint8).cpu().numpy()
         np.testing.assert_array_equal(cc[keep], codes[keep])
         assert (cc[~keep] == 0x4E).all()
+
+
+# ---- 3x3 layers whose pixels are one 128-byte chunk (64 channels of a 16-bit type, 128 of the
+# 8-bit one): the same kernel, a chunk per tap, the weights of a 64-channel slice resident ----
+# ---- 3x3 layers whose pixels are one 128-byte chunk, on the same kernel (nine chunks per row: the
+# nine taps).  The library sends such layers there by measured size rules (tens of thousands of
+# positions and more); the tests ask for the kernel with FC_RESIDENT_WEIGHTS so that sizes the
+# oracle finishes in seconds reach it, and one test runs a size the rule itself sends there ----
+RW = B.RESIDENT_WEIGHTS
+
+PW_3X3_LAYERS = [
+    # n, h, w, ci, co, k, s, p, d
+    (2, 60, 70, 64, 64, 3, 1, 1, 1),
+    (2, 50, 47, 64, 128, 3, 1, 1, 1),                 # two slices
+    (2, 120, 121, 64, 64, 3, 2, 1, 1),                # stride 2
+    (1, 90, 77, 64, 64, 3, 1, 2, 2),                  # dilation 2
+    (2, 61, 67, 64, 40, 3, (2, 1), (3, 2), (2, 1)),   # wide padding, mixed stride and dilation, a short slice
+    (1, 80, 83, 64, 64, 3, 1, 0, 1),                  # no padding
+    (1, 300, 310, 64, 64, 3, 1, 1, 1),                # several units per wave
+]
+
+
+@pytest.mark.parametrize("layer", PW_3X3_LAYERS)
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", "mixed", None])
+def test_pointwise_kernel_on_3x3_layers_matches_oracle(layer, mask_kind):
+    torch = G.torch_mod()
+    out, want, keep = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=245, flags_extra=RW)
+    _check_f32(out, want, keep)
+    o16, _, _ = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=245, out_dtype=synth.BF16, flags_extra=RW)
+    assert torch.equal(o16, out.to(o16.dtype))
+    # chained, list given
+    oc, _, _ = _run_layer(*layer, synth.BF16, mask_kind=mask_kind, seed=245, flags_extra=B.SKIP_ZERO_FILL | RW,
+                          precomputed=True)
+    _check_f32(oc, want, keep, zero_filled=False)
+
+
+@pytest.mark.parametrize("layer", [PW_3X3_LAYERS[0], PW_3X3_LAYERS[2], PW_3X3_LAYERS[4]])
+@pytest.mark.parametrize("irr", [0.0, 1.0, 0.97])
+def test_pointwise_kernel_on_3x3_layers_extreme_densities_f16(layer, irr):
+    out, want, keep = _run_layer(*layer, synth.F16, irr=irr, seed=246, flags_extra=RW)
+    _check_f32(out, want, keep)
+
+
+@pytest.mark.parametrize("layer", [(2, 60, 70, 128, 64, 3, 1, 1, 1), (2, 61, 67, 128, 128, 3, 2, 1, 1)])
+@pytest.mark.parametrize("mask_kind", ["objects", "bernoulli", None])
+def test_pointwise_kernel_on_3x3_layers_fp8_storage(layer, mask_kind):
+    from tests.test_gpu_fp8 import TOL_FP8
+    torch = G.torch_mod()
+    out, want, keep = _run_layer(*layer, synth.FP8, mask_kind=mask_kind, seed=247, flags_extra=RW)
+    got = G.to_f64(out)
+    rms = float(np.sqrt(np.mean(np.square(want[keep]))))
+    assert float(np.abs(got[keep] - want[keep]).max()) / rms <= TOL_FP8
+    assert not out.cpu().numpy()[~keep].view(np.uint32).any()
+    o8, _, _ = _run_layer(*layer, synth.FP8, mask_kind=mask_kind, seed=247, out_dtype=B.FP8, flags_extra=RW)
+    codes = o8.view(torch.uint8).cpu().numpy()
+    f32 = out.cpu().numpy()
+    expect = O.narrow_fp8(f32.astype(np.float64))
+    expect[f32 == 0] = 0
+    np.testing.assert_array_equal(codes[keep], expect[keep])
+    assert not codes[~keep].any()
+
+
+def test_pointwise_kernel_on_3x3_layer_nan_under_irrelevant_pixels_and_packed_masks():
+    """NaN under every irrelevant pixel must not reach a kept row (every tap is gated by the input
+    mask), with byte masks and with bit masks alike."""
+    torch = G.torch_mod()
+    n, h, w, ci, co = 2, 60, 70, 64, 64
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 248, 1)
+    wt = synth.he_weights(co, 3, 3, ci, dtype, 248, 2)
+    mask = synth.mask_objects(n, h, w, 0.48, 248, 4)
+    md, mbits = G.mask_dev(mask), bits_dev(mask)
+    xd, wd = G.to_dev(x, dtype), G.to_dev(wt, dtype)
+    xn = xd.clone()
+    xn[~md.bool().reshape(n, h, w)] = float("nan")
+    outs = []
+    for packed, xin in ((False, xd), (False, xn), (True, xn)):
+        desc = B.conv_desc(n, h, w, ci, co, in_dtype=dtype, out_dtype=B.F32, flags=RW | (B.PACKED_MASKS if packed else 0))
+        outs.append(B.focused_conv2d(desc, xin, wd, None, mask_in=mbits if packed else md))
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+    want = O.focused_conv2d(O.ConvShape(n, h, w, ci, co, 3, 3, (1, 1), (1, 1), (1, 1), relu=False), x, wt, bias=None,
+                            mask_in=mask, dtype=dtype)
+    _check_f32(outs[0], want, mask != 0)
+
+
+def test_3x3_layer_sent_to_the_resident_weights_kernel_by_the_size_rule_matches_the_flagged_run():
+    """93 000 positions without a mask and chained are sizes the dispatch rule sends to the
+    resident-weights kernel by itself: the same bits as with the flag, and within tolerance of
+    the oracle on sampled positions."""
+    torch = G.torch_mod()
+    n, h, w, ci, co = 1, 300, 310, 64, 64
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 249, 1)
+    wt = synth.he_weights(co, 3, 3, ci, dtype, 249, 2)
+    bias = synth.bias(co, 249, 3)
+    mask = synth.mask_objects(n, h, w, 0.48, 249, 4)
+    xd, wd, bd, md = G.to_dev(x, dtype), G.to_dev(wt, dtype), torch.from_numpy(bias).to(G.dev()), G.mask_dev(mask)
+    idx, count = B.active_index_compact(md)
+    for masked in (False, True):
+        outs = []
+        for extra in (0, RW):
+            desc = B.conv_desc(n, h, w, ci, co, (3, 3), (1, 1), (1, 1), (1, 1), dtype, B.F32,
+                               B.RELU | extra | (B.SKIP_ZERO_FILL if masked else 0))
+            out = torch.zeros((n, h, w, co), dtype=torch.float32, device=G.dev())
+            kw = dict(mask_in=md, mask_out=md, idx=idx, count=count) if masked else {}
+            B.focused_conv2d(desc, xd, wd, bd, out=out, **kw)
+            outs.append(out)
+        assert torch.equal(outs[0], outs[1])
+        # sampled kept positions against the oracle's definition, one by one
+        rng = np.random.default_rng(249)
+        kept = np.flatnonzero(mask.reshape(-1)) if masked else np.arange(n * h * w)
+        pos = np.sort(rng.choice(kept, size=2000, replace=False))
+        shape = O.ConvShape(n, h, w, ci, co, 3, 3, (1, 1), (1, 1), (1, 1), relu=True)
+        want = O.focused_conv2d_at(shape, x, wt, pos, bias=bias, mask_in=mask if masked else None, dtype=dtype)
+        got = outs[0].reshape(-1, co)[torch.from_numpy(pos).to(G.dev())].cpu().numpy().astype(np.float64)
+        rms = float(np.sqrt(np.mean(np.square(want))))
+        assert float(np.abs(got - want).max()) / rms <= TOL_F32_OUT

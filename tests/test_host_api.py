@@ -56,7 +56,8 @@ def test_descriptor_errors():
     assert rc(in_dtype=B.FP8, out_dtype=B.BF16) == 0 and rc(in_dtype=B.FP8, out_dtype=B.F32) == 0
     assert rc(in_dtype=B.FP8, out_dtype=B.FP8) == 0 and rc(in_dtype=B.FP8, out_dtype=B.F16) == -3
     assert rc(in_dtype=B.BF16, out_dtype=B.FP8) == 0 and rc(in_dtype=B.F32, out_dtype=B.FP8) == -3
-    assert rc(flags=64) == -3
+    assert rc(flags=128) == -3
+    assert rc(flags=B.RESIDENT_WEIGHTS) == 0
     assert rc(flags=B.RELU | B.SKIP_ZERO_FILL | B.WORKSPACE_READY) == 0
     assert B.WORKSPACE_COUNTER_BYTES == int(re.search(r"FC_WORKSPACE_COUNTER_BYTES\s*=\s*(\d+)", HEADER_TEXT).group(1))
     assert rc(n=40000, h=1000, w=1000, k=(1, 1), pad=(0, 0)) == -6
