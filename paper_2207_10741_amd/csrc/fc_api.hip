@@ -95,9 +95,10 @@ static bool conv_pw_wanted_3x3(const Geom &g, int in_dtype, bool masked)
     return g.m >= 500000 && g.m < 2000000;
 }
 
-// Does the pointwise kernel serve this layer?  1x1 layers without padding whose rows are whole
+// Does the resident-weights kernel serve this layer?  1x1 layers without padding whose rows are whole
 // 16-byte pieces on both sides and whose weights, cut into slices of 64 .. 256 output channels,
-// stay in LDS (see fc_conv_pw.hip), with the kept list at hand or no mask at all.  In such a
+// stay in LDS (see fc_conv_pw.hip), with the kept list at hand or no mask at all (3x3 layers:
+// the rule above; FC_RESIDENT_WEIGHTS: every layer the kernel supports).  In such a
 // layer every labelling rule reduces to the one pixel under the tap, so a kept row never has a
 // gated tap and the kernel reads no input mask while it gathers.  Measured against the tiled
 // kernel on the 1x1 layers of a ResNet-50 (batch 32, 16-bit and 8-bit storage) and of a

@@ -21,6 +21,13 @@
 // is the position's centre tap (stride allowed, no padding), or row j of a compacted input.  The
 // pixel that decided to keep a position is the only one the position reads, so no mask byte is
 // looked at in the loop.  fp32 accumulators, bias added after the reduction, one rounding.
+//
+// 3x3 layers whose pixels are one 128-byte chunk (64 channels of a 16-bit type, 128 of the 8-bit
+// one) run here as the 1x1 layer of their nine-pixel patches (TAPS = 9): nine chunks per row,
+// chunk t the pixel under tap t, slices of 64 output channels (72 KB of weights).  A tap outside
+// the image or under an irrelevant pixel is not read (its chunk arrives as zeros): the mask bytes
+// under the nine taps of a unit's rows are fetched into LDS a unit ahead, and every gathered row
+// carries a nine-bit set of the taps it reads.  Any stride, padding and dilation.
 #include "fc_dma_util.hpp"
 #include <atomic>
 

@@ -298,9 +298,10 @@ hipError_t launch_conv_line(const Geom &g, int in_dtype, int out_dtype, const vo
                             const uint8_t *mask_in, const uint8_t *mask_out, const void *w, const float *bias,
                             const int32_t *idx, const int32_t *count, void *out, hipStream_t s);
 
-// Pointwise matrix-core path (see fc_conv_pw.hip): 1x1 layers without padding whose rows are
-// whole 16-byte pieces and whose weights, cut into slices of output channels, stay in LDS
-// (bf16, f16 or E4M3 storage).  Needs the kept list (or no mask at all).
+// Resident-weights matrix-core path (see fc_conv_pw.hip): 1x1 layers without padding whose rows
+// are whole 16-byte pieces and whose weights, cut into slices of output channels, stay in LDS,
+// and 3x3 layers whose pixels are 128 bytes (bf16, f16 or E4M3 storage).  Needs the kept list
+// (or no mask at all).
 bool conv_pw_supported(const Geom &g, int in_dtype, int out_dtype);
 hipError_t launch_conv_pw(const Geom &g, int in_dtype, int out_dtype, const void *x, const uint8_t *mask_in,
                           const uint8_t *mask_out, const void *w, const float *bias, const int32_t *idx,
