@@ -79,17 +79,18 @@ bool conv_line_wanted(const Geom &g, int in_dtype, int out_dtype, bool focused)
     return (int64_t)(g.m + 31) / 32 <= 8 * 256;
 }
 
-// 3x3 layers of 64 16-bit channels into at most 64 (the first stage of ResNet-18/34 and the 3x3
+// 3x3 layers of 128-byte pixels (64 16-bit channels) into at most 64 channels (the first stage of ResNet-18/34 and the 3x3
 // of a ResNet-50's first stage, VGG's conv1_2): the nine taps' weights (72 KB) stay in LDS and
 // every wave runs its own pipeline, against 128-row tiles that stage the weights again for every
 // tile.  Measured against the tiled kernel at 48 % irrelevant pixels on 50 000 .. 2.5 M
 // positions: without a mask 12 .. 25 % faster up to 0.6 M positions (6 % slower at 2.5 M);
 // chained (no zero-fill) equal at 50 000, 1 .. 17 % faster from 100 000 on; with zero-fill 4 .. 7 %
 // slower up to 0.4 M (the zero-fill comes after a wave's units instead of between tiles), 16 %
-// faster at 0.6 M, equal at 2.5 M.  Into 128 channels the tiled kernels win.
-static bool conv_pw_wanted_3x3(const Geom &g, int in_dtype, bool masked)
+// faster at 0.6 M, equal at 2.5 M.  Into 128 channels the tiled kernels win or draw.  128 8-bit
+// channels into 64 follow the same pattern (0.6 M positions: 25 .. 28 % faster in all three modes).
+static bool conv_pw_wanted_3x3(const Geom &g, bool masked)
 {
-    if (in_dtype == FC_FP8 || g.c_out > 64) return false;
+    if (g.c_out > 64) return false;
     if (!masked) return g.m >= 40000 && g.m < 1500000;
     if (g.flags & (FC_SKIP_ZERO_FILL | FC_COMPACT_OUT)) return g.m >= 80000;
     return g.m >= 500000 && g.m < 2000000;
@@ -111,7 +112,7 @@ bool conv_pw_wanted(const Geom &g, int in_dtype, int out_dtype, bool masked)
 {
     if (g.m <= kInlineRankPositions || !conv_pw_supported(g, in_dtype, out_dtype)) return false;
     if (g.flags & FC_RESIDENT_WEIGHTS) return true; // the caller's choice
-    if (g.kh == 3) return conv_pw_wanted_3x3(g, in_dtype, masked);
+    if (g.kh == 3) return conv_pw_wanted_3x3(g, masked);
     const int kch = (g.c_in * (in_dtype == FC_FP8 ? 1 : 2) + 127) / 128; // 128-byte chunks of an input row
     if (in_dtype != FC_FP8 && kch == 4 && g.c_out <= 128) return false;
     if (kch >= 3 && g.c_out <= (kch > 4 ? 64 : 128) && g.m < 100000) return false;
