@@ -465,3 +465,31 @@ def test_3x3_layer_sent_to_the_resident_weights_kernel_by_the_size_rule_matches_
         got = outs[0].reshape(-1, co)[torch.from_numpy(pos).to(G.dev())].cpu().numpy().astype(np.float64)
         rms = float(np.sqrt(np.mean(np.square(want))))
         assert float(np.abs(got - want).max()) / rms <= TOL_F32_OUT
+
+
+def test_many_launches_of_a_3x3_layer_on_the_resident_weights_kernel_are_bit_identical():
+    """One unit per wave at most (2 906 units of 32 rows on 2 048 waves): every wave is in its
+    start-up, where the loads of the list entries, of the tap masks and of the first chunks
+    follow one another most closely.  Forty launches each, masked and dense, fp32 and bf16
+    outputs: every launch the same bits, the bf16 output the rounding of the fp32 one."""
+    torch = G.torch_mod()
+    n, h, w, ci, co = 1, 300, 310, 64, 64
+    dtype = synth.BF16
+    x = synth.activations((n, h, w, ci), dtype, 250, 1)
+    wt = synth.he_weights(co, 3, 3, ci, dtype, 250, 2)
+    mask = synth.mask_objects(n, h, w, 0.48, 250, 4)
+    xd, wd, md = G.to_dev(x, dtype), G.to_dev(wt, dtype), G.mask_dev(mask)
+    idx, count = B.active_index_compact(md)
+    for masked in (True, False):
+        kw = dict(mask_in=md, mask_out=md, idx=idx, count=count) if masked else {}
+        firsts = {}
+        for out_dtype in (B.F32, dtype):
+            desc = B.conv_desc(n, h, w, ci, co, (3, 3), (1, 1), (1, 1), (1, 1), dtype, out_dtype, B.RELU | RW)
+            for it in range(40):
+                out = torch.full((n, h, w, co), 7.0, dtype=B.torch_dtype(out_dtype), device=G.dev())
+                B.focused_conv2d(desc, xd, wd, None, out=out, **kw)
+                if out_dtype not in firsts:
+                    firsts[out_dtype] = out
+                else:
+                    assert torch.equal(out, firsts[out_dtype]), "launch %d differs from the first" % it
+        assert torch.equal(firsts[dtype], firsts[B.F32].to(firsts[dtype].dtype))
