@@ -433,12 +433,13 @@ def test_pointwise_kernel_on_3x3_layer_nan_under_irrelevant_pixels_and_packed_ma
     _check_f32(outs[0], want, mask != 0)
 
 
-def test_3x3_layer_sent_to_the_resident_weights_kernel_by_the_size_rule_matches_the_flagged_run():
-    """93 000 positions without a mask and chained are sizes the dispatch rule sends to the
-    resident-weights kernel by itself: the same bits as with the flag, and within tolerance of
-    the oracle on sampled positions."""
+@pytest.mark.parametrize("n,h,w", [(1, 300, 310), (16, 128, 128)])
+def test_3x3_layer_sent_to_the_resident_weights_kernel_by_the_size_rule_matches_the_flagged_run(n, h, w):
+    """93 000 positions, and the benchmark's C64 layer at its batch (262 144 positions), without a
+    mask and chained, are sizes the dispatch rule sends to the resident-weights kernel by itself:
+    the same bits as with the flag, and within tolerance of the oracle on sampled positions."""
     torch = G.torch_mod()
-    n, h, w, ci, co = 1, 300, 310, 64, 64
+    ci, co = 64, 64
     dtype = synth.BF16
     x = synth.activations((n, h, w, ci), dtype, 249, 1)
     wt = synth.he_weights(co, 3, 3, ci, dtype, 249, 2)
